@@ -1,0 +1,157 @@
+"""fp64 CPU oracle for segment-level causal attention.  TEST INFRASTRUCTURE ONLY.
+
+This file is the plain definition of what the HIP library must compute, written from
+the paper and kept deliberately slow and obvious.  It is imported only by the tests,
+by the smoke check and by the benchmark's CPU-baseline leg; the product path never
+calls it, and it shares no code with the GPU path (it does not import the package).
+
+What it computes (Appendix C, "Attention Contexts for Local and Long-Range Heads"):
+
+* Eq. 12: Attn(Q,K,V) = softmax(Q K^T / sqrt(d) + M) V, where the mask M lets a
+  segment query see every prefix row and the rows of its own segment up to itself.
+* Eq. 13: which prefix a head sees.  A *local* head sees the carried KV tail, i.e. the
+  last M key/value rows of the previous segment (Sec. 3.4, "Local Continuity
+  Channel").  A *long-range* head in a long-range layer sees forward-only past KV
+  (Sec. 3.4, "Long-Range Channel"); elsewhere it sees its own segment only.
+* First segment: C_0 = R_0 = empty (Sec. 3.1, "Operational interpretation").
+
+Readings taken where the paper is silent (each is repeated in the design notes):
+
+* The policy is a bit mask per KV head, TAIL = 1, PAST = 2; a head with both bits sees
+  the *union of positions* (a key is never counted twice).  The query heads of a GQA
+  group inherit the policy of their KV head, which is query head // group size.
+* "Past" here is every position before the current segment (minus `evicted` oldest
+  ones), not a top-k subset: the retrieval operator of Appendix D is outside this path.
+* The tail is the last min(T, length of the previous segment) rows of the previous
+  segment only; T <= S is required.  Segments start at multiples of S; only the last
+  one may be short.
+* LSE is the natural log of sum_j exp(scale * q.k_j) over the visible keys.
+
+Everything is written over absolute token positions with an explicit boolean mask per
+query row, dense scores over all N keys, -inf where masked, and a plain softmax.
+Inputs are bf16 bit patterns (uint16) or floats; bf16 is widened exactly to fp64.
+All pins for this file live in tests/test_oracle_*.py; no function here is unpinned.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+POLICY_SEG = 0
+POLICY_TAIL = 1
+POLICY_PAST = 2
+
+
+def widen(x: np.ndarray) -> np.ndarray:
+    """Exact float64 value of a uint16 bf16 bit pattern (or of any float array)."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def visible_mask(p: int, n: int, seg_len: int, tail_len: int, policy: int,
+                 evicted: int = 0) -> np.ndarray:
+    """Boolean [n]: which key positions query position p may attend to (Eq. 12 mask,
+    Eq. 13 context).  Segment i = p // S starts at s = i*S."""
+    if not (0 <= tail_len <= seg_len):
+        raise ValueError("need 0 <= tail_len <= seg_len")
+    if not (0 <= p < n):
+        raise ValueError("query position outside the sequence")
+    s = (p // seg_len) * seg_len
+    j = np.arange(n)
+    vis = (j >= s) & (j <= p)                      # own segment, causal (all cases of Eq. 13)
+    if policy & POLICY_TAIL:                       # carried tail: last T rows of segment i-1
+        vis |= (j >= max(0, s - tail_len)) & (j < s)
+    if policy & POLICY_PAST:                       # forward-only past: every earlier row kept
+        vis |= (j >= evicted) & (j < s)
+    return vis
+
+
+def _rows_arg(rows, n):
+    if rows is None:
+        return np.arange(n, dtype=np.int64)
+    rows = np.asarray(rows, dtype=np.int64).reshape(-1)
+    if rows.size and (rows.min() < 0 or rows.max() >= n):
+        raise ValueError("row outside the sequence")
+    return rows
+
+
+def attend(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
+           scale: Optional[float] = None, rows=None, evicted: Optional[Sequence[int]] = None,
+           return_probs: bool = False, max_block_bytes: int = 1 << 28):
+    """Segment-level attention for the query positions `rows` (default: all).
+
+    q [B,N,Hq,D]; k, v [B,N,Hkv,D]; returns O [B,R,Hq,D] and LSE [B,Hq,R] in float64
+    (and the probabilities [B,Hq,R,N] if return_probs).  evicted[h] = number of oldest
+    rows KV head h no longer holds (only PAST visibility is affected)."""
+    q, k, v = widen(q), widen(k), widen(v)
+    B, N, Hq, D = q.shape
+    Hkv = k.shape[2]
+    if k.shape != (B, N, Hkv, D) or v.shape != k.shape:
+        raise ValueError("shape mismatch")
+    if Hq % Hkv or len(kv_policy) != Hkv:
+        raise ValueError("bad head configuration")
+    g = Hq // Hkv
+    scale = 1.0 / np.sqrt(D) if scale is None else float(scale)
+    rows = _rows_arg(rows, N)
+    R = rows.size
+    ev = [0] * Hkv if evicted is None else [int(e) for e in evicted]
+    out = np.zeros((B, R, Hq, D))
+    lse = np.zeros((B, Hq, R))
+    probs = np.zeros((B, Hq, R, N)) if return_probs else None
+    step = max(1, int(max_block_bytes // (8 * max(N, 1))))
+    for kvh in range(Hkv):
+        pol = int(kv_policy[kvh])
+        for r0 in range(0, R, step):
+            rr = rows[r0:r0 + step]
+            mask = np.stack([visible_mask(int(p), N, seg_len, tail_len, pol, ev[kvh]) for p in rr]) \
+                if rr.size else np.zeros((0, N), dtype=bool)
+            for b in range(B):
+                kb, vb = k[b, :, kvh, :], v[b, :, kvh, :]
+                for h in range(kvh * g, (kvh + 1) * g):
+                    z = (q[b, rr, h, :] @ kb.T) * scale          # dense scores, all N keys
+                    z = np.where(mask, z, -np.inf)               # + M of Eq. 12
+                    zmax = z.max(axis=1, keepdims=True)
+                    e = np.exp(z - zmax)
+                    denom = e.sum(axis=1, keepdims=True)
+                    pr = e / denom                               # softmax
+                    out[b, r0:r0 + rr.size, h, :] = pr @ vb
+                    lse[b, h, r0:r0 + rr.size] = (zmax + np.log(denom))[:, 0]
+                    if return_probs:
+                        probs[b, h, r0:r0 + rr.size, :] = pr
+    if return_probs:
+        return out, lse, probs
+    return out, lse
+
+
+def decode_attend(q, k_ctx, v_ctx, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
+                  scale: Optional[float] = None, evicted: Optional[Sequence[int]] = None
+                  ) -> Tuple[np.ndarray, np.ndarray]:
+    """One decoding step of one sequence (Eq. 2's conditioning on x_<t of the current
+    segment, C_{i-1} and R_{i-1}).  q [Hq,D] is the query of the newest token; k_ctx,
+    v_ctx [n,Hkv,D] hold the keys/values of all n tokens so far, the newest included.
+    By the forward identity of Sec. 3.1 this is row n-1 of the prefill of the same n
+    tokens.  Returns O [Hq,D] and LSE [Hq]."""
+    q = widen(q)
+    k_ctx, v_ctx = widen(k_ctx), widen(v_ctx)
+    n = k_ctx.shape[0]
+    qfull = np.zeros((1, n, q.shape[0], q.shape[1]))
+    qfull[0, n - 1] = q
+    o, l = attend(qfull, k_ctx[None], v_ctx[None], seg_len=seg_len, tail_len=tail_len,
+                  kv_policy=kv_policy, scale=scale, rows=[n - 1], evicted=evicted)
+    return o[0, 0], l[0, :, 0]
+
+
+def visible_pairs(n: int, seg_len: int, tail_len: int, policy: int, evicted: int = 0) -> int:
+    """Number of (query, key) pairs one head evaluates: popcount of the mask."""
+    return int(sum(int(visible_mask(p, n, seg_len, tail_len, policy, evicted).sum())
+                   for p in range(n)))
+
+
+def tail_of(k_seg, v_seg, tail_len: int):
+    """Carried state C_i of a finished segment: its last min(T, m) key/value rows."""
+    m = k_seg.shape[0]
+    t = min(tail_len, m)
+    return k_seg[m - t:], v_seg[m - t:]

@@ -1,0 +1,79 @@
+"""The pins must be sharp: a plausible mistake planted anywhere in the oracle (on the CPU,
+in a private copy of its source) has to make at least one pin fail."""
+import os
+import types
+
+import pytest
+
+import test_oracle_pins as pins
+from conftest import ROOT
+
+SRC = open(os.path.join(ROOT, "oracle", "segattn_oracle.py")).read()
+
+MUTANTS = {
+    "causal_excludes_diagonal": ("vis = (j >= s) & (j <= p)", "vis = (j >= s) & (j < p) | (j == s)"),
+    "causal_sees_one_ahead": ("(j <= p)", "(j <= p + 1)"),
+    "tail_one_row_short": ("(j >= max(0, s - tail_len)) & (j < s)", "(j >= max(0, s - tail_len + 1)) & (j < s)"),
+    "tail_one_row_long": ("(j >= max(0, s - tail_len)) & (j < s)", "(j >= max(0, s - tail_len - 1)) & (j < s)"),
+    "tail_from_two_segments_back": ("(j >= max(0, s - tail_len)) & (j < s)",
+                                    "(j >= max(0, s - seg_len - tail_len)) & (j < s - seg_len + tail_len)"),
+    "past_ignores_policy_bit": ("if policy & POLICY_PAST:", "if policy & POLICY_TAIL:"),
+    "past_includes_future": ("vis |= (j >= evicted) & (j < s)", "vis |= (j >= evicted)"),
+    "eviction_ignored": ("vis |= (j >= evicted) & (j < s)", "vis |= (j < s)"),
+    "segment_start_off_by_one": ("s = (p // seg_len) * seg_len", "s = ((p + 1) // seg_len) * seg_len"),
+    "scale_dropped": ("@ kb.T) * scale", "@ kb.T)"),
+    "scale_is_inverse_d": ("1.0 / np.sqrt(D)", "1.0 / D"),
+    "head_map_modulo": ("for h in range(kvh * g, (kvh + 1) * g):", "for h in range(kvh, Hq, Hkv):"),
+    "values_from_keys": ("pr @ vb", "pr @ kb"),
+    "lse_without_max": ("(zmax + np.log(denom))", "(np.log(denom))"),
+    "lse_base_2": ("np.log(denom)", "np.log2(denom)"),
+    "no_normalisation": ("pr = e / denom", "pr = e"),
+    "mask_added_as_zero": ("np.where(mask, z, -np.inf)", "np.where(mask, z, 0.0)"),
+    "decode_uses_previous_row": ("rows=[n - 1], evicted=evicted", "rows=[max(n - 2, 0)], evicted=evicted"),
+    "bf16_widen_shift": ("<< np.uint32(16)", "<< np.uint32(15)"),
+    "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
+}
+
+
+def _pin_calls():
+    calls = []
+    for name in sorted(dir(pins)):
+        fn = getattr(pins, name)
+        if not name.startswith("test_") or not callable(fn):
+            continue
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        if not marks:
+            calls.append((name, fn, {}))
+            continue
+        combos = [{}]
+        for m in marks:
+            keys = [k.strip() for k in m.args[0].split(",")]
+            new = []
+            for vals in m.args[1]:
+                vals = vals if isinstance(vals, (tuple, list)) and len(keys) > 1 else (vals,)
+                for c in combos:
+                    new.append({**c, **dict(zip(keys, vals))})
+            combos = new
+        calls.extend((name, fn, c) for c in combos)
+    return calls
+
+
+@pytest.mark.parametrize("mutant", sorted(MUTANTS))
+def test_planted_mistake_is_caught(mutant, monkeypatch):
+    old, new = MUTANTS[mutant]
+    assert SRC.count(old) >= 1, "mutation site not found: oracle source changed"
+    mod = types.ModuleType("oracle_mutant")
+    exec(compile(SRC.replace(old, new), "oracle_mutant", "exec"), mod.__dict__)
+    monkeypatch.setattr(pins, "orc", mod)
+    failed = []
+    for name, fn, kwargs in _pin_calls():
+        try:
+            fn(**kwargs)
+        except (AssertionError, ValueError, IndexError, FloatingPointError):
+            failed.append(name)
+    assert failed, f"no pin notices the planted mistake '{mutant}'"
+
+
+def test_unmutated_oracle_passes_all_pins():
+    for name, fn, kwargs in _pin_calls():
+        fn(**kwargs)

@@ -1,0 +1,321 @@
+"""Pins for the fp64 oracle: everything here checks oracle/ against something that is
+NOT the oracle -- hand-computed fixtures, textbook loops written out below, closed forms
+and invariants of Eq. 12 / Eq. 13 (Appendix C).  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import segattn_oracle as orc
+from conftest import golden_path
+
+POL = {"SEG": 0, "TAIL": 1, "PAST": 2, "TAIL|PAST": 3}
+
+
+def _read(name):
+    rows = []
+    with open(golden_path(name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line.split())
+    return rows
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ---------------------------------------------------------------- independent references
+def textbook_rows(q, k, v, scale, lo_of, hi_of):
+    """Softmax attention of one head, key range [lo_of(p), hi_of(p)] per row, written as
+    scalar Python loops (no matmul, no mask array): the textbook definition."""
+    n, d = q.shape
+    out = np.zeros((n, d))
+    lse = np.zeros(n)
+    for p in range(n):
+        js = list(range(lo_of(p), hi_of(p) + 1))
+        z = [scale * sum(q[p, c] * k[j, c] for c in range(d)) for j in js]
+        zm = max(z)
+        w = [math.exp(x - zm) for x in z]
+        tot = sum(w)
+        for c in range(d):
+            out[p, c] = sum(wi * v[j, c] for wi, j in zip(w, js)) / tot
+        lse[p] = zm + math.log(tot)
+    return out, lse
+
+
+def concat_formulation(q, k, v, S, T, policy, scale):
+    """Literal Eq. 13: per segment build [prefix ; segment] by concatenation (prefix =
+    carried tail for a local head, the whole earlier history for a long-range head,
+    nothing otherwise), prefix fully visible, segment causal (Eq. 12's mask)."""
+    n, d = q.shape
+    out = np.zeros((n, d))
+    lse = np.zeros(n)
+    for s in range(0, n, S):
+        m = min(S, n - s)
+        if policy & 2:
+            pk, pv = k[:s], v[:s]
+        elif policy & 1:
+            lo = max(0, s - T)
+            pk, pv = k[lo:s], v[lo:s]
+        else:
+            pk, pv = k[:0], v[:0]
+        kc = np.concatenate([pk, k[s:s + m]])
+        vc = np.concatenate([pv, v[s:s + m]])
+        P = pk.shape[0]
+        for t in range(m):
+            z = scale * (kc[:P + t + 1] @ q[s + t])
+            w = np.exp(z - z.max())
+            out[s + t] = (w / w.sum()) @ vc[:P + t + 1]
+            lse[s + t] = z.max() + math.log(w.sum())
+    return out, lse
+
+
+# ---------------------------------------------------------------- hand-computed fixtures
+def test_hand_case_constant_scores():
+    v = np.arange(1.0, 7.0).reshape(1, 6, 1, 1)
+    q = np.zeros((1, 6, 1, 1))
+    k = _rand((1, 6, 1, 1), 0)          # irrelevant: q = 0
+    for name, p, o_exp, cnt in _read("hand_case_constant_scores.txt"):
+        o, l = orc.attend(q, k, v, seg_len=3, tail_len=1, kv_policy=[POL[name]])
+        assert o[0, int(p), 0, 0] == pytest.approx(float(o_exp), abs=1e-14), (name, p)
+        assert l[0, 0, int(p)] == pytest.approx(math.log(int(cnt)), abs=1e-14), (name, p)
+
+
+def test_hand_case_log_keys():
+    q = np.ones((1, 3, 1, 1))
+    k = np.array([0.0, math.log(2), math.log(3)]).reshape(1, 3, 1, 1)
+    v = np.array([1.0, 2.0, 3.0]).reshape(1, 3, 1, 1)
+    o, l = orc.attend(q, k, v, seg_len=8, tail_len=0, kv_policy=[0], scale=1.0)
+    for p, num, den, el in _read("hand_case_log_keys.txt"):
+        assert o[0, int(p), 0, 0] == pytest.approx(int(num) / int(den), abs=1e-14)
+        assert l[0, 0, int(p)] == pytest.approx(math.log(int(el)), abs=1e-14)
+
+
+def test_default_scale_is_inverse_sqrt_d():
+    # Eq. 12 divides by sqrt(d): with d=4, q=(1,1,1,1), k_j = c_j*(1,1,1,1): z_j = 4 c_j / 2.
+    q = np.ones((1, 2, 1, 4))
+    k = np.stack([np.zeros(4), np.full(4, math.log(3) / 2)]).reshape(1, 2, 1, 4)
+    v = np.array([[0.0] * 4, [4.0] * 4]).reshape(1, 2, 1, 4)
+    o, l = orc.attend(q, k, v, seg_len=2, tail_len=0, kv_policy=[0])
+    assert l[0, 0, 1] == pytest.approx(math.log(1 + 3), abs=1e-14)      # exp(0)+exp(ln 3)
+    assert o[0, 1, 0, 0] == pytest.approx(3.0, abs=1e-14)               # (0*1 + 4*3)/4
+
+
+# ---------------------------------------------------------------- reductions to textbook loops
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+def test_single_segment_is_plain_causal(policy):
+    n, d = 13, 3
+    q, k, v = _rand((n, d), 1), _rand((n, d), 2), _rand((n, d), 3)
+    o, l = orc.attend(q[None, :, None], k[None, :, None], v[None, :, None],
+                      seg_len=16, tail_len=5, kv_policy=[policy], scale=0.7)
+    oe, le = textbook_rows(q, k, v, 0.7, lambda p: 0, lambda p: p)
+    np.testing.assert_allclose(o[0, :, 0], oe, atol=1e-13)
+    np.testing.assert_allclose(l[0, 0], le, atol=1e-13)
+
+
+@pytest.mark.parametrize("policy", [2, 3])
+def test_past_with_full_history_is_plain_causal(policy):
+    n, d, S, T = 23, 2, 5, 2
+    q, k, v = _rand((n, d), 4), _rand((n, d), 5), _rand((n, d), 6)
+    o, l = orc.attend(q[None, :, None], k[None, :, None], v[None, :, None],
+                      seg_len=S, tail_len=T, kv_policy=[policy])
+    oe, le = textbook_rows(q, k, v, 1 / math.sqrt(d), lambda p: 0, lambda p: p)
+    np.testing.assert_allclose(o[0, :, 0], oe, atol=1e-13)
+    np.testing.assert_allclose(l[0, 0], le, atol=1e-13)
+
+
+@pytest.mark.parametrize("T", [0, 1, 3, 7])
+def test_tail_head_is_segment_banded(T):
+    n, d, S = 26, 2, 7                     # ragged last segment (26 = 3*7 + 5)
+    q, k, v = _rand((n, d), 7), _rand((n, d), 8), _rand((n, d), 9)
+    o, l = orc.attend(q[None, :, None], k[None, :, None], v[None, :, None],
+                      seg_len=S, tail_len=T, kv_policy=[1])
+    lo = lambda p: max(0, (p // S) * S - T)
+    oe, le = textbook_rows(q, k, v, 1 / math.sqrt(d), lo, lambda p: p)
+    np.testing.assert_allclose(o[0, :, 0], oe, atol=1e-13)
+    np.testing.assert_allclose(l[0, 0], le, atol=1e-13)
+
+
+def test_seg_head_and_zero_tail_are_block_diagonal():
+    n, d, S = 20, 3, 6
+    q, k, v = _rand((n, d), 10), _rand((n, d), 11), _rand((n, d), 12)
+    oe, le = textbook_rows(q, k, v, 1 / math.sqrt(d), lambda p: (p // S) * S, lambda p: p)
+    for policy, T in ((0, 4), (1, 0)):
+        o, l = orc.attend(q[None, :, None], k[None, :, None], v[None, :, None],
+                          seg_len=S, tail_len=T, kv_policy=[policy])
+        np.testing.assert_allclose(o[0, :, 0], oe, atol=1e-13)
+        np.testing.assert_allclose(l[0, 0], le, atol=1e-13)
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+@pytest.mark.parametrize("S,T,n", [(8, 0, 29), (8, 1, 32), (8, 8, 27), (5, 3, 64), (64, 16, 40)])
+def test_mask_formulation_equals_concatenation_formulation(policy, S, T, n):
+    d = 4
+    q, k, v = _rand((n, d), 20 + n), _rand((n, d), 21 + n), _rand((n, d), 22 + n)
+    o, l = orc.attend(q[None, :, None], k[None, :, None], v[None, :, None],
+                      seg_len=S, tail_len=T, kv_policy=[policy])
+    oe, le = concat_formulation(q, k, v, S, T, policy, 1 / math.sqrt(d))
+    np.testing.assert_allclose(o[0, :, 0], oe, atol=1e-13)
+    np.testing.assert_allclose(l[0, 0], le, atol=1e-13)
+
+
+def test_gqa_head_map_and_batch_are_independent_problems():
+    """Query head h reads KV head h // g; batches do not mix.  Each (b, h) must equal the
+    single-head problem solved on its own."""
+    B, n, Hq, Hkv, d, S, T = 2, 19, 6, 3, 4, 6, 2
+    pol = [1, 3, 0]
+    q, k, v = _rand((B, n, Hq, d), 30), _rand((B, n, Hkv, d), 31), _rand((B, n, Hkv, d), 32)
+    o, l = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=pol)
+    for b in range(B):
+        for h in range(Hq):
+            kv = h // 2
+            oe, le = concat_formulation(q[b, :, h], k[b, :, kv], v[b, :, kv], S, T, pol[kv], 0.5)
+            np.testing.assert_allclose(o[b, :, h], oe, atol=1e-13)
+            np.testing.assert_allclose(l[b, h], le, atol=1e-13)
+
+
+# ---------------------------------------------------------------- closed forms and invariants
+def test_visible_pair_count_matches_cost_model_closed_form():
+    for N, S, T, name, pairs in _read("visible_pairs_closed_form.txt"):
+        N, S, T, pairs = int(N), int(S), int(T), int(pairs)
+        n = N // S
+        closed = n * S * (S + 1) // 2 + (n - 1) * S * T if name == "TAIL" else N * (N + 1) // 2
+        assert closed == pairs
+    # popcount of the oracle's mask against the same closed form (general m_i, ragged tail)
+    for N, S, T in ((2048, 512, 128), (100, 16, 5), (77, 10, 10), (64, 8, 0)):
+        starts = list(range(0, N, S))
+        tail_pairs = sum((min(S, N - s) * (min(S, N - s) + 1)) // 2 + min(S, N - s) * min(T, s)
+                         for s in starts)
+        seg_pairs = sum((min(S, N - s) * (min(S, N - s) + 1)) // 2 for s in starts)
+        assert orc.visible_pairs(N, S, T, 1) == tail_pairs
+        assert orc.visible_pairs(N, S, T, 0) == seg_pairs
+        assert orc.visible_pairs(N, S, T, 2) == N * (N + 1) // 2
+        assert orc.visible_pairs(N, S, T, 3) == N * (N + 1) // 2
+    assert orc.visible_pairs(2048, 512, 128, 1) == 721920
+
+
+def test_effective_context_per_token_matches_cost_model():
+    """Sec. 3.5: a local head's query sees at most S + M keys; a SEG head at most S."""
+    N, S, T = 96, 16, 6
+    assert max(orc.visible_mask(p, N, S, T, 1).sum() for p in range(N)) == S + T
+    assert max(orc.visible_mask(p, N, S, T, 0).sum() for p in range(N)) == S
+    assert max(orc.visible_mask(p, N, S, T, 2).sum() for p in range(N)) == N
+
+
+def test_probabilities_sum_to_one_and_respect_mask():
+    B, n, Hq, Hkv, d, S, T = 1, 37, 4, 4, 8, 8, 3
+    q, k, v = _rand((B, n, Hq, d), 40), _rand((B, n, Hkv, d), 41), _rand((B, n, Hkv, d), 42)
+    pol = [0, 1, 2, 3]
+    o, l, pr = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=pol, return_probs=True)
+    np.testing.assert_allclose(pr.sum(-1), 1.0, atol=1e-14)
+    for h in range(4):
+        for p in range(n):
+            vis = orc.visible_mask(p, n, S, T, pol[h])
+            assert np.all(pr[0, h, p][~vis] == 0.0)
+            assert np.all(pr[0, h, p][vis] > 0.0)
+            assert vis[p]                              # the diagonal is always visible
+
+
+def test_zero_queries_give_mean_of_visible_values():
+    n, Hkv, d, S, T = 41, 4, 5, 9, 4
+    k, v = _rand((1, n, Hkv, d), 50), _rand((1, n, Hkv, d), 51)
+    q = np.zeros((1, n, Hkv, d))
+    pol = [0, 1, 2, 3]
+    o, l = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=pol)
+    for h in range(4):
+        for p in range(n):
+            vis = orc.visible_mask(p, n, S, T, pol[h])
+            np.testing.assert_allclose(o[0, p, h], v[0, vis, h].mean(0), atol=1e-14)
+            assert l[0, h, p] == pytest.approx(math.log(vis.sum()), abs=1e-14)
+
+
+def test_shifting_all_keys_shifts_lse_only():
+    """Adding one vector u to every key adds scale*q_p.u to every score of row p:
+    O unchanged, LSE shifted by that constant."""
+    n, d, S, T = 30, 6, 7, 3
+    q, k, v = _rand((1, n, 2, d), 60), _rand((1, n, 2, d), 61), _rand((1, n, 2, d), 62)
+    u = _rand((d,), 63)
+    o1, l1 = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=[1, 3], scale=0.3)
+    o2, l2 = orc.attend(q, k + u, v, seg_len=S, tail_len=T, kv_policy=[1, 3], scale=0.3)
+    np.testing.assert_allclose(o1, o2, atol=1e-12)
+    shift = 0.3 * np.einsum("bnhd,d->bhn", q, u)
+    np.testing.assert_allclose(l2 - l1, shift, atol=1e-12)
+
+
+def test_value_linearity_and_output_in_convex_hull():
+    n, d, S, T = 25, 3, 6, 2
+    q, k = _rand((1, n, 1, d), 70), _rand((1, n, 1, d), 71)
+    v1, v2 = _rand((1, n, 1, d), 72), _rand((1, n, 1, d), 73)
+    o1, _ = orc.attend(q, k, v1, seg_len=S, tail_len=T, kv_policy=[1])
+    o2, _ = orc.attend(q, k, v2, seg_len=S, tail_len=T, kv_policy=[1])
+    o12, _ = orc.attend(q, k, 2 * v1 - 3 * v2, seg_len=S, tail_len=T, kv_policy=[1])
+    np.testing.assert_allclose(o12, 2 * o1 - 3 * o2, atol=1e-12)
+    for p in range(n):
+        vis = orc.visible_mask(p, n, S, T, 1)
+        assert np.all(o1[0, p, 0] <= v1[0, vis, 0].max(0) + 1e-12)
+        assert np.all(o1[0, p, 0] >= v1[0, vis, 0].min(0) - 1e-12)
+
+
+def test_eviction_hides_oldest_past_rows_but_not_the_tail():
+    n, d, S, T = 40, 3, 8, 3
+    q, k, v = _rand((n, d), 80), _rand((n, d), 81), _rand((n, d), 82)
+    ev = 13
+    o, l = orc.attend(q[None, :, None], k[None, :, None], v[None, :, None],
+                      seg_len=S, tail_len=T, kv_policy=[3], evicted=[ev])
+    def lo(p):                     # [max(0,s-T), s) united with [ev, s): both end at s
+        s = (p // S) * S
+        return min(max(0, s - T), min(ev, s))
+    oe, le = textbook_rows(q, k, v, 1 / math.sqrt(d), lo, lambda p: p)
+    np.testing.assert_allclose(o[0, :, 0], oe, atol=1e-13)
+    np.testing.assert_allclose(l[0, 0], le, atol=1e-13)
+
+
+# ---------------------------------------------------------------- rows, decode, inputs
+def test_row_subset_equals_rows_of_full_result():
+    w = W.small(seq_len=70, seg_len=16, tail_len=5, n_q_heads=4, n_kv_heads=2, head_dim=8)
+    q, k, v = W.prefill_inputs(w)
+    o, l = orc.attend(q, k, v, seg_len=16, tail_len=5, kv_policy=w.kv_policy)
+    rows = [0, 15, 16, 17, 69, 33]
+    o2, l2 = orc.attend(q, k, v, seg_len=16, tail_len=5, kv_policy=w.kv_policy, rows=rows,
+                        max_block_bytes=1500)
+    np.testing.assert_array_equal(o2, o[:, rows])
+    np.testing.assert_array_equal(l2, l[:, :, rows])
+
+
+def test_decode_row_is_last_prefill_row():
+    """Forward identity (Sec. 3.1): decoding token n-1 is row n-1 of prefilling n tokens."""
+    n, Hq, Hkv, d, S, T = 45, 4, 2, 8, 16, 4
+    q, k, v = _rand((1, n, Hq, d), 90), _rand((1, n, Hkv, d), 91), _rand((1, n, Hkv, d), 92)
+    o, l = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=[1, 3])
+    for m in (1, 16, 17, 32, 45):
+        od, ld = orc.decode_attend(q[0, m - 1], k[0, :m], v[0, :m], seg_len=S, tail_len=T,
+                                   kv_policy=[1, 3])
+        np.testing.assert_allclose(od, o[0, m - 1], atol=1e-14)
+        np.testing.assert_allclose(ld, l[0, :, m - 1], atol=1e-14)
+
+
+def test_bf16_widening_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4000, 0x3FC0, 0x0000, 0x4049, 0x3DCD], dtype=np.uint16)
+    exp = [1.0, -1.0, 2.0, 1.5, 0.0, 3.140625, 0.10009765625]
+    np.testing.assert_array_equal(orc.widen(bits), np.array(exp))
+
+
+def test_tail_of_is_last_rows():
+    k = np.arange(10.0).reshape(5, 2)
+    kt, vt = orc.tail_of(k, -k, 3)
+    np.testing.assert_array_equal(kt, k[2:])
+    kt, vt = orc.tail_of(k, -k, 8)
+    np.testing.assert_array_equal(vt, -k)
+
+
+def test_rejects_bad_arguments():
+    q = np.zeros((1, 4, 2, 2))
+    with pytest.raises(ValueError):
+        orc.attend(q, q, q, seg_len=2, tail_len=3, kv_policy=[1, 1])       # T > S
+    with pytest.raises(ValueError):
+        orc.attend(q, q[:, :, :1], q, seg_len=2, tail_len=1, kv_policy=[1])  # V shape
+    with pytest.raises(ValueError):
+        orc.attend(q, q, q, seg_len=2, tail_len=1, kv_policy=[1, 1], rows=[4])
