@@ -1,0 +1,180 @@
+/*
+ * segattn.h -- C ABI of libsegattn: segment-level causal attention for AMD MI355X (gfx950).
+ *
+ * The library implements the attention step of segmented execution (Sec. 3.1, Eq. 1: the
+ * same forward operator F(x_i, C_{i-1}, R_{i-1}) at training and inference time) for one
+ * attention layer:
+ *
+ *   - Eq. 12 (Appendix C): O = softmax(Q K^T * scale + M) V, where the mask M lets a
+ *     segment query see every prefix row and the rows of its own segment up to itself;
+ *   - Eq. 13 (Appendix C): the prefix a head sees -- the carried KV tail C_{i-1} (last T
+ *     key/value rows of the previous segment; Sec. 3.4 "Local Continuity Channel"), the
+ *     forward-only past KV (Sec. 3.4 "Long-Range Channel"), or nothing;
+ *   - the cross-segment state itself: tail hand-off and append-only past pool
+ *     (Sec. 3.4, Appendix D "Memory layout"; the paper applies no eviction, the evict call
+ *     here is an extension).
+ *
+ * Conventions that hold for every entry point
+ *   Pointers   Every q/k/v/out/lse/cache pointer is a DEVICE pointer unless the comment says
+ *              "host".  All of them are borrowed for the duration of the enqueued work; the
+ *              library never allocates or frees device memory.  The caller allocates one
+ *              cache arena of segattn_cache_bytes() bytes (256-byte aligned) and keeps it
+ *              alive until segattn_destroy().
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *              only enqueued; no entry point synchronises with the device.  All calls on one
+ *              context must be issued on one stream or be ordered by the caller.
+ *   Layouts    Dense, token-major:  q, out [B, rows, Hq, D];  k, v [B, rows, Hkv, D];
+ *              lse [B, Hq, rows].  q/k/v are bf16.  out is bf16, or fp32 when the
+ *              configuration sets out_fp32 or fp32_check.  lse is fp32, the natural logarithm of
+ *              sum_j exp(scale * q.k_j) over the visible keys.  Query head h reads KV head
+ *              h / (Hq / Hkv).
+ *   Errors     Every call validates its arguments and the context state before it enqueues
+ *              anything and returns a segattn_status; nothing aborts or throws.  After an
+ *              error the context is unchanged.
+ *   Threads    A context is not thread-safe; distinct contexts are independent.
+ */
+#ifndef SEGATTN_H
+#define SEGATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct segattn_ctx segattn_ctx; /* opaque; host-side bookkeeping only */
+
+typedef enum {
+  SEGATTN_OK = 0,
+  SEGATTN_EINVAL = 1,    /* bad argument or unsupported configuration               */
+  SEGATTN_ECAPACITY = 2, /* a PAST head would hold more than past_capacity rows      */
+  SEGATTN_ESTATE = 3,    /* call not valid in the current cache state                */
+  SEGATTN_EHIP = 4       /* the HIP runtime reported an error on launch / copy       */
+} segattn_status;
+
+/* Per-KV-head access policy (Eq. 13), a bit mask.  SEG: own segment only (a long-range head
+ * outside a long-range layer).  TAIL: plus the carried tail (a local head).  PAST: plus every
+ * row the head's past pool holds (a long-range head in a long-range layer; here the whole
+ * history rather than a retrieved top-k subset).  TAIL|PAST sees the union of positions. */
+enum { SEGATTN_SEG = 0, SEGATTN_TAIL = 1, SEGATTN_PAST = 2 };
+
+typedef struct {
+  int32_t batch;           /* B >= 1                                                      */
+  int32_t n_q_heads;       /* Hq, a multiple of n_kv_heads                                */
+  int32_t n_kv_heads;      /* Hkv, 1..128                                                 */
+  int32_t head_dim;        /* D, 64 or 128                                                */
+  int32_t seg_len;         /* S >= 1: segments start at multiples of S (Sec. 3.5)         */
+  int32_t tail_len;        /* T, 0 <= T <= S: rows of the carried tail (the paper's M)    */
+  int64_t past_capacity;   /* rows a PAST head's pool can hold (history + open segment);
+                              must be >= S when any head is PAST; < 2^31                  */
+  const uint8_t *kv_policy;/* host, [Hkv] policy bit masks; copied                        */
+  float scale;             /* score scale; 0 means 1/sqrt(D) (Eq. 12)                     */
+  int32_t fp32_check;      /* 1: fp32 FMA arithmetic and fp32 `out` (validation mode)     */
+  int32_t out_fp32;        /* 1: `out` is fp32 (the unrounded accumulator) also in bf16
+                              MFMA mode; implied by fp32_check                            */
+} segattn_config;
+
+/* ---- context --------------------------------------------------------------------------- */
+
+/* Bytes of device memory the cache arena needs for this configuration (0 if invalid).
+ * Per TAIL/SEG head: (T + S) rows of K and of V; per PAST head: past_capacity rows; plus
+ * per-(sequence, head) counters and the split-K workspace of the decode path. */
+size_t segattn_cache_bytes(const segattn_config *cfg);
+
+/* Create a context over a caller-allocated arena (device, >= segattn_cache_bytes(), aligned
+ * to 256 bytes).  The cache starts empty (C_0 = R_0 = empty) once segattn_reset() has been
+ * enqueued; create itself touches no device memory.  EINVAL on a bad configuration. */
+segattn_status segattn_create(const segattn_config *cfg, void *cache_dev, size_t cache_bytes,
+                              segattn_ctx **out_ctx);
+void segattn_destroy(segattn_ctx *ctx); /* frees host bookkeeping only, never the arena */
+
+/* Empty the cache of every sequence: no tail, no past, no open segment. */
+segattn_status segattn_reset(segattn_ctx *ctx, void *stream);
+
+/* ---- prefill ---------------------------------------------------------------------------- */
+
+/* Attention for the next m rows of the open segment of every sequence (Eq. 12 / Eq. 13).
+ * q [B,m,Hq,D], k,v [B,m,Hkv,D]; out [B,m,Hq,D]; lse [B,Hq,m].  Row t of the call sits at
+ * in-segment offset fill+t, where fill is the number of rows already committed to the open
+ * segment; it sees the head's prefix held in the cache, those fill rows, and rows 0..t of k/v.
+ * Requires 1 <= m and fill + m <= S for every sequence (ESTATE otherwise).  Reads the cache,
+ * does not change it: follow with seg_kv_commit() on the same stream. */
+segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, const void *v,
+                            int32_t m, void *out, float *lse, void *stream);
+
+/* Stateless whole-sequence form: one launch over all ceil(n/S) segments of q [B,n,Hq,D],
+ * k,v [B,n,Hkv,D] by absolute position; only the last segment may be short.  Needs no
+ * context and no cache: each segment's prefix is read from k/v directly (the tail is rows
+ * [s-T, s) and the past rows [0, s) of a segment starting at s).  out [B,n,Hq,D] (bf16, or
+ * fp32 if cfg->out_fp32 or cfg->fp32_check), lse [B,Hq,n].  cfg->past_capacity is ignored. */
+segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const void *k,
+                                const void *v, int64_t n, void *out, float *lse, void *stream);
+
+/* ---- cache operations -------------------------------------------------------------------- */
+
+/* Append m rows k,v [B,m,Hkv,D] to the open segment of every sequence.  When that makes the
+ * segment complete (S rows) it is closed: the tail of every non-PAST head becomes the
+ * segment's last T rows and the rest is dropped (this is what bounds memory, Sec. 3.5
+ * "Memory Complexity"); a PAST head keeps all rows (append-only pool).  ESTATE if
+ * fill + m > S for some sequence, ECAPACITY if a PAST pool would overflow. */
+segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int32_t m,
+                             void *stream);
+
+/* Append `rows` explicit rows k,v [B,rows,D] (e.g. rows gathered by a retrieval step,
+ * Appendix D "Output") to the past pool of one PAST head, for every sequence.  Only valid
+ * between segments (no open segment: ESTATE otherwise); EINVAL if the head is not PAST. */
+segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void *k,
+                                  const void *v, int64_t rows, void *stream);
+
+/* Hide the n_oldest oldest rows of one PAST head's pool from now on (all sequences).  Pure
+ * bookkeeping: nothing is copied and the rows' storage is not reused.  If the head also has
+ * the TAIL bit, rows inside the current tail window stay visible.  Evicting more rows than
+ * the pool holds hides all of them. */
+segattn_status seg_kv_past_evict(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest,
+                                 void *stream);
+
+/* Host copies of the cache counters (any pointer may be NULL): past [B,Hkv] = visible pool
+ * rows of PAST heads (closed segments only; 0 for other heads), tail [B] = rows in the
+ * carried tail, seg_fill [B] = rows in the open segment. */
+segattn_status seg_kv_lengths(const segattn_ctx *ctx, int64_t *past, int32_t *tail,
+                              int32_t *seg_fill);
+
+/* Declare the cache contents after the caller has written K/V rows into the arena itself
+ * (restore from a snapshot, benchmark set-up): host arrays closed_rows [B] = rows in closed
+ * segments (a multiple of S), tail [B] (<= min(T, closed_rows)), seg_fill [B] (< S).
+ * Row placement is given by segattn_cache_span(). */
+segattn_status seg_kv_set_lengths(segattn_ctx *ctx, const int64_t *closed_rows,
+                                  const int32_t *tail, const int32_t *seg_fill, void *stream);
+
+/* Where the rows of (sequence b, KV head h) live inside the arena: K row r is the D bf16
+ * values at byte offset *k_off + r*D*2, V likewise from *v_off; *cap_rows rows exist.
+ * PAST head: row index = absolute position of the token (history, then the open segment).
+ * Other heads: rows [T - tail, T) hold the tail, rows [T, T + seg_fill) the open segment. */
+segattn_status segattn_cache_span(const segattn_ctx *ctx, int32_t b, int32_t kv_head,
+                                  size_t *k_off, size_t *v_off, int64_t *cap_rows);
+
+/* Bytes of K/V rows currently held (visible or not yet dropped) over all sequences and
+ * heads: the quantity Sec. 3.5 bounds by S + T per local head plus the pool of PAST heads. */
+size_t segattn_resident_bytes(const segattn_ctx *ctx);
+
+/* ---- decode ----------------------------------------------------------------------------- */
+
+/* One decoding step for every sequence (Eq. 2's conditioning on x_<t, C_{i-1}, R_{i-1}):
+ * q [B,Hq,D], k_new,v_new [B,Hkv,D] belong to the newest token.  Appends the row to the open
+ * segment, attends over [prefix | open segment] with a split-K kernel and a combine pass,
+ * writes out [B,Hq,D] and lse [B,Hq], and closes the segment when it reaches S rows (same
+ * rule as seg_kv_commit).  ECAPACITY if a PAST pool would overflow. */
+segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_new,
+                               const void *v_new, void *out, float *lse, void *stream);
+
+/* ---- misc ------------------------------------------------------------------------------- */
+const char *segattn_strerror(segattn_status st);
+/* Name and average device time bookkeeping are not kept by the library; the version string
+ * names the kernels' target ISA, e.g. "segattn 0.1 gfx950". */
+const char *segattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEGATTN_H */

@@ -1,0 +1,179 @@
+"""ctypes binding of libsegattn's C ABI (include/segattn.h): same names, argument
+marshalling only.  Device buffers are passed as torch tensors (their data_ptr()) or raw
+integer addresses; nothing here computes anything."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
+
+SEGATTN_OK, SEGATTN_EINVAL, SEGATTN_ECAPACITY, SEGATTN_ESTATE, SEGATTN_EHIP = range(5)
+SEGATTN_SEG, SEGATTN_TAIL, SEGATTN_PAST = 0, 1, 2
+
+
+class SegattnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class segattn_config(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("seg_len", ctypes.c_int32), ("tail_len", ctypes.c_int32),
+        ("past_capacity", ctypes.c_int64), ("kv_policy", ctypes.POINTER(ctypes.c_uint8)),
+        ("scale", ctypes.c_float), ("fp32_check", ctypes.c_int32), ("out_fp32", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsegattn.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_11744_amd.build` "
+                "(hipcc, gfx950); libsegattn has no CPU or PyTorch fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        cfgp = ctypes.POINTER(segattn_config)
+        sig = {
+            "segattn_cache_bytes": (sz, [cfgp]),
+            "segattn_create": (ctypes.c_int, [cfgp, vp, sz, ctypes.POINTER(vp)]),
+            "segattn_destroy": (None, [vp]),
+            "segattn_reset": (ctypes.c_int, [vp, vp]),
+            "seg_attn_fwd": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, vp, vp]),
+            "seg_attn_fwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, i64, vp, vp, vp]),
+            "seg_kv_commit": (ctypes.c_int, [vp, vp, vp, i32, vp]),
+            "seg_kv_past_append": (ctypes.c_int, [vp, i32, vp, vp, i64, vp]),
+            "seg_kv_past_evict": (ctypes.c_int, [vp, i32, i64, vp]),
+            "seg_kv_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]),
+            "seg_kv_set_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), vp]),
+            "segattn_cache_span": (ctypes.c_int, [vp, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(i64)]),
+            "segattn_resident_bytes": (sz, [vp]),
+            "seg_attn_decode": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
+            "segattn_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+            "segattn_version": (ctypes.c_char_p, []),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
+           "seg_attn_fwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_evict",
+           "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
+           "seg_attn_decode", "segattn_strerror", "segattn_version")
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def _check(st: int, where: str) -> None:
+    if st != SEGATTN_OK:
+        raise SegattnError(st, where)
+
+
+def make_config(*, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seg_len: int,
+                tail_len: int, kv_policy: Sequence[int], past_capacity: int = 0, scale: float = 0.0,
+                fp32_check: bool = False, out_fp32: bool = False) -> segattn_config:
+    pol = (ctypes.c_uint8 * len(kv_policy))(*[int(p) for p in kv_policy])
+    cfg = segattn_config(batch, n_q_heads, n_kv_heads, head_dim, seg_len, tail_len, past_capacity,
+                         ctypes.cast(pol, ctypes.POINTER(ctypes.c_uint8)), scale,
+                         int(fp32_check), int(out_fp32))
+    cfg._policy_keepalive = pol
+    return cfg
+
+
+def strerror(status: int) -> str:
+    return lib().segattn_strerror(int(status)).decode()
+
+
+def segattn_version() -> str:
+    return lib().segattn_version().decode()
+
+
+def segattn_cache_bytes(cfg: segattn_config) -> int:
+    return int(lib().segattn_cache_bytes(ctypes.byref(cfg)))
+
+
+def segattn_create(cfg: segattn_config, cache, cache_bytes: int) -> int:
+    ctx = ctypes.c_void_p()
+    _check(lib().segattn_create(ctypes.byref(cfg), _ptr(cache), cache_bytes, ctypes.byref(ctx)), "segattn_create")
+    return ctx.value
+
+
+def segattn_destroy(ctx: int) -> None:
+    lib().segattn_destroy(ctx)
+
+
+def segattn_reset(ctx: int, stream=None) -> None:
+    _check(lib().segattn_reset(ctx, _ptr(stream)), "segattn_reset")
+
+
+def seg_attn_fwd(ctx: int, q, k, v, m: int, out, lse, stream=None) -> None:
+    _check(lib().seg_attn_fwd(ctx, _ptr(q), _ptr(k), _ptr(v), m, _ptr(out), _ptr(lse), _ptr(stream)), "seg_attn_fwd")
+
+
+def seg_attn_fwd_seq(cfg: segattn_config, q, k, v, n: int, out, lse, stream=None) -> None:
+    _check(lib().seg_attn_fwd_seq(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), n, _ptr(out), _ptr(lse),
+                                  _ptr(stream)), "seg_attn_fwd_seq")
+
+
+def seg_kv_commit(ctx: int, k, v, m: int, stream=None) -> None:
+    _check(lib().seg_kv_commit(ctx, _ptr(k), _ptr(v), m, _ptr(stream)), "seg_kv_commit")
+
+
+def seg_kv_past_append(ctx: int, kv_head: int, k, v, rows: int, stream=None) -> None:
+    _check(lib().seg_kv_past_append(ctx, kv_head, _ptr(k), _ptr(v), rows, _ptr(stream)), "seg_kv_past_append")
+
+
+def seg_kv_past_evict(ctx: int, kv_head: int, n_oldest: int, stream=None) -> None:
+    _check(lib().seg_kv_past_evict(ctx, kv_head, n_oldest, _ptr(stream)), "seg_kv_past_evict")
+
+
+def seg_kv_lengths(ctx: int, batch: int, n_kv_heads: int):
+    past = (ctypes.c_int64 * (batch * n_kv_heads))()
+    tail = (ctypes.c_int32 * batch)()
+    fill = (ctypes.c_int32 * batch)()
+    _check(lib().seg_kv_lengths(ctx, past, tail, fill), "seg_kv_lengths")
+    return ([list(past[b * n_kv_heads:(b + 1) * n_kv_heads]) for b in range(batch)], list(tail), list(fill))
+
+
+def seg_kv_set_lengths(ctx: int, closed_rows: Sequence[int], tail: Sequence[int], seg_fill: Sequence[int],
+                       stream=None) -> None:
+    n = len(closed_rows)
+    _check(lib().seg_kv_set_lengths(ctx, (ctypes.c_int64 * n)(*[int(x) for x in closed_rows]),
+                                    (ctypes.c_int32 * n)(*[int(x) for x in tail]),
+                                    (ctypes.c_int32 * n)(*[int(x) for x in seg_fill]), _ptr(stream)),
+           "seg_kv_set_lengths")
+
+
+def segattn_cache_span(ctx: int, b: int, kv_head: int):
+    k_off, v_off, cap = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_int64()
+    _check(lib().segattn_cache_span(ctx, b, kv_head, ctypes.byref(k_off), ctypes.byref(v_off), ctypes.byref(cap)),
+           "segattn_cache_span")
+    return k_off.value, v_off.value, cap.value
+
+
+def segattn_resident_bytes(ctx: int) -> int:
+    return int(lib().segattn_resident_bytes(ctx))
+
+
+def seg_attn_decode(ctx: int, q, k_new, v_new, out, lse, stream=None) -> None:
+    _check(lib().seg_attn_decode(ctx, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(lse), _ptr(stream)),
+           "seg_attn_decode")

@@ -1,0 +1,402 @@
+// C ABI of libsegattn: argument validation, host mirror of the cache counters, launches.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "segattn_internal.h"
+
+using namespace segattn;
+
+namespace {
+
+constexpr int kDecodeChunk = 512;
+constexpr unsigned long long kAlign = 256;
+
+unsigned long long align_up(unsigned long long x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool build_problem(const segattn_config *cfg, bool need_cache, Problem &p) {
+  if (!cfg || !cfg->kv_policy) return false;
+  if (cfg->batch < 1 || cfg->n_kv_heads < 1 || cfg->n_kv_heads > kMaxKvHeads) return false;
+  if (cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return false;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return false;
+  if (cfg->seg_len < 1 || cfg->tail_len < 0 || cfg->tail_len > cfg->seg_len) return false;
+  if ((long long)cfg->seg_len + cfg->tail_len >= (1ll << 30)) return false;
+  if (!(cfg->scale >= 0.f) || isinf(cfg->scale)) return false;
+  memset(&p, 0, sizeof(p));
+  p.B = cfg->batch;
+  p.Hq = cfg->n_q_heads;
+  p.Hkv = cfg->n_kv_heads;
+  p.g = p.Hq / p.Hkv;
+  p.D = cfg->head_dim;
+  p.S = cfg->seg_len;
+  p.T = cfg->tail_len;
+  p.scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)p.D);
+  p.scale_log2e = p.scale * 1.4426950408889634f;
+  p.fp32_math = cfg->fp32_check ? 1 : 0;
+  p.out_fp32 = (cfg->fp32_check || cfg->out_fp32) ? 1 : 0;
+  int n_past = 0;
+  for (int h = 0; h < p.Hkv; ++h) {
+    if (cfg->kv_policy[h] > 3) return false;
+    p.policy[h] = cfg->kv_policy[h];
+    p.past_before[h] = (unsigned short)n_past;
+    if (p.policy[h] & SEGATTN_PAST) ++n_past;
+  }
+  p.n_past = n_past;
+  int o = 0;
+  for (int h = 0; h < p.Hkv; ++h)
+    if (p.policy[h] & SEGATTN_PAST) p.order[o++] = (unsigned char)h;
+  for (int h = 0; h < p.Hkv; ++h)
+    if (!(p.policy[h] & SEGATTN_PAST)) p.order[o++] = (unsigned char)h;
+  if (need_cache && n_past > 0) {
+    if (cfg->past_capacity < cfg->seg_len || cfg->past_capacity >= (1ll << 31) - 4096) return false;
+  }
+  return true;
+}
+
+bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsigned long long &total) {
+  memset(&g, 0, sizeof(g));
+  g.pool_cap = p.n_past ? (unsigned long long)cfg->past_capacity : 0;
+  g.decode_chunk = kDecodeChunk;
+  g.ws_splits_past = (int)((g.pool_cap + kDecodeChunk - 1) / kDecodeChunk);
+  g.ws_splits_other = (p.T + p.S + kDecodeChunk - 1) / kDecodeChunk;
+  g.rows_per_seq = (unsigned long long)p.n_past * g.pool_cap +
+                   (unsigned long long)(p.Hkv - p.n_past) * (unsigned long long)(p.T + p.S);
+  g.meta_off = 0;
+  const unsigned long long meta_bytes = (unsigned long long)p.B * p.Hkv * kMetaInts * 4ull;
+  g.ws_off = align_up(meta_bytes);
+  const unsigned long long slots = (unsigned long long)p.B * p.g *
+                                   ((unsigned long long)p.n_past * g.ws_splits_past +
+                                    (unsigned long long)(p.Hkv - p.n_past) * g.ws_splits_other);
+  g.kv_off = align_up(g.ws_off + slots * (2ull + p.D) * 4ull);
+  total = g.kv_off + (unsigned long long)p.B * g.rows_per_seq * 2ull * p.D * 2ull;
+  return total < (1ull << 46);
+}
+
+segattn_status hip_status(hipError_t e) { return e == hipSuccess ? SEGATTN_OK : SEGATTN_EHIP; }
+
+}  // namespace
+
+struct segattn_ctx {
+  Problem p;
+  CacheGeom g;
+  unsigned char *cache;
+  bool ready;                       // reset or set_lengths has been enqueued
+  std::vector<long long> closed;    // [B] rows in closed segments
+  std::vector<int> tail, fill;      // [B]
+  std::vector<long long> pool, lo;  // [B*Hkv] (PAST heads)
+  std::vector<int> staging;         // host image of the device counters for set_lengths
+};
+
+extern "C" {
+
+size_t segattn_cache_bytes(const segattn_config *cfg) {
+  Problem p;
+  CacheGeom g;
+  unsigned long long total;
+  if (!build_problem(cfg, true, p) || !build_geom(cfg, p, g, total)) return 0;
+  return (size_t)total;
+}
+
+segattn_status segattn_create(const segattn_config *cfg, void *cache_dev, size_t cache_bytes,
+                              segattn_ctx **out_ctx) {
+  if (!out_ctx) return SEGATTN_EINVAL;
+  *out_ctx = nullptr;
+  Problem p;
+  CacheGeom g;
+  unsigned long long total;
+  if (!build_problem(cfg, true, p) || !build_geom(cfg, p, g, total)) return SEGATTN_EINVAL;
+  if (!cache_dev || cache_bytes < total || ((uintptr_t)cache_dev % kAlign)) return SEGATTN_EINVAL;
+  segattn_ctx *c = new (std::nothrow) segattn_ctx();
+  if (!c) return SEGATTN_EINVAL;
+  c->p = p;
+  c->g = g;
+  c->cache = (unsigned char *)cache_dev;
+  c->ready = false;
+  c->closed.assign(p.B, 0);
+  c->tail.assign(p.B, 0);
+  c->fill.assign(p.B, 0);
+  c->pool.assign((size_t)p.B * p.Hkv, 0);
+  c->lo.assign((size_t)p.B * p.Hkv, 0);
+  *out_ctx = c;
+  return SEGATTN_OK;
+}
+
+void segattn_destroy(segattn_ctx *ctx) { delete ctx; }
+
+segattn_status segattn_reset(segattn_ctx *ctx, void *stream) {
+  if (!ctx) return SEGATTN_EINVAL;
+  hipError_t e = launch_cache_reset(ctx->p, ctx->cache, ctx->g, (hipStream_t)stream);
+  if (e != hipSuccess) return SEGATTN_EHIP;
+  std::fill(ctx->closed.begin(), ctx->closed.end(), 0);
+  std::fill(ctx->tail.begin(), ctx->tail.end(), 0);
+  std::fill(ctx->fill.begin(), ctx->fill.end(), 0);
+  std::fill(ctx->pool.begin(), ctx->pool.end(), 0);
+  std::fill(ctx->lo.begin(), ctx->lo.end(), 0);
+  ctx->ready = true;
+  return SEGATTN_OK;
+}
+
+segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, const void *v, int32_t m,
+                            void *out, float *lse, void *stream) {
+  if (!ctx || !q || !k || !v || !out || !lse || m < 1) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  const Problem &p = ctx->p;
+  for (int b = 0; b < p.B; ++b)
+    if ((long long)ctx->fill[b] + m > p.S) return SEGATTN_ESTATE;
+  PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.out = out;
+  a.lse = lse;
+  a.cache = ctx->cache;
+  a.geom = ctx->g;
+  a.n_rows = m;
+  a.n_seg = 1;
+  const int rows = prefill_rows_per_workgroup(p);
+  a.q_blocks_per_seg = (m + rows - 1) / rows;
+  return hip_status(launch_prefill(p, a, (hipStream_t)stream));
+}
+
+segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const void *k, const void *v,
+                                int64_t n, void *out, float *lse, void *stream) {
+  Problem p;
+  if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
+  if (!q || !k || !v || !out || !lse || n < 1 || n >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
+  PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.out = out;
+  a.lse = lse;
+  a.cache = nullptr;
+  a.n_rows = (int)n;
+  a.n_seg = (int)((n + p.S - 1) / p.S);
+  const int rows = prefill_rows_per_workgroup(p);
+  const long long seg_rows = n < p.S ? n : p.S;
+  a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
+  return hip_status(launch_prefill(p, a, (hipStream_t)stream));
+}
+
+segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int32_t m, void *stream) {
+  if (!ctx || !k || !v || m < 1) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  const Problem &p = ctx->p;
+  bool any_full = false;
+  for (int b = 0; b < p.B; ++b) {
+    if ((long long)ctx->fill[b] + m > p.S) return SEGATTN_ESTATE;
+    for (int h = 0; h < p.Hkv; ++h)
+      if ((p.policy[h] & SEGATTN_PAST) &&
+          ctx->pool[(size_t)b * p.Hkv + h] + ctx->fill[b] + m > (long long)ctx->g.pool_cap)
+        return SEGATTN_ECAPACITY;
+    any_full |= ctx->fill[b] + m == p.S;
+  }
+  CopyArgs a;
+  memset(&a, 0, sizeof(a));
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.cache = ctx->cache;
+  a.geom = ctx->g;
+  a.m = m;
+  hipError_t e = launch_cache_append(p, a, (hipStream_t)stream);
+  if (e == hipSuccess) e = launch_cache_close(p, ctx->cache, ctx->g, m, (hipStream_t)stream);
+  if (e != hipSuccess) return SEGATTN_EHIP;
+  (void)any_full;
+  for (int b = 0; b < p.B; ++b) {
+    ctx->fill[b] += m;
+    if (ctx->fill[b] == p.S) {
+      ctx->fill[b] = 0;
+      ctx->tail[b] = p.T;
+      ctx->closed[b] += p.S;
+      for (int h = 0; h < p.Hkv; ++h)
+        if (p.policy[h] & SEGATTN_PAST) ctx->pool[(size_t)b * p.Hkv + h] += p.S;
+    }
+  }
+  return SEGATTN_OK;
+}
+
+segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void *k, const void *v,
+                                  int64_t rows, void *stream) {
+  if (!ctx || !k || !v || rows < 1 || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;
+  const Problem &p = ctx->p;
+  if (!(p.policy[kv_head] & SEGATTN_PAST)) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  for (int b = 0; b < p.B; ++b) {
+    if (ctx->fill[b] != 0) return SEGATTN_ESTATE;
+    if (ctx->pool[(size_t)b * p.Hkv + kv_head] + rows > (long long)ctx->g.pool_cap) return SEGATTN_ECAPACITY;
+  }
+  CopyArgs a;
+  memset(&a, 0, sizeof(a));
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.cache = ctx->cache;
+  a.geom = ctx->g;
+  a.m = (int)rows;
+  a.kv_head = kv_head;
+  if (launch_cache_past_append(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  for (int b = 0; b < p.B; ++b) ctx->pool[(size_t)b * p.Hkv + kv_head] += rows;
+  return SEGATTN_OK;
+}
+
+segattn_status seg_kv_past_evict(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest, void *stream) {
+  if (!ctx || n_oldest < 0 || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;
+  const Problem &p = ctx->p;
+  if (!(p.policy[kv_head] & SEGATTN_PAST)) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  if (launch_cache_evict(p, ctx->cache, ctx->g, kv_head, n_oldest, (hipStream_t)stream) != hipSuccess)
+    return SEGATTN_EHIP;
+  for (int b = 0; b < p.B; ++b) {
+    const size_t i = (size_t)b * p.Hkv + kv_head;
+    long long limit = ctx->pool[i];
+    if (p.policy[kv_head] & SEGATTN_TAIL) limit -= ctx->tail[b];
+    long long lo_new = ctx->lo[i] + n_oldest < limit ? ctx->lo[i] + n_oldest : limit;
+    if (lo_new < ctx->lo[i]) lo_new = ctx->lo[i];
+    ctx->lo[i] = lo_new;
+  }
+  return SEGATTN_OK;
+}
+
+segattn_status seg_kv_lengths(const segattn_ctx *ctx, int64_t *past, int32_t *tail, int32_t *seg_fill) {
+  if (!ctx) return SEGATTN_EINVAL;
+  const Problem &p = ctx->p;
+  for (int b = 0; b < p.B; ++b) {
+    if (tail) tail[b] = ctx->tail[b];
+    if (seg_fill) seg_fill[b] = ctx->fill[b];
+    if (past)
+      for (int h = 0; h < p.Hkv; ++h) {
+        const size_t i = (size_t)b * p.Hkv + h;
+        past[i] = (p.policy[h] & SEGATTN_PAST) ? ctx->pool[i] - ctx->lo[i] : 0;
+      }
+  }
+  return SEGATTN_OK;
+}
+
+segattn_status seg_kv_set_lengths(segattn_ctx *ctx, const int64_t *closed_rows, const int32_t *tail,
+                                  const int32_t *seg_fill, void *stream) {
+  if (!ctx || !closed_rows || !tail || !seg_fill) return SEGATTN_EINVAL;
+  const Problem &p = ctx->p;
+  for (int b = 0; b < p.B; ++b) {
+    if (closed_rows[b] < 0 || closed_rows[b] % p.S) return SEGATTN_EINVAL;
+    if (seg_fill[b] < 0 || seg_fill[b] >= p.S) return SEGATTN_EINVAL;
+    if (tail[b] < 0 || tail[b] > p.T || tail[b] > closed_rows[b]) return SEGATTN_EINVAL;
+    if (p.n_past && closed_rows[b] + seg_fill[b] > (long long)ctx->g.pool_cap) return SEGATTN_ECAPACITY;
+  }
+  ctx->staging.assign((size_t)p.B * p.Hkv * kMetaInts, 0);
+  for (int b = 0; b < p.B; ++b)
+    for (int h = 0; h < p.Hkv; ++h) {
+      int *m = &ctx->staging[((size_t)b * p.Hkv + h) * kMetaInts];
+      m[META_POOL] = (p.policy[h] & SEGATTN_PAST) ? (int)closed_rows[b] : 0;
+      m[META_TAIL] = tail[b];
+      m[META_FILL] = seg_fill[b];
+      m[META_LO] = 0;
+    }
+  if (hipMemcpyAsync(ctx->cache + ctx->g.meta_off, ctx->staging.data(), ctx->staging.size() * sizeof(int),
+                     hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
+    return SEGATTN_EHIP;
+  for (int b = 0; b < p.B; ++b) {
+    ctx->closed[b] = closed_rows[b];
+    ctx->tail[b] = tail[b];
+    ctx->fill[b] = seg_fill[b];
+    for (int h = 0; h < p.Hkv; ++h) {
+      ctx->pool[(size_t)b * p.Hkv + h] = (p.policy[h] & SEGATTN_PAST) ? closed_rows[b] : 0;
+      ctx->lo[(size_t)b * p.Hkv + h] = 0;
+    }
+  }
+  ctx->ready = true;
+  return SEGATTN_OK;
+}
+
+segattn_status segattn_cache_span(const segattn_ctx *ctx, int32_t b, int32_t kv_head, size_t *k_off,
+                                  size_t *v_off, int64_t *cap_rows) {
+  if (!ctx || b < 0 || b >= ctx->p.B || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;
+  if (k_off) *k_off = (size_t)k_block_off(ctx->p, ctx->g, b, kv_head);
+  if (v_off) *v_off = (size_t)v_block_off(ctx->p, ctx->g, b, kv_head);
+  if (cap_rows) *cap_rows = (int64_t)head_cap(ctx->p, ctx->g, kv_head);
+  return SEGATTN_OK;
+}
+
+size_t segattn_resident_bytes(const segattn_ctx *ctx) {
+  if (!ctx) return 0;
+  const Problem &p = ctx->p;
+  unsigned long long rows = 0;
+  for (int b = 0; b < p.B; ++b)
+    for (int h = 0; h < p.Hkv; ++h) {
+      if (p.policy[h] & SEGATTN_PAST) rows += ctx->pool[(size_t)b * p.Hkv + h] + ctx->fill[b];
+      else rows += ((p.policy[h] & SEGATTN_TAIL) ? ctx->tail[b] : 0) + ctx->fill[b];
+    }
+  return (size_t)(rows * 2ull * p.D * 2ull);
+}
+
+segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_new, const void *v_new,
+                               void *out, float *lse, void *stream) {
+  if (!ctx || !q || !k_new || !v_new || !out || !lse) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  const Problem &p = ctx->p;
+  long long max_window = 0;
+  bool any_full = false;
+  for (int b = 0; b < p.B; ++b) {
+    for (int h = 0; h < p.Hkv; ++h) {
+      const size_t i = (size_t)b * p.Hkv + h;
+      long long win;
+      if (p.policy[h] & SEGATTN_PAST) {
+        if (ctx->pool[i] + ctx->fill[b] + 1 > (long long)ctx->g.pool_cap) return SEGATTN_ECAPACITY;
+        win = ctx->pool[i] - ctx->lo[i] + ctx->fill[b] + 1;
+      } else {
+        win = ((p.policy[h] & SEGATTN_TAIL) ? ctx->tail[b] : 0) + ctx->fill[b] + 1;
+      }
+      if (win > max_window) max_window = win;
+    }
+    any_full |= ctx->fill[b] + 1 == p.S;
+  }
+  const hipStream_t st = (hipStream_t)stream;
+  CopyArgs ca;
+  memset(&ca, 0, sizeof(ca));
+  ca.k = (const unsigned short *)k_new;
+  ca.v = (const unsigned short *)v_new;
+  ca.cache = ctx->cache;
+  ca.geom = ctx->g;
+  ca.m = 1;
+  if (launch_cache_decode_append(p, ca, st) != hipSuccess) return SEGATTN_EHIP;
+  DecodeArgs da;
+  memset(&da, 0, sizeof(da));
+  da.q = (const unsigned short *)q;
+  da.k_new = ca.k;
+  da.v_new = ca.v;
+  da.out = out;
+  da.lse = lse;
+  da.cache = ctx->cache;
+  da.geom = ctx->g;
+  da.max_splits = (int)((max_window + kDecodeChunk - 1) / kDecodeChunk);
+  if (launch_decode(p, da, p.B, st) != hipSuccess) return SEGATTN_EHIP;
+  if (any_full && launch_cache_close(p, ctx->cache, ctx->g, 0, st) != hipSuccess) return SEGATTN_EHIP;
+  for (int b = 0; b < p.B; ++b) {
+    ctx->fill[b] += 1;
+    if (ctx->fill[b] == p.S) {
+      ctx->fill[b] = 0;
+      ctx->tail[b] = p.T;
+      ctx->closed[b] += p.S;
+      for (int h = 0; h < p.Hkv; ++h)
+        if (p.policy[h] & SEGATTN_PAST) ctx->pool[(size_t)b * p.Hkv + h] += p.S;
+    }
+  }
+  return SEGATTN_OK;
+}
+
+const char *segattn_strerror(segattn_status st) {
+  switch (st) {
+    case SEGATTN_OK: return "ok";
+    case SEGATTN_EINVAL: return "invalid argument or unsupported configuration";
+    case SEGATTN_ECAPACITY: return "past pool capacity exceeded";
+    case SEGATTN_ESTATE: return "call not valid in the current cache state";
+    case SEGATTN_EHIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char *segattn_version(void) { return "segattn 0.1 gfx950"; }
+
+}  // extern "C"

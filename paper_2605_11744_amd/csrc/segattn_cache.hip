@@ -1,0 +1,200 @@
+// Cross-segment state of libsegattn (Sec. 3.4): the carried KV tail C_i of local heads and the
+// append-only past pool of long-range heads, kept in one caller-owned arena.  All kernels
+// here are plain copies (HBM-bound) plus the per-(sequence, head) counters they maintain:
+//   counters[b][h] = { pool rows, tail rows, open-segment rows, first visible pool row }.
+// The host keeps a mirror of the counters for validation; the device copy is only ever
+// changed by these kernels, in stream order, so a sequence of calls can be graph-captured.
+#include "segattn_internal.h"
+
+namespace segattn {
+
+__device__ inline int *meta_of(unsigned char *cache, const CacheGeom &g, const Problem &p, int b, int h) {
+  return (int *)(cache + g.meta_off) + ((long long)b * p.Hkv + h) * kMetaInts;
+}
+
+__global__ void cache_reset_kernel(const Problem p, unsigned char *cache, const CacheGeom g) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < p.B * p.Hkv * kMetaInts) ((int *)(cache + g.meta_off))[i] = 0;
+}
+
+// Rows k,v [B,m,Hkv,D] -> open segment of every (b,h).  grid = (row chunks, B*Hkv).
+// A non-PAST head whose whole segment arrives in one call (fill = 0, m = S) keeps only the
+// last T rows, written straight into the tail slots; everything else of it is dropped.
+template <int D>
+__global__ __launch_bounds__(256) void cache_append_kernel(const Problem p, const CopyArgs a) {
+  constexpr int CPR = D / 8;  // 16-byte chunks per row
+  const int b = blockIdx.y / p.Hkv, h = blockIdx.y % p.Hkv;
+  const int *meta = meta_of(a.cache, a.geom, p, b, h);
+  const int fill = meta[META_FILL];
+  const bool past = p.policy[h] & SEGATTN_PAST;
+  int src0 = 0, dst0, n = a.m;
+  if (past) {
+    dst0 = meta[META_POOL] + fill;
+  } else if (fill == 0 && a.m == p.S) {
+    src0 = p.S - p.T;
+    n = p.T;
+    dst0 = 0;
+  } else {
+    dst0 = p.T + fill;
+  }
+  const uint4 *ks = (const uint4 *)(a.k + ((long long)b * a.m * p.Hkv + h) * D);
+  const uint4 *vs = (const uint4 *)(a.v + ((long long)b * a.m * p.Hkv + h) * D);
+  uint4 *kd = (uint4 *)(a.cache + k_block_off(p, a.geom, b, h));
+  uint4 *vd = (uint4 *)(a.cache + v_block_off(p, a.geom, b, h));
+  const long long src_stride = (long long)p.Hkv * CPR;
+  const int rows_per_block = 256 / CPR * 8;
+  const int r_begin = blockIdx.x * rows_per_block;
+  const int r_end = min(n, r_begin + rows_per_block);
+  const int c = threadIdx.x % CPR;
+  for (int r = r_begin + threadIdx.x / CPR; r < r_end; r += 256 / CPR) {
+    kd[(long long)(dst0 + r) * CPR + c] = ks[(long long)(src0 + r) * src_stride + c];
+    vd[(long long)(dst0 + r) * CPR + c] = vs[(long long)(src0 + r) * src_stride + c];
+  }
+}
+
+// Close the open segment of every (b,h) whose fill reaches S after adding `add` rows:
+// tail <- last T rows of the segment (non-PAST heads), pool += S (PAST heads), fill <- 0.
+// One workgroup per (b,h): it alone reads and writes that head's counters.
+template <int D>
+__global__ __launch_bounds__(256) void cache_close_kernel(const Problem p, unsigned char *cache,
+                                                         const CacheGeom g, const int add) {
+  constexpr int CPR = D / 8;
+  const int b = blockIdx.x / p.Hkv, h = blockIdx.x % p.Hkv;
+  int *meta = meta_of(cache, g, p, b, h);
+  const int fill_old = meta[META_FILL], pool = meta[META_POOL];
+  __syncthreads();
+  const int fill = fill_old + add;
+  const bool past = p.policy[h] & SEGATTN_PAST;
+  if (fill < p.S) {
+    if (threadIdx.x == 0) meta[META_FILL] = fill;
+    return;
+  }
+  if (!past && p.T > 0 && !(fill_old == 0 && add == p.S)) {
+    uint4 *kd = (uint4 *)(cache + k_block_off(p, g, b, h));
+    uint4 *vd = (uint4 *)(cache + v_block_off(p, g, b, h));
+    const long long n = (long long)p.T * CPR, src = (long long)p.S * CPR;  // rows [S, S+T) -> [0, T)
+    for (long long i = threadIdx.x; i < n; i += 256) {
+      kd[i] = kd[src + i];
+      vd[i] = vd[src + i];
+    }
+  }
+  if (threadIdx.x == 0) {
+    meta[META_FILL] = 0;
+    meta[META_TAIL] = p.T;
+    if (past) meta[META_POOL] = pool + p.S;
+  }
+}
+
+// One new row k,v [B,Hkv,D] per sequence -> open segment; fill += 1.  One wave per (b,h).
+template <int D>
+__global__ __launch_bounds__(64) void cache_decode_append_kernel(const Problem p, const CopyArgs a) {
+  constexpr int CPR = D / 8;
+  const int b = blockIdx.x / p.Hkv, h = blockIdx.x % p.Hkv;
+  int *meta = meta_of(a.cache, a.geom, p, b, h);
+  const int fill = meta[META_FILL];
+  const int row = ((p.policy[h] & SEGATTN_PAST) ? meta[META_POOL] : p.T) + fill;
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < 2 * CPR) {
+    const bool is_v = t >= CPR;
+    const int c = is_v ? t - CPR : t;
+    const uint4 *src = (const uint4 *)((is_v ? a.v : a.k) + ((long long)b * p.Hkv + h) * D);
+    uint4 *dst = (uint4 *)(a.cache + (is_v ? v_block_off(p, a.geom, b, h) : k_block_off(p, a.geom, b, h)));
+    dst[(long long)row * CPR + c] = src[c];
+  }
+  if (t == 0) meta[META_FILL] = fill + 1;
+}
+
+// Explicit rows k,v [B,rows,D] -> pool of one PAST head.  grid = (row chunks, B).  The pool
+// counter is advanced by cache_pool_add_kernel afterwards.
+template <int D>
+__global__ __launch_bounds__(256) void cache_past_append_kernel(const Problem p, const CopyArgs a) {
+  constexpr int CPR = D / 8;
+  const int b = blockIdx.y, h = a.kv_head;
+  const int pool = meta_of(a.cache, a.geom, p, b, h)[META_POOL];
+  const uint4 *ks = (const uint4 *)(a.k + (long long)b * a.m * D);
+  const uint4 *vs = (const uint4 *)(a.v + (long long)b * a.m * D);
+  uint4 *kd = (uint4 *)(a.cache + k_block_off(p, a.geom, b, h)) + (long long)pool * CPR;
+  uint4 *vd = (uint4 *)(a.cache + v_block_off(p, a.geom, b, h)) + (long long)pool * CPR;
+  const long long n = (long long)a.m * CPR;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    kd[i] = ks[i];
+    vd[i] = vs[i];
+  }
+}
+
+__global__ void cache_pool_add_kernel(const Problem p, unsigned char *cache, const CacheGeom g,
+                                      const int h, const int rows) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < p.B) meta_of(cache, g, p, b, h)[META_POOL] += rows;
+}
+
+// Hide the n oldest pool rows of one PAST head; rows of the current tail window stay visible
+// when the head also has the TAIL bit.
+__global__ void cache_evict_kernel(const Problem p, unsigned char *cache, const CacheGeom g, const int h,
+                                   const long long n) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= p.B) return;
+  int *meta = meta_of(cache, g, p, b, h);
+  const long long lo = meta[META_LO];
+  long long limit = meta[META_POOL];
+  if (p.policy[h] & SEGATTN_TAIL) limit -= meta[META_TAIL];
+  long long lo_new = lo + n < limit ? lo + n : limit;
+  if (lo_new < lo) lo_new = lo;
+  meta[META_LO] = (int)lo_new;
+}
+
+// ---- launchers ----------------------------------------------------------------------------
+hipError_t launch_cache_reset(const Problem &p, unsigned char *cache, const CacheGeom &g, hipStream_t st) {
+  const int n = p.B * p.Hkv * kMetaInts;
+  hipLaunchKernelGGL(cache_reset_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, cache, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_append(const Problem &p, const CopyArgs &a, hipStream_t st) {
+  const int cpr = p.D / 8;
+  const int rows_per_block = 256 / cpr * 8;
+  const dim3 grid((a.m + rows_per_block - 1) / rows_per_block, p.B * p.Hkv);
+  if (p.D == 128) hipLaunchKernelGGL(cache_append_kernel<128>, grid, dim3(256), 0, st, p, a);
+  else hipLaunchKernelGGL(cache_append_kernel<64>, grid, dim3(256), 0, st, p, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_close(const Problem &p, unsigned char *cache, const CacheGeom &g, int add,
+                              hipStream_t st) {
+  const dim3 grid(p.B * p.Hkv);
+  if (p.D == 128) hipLaunchKernelGGL(cache_close_kernel<128>, grid, dim3(256), 0, st, p, cache, g, add);
+  else hipLaunchKernelGGL(cache_close_kernel<64>, grid, dim3(256), 0, st, p, cache, g, add);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_decode_append(const Problem &p, const CopyArgs &a, hipStream_t st) {
+  const dim3 grid(p.B * p.Hkv);
+  if (p.D == 128) hipLaunchKernelGGL(cache_decode_append_kernel<128>, grid, dim3(64), 0, st, p, a);
+  else hipLaunchKernelGGL(cache_decode_append_kernel<64>, grid, dim3(64), 0, st, p, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStream_t st) {
+  const long long n = (long long)a.m * (p.D / 8);
+  long long blocks = (n + 2047) / 2048;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 4096) blocks = 4096;
+  const dim3 grid((unsigned)blocks, p.B);
+  if (p.D == 128) hipLaunchKernelGGL(cache_past_append_kernel<128>, grid, dim3(256), 0, st, p, a);
+  else hipLaunchKernelGGL(cache_past_append_kernel<64>, grid, dim3(256), 0, st, p, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(cache_pool_add_kernel, dim3((p.B + 63) / 64), dim3(64), 0, st, p, a.cache, a.geom,
+                     a.kv_head, a.m);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
+                              long long n_oldest, hipStream_t st) {
+  hipLaunchKernelGGL(cache_evict_kernel, dim3((p.B + 63) / 64), dim3(64), 0, st, p, cache, g, kv_head,
+                     n_oldest);
+  return hipGetLastError();
+}
+
+}  // namespace segattn

@@ -1,0 +1,116 @@
+// Internal declarations shared by the translation units of libsegattn (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "segattn.h"
+
+namespace segattn {
+
+constexpr int kMaxKvHeads = 128;
+constexpr int kMetaInts = 4;  // per (sequence, KV head): pool rows, tail rows, open-segment rows, first visible pool row
+
+enum MetaSlot { META_POOL = 0, META_TAIL = 1, META_FILL = 2, META_LO = 3 };
+
+// Geometry of the cache arena, identical on host and device.
+//   [ counters : B*Hkv*4 int32 ][ decode workspace ][ K/V rows ]
+// K/V rows of (b, h): K block of cap(h) rows, then V block of cap(h) rows, D bf16 each;
+// cap(h) = pool_cap for a PAST head, T + S otherwise.
+struct CacheGeom {
+  unsigned long long meta_off, ws_off, kv_off;
+  unsigned long long rows_per_seq;     // sum of cap(h) over heads
+  unsigned long long pool_cap;         // rows per PAST head
+  int ws_splits_past, ws_splits_other; // split-K slots per query head (PAST / other heads)
+  int decode_chunk;                    // keys per split
+};
+
+// Everything a kernel needs to know about the problem; passed by value as kernel argument.
+struct Problem {
+  int B, Hq, Hkv, g, D, S, T;
+  float scale;          // multiplies q.k
+  float scale_log2e;    // scale * log2(e)
+  int out_fp32;         // `out` holds fp32 instead of bf16
+  int fp32_math;        // validation mode: fp32 FMA kernels
+  int n_past;           // number of PAST heads
+  unsigned char policy[kMaxKvHeads];
+  unsigned char order[kMaxKvHeads];     // KV heads, PAST heads first
+  unsigned short past_before[kMaxKvHeads];  // number of PAST heads with a smaller index
+};
+
+// Arguments of the prefill kernels.  SEQ mode (cache == nullptr): q/k/v hold n_rows = N tokens
+// per sequence and every segment is processed in this launch.  CTX mode: q/k/v hold the
+// n_rows = m new rows of the open segment and the prefix comes from the cache arena.
+struct PrefillArgs {
+  const unsigned short *q, *k, *v;
+  void *out;
+  float *lse;
+  unsigned char *cache;  // arena base or nullptr
+  CacheGeom geom;
+  int n_rows;            // N (SEQ) or m (CTX)
+  int n_seg;             // segments covered by the launch (1 in CTX mode)
+  int q_blocks_per_seg;  // ceil(min(S, n_rows) / rows per workgroup)
+};
+
+struct DecodeArgs {
+  const unsigned short *q, *k_new, *v_new;
+  void *out;
+  float *lse;
+  unsigned char *cache;
+  CacheGeom geom;
+  int max_splits;        // grid.x of the split kernel
+};
+
+struct CopyArgs {
+  const unsigned short *k, *v;   // source rows
+  unsigned char *cache;
+  CacheGeom geom;
+  int m;                 // rows per sequence in the source
+  int kv_head;           // past_append: target head; otherwise unused
+};
+
+// ---- helpers usable on host and device ----------------------------------------------------
+__host__ __device__ inline unsigned long long head_row_offset(const Problem &p, const CacheGeom &g,
+                                                              int h) {
+  unsigned long long np = p.past_before[h];
+  return np * g.pool_cap + (unsigned long long)(h - (int)np) * (unsigned long long)(p.T + p.S);
+}
+__host__ __device__ inline unsigned long long head_cap(const Problem &p, const CacheGeom &g, int h) {
+  return (p.policy[h] & SEGATTN_PAST) ? g.pool_cap : (unsigned long long)(p.T + p.S);
+}
+__host__ __device__ inline unsigned long long k_block_off(const Problem &p, const CacheGeom &g, int b,
+                                                          int h) {
+  return g.kv_off + ((unsigned long long)b * g.rows_per_seq + head_row_offset(p, g, h)) * 2ull *
+                        (unsigned long long)p.D * 2ull;
+}
+__host__ __device__ inline unsigned long long v_block_off(const Problem &p, const CacheGeom &g, int b,
+                                                          int h) {
+  return k_block_off(p, g, b, h) + head_cap(p, g, h) * (unsigned long long)p.D * 2ull;
+}
+// First row of the visible window and first row of the open segment inside the (b,h) block.
+__host__ __device__ inline void window_of(const Problem &p, int h, const int *meta, int &lo,
+                                          int &seg_row0) {
+  const int pol = p.policy[h];
+  if (pol & SEGATTN_PAST) {
+    lo = meta[META_LO];
+    seg_row0 = meta[META_POOL];
+  } else {
+    lo = (pol & SEGATTN_TAIL) ? p.T - meta[META_TAIL] : p.T;
+    seg_row0 = p.T;
+  }
+}
+
+// ---- launchers (defined in the .hip files) ------------------------------------------------
+hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st);
+hipError_t launch_decode(const Problem &p, const DecodeArgs &a, int B, hipStream_t st);
+hipError_t launch_cache_reset(const Problem &p, unsigned char *cache, const CacheGeom &g, hipStream_t st);
+hipError_t launch_cache_append(const Problem &p, const CopyArgs &a, hipStream_t st);
+hipError_t launch_cache_close(const Problem &p, unsigned char *cache, const CacheGeom &g, int add,
+                              hipStream_t st);
+hipError_t launch_cache_decode_append(const Problem &p, const CopyArgs &a, hipStream_t st);
+hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStream_t st);
+hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
+                              long long n_oldest, hipStream_t st);
+int prefill_rows_per_workgroup(const Problem &p);
+
+}  // namespace segattn

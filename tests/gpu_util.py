@@ -1,0 +1,101 @@
+"""Helpers for the GPU parity tests: move seeded bf16 bit patterns to the device, call the
+C ABI through the Python binding, bring results back as float64 numpy arrays."""
+import numpy as np
+import torch
+
+import paper_2605_11744_amd as sa
+
+# Parity bars (bf16 MFMA path: max-abs / mean-abs; fp32 validation mode: max-abs).
+BF16_MAX_ABS, BF16_MEAN_ABS, FP32_MAX_ABS = 1e-2, 1e-3, 1e-4
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.cuda().view(torch.bfloat16)
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def config_of(w, *, fp32_check=False, out_fp32=False, past_capacity=0, batch=None, scale=0.0):
+    return sa.make_config(batch=w.batch if batch is None else batch, n_q_heads=w.n_q_heads,
+                          n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, seg_len=w.seg_len,
+                          tail_len=w.tail_len, kv_policy=w.kv_policy, past_capacity=past_capacity,
+                          scale=scale, fp32_check=fp32_check, out_fp32=out_fp32)
+
+
+def fwd_seq(w, q_bits, k_bits, v_bits, *, fp32_check=False, out_fp32=True, scale=0.0):
+    """One stateless launch over the whole sequence; returns (O [B,N,Hq,D], LSE [B,Hq,N]) as float64."""
+    B, N = q_bits.shape[0], q_bits.shape[1]
+    cfg = config_of(w, fp32_check=fp32_check, out_fp32=out_fp32, batch=B, scale=scale)
+    q, k, v = dev_bf16(q_bits), dev_bf16(k_bits), dev_bf16(v_bits)
+    odt = torch.float32 if (fp32_check or out_fp32) else torch.bfloat16
+    out = torch.full((B, N, w.n_q_heads, w.head_dim), float("nan"), dtype=odt, device="cuda")
+    lse = torch.full((B, w.n_q_heads, N), float("nan"), dtype=torch.float32, device="cuda")
+    sa.seg_attn_fwd_seq(cfg, q, k, v, N, out, lse, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return to_f64(out), to_f64(lse)
+
+
+def assert_parity(o_gpu, l_gpu, o_ref, l_ref, *, fp32_check, what=""):
+    eo, el = np.abs(o_gpu - o_ref), np.abs(l_gpu - l_ref)
+    assert np.isfinite(o_gpu).all() and np.isfinite(l_gpu).all(), f"{what}: non-finite output"
+    if fp32_check:
+        assert eo.max() <= FP32_MAX_ABS, f"{what}: O max-abs {eo.max():.3e}"
+        assert el.max() <= FP32_MAX_ABS, f"{what}: LSE max-abs {el.max():.3e}"
+    else:
+        assert eo.max() <= BF16_MAX_ABS, f"{what}: O max-abs {eo.max():.3e}"
+        assert el.max() <= BF16_MAX_ABS, f"{what}: LSE max-abs {el.max():.3e}"
+        assert eo.mean() <= BF16_MEAN_ABS, f"{what}: O mean-abs {eo.mean():.3e}"
+        assert el.mean() <= BF16_MEAN_ABS, f"{what}: LSE mean-abs {el.mean():.3e}"
+    return eo.max(), eo.mean(), el.max(), el.mean()
+
+
+class Cache:
+    """A context over a torch-allocated arena."""
+
+    def __init__(self, w, *, past_capacity, fp32_check=False, out_fp32=True, batch=None, scale=0.0):
+        self.w = w
+        self.B = w.batch if batch is None else batch
+        self.cfg = config_of(w, fp32_check=fp32_check, out_fp32=out_fp32, past_capacity=past_capacity,
+                             batch=self.B, scale=scale)
+        self.odt = torch.float32 if (fp32_check or out_fp32) else torch.bfloat16
+        self.bytes = sa.segattn_cache_bytes(self.cfg)
+        assert self.bytes > 0
+        self.arena = torch.empty(self.bytes, dtype=torch.uint8, device="cuda")
+        self.ctx = sa.segattn_create(self.cfg, self.arena, self.bytes)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        sa.segattn_reset(self.ctx, self.stream)
+
+    def close(self):
+        if self.ctx:
+            torch.cuda.synchronize()
+            sa.segattn_destroy(self.ctx)
+            self.ctx = None
+
+    def fwd(self, q_bits, k_bits, v_bits):
+        m = q_bits.shape[1]
+        q, k, v = dev_bf16(q_bits), dev_bf16(k_bits), dev_bf16(v_bits)
+        out = torch.full((self.B, m, self.w.n_q_heads, self.w.head_dim), float("nan"), dtype=self.odt, device="cuda")
+        lse = torch.full((self.B, self.w.n_q_heads, m), float("nan"), dtype=torch.float32, device="cuda")
+        sa.seg_attn_fwd(self.ctx, q, k, v, m, out, lse, self.stream)
+        sa.seg_kv_commit(self.ctx, k, v, m, self.stream)
+        torch.cuda.synchronize()
+        return to_f64(out), to_f64(lse)
+
+    def decode(self, q_bits, k_bits, v_bits):
+        q, k, v = dev_bf16(q_bits), dev_bf16(k_bits), dev_bf16(v_bits)
+        out = torch.full((self.B, self.w.n_q_heads, self.w.head_dim), float("nan"), dtype=self.odt, device="cuda")
+        lse = torch.full((self.B, self.w.n_q_heads), float("nan"), dtype=torch.float32, device="cuda")
+        sa.seg_attn_decode(self.ctx, q, k, v, out, lse, self.stream)
+        torch.cuda.synchronize()
+        return to_f64(out), to_f64(lse)
+
+    def rows_view(self, b, kv_head):
+        """(K, V) views [cap, D] (bf16) of the arena block of (b, kv_head)."""
+        k_off, v_off, cap = sa.segattn_cache_span(self.ctx, b, kv_head)
+        D = self.w.head_dim
+        kv = self.arena[k_off:k_off + cap * D * 2].view(torch.bfloat16).view(cap, D)
+        vv = self.arena[v_off:v_off + cap * D * 2].view(torch.bfloat16).view(cap, D)
+        return kv, vv
