@@ -1,0 +1,176 @@
+"""GPU parity for the stateful path: seg_attn_fwd + seg_kv_commit segment by segment,
+tail hand-off, past pool append / evict, and decode steps, against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import segattn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _oracle(w, q, k, v, **kw):
+    return orc.attend(q, k, v, seg_len=w.seg_len, tail_len=w.tail_len, kv_policy=w.kv_policy, **kw)
+
+
+STREAM_CASES = [
+    # (workload kwargs, chunk sizes cycled through while streaming)
+    (dict(seq_len=300, seg_len=64, tail_len=16, n_q_heads=8, n_kv_heads=4, head_dim=128), [64]),
+    (dict(seq_len=300, seg_len=64, tail_len=64, n_q_heads=4, n_kv_heads=4, head_dim=64), [64]),
+    (dict(seq_len=520, seg_len=128, tail_len=40, n_q_heads=16, n_kv_heads=4, head_dim=128, batch=2), [50, 78, 128, 1, 127]),
+    (dict(seq_len=257, seg_len=256, tail_len=0, n_q_heads=8, n_kv_heads=4, head_dim=64), [200, 56, 1]),
+]
+
+
+@pytest.mark.parametrize("fp32_check", [True, False])
+@pytest.mark.parametrize("case", range(len(STREAM_CASES)))
+def test_streaming_prefill_equals_oracle(case, fp32_check):
+    import gpu_util as G
+    kw, chunks = STREAM_CASES[case]
+    w = W.small(f"stream{case}", index=200 + case, **kw)
+    q, k, v = W.prefill_inputs(w)
+    o_ref, l_ref = _oracle(w, q, k, v)
+    c = G.Cache(w, past_capacity=((w.seq_len + w.seg_len) // w.seg_len) * w.seg_len, fp32_check=fp32_check)
+    try:
+        o = np.zeros_like(o_ref)
+        l = np.zeros_like(l_ref)
+        pos, i = 0, 0
+        while pos < w.seq_len:
+            room = w.seg_len - pos % w.seg_len
+            m = min(chunks[i % len(chunks)], room, w.seq_len - pos)
+            i += 1
+            oc, lc = c.fwd(q[:, pos:pos + m], k[:, pos:pos + m], v[:, pos:pos + m])
+            o[:, pos:pos + m] = oc
+            l[:, :, pos:pos + m] = lc
+            pos += m
+        G.assert_parity(o, l, o_ref, l_ref, fp32_check=fp32_check, what=f"stream{case}")
+        # counters: closed segments, tail, open segment, resident rows (Sec. 3.5 memory bound)
+        import paper_2605_11744_amd as sa
+        past, tail, fill = sa.seg_kv_lengths(c.ctx, c.B, w.n_kv_heads)
+        closed = (w.seq_len // w.seg_len) * w.seg_len
+        exp_tail = w.tail_len if closed else 0
+        assert fill == [w.seq_len - closed] * c.B and tail == [exp_tail] * c.B
+        rows = 0
+        for h, pol in enumerate(w.kv_policy):
+            assert all(past[b][h] == (closed if pol & 2 else 0) for b in range(c.B))
+            rows += (closed if pol & 2 else (exp_tail if pol & 1 else 0)) + (w.seq_len - closed)
+        assert sa.segattn_resident_bytes(c.ctx) == c.B * rows * 2 * w.head_dim * 2
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("fp32_check", [True, False])
+def test_decode_after_prefill_crosses_segment_boundaries(fp32_check):
+    """Prefill n0 tokens, then decode token by token across two segment closures: every step
+    must equal the oracle's row for that position (forward identity, Sec. 3.1)."""
+    import gpu_util as G
+    w = W.small("dec_after_prefill", index=210, seq_len=200, seg_len=48, tail_len=20, n_q_heads=8,
+                n_kv_heads=4, head_dim=128, batch=2)
+    q, k, v = W.prefill_inputs(w)
+    o_ref, l_ref = _oracle(w, q, k, v)
+    n0 = 70
+    c = G.Cache(w, past_capacity=240, fp32_check=fp32_check)
+    try:
+        pos = 0
+        while pos < n0:
+            m = min(w.seg_len - pos % w.seg_len, n0 - pos)
+            c.fwd(q[:, pos:pos + m], k[:, pos:pos + m], v[:, pos:pos + m])
+            pos += m
+        o = np.zeros_like(o_ref[:, n0:])
+        l = np.zeros_like(l_ref[:, :, n0:])
+        for p in range(n0, w.seq_len):
+            od, ld = c.decode(q[:, p], k[:, p], v[:, p])
+            o[:, p - n0] = od
+            l[:, :, p - n0] = ld
+        G.assert_parity(o, l, o_ref[:, n0:], l_ref[:, :, n0:], fp32_check=fp32_check, what="decode steps")
+    finally:
+        c.close()
+
+
+def test_decode_ragged_batch_from_restored_cache():
+    """Sequences of different lengths: rows are written into the arena through
+    segattn_cache_span, lengths declared with seg_kv_set_lengths, one decode step checked
+    against the decode oracle per sequence."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    S, T = 64, 24
+    w = W.Workload("dec_ragged", 220, 3, 0, 16, 4, 128, S, T, (1, 3, 0, 2), decode=True, max_context=64 * 9)
+    k_done = np.array([1, 8, 3])
+    c_fill = np.array([64, 1, 37])
+    q, ks, vs, _, _ = W.decode_inputs(w, k_done, c_fill)
+    c = G.Cache(w, past_capacity=64 * 9)
+    try:
+        k_new = np.zeros((3, 4, 128), dtype=np.uint16)
+        v_new = np.zeros((3, 4, 128), dtype=np.uint16)
+        for b in range(3):
+            for h, pol in enumerate(w.kv_policy):
+                kk, vv = ks[b][h], vs[b][h]            # kept rows, newest (being decoded) last
+                k_new[b, h], v_new[b, h] = kk[-1], vv[-1]
+                kd, vd = c.rows_view(b, h)
+                n_prev = kk.shape[0] - 1
+                first = 0 if pol & 2 else (T - min(T, int(k_done[b]) * S) if pol & 1 else T)
+                if n_prev:
+                    kd[first:first + n_prev] = G.dev_bf16(kk[:-1])
+                    vd[first:first + n_prev] = G.dev_bf16(vv[:-1])
+        sa.seg_kv_set_lengths(c.ctx, list(k_done * S), [T] * 3, list(c_fill - 1), c.stream)
+        o, l = c.decode(q, k_new, v_new)
+        for b in range(3):
+            n_b = int(k_done[b]) * S + int(c_fill[b])
+            kf = np.zeros((n_b, 4, 128))
+            vf = np.zeros((n_b, 4, 128))
+            for h in range(4):
+                kept = ks[b][h].shape[0]
+                kf[n_b - kept:, h] = orc.widen(ks[b][h])
+                vf[n_b - kept:, h] = orc.widen(vs[b][h])
+            o_ref, l_ref = orc.decode_attend(q[b], kf, vf, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
+            G.assert_parity(o[b], l[b], o_ref, l_ref, fp32_check=False, what=f"ragged decode b={b}")
+        # sequence 0 filled its segment with this token: it must have been closed
+        past, tail, fill = sa.seg_kv_lengths(c.ctx, 3, 4)
+        assert fill == [0, 1, 37] and past[0][1] == 128 and past[0][3] == 128
+    finally:
+        c.close()
+
+
+def test_evict_hides_oldest_pool_rows():
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    w = W.small("evict", index=230, seq_len=256, seg_len=64, tail_len=16, n_q_heads=4, n_kv_heads=2,
+                head_dim=64, kv_policy=[3, 2])
+    q, k, v = W.prefill_inputs(w)
+    c = G.Cache(w, past_capacity=256)
+    try:
+        for s in range(0, 192, 64):
+            c.fwd(q[:, s:s + 64], k[:, s:s + 64], v[:, s:s + 64])
+        sa.seg_kv_past_evict(c.ctx, 0, 100, c.stream)
+        sa.seg_kv_past_evict(c.ctx, 1, 50, c.stream)
+        sa.seg_kv_past_evict(c.ctx, 0, 1000, c.stream)   # clamps at the tail window: 192 - 16
+        o, l = c.fwd(q[:, 192:], k[:, 192:], v[:, 192:])
+        o_ref, l_ref = _oracle(w, q, k, v, rows=np.arange(192, 256), evicted=[192, 50])
+        G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="evict")
+        past, _, _ = sa.seg_kv_lengths(c.ctx, 1, 2)
+        assert past[0] == [256 - 176, 256 - 50]      # the last fwd committed a fourth segment
+    finally:
+        c.close()
+
+
+def test_past_append_explicit_rows_act_as_prefix():
+    """Rows handed to seg_kv_past_append become the long-range prefix of the next segment
+    (Eq. 13, second case, with gathered rows in place of the whole history)."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    R = 40
+    w = W.small("append", index=240, seq_len=128, seg_len=64, tail_len=R, n_q_heads=4, n_kv_heads=1,
+                head_dim=128, kv_policy=[2])
+    q, k, v = W.prefill_inputs(w)
+    c = G.Cache(w, past_capacity=192)
+    try:
+        kp = G.dev_bf16(k[:, 64 - R:64, 0])
+        vp = G.dev_bf16(v[:, 64 - R:64, 0])
+        sa.seg_kv_past_append(c.ctx, 0, kp, vp, R, c.stream)
+        o, l = c.fwd(q[:, 64:], k[:, 64:], v[:, 64:])
+        # the same rows seen as a carried tail of length R by the oracle
+        o_ref, l_ref = orc.attend(q, k, v, seg_len=64, tail_len=R, kv_policy=[1], rows=np.arange(64, 128))
+        G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="past_append")
+    finally:
+        c.close()

@@ -1,0 +1,100 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and validates arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_11744_amd as sa
+from conftest import ROOT
+
+
+def _header_symbols():
+    text = open(os.path.join(ROOT, "include", "segattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(seg(?:attn)?_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sa.lib()
+    names = _header_symbols()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(sa.EXPORTS) == names
+    assert "gfx950" in sa.segattn_version()
+
+
+def _cfg(**kw):
+    base = dict(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, seg_len=64, tail_len=16,
+                kv_policy=[1, 3], past_capacity=256)
+    base.update(kw)
+    return sa.make_config(**base)
+
+
+def test_cache_bytes_accounts_for_rows_counters_and_workspace():
+    cfg = _cfg()
+    total = sa.segattn_cache_bytes(cfg)
+    kv_rows = 256 + (16 + 64)                      # PAST head: capacity; TAIL head: T + S
+    kv_bytes = kv_rows * 2 * 128 * 2
+    assert kv_bytes < total < kv_bytes + 64 * 1024
+    assert sa.segattn_cache_bytes(_cfg(batch=3)) > 3 * kv_bytes
+
+
+@pytest.mark.parametrize("bad", [
+    dict(head_dim=96), dict(n_q_heads=7), dict(tail_len=65), dict(seg_len=0), dict(batch=0),
+    dict(kv_policy=[1, 4]), dict(past_capacity=32), dict(tail_len=-1), dict(scale=-1.0),
+    dict(n_kv_heads=0, n_q_heads=0, kv_policy=[]),
+])
+def test_invalid_configurations_are_rejected(bad):
+    cfg = _cfg(**bad)
+    assert sa.segattn_cache_bytes(cfg) == 0
+    with pytest.raises(sa.SegattnError) as e:
+        sa.segattn_create(cfg, 256, 1 << 30)
+    assert e.value.status == sa.SEGATTN_EINVAL
+
+
+def test_create_checks_arena_and_calls_check_state_and_pointers():
+    cfg = _cfg()
+    need = sa.segattn_cache_bytes(cfg)
+    with pytest.raises(sa.SegattnError):
+        sa.segattn_create(cfg, 0, need)                 # null arena
+    with pytest.raises(sa.SegattnError):
+        sa.segattn_create(cfg, 4096 + 8, need)          # misaligned
+    with pytest.raises(sa.SegattnError):
+        sa.segattn_create(cfg, 4096, need - 1)          # too small
+    ctx = sa.segattn_create(cfg, 4096, need)            # create touches no device memory
+    try:
+        with pytest.raises(sa.SegattnError) as e:       # nothing reset yet
+            sa.seg_attn_fwd(ctx, 4096, 4096, 4096, 8, 4096, 4096)
+        assert e.value.status == sa.SEGATTN_ESTATE
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_attn_fwd(ctx, 0, 4096, 4096, 8, 4096, 4096)
+        assert e.value.status == sa.SEGATTN_EINVAL
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_past_append(ctx, 0, 4096, 4096, 4)    # head 0 is not PAST
+        assert e.value.status == sa.SEGATTN_EINVAL
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_set_lengths(ctx, [65], [0], [0])      # not a multiple of S
+        assert e.value.status == sa.SEGATTN_EINVAL
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_set_lengths(ctx, [512], [16], [0])    # beyond the pool capacity
+        assert e.value.status == sa.SEGATTN_ECAPACITY
+        assert sa.segattn_cache_span(ctx, 0, 1)[2] == 256 and sa.segattn_cache_span(ctx, 0, 0)[2] == 80
+        with pytest.raises(sa.SegattnError):
+            sa.segattn_cache_span(ctx, 1, 0)
+        assert sa.segattn_resident_bytes(ctx) == 0
+    finally:
+        sa.segattn_destroy(ctx)
+
+
+def test_fwd_seq_validates_before_launching():
+    cfg = _cfg()
+    with pytest.raises(sa.SegattnError) as e:
+        sa.seg_attn_fwd_seq(cfg, 4096, 4096, 0, 128, 4096, 4096)
+    assert e.value.status == sa.SEGATTN_EINVAL
+    with pytest.raises(sa.SegattnError) as e:
+        sa.seg_attn_fwd_seq(cfg, 4096, 4096, 4096, 0, 4096, 4096)
+    assert e.value.status == sa.SEGATTN_EINVAL
+    assert sa.strerror(sa.SEGATTN_ECAPACITY).startswith("past pool")
