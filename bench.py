@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of libsegattn on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic 128K-token prompt (B=1, 32 query
+/ 8 KV heads, D=128, S=4096, T=1024, 2 of 8 KV groups with full past access):
+
+  1. seg_attn_fwd_seq   one launch over all 32 segments (range resolution, work ordering, MFMA
+                        QK^T / online softmax / PV, epilogue with LSE);
+  2. seg_kv_commit      once per segment: tail hand-off and past-pool append, leaving the cache
+                        exactly as segment-by-segment execution would;
+  3. seg_kv_past_evict  (bookkeeping only; evicts 0 rows) and
+  4. seg_attn_decode    one token on top of the 128K context (split-K + combine).
+
+`value` = mask-useful prefill FLOPs (4*D per visible (query, key) pair; softmax work, masked
+halves of diagonal tiles and skipped tiles count zero) divided by the time of the whole step,
+inputs resident in HBM.  The roofline object prices the dominant kernel (the MFMA prefill
+kernel) against the dense bf16 MFMA peak, from HIP-event timings of that launch alone.
+
+Also reported on the same JSON line: the decode workload (B=64, contexts up to 64K) as
+achieved HBM GB/s, segment-by-segment execution of the same prompt (bounded resident KV),
+memory figures, and the fp64 oracle timed on the host cores on a bounded row sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def visible_pairs(w) -> int:
+    """Closed form of the cost model (Sec. 3.5): m(m+1)/2 + m*P pairs per segment."""
+    N, S, T = w.seq_len, w.seg_len, w.tail_len
+    total = 0
+    for pol in w.kv_policy:
+        pairs = 0
+        for s in range(0, N, S):
+            m = min(S, N - s)
+            prefix = s if pol & 2 else (min(T, s) if pol & 1 else 0)
+            pairs += m * (m + 1) // 2 + m * prefix
+        total += pairs * w.group
+    return total * w.batch
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c4_128k_prefill")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the decode and streaming legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2605_11744_amd as sa
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sa.lib()  # fails loudly if libsegattn.so has not been built
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    N, Hq, Hkv, D, S, T = w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seg_len, w.tail_len
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    def dense(t):  # a row slice of a B=1 tensor is already dense; copy otherwise
+        return t if t.is_contiguous() else t.contiguous()
+
+    qb, kb, vb = W.prefill_inputs(w)
+    q, k, v = dev(qb), dev(kb), dev(vb)
+    out = torch.empty((w.batch, N, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((w.batch, Hq, N), dtype=torch.float32, device="cuda")
+    cfg = sa.make_config(batch=w.batch, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, seg_len=S, tail_len=T,
+                         kv_policy=w.kv_policy, past_capacity=N + S)
+    arena_bytes = sa.segattn_cache_bytes(cfg)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    ctx = sa.segattn_create(cfg, arena, arena_bytes)
+    past_heads = [h for h, p in enumerate(w.kv_policy) if p & 2]
+    q1 = torch.randn((w.batch, Hq, D), device="cuda").to(torch.bfloat16)
+    k1 = torch.randn((w.batch, Hkv, D), device="cuda").to(torch.bfloat16)
+    v1 = torch.randn((w.batch, Hkv, D), device="cuda").to(torch.bfloat16)
+    o1 = torch.empty((w.batch, Hq, D), dtype=torch.bfloat16, device="cuda")
+    l1 = torch.empty((w.batch, Hq), dtype=torch.float32, device="cuda")
+    n_seg = (N + S - 1) // S
+    ev_k0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev_k1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+
+    def step(i=None):
+        sa.segattn_reset(ctx, stream)
+        if i is not None:
+            ev_k0[i].record()
+        sa.seg_attn_fwd_seq(cfg, q, k, v, N, out, lse, stream)
+        if i is not None:
+            ev_k1[i].record()
+        for s in range(n_seg):
+            m = min(S, N - s * S)
+            sa.seg_kv_commit(ctx, dense(k[:, s * S:s * S + m]), dense(v[:, s * S:s * S + m]), m, stream)
+        for h in past_heads[:1]:
+            sa.seg_kv_past_evict(ctx, h, 0, stream)
+        sa.seg_attn_decode(ctx, q1, k1, v1, o1, l1, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = sum(a.elapsed_time(b) for a, b in zip(ev_k0, ev_k1)) / args.steps
+    flops = 4 * D * visible_pairs(w)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+    resident = sa.segattn_resident_bytes(ctx)
+    dense_kv = w.batch * Hkv * (N + 1) * D * 2 * 2
+
+    result = {
+        "metric": "segmented-attn prefill TFLOP/s (useful FLOPs) + % bf16 MFMA peak at 128K",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "seq_len": N, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": D, "seg_len": S, "tail_len": T, "kv_policy": list(w.kv_policy),
+                   "step": "fwd_seq + commit x%d + evict + decode x1" % n_seg},
+        "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "kernel_ms": round(kern_ms, 4), "traffic": None},
+        "memory": {"resident_kv_bytes_after_step": resident, "dense_causal_kv_bytes": dense_kv,
+                   "ratio": round(dense_kv / resident, 3),
+                   "torch_peak_allocated_bytes": int(torch.cuda.max_memory_allocated())},
+    }
+    sa.segattn_destroy(ctx)
+    del arena
+
+    if not args.no_extras:
+        result["streaming"] = streaming_leg(sa, W, w, q, k, v, out, lse, flops)
+        del q, k, v, out, lse
+        torch.cuda.empty_cache()
+        result["decode"] = decode_leg(sa, W)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(W, w, qb, kb, vb)
+    print(json.dumps(result))
+    return 0
+
+
+def streaming_leg(sa, W, w, q, k, v, out, lse, flops):
+    """Segment-by-segment execution (seg_attn_fwd + seg_kv_commit per segment): the mode whose
+    resident KV is bounded by S + T per local head plus the pool of the PAST heads."""
+    import torch
+    N, S = w.seq_len, w.seg_len
+    cfg = sa.make_config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seg_len=S, tail_len=w.tail_len, kv_policy=w.kv_policy, past_capacity=N)
+    nbytes = sa.segattn_cache_bytes(cfg)
+    arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ctx = sa.segattn_create(cfg, arena, nbytes)
+    stream = torch.cuda.current_stream().cuda_stream
+    lse_seg = torch.empty((w.batch, w.n_q_heads, S), dtype=torch.float32, device="cuda")
+
+    def run():
+        sa.segattn_reset(ctx, stream)
+        for s in range(0, N, S):
+            m = min(S, N - s)
+            assert w.batch == 1  # row slices of a B=1 tensor are dense
+            sa.seg_attn_fwd(ctx, q[:, s:s + m], k[:, s:s + m], v[:, s:s + m], m, out[:, s:s + m], lse_seg, stream)
+            sa.seg_kv_commit(ctx, k[:, s:s + m], v[:, s:s + m], m, stream)
+
+    run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 3
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / reps
+    res = {"ms": round(ms, 3), "tflops_useful": round(flops / ms / 1e9, 2),
+           "resident_kv_bytes": sa.segattn_resident_bytes(ctx), "arena_bytes": nbytes}
+    sa.segattn_destroy(ctx)
+    return res
+
+
+def decode_leg(sa, W):
+    """B=64 decode: contexts drawn from the seed (k_b closed segments + c_b open rows, <= 64K);
+    cache rows are random bf16 written on the GPU (timing only; parity is in the tests)."""
+    import torch
+    w = W.C5
+    k_done, c_fill = W.decode_lengths(w)
+    B, Hq, Hkv, D, S, T = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seg_len, w.tail_len
+    cfg = sa.make_config(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, seg_len=S, tail_len=T,
+                         kv_policy=w.kv_policy, past_capacity=w.max_context)
+    nbytes = sa.segattn_cache_bytes(cfg)
+    arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(w.seed)
+    view = arena[: nbytes // 2 * 2].view(torch.bfloat16)
+    step = 1 << 26
+    for i in range(0, view.numel(), step):
+        n = min(step, view.numel() - i)
+        view[i:i + n] = torch.randn(n, device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    ctx = sa.segattn_create(cfg, arena, nbytes)
+    stream = torch.cuda.current_stream().cuda_stream
+    q = torch.randn((B, Hq, D), device="cuda", generator=g).to(torch.bfloat16)
+    kn = torch.randn((B, Hkv, D), device="cuda", generator=g).to(torch.bfloat16)
+    vn = torch.randn((B, Hkv, D), device="cuda", generator=g).to(torch.bfloat16)
+    out = torch.empty((B, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, Hq), dtype=torch.float32, device="cuda")
+    closed = [int(x) * S for x in k_done]
+    fill0 = [int(c) - 1 for c in c_fill]
+    rows = 0
+    for b in range(B):
+        for pol in w.kv_policy:
+            rows += W.decode_rows_kept(pol, int(k_done[b]), int(c_fill[b]), S, T)
+    kv_bytes = rows * D * 2 * 2
+    times = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for it in range(7):
+        sa.seg_kv_set_lengths(ctx, closed, [T] * B, fill0, stream)
+        e0.record()
+        sa.seg_attn_decode(ctx, q, kn, vn, out, lse, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            times.append(e0.elapsed_time(e1))
+    ms = sum(times) / len(times)
+    sa.segattn_destroy(ctx)
+    return {"workload": w.name, "ms_per_step": round(ms, 4), "kv_bytes_read": kv_bytes,
+            "achieved_GBps": round(kv_bytes / ms / 1e6, 1), "peak_GBps": PEAK_HBM_GBS,
+            "frac_of_hbm_peak": round(kv_bytes / ms / 1e6 / PEAK_HBM_GBS, 4),
+            "tokens_per_s": round(B / ms * 1e3, 1), "data": "random bf16 cache rows, seeded context lengths"}
+
+
+def cpu_baseline(W, w, qb, kb, vb):
+    """The fp64 oracle as it stands, on the host cores, on a bounded sample of the same
+    workload: `n_rows` seeded query positions, all heads."""
+    import numpy as np
+    from oracle import segattn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    rng = np.random.Generator(np.random.Philox(key=w.seed))
+    n_rows = 384
+    rows = np.sort(rng.choice(w.seq_len, size=n_rows, replace=False))
+    t0 = time.perf_counter()
+    orc.attend(qb, kb, vb, seg_len=w.seg_len, tail_len=w.tail_len, kv_policy=w.kv_policy, rows=rows)
+    dt = time.perf_counter() - t0
+    pairs = 0
+    for pol in w.kv_policy:
+        for p in rows:
+            s = (int(p) // w.seg_len) * w.seg_len
+            prefix = s if pol & 2 else (min(w.tail_len, s) if pol & 1 else 0)
+            pairs += (int(p) - s + 1 + prefix) * w.group
+    useful = 4 * w.head_dim * pairs
+    return {"value": round(useful / dt / 1e12, 6), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n_rows} seeded query rows x {w.n_q_heads} heads of {w.name} "
+                      f"(dense fp64 scores over all {w.seq_len} keys, explicit mask); {dt:.1f} s",
+            "seconds": round(dt, 2)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
