@@ -10,7 +10,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
-SOURCES = ("segattn_api.hip", "segattn_prefill.hip", "segattn_decode.hip", "segattn_cache.hip")
+SOURCES = ("segattn_api.hip", "segattn_prefill_mfma.hip", "segattn_prefill_fp32.hip", "segattn_decode.hip",
+           "segattn_cache.hip")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept out of the generated code on purpose

@@ -1,0 +1,111 @@
+// Work decomposition shared by the prefill kernels of libsegattn: which workgroup handles
+// which (sequence, KV head, head sub-group, segment, query block), and where its keys live.
+//
+// A workgroup's keys form two spans: span 0 = the prefix the head's policy grants (carried
+// tail and/or past rows, Eq. 13; every row visible to every query of the workgroup) and
+// span 1 = the rows of the query's own segment (causal, Eq. 12's mask).
+#pragma once
+#include "segattn_internal.h"
+
+namespace segattn {
+
+// One workgroup's share of the problem.
+struct WorkItem {
+  const unsigned short *k0, *v0, *k1, *v1;  // first row of span 0 / span 1 for this KV head
+  long long stride0, stride1;               // elements between consecutive rows
+  int n0, n1;                               // rows in span 0; rows of the segment present
+  const unsigned short *q;                  // row 0 of the segment's queries, head 0
+  unsigned char *out;                       // row 0 of the segment's outputs, head 0
+  float *lse;                               // lse of (b, head 0, segment row 0)
+  long long lse_head_stride;                // floats between heads in lse
+  int t0;                                   // first in-segment query row of the workgroup
+  int kv, hsub, b;
+  bool valid;
+};
+
+// blockIdx -> (sequence, KV head, head sub-group, segment, query block), longest work first:
+// all PAST workgroups by descending absolute query block, then the others by descending
+// in-segment query block.
+__device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int bid, int rows_per_wg,
+                                   int heads_per_wg) {
+  WorkItem w;
+  const int nhs = p.g / heads_per_wg;
+  const int nqb = a.q_blocks_per_seg;
+  const int n_other = p.Hkv - p.n_past;
+  const long long past_items = (long long)p.B * p.n_past * nhs * a.n_seg * nqb;
+  int seg, qblk, hidx, b, hs;
+  if (bid < past_items) {
+    const int per = p.B * p.n_past * nhs;
+    const int gq = a.n_seg * nqb - 1 - bid / per;
+    int rest = bid % per;
+    seg = gq / nqb;
+    qblk = gq % nqb;
+    hs = rest % nhs;
+    rest /= nhs;
+    hidx = rest % p.n_past;
+    b = rest / p.n_past;
+  } else {
+    const int y = bid - (int)past_items;
+    const int per = p.B * n_other * nhs * a.n_seg;
+    qblk = nqb - 1 - y / per;
+    int rest = y % per;
+    hs = rest % nhs;
+    rest /= nhs;
+    hidx = p.n_past + rest % n_other;
+    rest /= n_other;
+    b = rest % p.B;
+    seg = rest / p.B;
+  }
+  const int kv = p.order[hidx];
+  const int pol = p.policy[kv];
+  w.kv = kv;
+  w.hsub = hs;
+  w.b = b;
+  w.t0 = qblk * rows_per_wg;
+  const long long kv_stride = (long long)p.Hkv * p.D;
+  if (a.cache == nullptr) {  // SEQ mode: prefix read from k/v by absolute position
+    const long long N = a.n_rows;
+    const long long s = (long long)seg * p.S;
+    const long long m_i = (N - s < p.S) ? (N - s) : p.S;
+    long long lo = s;
+    if (pol & SEGATTN_PAST) lo = 0;
+    else if (pol & SEGATTN_TAIL) lo = (s - p.T > 0) ? s - p.T : 0;
+    w.n0 = (int)(s - lo);
+    w.n1 = (int)m_i;
+    w.k0 = a.k + ((long long)b * N + lo) * kv_stride + (long long)kv * p.D;
+    w.v0 = a.v + ((long long)b * N + lo) * kv_stride + (long long)kv * p.D;
+    w.k1 = a.k + ((long long)b * N + s) * kv_stride + (long long)kv * p.D;
+    w.v1 = a.v + ((long long)b * N + s) * kv_stride + (long long)kv * p.D;
+    w.stride0 = w.stride1 = kv_stride;
+    w.q = a.q + ((long long)b * N + s) * p.Hq * p.D;
+    const long long osz = p.out_fp32 ? 4 : 2;
+    w.out = (unsigned char *)a.out + ((long long)b * N + s) * p.Hq * p.D * osz;
+    w.lse = a.lse + (long long)b * p.Hq * N + s;
+    w.lse_head_stride = N;
+  } else {  // CTX mode: prefix (and the committed part of the open segment) from the cache
+    const int *meta = (const int *)(a.cache + a.geom.meta_off) + ((long long)b * p.Hkv + kv) * kMetaInts;
+    int lo, seg_row0;
+    window_of(p, kv, meta, lo, seg_row0);
+    const int hi = seg_row0 + meta[META_FILL];
+    const long long m = a.n_rows;
+    w.n0 = hi - lo;
+    w.n1 = (int)m;
+    w.k0 = (const unsigned short *)(a.cache + k_block_off(p, a.geom, b, kv)) + (long long)lo * p.D;
+    w.v0 = (const unsigned short *)(a.cache + v_block_off(p, a.geom, b, kv)) + (long long)lo * p.D;
+    w.stride0 = p.D;
+    w.k1 = a.k + (long long)b * m * kv_stride + (long long)kv * p.D;
+    w.v1 = a.v + (long long)b * m * kv_stride + (long long)kv * p.D;
+    w.stride1 = kv_stride;
+    w.q = a.q + (long long)b * m * p.Hq * p.D;
+    const long long osz = p.out_fp32 ? 4 : 2;
+    w.out = (unsigned char *)a.out + (long long)b * m * p.Hq * p.D * osz;
+    w.lse = a.lse + (long long)b * p.Hq * m;
+    w.lse_head_stride = m;
+  }
+  w.valid = w.t0 < w.n1;
+  return w;
+}
+
+__device__ inline float bf16_bits_to_f32(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+
+}  // namespace segattn
