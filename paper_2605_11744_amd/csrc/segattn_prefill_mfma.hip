@@ -42,6 +42,7 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
 #define GLB_AS __attribute__((address_space(1)))
 
@@ -59,7 +60,10 @@ struct StepGeom {
   static constexpr int kInstrPerWave = kInstr / 4;
   static constexpr int kRowsPerInstr = 1024 / kRowBytes;
   static constexpr int kRowsPer256 = 256 / kRowBytes;          // rows sharing one 64-bank window
-  __device__ static constexpr int swz_k(int row) { return (row / kRowsPer256) % kChunks; }
+  // K rows are read 16 lanes = 16 consecutive rows at one logical chunk: XOR-ing the low three
+  // chunk bits with the row leaves a 2-way bank conflict for 256-byte rows (cheap: K reads are
+  // 8 per step) and keeps the upper chunk bit an immediate offset of the read.
+  __device__ static constexpr int swz_k(int row) { return (row / kRowsPer256) & 7; }
   __device__ static constexpr int swz_v(int row) { return 4 * ((row / kRowsPer256) % (kChunks / 4)); }
 };
 
@@ -73,6 +77,29 @@ __device__ inline float half_sum(float x) {
   const auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
   return __int_as_float(sw[0]) + __int_as_float(sw[1]);
 }
+
+// The output accumulators live in accumulation registers (AGPRs): the matrix cores read and
+// write them there directly and the vector registers stay free for the softmax.  The few
+// places that touch them with the vector ALU go through these helpers.
+__device__ inline float acc_zero() {
+  float x;
+  asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(x));
+  return x;
+}
+__device__ inline float acc_scale(float x, float alpha) {  // x * alpha, x and the result in AGPRs
+  float t;
+  asm volatile("v_accvgpr_read_b32 %1, %0\n\ts_nop 1\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1"
+               : "+a"(x), "=&v"(t)
+               : "v"(alpha));
+  return x;
+}
+__device__ inline float acc_get(float x) {
+  float t;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(x));
+  return t;
+}
+// MFMA results must have left the pipeline before the helpers above read them.
+__device__ inline void acc_drain() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
 
 template <int D, int HS>
 __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, const PrefillArgs a) {
@@ -132,59 +159,94 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     ld_cv[i] = (unsigned)((slot_chunk ^ G::swz_v(r)) * 16);
   }
   unsigned off_k[LPW], off_v[LPW];
-  int off_span = -1;
   LDS_AS unsigned char *const lds = (LDS_AS unsigned char *)smem;
+  constexpr int kRing = kSlots * G::kSlotBytes;
+  auto next_slot = [](int off) { return off + G::kSlotBytes == kRing ? 0 : off + G::kSlotBytes; };
 
-  auto issue = [&](int js) {  // enqueue the loads of step js (js < n) into its ring slot
-    const int s1 = js >= nst0 ? 1 : 0;
-    const int j0 = (s1 ? js - nst0 : js) * kStepKeys;
-    const int nrows = s1 ? w.n1 : w.n0;
-    const unsigned stride_b = (unsigned)((s1 ? w.stride1 : w.stride0) * 2);
-    const unsigned char *kp = (const unsigned char *)(s1 ? w.k1 : w.k0) + (long long)j0 * stride_b;
-    const unsigned char *vp = (const unsigned char *)(s1 ? w.v1 : w.v0) + (long long)j0 * stride_b;
-    const int nvalid = nrows - j0;  // >= 1; rows past it are clamped (and masked by the consumer)
-    LDS_AS unsigned char *dst = lds + (js % kSlots) * G::kSlotBytes + wave * LPW * 1024;
-    if (off_span != s1) {
-      off_span = s1;
+  // loader state: the next step to fetch, where its rows start, how many rows its span has left
+  int ld_js = 0, ld_span = -1, ld_left = 0, ld_slot = 0;
+  int ld_full_end = 0;  // first step of the current span (or n) that is not a plain full step
+  const unsigned char *ld_kp = nullptr, *ld_vp = nullptr;
+  unsigned ld_stride = 0;
+  auto enter_span = [&](int s1) {
+    ld_span = s1;
+    ld_kp = (const unsigned char *)(s1 ? w.k1 : w.k0);
+    ld_vp = (const unsigned char *)(s1 ? w.v1 : w.v0);
+    ld_left = s1 ? w.n1 : w.n0;
+    ld_stride = (unsigned)((s1 ? w.stride1 : w.stride0) * 2);
+    ld_full_end = (s1 ? nst0 : 0) + ld_left / kStepKeys;
+    if (ld_full_end > n) ld_full_end = n;
 #pragma unroll
-      for (int i = 0; i < LPW; ++i) {
-        off_k[i] = (unsigned)ld_row[i] * stride_b + ld_ck[i];
-        off_v[i] = (unsigned)ld_row[i] * stride_b + ld_cv[i];
-      }
+    for (int i = 0; i < LPW; ++i) {
+      off_k[i] = (unsigned)ld_row[i] * ld_stride + ld_ck[i];
+      off_v[i] = (unsigned)ld_row[i] * ld_stride + ld_cv[i];
     }
-    if (nvalid >= kStepKeys) {
+  };
+  enter_span(nst0 > 0 ? 0 : 1);
+  auto issue = [&]() {  // enqueue the loads of step ld_js (< n) into its ring slot, then advance
+    LDS_AS unsigned char *dst = lds + ld_slot + wave * (LPW * 1024);
+    if (ld_left >= kStepKeys) {
 #pragma unroll
       for (int i = 0; i < LPW; ++i) {
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(kp + off_k[i]), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(vp + off_v[i]),
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_kp + off_k[i]), (LDS_AS void *)(dst + i * 1024), 16, 0,
+                                         0);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + off_v[i]),
                                          (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
       }
-    } else {
+    } else {  // ragged end of the span: rows past it are clamped (and masked by the consumer)
 #pragma unroll
       for (int i = 0; i < LPW; ++i) {
-        const int r = ld_row[i] < nvalid ? ld_row[i] : nvalid - 1;
-        const unsigned ro = (unsigned)r * stride_b;
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(kp + (ro + ld_ck[i])), (LDS_AS void *)(dst + i * 1024),
+        const int r = ld_row[i] < ld_left ? ld_row[i] : ld_left - 1;
+        const unsigned ro = (unsigned)r * ld_stride;
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_kp + (ro + ld_ck[i])), (LDS_AS void *)(dst + i * 1024),
                                          16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(vp + (ro + ld_cv[i])),
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + (ro + ld_cv[i])),
                                          (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
       }
     }
+    ld_js += 1;
+    ld_slot = next_slot(ld_slot);
+    ld_kp += (size_t)kStepKeys * ld_stride;
+    ld_vp += (size_t)kStepKeys * ld_stride;
+    ld_left -= kStepKeys;
+    if (ld_span == 0 && ld_js == nst0) enter_span(1);
   };
-  // Before computing step j: the loads of steps <= j+1 have landed for every wave; then the
-  // loads of step j+3 are enqueued (their slot was last read in step j-1).
-  auto sync = [&](int j) {
-    if (j + 2 < n) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPW));  // vmcnt(2*LPW): step j+2 may be in flight
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0)
+  // Branch-free variant for the hot loop: a full step of the current span, no span switch after it
+  // (the caller guarantees ld_js + 1 < ld_full_end).
+  auto issue_hot = [&]() {
+    LDS_AS unsigned char *dst = lds + ld_slot + wave * (LPW * 1024);
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+      __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_kp + off_k[i]), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + off_v[i]),
+                                       (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
+    }
+    ld_js += 1;
+    ld_slot = next_slot(ld_slot);
+    ld_kp += (size_t)kStepKeys * ld_stride;
+    ld_vp += (size_t)kStepKeys * ld_stride;
+    ld_left -= kStepKeys;
+  };
+  // Executed once per step j by every wave (in the prologue for j = 0, in the middle of step j
+  // otherwise): the loads of steps <= j+2 have landed for every wave and every wave is done
+  // reading the slot of step j-1, which now receives the loads of step j+4.
+  auto sync_step = [&](int j) {
+    const int in_flight = ld_js - 1 - (j + 2);  // whole steps that may stay outstanding
+    if (in_flight >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));
+    else if (in_flight == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPW));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
-    if (j + 3 < n) issue(j + 3);
+    if (ld_js < n) issue();
   };
 
-  issue(0);
-  if (1 < n) issue(1);
-  if (2 < n) issue(2);
+  issue();
+  if (1 < n) issue();
+  if (2 < n) issue();
+  if (3 < n) issue();
 
-  // ---- Q^T operands: Qr[qb][kc] = Q[row(qb, col)][16 kc + 8 hi .. +7]
+  // ---- Q^T operands: Qr[qb][kc] = Q[row(qb, col)][16 kc + 8 hi .. +7], parked in accumulation
+  //      registers (they are only ever MFMA operands) so that the vector registers stay free
+  //      for the softmax and for operand prefetch.
   bf16x8 Qr[QB][NC];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -192,13 +254,25 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     t = t < last_row ? t : last_row;
     const unsigned short *qrow = w.q + ((long long)t * p.Hq + head) * D + 8 * hi;
 #pragma unroll
-    for (int kc = 0; kc < NC; ++kc) Qr[qb][kc] = __builtin_bit_cast(bf16x8, *(const uint4 *)(qrow + 16 * kc));
+    for (int kc = 0; kc < NC; ++kc) {
+      const i32x4 v = __builtin_bit_cast(i32x4, *(const uint4 *)(qrow + 16 * kc));
+      int a0, a1, a2, a3;
+      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a0) : "v"(v[0]));
+      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a1) : "v"(v[1]));
+      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a2) : "v"(v[2]));
+      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a3) : "v"(v[3]));
+      const i32x4 q4 = {a0, a1, a2, a3};
+      Qr[qb][kc] = __builtin_bit_cast(bf16x8, q4);
+    }
   }
 
   // ---- per-lane LDS read offsets inside a slot
-  int koff[NC];  // K operand: row col, chunk 2kc+hi
+  // K operand of k-chunk kc: row col, logical chunk 2kc+hi = 8 (kc/4) + (2 (kc%4) + hi); the
+  // swizzle touches the low three bits only, so 4 lane offsets + an immediate cover all kc.
+  constexpr int NKA = NC < 4 ? NC : 4;
+  int koff[NKA];
 #pragma unroll
-  for (int kc = 0; kc < NC; ++kc) koff[kc] = col * G::kRowBytes + (((2 * kc + hi) ^ G::swz_k(col)) << 4);
+  for (int i = 0; i < NKA; ++i) koff[i] = col * G::kRowBytes + (((2 * i + hi) ^ G::swz_k(col)) << 4);
   int voff[NB];  // V^T operand: row 4hi + i16/4 (+16 h2 + 8 u), columns 32 nb + 16 g16 + 4 (i16%4) ..+3
   {
     const int vrow = 4 * hi + (i16 >> 2);
@@ -218,31 +292,36 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) O[qb][nb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) O[qb][nb][r] = acc_zero();
   }
 
-  // S^T of the step held in ring slot `slot`
-  auto compute_s = [&](int slot, f32x16(&S)[QB]) {
-    const LDS_AS unsigned char *kb = lds + slot * G::kSlotBytes;
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // ---- operand fetch from LDS.  Inline asm: the order and the waits are ours (the compiler
+  //      would make a transposing read wait for every outstanding global->LDS load).
+  // K operand of k-chunk kc for the step in the slot at byte offset `so`
+  auto k_load = [&](int so, i32x4(&Kr)[NC]) {
+    unsigned ka[NKA];
 #pragma unroll
-    for (int kc = 0; kc < NC; ++kc) {
-      const bf16x8 ka = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4 *)(kb + koff[kc]));
+    for (int i = 0; i < NKA; ++i) ka[i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + so);
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, Qr[qb][kc], kc == 0 ? zero : S[qb], 0, 0, 0);
+    for (int kc = 0; kc < NC; ++kc)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
+  };
+  auto k_wait = [&](i32x4(&Kr)[NC]) {
+    if constexpr (NC == 8) {
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(Kr[0]), "+v"(Kr[1]), "+v"(Kr[2]), "+v"(Kr[3]), "+v"(Kr[4]), "+v"(Kr[5]), "+v"(Kr[6]),
+                     "+v"(Kr[7]));
+    } else {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(Kr[0]), "+v"(Kr[1]), "+v"(Kr[2]), "+v"(Kr[3]));
     }
   };
-  // O^T += V^T . P^T for the step in `slot`.  k-slot e of half-wave hi in chunk h2 is key
-  // 16 h2 + 8 (e/4) + 4 hi + e%4 (the accumulator layout of S^T), so V^T is fetched for exactly
-  // those keys: two transposing reads of 4 keys each.  The reads are issued by pv_load (inline
-  // asm: the compiler would otherwise order the transposing read after every outstanding
-  // global->LDS load) and awaited by pv_wait right before the products that consume them.
-  auto pv_load = [&](int slot, s16x4(&Vr)[2][NB][2]) {
-    const unsigned vb = (unsigned)(size_t)(lds + slot * G::kSlotBytes);
+  // V^T operand: k-slot e of half-wave hi in chunk h2 is key 16 h2 + 8 (e/4) + 4 hi + e%4 (the
+  // accumulator layout of S^T), so V^T is fetched for exactly those keys: two transposing reads
+  // of 4 keys each per (h2, 32-row block nb).
+  auto v_load = [&](int so, s16x4(&Vr)[2][NB][2]) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const unsigned va = vb + (unsigned)voff[nb];
+      const unsigned va = (unsigned)(size_t)lds + (unsigned)(voff[nb] + so);
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(Vr[h2][nb][0]) : "v"(va), "n"(16 * h2 * G::kRowBytes));
@@ -252,7 +331,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       }
     }
   };
-  auto pv_wait = [&](s16x4(&Vr)[2][NB][2]) {
+  auto v_wait = [&](s16x4(&Vr)[2][NB][2]) {
     if constexpr (NB == 4) {
       asm volatile("s_waitcnt lgkmcnt(0)"
                    : "+v"(Vr[0][0][0]), "+v"(Vr[0][0][1]), "+v"(Vr[0][1][0]), "+v"(Vr[0][1][1]), "+v"(Vr[0][2][0]),
@@ -265,26 +344,53 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
                      "+v"(Vr[1][0][1]), "+v"(Vr[1][1][0]), "+v"(Vr[1][1][1]));
     }
   };
-  auto pv_mma = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2]) {
+  // ---- matrix products
+  auto s_mma = [&](const i32x4(&Kr)[NC], f32x16(&S)[QB]) {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int h2 = 0; h2 < 2; ++h2)
+    for (int kc = 0; kc < NC; ++kc)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const bf16x8 va =
-            __builtin_bit_cast(bf16x8, __builtin_shufflevector(Vr[h2][nb][0], Vr[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7));
+      for (int qb = 0; qb < QB; ++qb)
+        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, Kr[kc]), Qr[qb][kc],
+                                                        kc == 0 ? zero : S[qb], 0, 0, 0);
+  };
+  auto pv_mma = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          O[qb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, P[qb][h2], O[qb][nb], 0, 0, 0);
+    for (int nb = 0; nb < NB; ++nb) {
+      const bf16x8 va =
+          __builtin_bit_cast(bf16x8, __builtin_shufflevector(Vr[h2][nb][0], Vr[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        O[qb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, P[qb][h2], O[qb][nb], 0, 0, 0);
+    }
+  };
+  auto compute_s = [&](int so, f32x16(&S)[QB]) {  // unpipelined S^T of the step in slot `so`
+    i32x4 Kr[NC];
+    k_load(so, Kr);
+    k_wait(Kr);
+    s_mma(Kr, S);
+  };
+  auto pv = [&](int so, const bf16x8(&P)[QB][2]) {  // unpipelined O^T += V^T P^T
+    s16x4 Vr[2][NB][2];
+    v_load(so, Vr);
+    v_wait(Vr);
+    pv_mma(Vr, P, 0);
+    pv_mma(Vr, P, 1);
+  };
+  // S^T accumulators -> vector registers, at this point of the program (the accumulation
+  // registers are then free for the next step's product)
+  auto s_fetch = [&](const f32x16(&S)[QB], float(&Sv)[QB][16]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float x = S[qb][r];
+        asm volatile("" : "+v"(x));
+        Sv[qb][r] = x;
       }
   };
-  auto pv = [&](int slot, const bf16x8(&P)[QB][2]) {
-    s16x4 Vr[2][NB][2];
-    pv_load(slot, Vr);
-    pv_wait(Vr);
-    pv_mma(Vr, P);
-  };
   // P = exp2(S c - m_ref c) as bf16, its row sums (of the rounded values) and the row maxima of S
-  auto softmax = [&](const f32x16(&S)[QB], bf16x8(&P)[QB][2], float(&psum)[QB], float(&rmax)[QB]) {
+  auto softmax = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB], float(&rmax)[QB]) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -310,8 +416,17 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       rmax[qb] = mx;
     }
   };
+  auto rescale = [&](int qb, float alpha) {  // rare: O^T and l of query block qb times alpha
+    l_run[qb] *= alpha;
+    acc_drain();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) O[qb][nb][r] = acc_scale(O[qb][nb][r], alpha);
+    acc_drain();
+  };
   // Validate the P just formed against the step's own maximum; rescale and redo if needed.
-  auto settle = [&](const f32x16(&S)[QB], bf16x8(&P)[QB][2], float(&psum)[QB], float(&rmax)[QB]) {
+  auto settle = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB], float(&rmax)[QB]) {
     bool need[QB];
     float mx[QB];
     bool any = false;
@@ -322,42 +437,90 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       any |= need[qb];
     }
     if (__builtin_amdgcn_ballot_w64(any) != 0) {
+      // The first P stays "used" on this path too, so that its computation is not sunk below
+      // the branch (it has to overlap with the matrix products above).
+      asm volatile("" ::"v"(P[0][0]), "v"(P[0][1]), "v"(P[1][0]), "v"(P[1][1]), "v"(psum[0]), "v"(psum[1]));
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const float m_new = need[qb] ? mx[qb] : m_ref[qb];
         const float alpha = need[qb] ? __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c) : 1.f;
         m_ref[qb] = m_new;
-        l_run[qb] *= alpha;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) O[qb][nb][r] *= alpha;
+        rescale(qb, alpha);
       }
       softmax(S, P, psum, rmax);
     }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb];
   };
-  // One pipelined step j: S^T(j+1) -> Sn, PV of step j-1 with Pp, P(j) <- Sc.
-  auto fast_step = [&](int j, auto do_s, const f32x16(&Sc)[QB], f32x16(&Sn)[QB], const bf16x8(&Pp)[QB][2],
-                       bf16x8(&Pc)[QB][2]) {
+
+  // ring offsets of steps j-1, j, j+1, j+2
+  int so_m1 = 0, so_0 = 0, so_p1 = G::kSlotBytes, so_p2 = 2 * G::kSlotBytes;
+  auto advance = [&]() {
+    so_m1 = so_0;
+    so_0 = so_p1;
+    so_p1 = so_p2;
+    so_p2 = next_slot(so_p2);
+  };
+
+  // One pipelined step j >= 1.  On entry Kr holds the K operands of step j+1 (if do_s), Sc is
+  // S^T of step j and Pp is P of step j-1.  The step forms S^T(j+1) -> Sn, adds PV of step j-1,
+  // turns Sc into Pc, runs the step's sync in the middle and, if fetch_k, leaves the K operands
+  // of step j+2 in Kr.
+  auto fast_step = [&](int j, auto do_s, auto fetch_k, i32x4(&Kr)[NC], const float(&Sc)[QB][16],
+                       float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) {
     float psum[QB], rmax[QB];
     s16x4 Vr[2][NB][2];
-    pv_load((j - 1) % kSlots, Vr);
-    if constexpr (decltype(do_s)::value) compute_s((j + 1) % kSlots, Sn);
-    pv_wait(Vr);
-    pv_mma(Vr, Pp);
+    f32x16 Sacc[QB];
+    v_load(so_m1, Vr);
+    if constexpr (decltype(do_s)::value) s_mma(Kr, Sacc);
+    v_wait(Vr);
+    pv_mma(Vr, Pp, 0);
+    sync_step(j);
+    if constexpr (decltype(fetch_k)::value) k_load(so_p2, Kr);
+    pv_mma(Vr, Pp, 1);
     softmax(Sc, Pc, psum, rmax);
+    if constexpr (decltype(do_s)::value) s_fetch(Sacc, Sn);
+    if constexpr (decltype(fetch_k)::value) k_wait(Kr);
     settle(Sc, Pc, psum, rmax);
   };
-  // An unpipelined step with element masks: keys with in-span index >= lim[qb] are invisible.
-  auto slow_step = [&](int j) {
-    const bool s1 = j >= nst0;
-    const int j0 = (s1 ? j - nst0 : j) * kStepKeys;
-    f32x16 S[QB];
+  // The same step for the hot loop: one basic block up to the final check.  The sync is
+  // branch-free (exactly one step of loads stays in flight, the loads issued are a full step of
+  // the current span) and the instruction mix is laid out explicitly: matrix products
+  // interleaved with the softmax arithmetic that runs in their shadow.
+  auto hot_step = [&](i32x4(&Kr)[NC], const float(&Sc)[QB][16], float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2],
+                      bf16x8(&Pc)[QB][2]) {
+    float psum[QB], rmax[QB];
+    s16x4 Vr[2][NB][2];
+    f32x16 Sacc[QB];
+    v_load(so_m1, Vr);
+    s_mma(Kr, Sacc);
+    softmax(Sc, Pc, psum, rmax);
+    v_wait(Vr);
+    pv_mma(Vr, Pp, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPW));
+    __builtin_amdgcn_s_barrier();
+    issue_hot();
+    k_load(so_p2, Kr);
+    pv_mma(Vr, Pp, 1);
+    s_fetch(Sacc, Sn);
+    k_wait(Kr);
+    // 2*NC + 4*NB matrix products; the softmax is about 3.5 vector instructions per element
+#pragma unroll
+    for (int i = 0; i < 2 * NC + 4 * NB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // five VALU
+    }
+    settle(Sc, Pc, psum, rmax);
+  };
+  // An unpipelined step (slot so, span-local first key j0) with element masks: keys with
+  // in-span index >= lim[qb] are invisible.
+  auto slow_step = [&](int so, bool s1, int j0) {
+    f32x16 Sacc[QB];
+    float S[QB][16];
     bf16x8 P[QB][2];
     float psum[QB], rmax[QB];
-    compute_s(j % kSlots, S);
+    compute_s(so, Sacc);
+    s_fetch(Sacc, S);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       int t = tw0 + 32 * qb + col;
@@ -373,30 +536,31 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[qb][r]);
       mx = half_max(mx);
       const bool need = mx > m_ref[qb] + tau;  // true on the very first step (m_ref = -inf, mx finite)
-      const float m_new = need ? mx : m_ref[qb];
-      const float alpha = need ? __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c) : 1.f;
-      m_ref[qb] = m_new;
-      l_run[qb] *= alpha;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[qb][nb][r] *= alpha;
+      if (__builtin_amdgcn_ballot_w64(need) != 0) {
+        const float m_new = need ? mx : m_ref[qb];
+        const float alpha = need ? __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c) : 1.f;
+        m_ref[qb] = m_new;
+        rescale(qb, alpha);
+      }
     }
     softmax(S, P, psum, rmax);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb];
-    pv(j % kSlots, P);
+    pv(so, P);
   };
 
   // =========================== main sequence ===========================
-  sync(0);
-  f32x16 Sa[QB], Sb[QB];
+  sync_step(0);
+  float Sa[QB][16], Sb[QB][16];
   bf16x8 Pa[QB][2], Pb[QB][2];
+  i32x4 Kr[NC];
   int j = 0;
   if (f > 0) {
     {  // step 0 without overlap: exact maximum as the first reference
       float psum[QB], rmax[QB];
-      compute_s(0, Sa);
+      f32x16 Sacc[QB];
+      compute_s(so_0, Sacc);
+      s_fetch(Sacc, Sa);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         float mx = Sa[qb][0];
@@ -407,46 +571,80 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       softmax(Sa, Pb, psum, rmax);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) l_run[qb] = psum[qb];
-      if (f > 1) compute_s(1 % kSlots, Sa);
+      if (f > 1) {
+        compute_s(so_p1, Sacc);
+        s_fetch(Sacc, Sa);
+      }
+      if (f > 2) {  // K operands of step 2 for the product formed in step 1
+        k_load(so_p2, Kr);
+        k_wait(Kr);
+      }
     }
     j = 1;
-    while (j + 2 < f) {
-      sync(j);
-      fast_step(j, std::true_type{}, Sa, Sb, Pb, Pa);
-      sync(j + 1);
-      fast_step(j + 1, std::true_type{}, Sb, Sa, Pa, Pb);
+    advance();
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    for (;;) {
+      // hot pairs: the next two loads are plain full steps of the current span
+      while (j + 3 < f && ld_js + 2 < ld_full_end) {
+        hot_step(Kr, Sa, Sb, Pb, Pa);
+        advance();
+        hot_step(Kr, Sb, Sa, Pa, Pb);
+        advance();
+        j += 2;
+      }
+      if (!(j + 3 < f)) break;
+      // steps j and j+1 both form the next S^T and fetch the K operands after it
+      fast_step(j, yes, yes, Kr, Sa, Sb, Pb, Pa);
+      advance();
+      fast_step(j + 1, yes, yes, Kr, Sb, Sa, Pa, Pb);
+      advance();
       j += 2;
     }
-    if (f - j == 2) {
-      sync(j);
-      fast_step(j, std::true_type{}, Sa, Sb, Pb, Pa);
-      sync(j + 1);
-      fast_step(j + 1, std::false_type{}, Sb, Sa, Pa, Pb);
-      j += 2;
-    } else if (f - j == 1) {
-      sync(j);
-      fast_step(j, std::false_type{}, Sa, Sb, Pb, Pa);
+    const int rest = f - j;  // 0..3 pipelined steps left; Kr holds K(j+1) if rest >= 2
+    if (rest == 3) {
+      fast_step(j, yes, yes, Kr, Sa, Sb, Pb, Pa);
+      advance();
+      fast_step(j + 1, yes, no, Kr, Sb, Sa, Pa, Pb);
+      advance();
+      fast_step(j + 2, no, no, Kr, Sa, Sb, Pb, Pa);
+      advance();
+    } else if (rest == 2) {
+      fast_step(j, yes, no, Kr, Sa, Sb, Pb, Pa);
+      advance();
+      fast_step(j + 1, no, no, Kr, Sb, Sa, Pa, Pb);
+      advance();
+    } else if (rest == 1) {
+      fast_step(j, no, no, Kr, Sa, Sb, Pb, Pa);
+      advance();
+    }
+    if (rest == 3 || rest == 1) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         Pb[qb][0] = Pa[qb][0];
         Pb[qb][1] = Pa[qb][1];
       }
-      j += 1;
     }
+    if (rest > 0) j += rest;
   }
-  // here j == f and, if f > 0, P(f-1) waits in Pb
+  // here j == f, so_0 is the slot of step j and, if f > 0, P(f-1) waits in Pb
   bool pending = f > 0;
   for (; j < n; ++j) {
-    if (j > 0) sync(j);
     if (pending) {
-      pv((j - 1) % kSlots, Pb);
+      pv(so_m1, Pb);
       pending = false;
     }
-    if (j < j_active_end) slow_step(j);
+    if (j < j_active_end) {
+      const bool s1 = j >= nst0;
+      slow_step(so_0, s1, (s1 ? j - nst0 : j) * kStepKeys);
+    }
+    if (j > 0) sync_step(j);
+    advance();
   }
-  if (pending) pv((n - 1) % kSlots, Pb);
+  if (pending) pv(so_m1, Pb);
 
   // ---- epilogue: normalise, write O (row t, head, d) and LSE
+  acc_drain();
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int t = tw0 + 32 * qb + col;
@@ -460,8 +658,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         const int d = 32 * nb + 8 * rg + 4 * hi;
-        const f32x4 o = {O[qb][nb][4 * rg + 0] * inv, O[qb][nb][4 * rg + 1] * inv, O[qb][nb][4 * rg + 2] * inv,
-                         O[qb][nb][4 * rg + 3] * inv};
+        const f32x4 o = {acc_get(O[qb][nb][4 * rg + 0]) * inv, acc_get(O[qb][nb][4 * rg + 1]) * inv,
+                         acc_get(O[qb][nb][4 * rg + 2]) * inv, acc_get(O[qb][nb][4 * rg + 3]) * inv};
         if (p.out_fp32) {
           *(f32x4 *)((float *)w.out + orow + d) = o;
         } else {
