@@ -1,0 +1,124 @@
+"""GPU parity at the benchmark's full sizes and launch configuration: the library runs the
+whole workload exactly as bench.py does (bf16 output, one seg_attn_fwd_seq launch; the
+B=64 decode step), and the fp64 oracle recomputes a sample of the outputs one by one.
+Properties that hold at any size (finite, inside the convex hull of V) cover the rest."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import segattn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _sample_rows(w, n_random, seed):
+    S, T, N = w.seg_len, w.tail_len, w.seq_len
+    fixed = {0, 1, 31, 32, 63, 64, S - 1, S, S + 1, S + T - 1, S + T, 2 * S - 1, 2 * S, N // 2 - 1, N // 2,
+             N - S, N - S + 1, N - 65, N - 64, N - 1}
+    rng = np.random.default_rng(seed)
+    rows = sorted({r for r in fixed if 0 <= r < N} | set(int(x) for x in rng.integers(0, N, n_random)))
+    return np.array(rows, dtype=np.int64)
+
+
+def _check_rows(w, q, k, v, o_gpu, l_gpu, rows, bf16_out):
+    """o_gpu [B,R,Hq,D], l_gpu [B,Hq,R] are the GPU results at `rows`."""
+    o_ref, l_ref = orc.attend(q, k, v, seg_len=w.seg_len, tail_len=w.tail_len, kv_policy=w.kv_policy, rows=rows)
+    eo, el = np.abs(o_gpu - o_ref), np.abs(l_gpu - l_ref)
+    # a bf16 result carries its own rounding (half an ulp: 2^-9 relative) on top of the 1e-2 bar
+    slack = np.abs(o_ref) * 2.0 ** -8 if bf16_out else 0.0
+    assert np.all(eo <= 1e-2 + slack), f"O max-abs {eo.max():.3e}"
+    assert eo.mean() <= 1e-3, f"O mean-abs {eo.mean():.3e}"
+    assert el.max() <= 1e-2 and el.mean() <= 1e-3, f"LSE max {el.max():.3e} mean {el.mean():.3e}"
+    return eo.max(), eo.mean(), el.max()
+
+
+def _run_full(w, bf16_out):
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    q, k, v = W.prefill_inputs(w)
+    cfg = G.config_of(w, out_fp32=not bf16_out)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    odt = torch.bfloat16 if bf16_out else torch.float32
+    out = torch.full((w.batch, w.seq_len, w.n_q_heads, w.head_dim), float("nan"), dtype=odt, device="cuda")
+    lse = torch.full((w.batch, w.n_q_heads, w.seq_len), float("nan"), dtype=torch.float32, device="cuda")
+    sa.seg_attn_fwd_seq(cfg, qd, kd, vd, w.seq_len, out, lse, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    # properties at any size: everything written, finite, O inside the convex hull of V per KV head
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    vmax = vd.float().amax(dim=1).repeat_interleave(w.group, dim=1)      # [B, Hq, D]
+    vmin = vd.float().amin(dim=1).repeat_interleave(w.group, dim=1)
+    of = out.float()
+    tol = 0.04 if bf16_out else 1e-3
+    assert bool((of <= vmax[:, None] + tol).all()) and bool((of >= vmin[:, None] - tol).all())
+    return q, k, v, out, lse
+
+
+@pytest.mark.parametrize("name,n_random,bf16_out", [
+    ("c2_16k_gqa_outliers", 160, True), ("c2_16k_gqa_outliers", 64, False),
+    ("c3_32k_llama3_8b_layer", 100, True), ("c4_128k_prefill", 44, True),
+])
+def test_prefill_full_size_sampled_rows(name, n_random, bf16_out):
+    import gpu_util as G
+    w = W.WORKLOADS[name]
+    q, k, v, out, lse = _run_full(w, bf16_out)
+    rows = _sample_rows(w, n_random, w.seed)
+    idx = torch.from_numpy(rows).cuda()
+    o_gpu = G.to_f64(out.index_select(1, idx))
+    l_gpu = G.to_f64(lse.index_select(2, idx))
+    _check_rows(w, q, k, v, o_gpu, l_gpu, rows, bf16_out)
+
+
+def test_prefill_interleaved_policy_full_size():
+    """Same FLOPs, different load balance: PAST heads spread over the KV heads (Table 11 contrasts
+    contiguous and interleaved head groupings)."""
+    import gpu_util as G
+    w = W.interleaved(W.C2)
+    assert w.kv_policy != W.C2.kv_policy
+    q, k, v, out, lse = _run_full(w, True)
+    rows = _sample_rows(w, 64, w.seed + 7)
+    idx = torch.from_numpy(rows).cuda()
+    _check_rows(w, q, k, v, G.to_f64(out.index_select(1, idx)), G.to_f64(lse.index_select(2, idx)), rows, True)
+
+
+def test_decode_c5_full_batch():
+    """The B=64 decode workload exactly as the benchmark runs it (bf16 output), every output
+    checked: cache rows written through segattn_cache_span, lengths declared, one step."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    w = W.C5
+    S, T, D, Hkv = w.seg_len, w.tail_len, w.head_dim, w.n_kv_heads
+    q, ks, vs, k_done, c_fill = W.decode_inputs(w)
+    c = G.Cache(w, past_capacity=w.max_context, out_fp32=False)
+    try:
+        k_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
+        v_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
+        for b in range(w.batch):
+            for h, pol in enumerate(w.kv_policy):
+                kk, vv = ks[b][h], vs[b][h]
+                k_new[b, h], v_new[b, h] = kk[-1], vv[-1]
+                kd, vd = c.rows_view(b, h)
+                n_prev = kk.shape[0] - 1
+                first = 0 if pol & 2 else (T - min(T, int(k_done[b]) * S) if pol & 1 else T)
+                if n_prev:
+                    kd[first:first + n_prev] = G.dev_bf16(kk[:-1])
+                    vd[first:first + n_prev] = G.dev_bf16(vv[:-1])
+        sa.seg_kv_set_lengths(c.ctx, [int(x) * S for x in k_done], [T] * w.batch, [int(x) - 1 for x in c_fill], c.stream)
+        o, l = c.decode(q, k_new, v_new)
+        worst = 0.0
+        for b in range(w.batch):
+            n_b = int(k_done[b]) * S + int(c_fill[b])
+            kf = np.zeros((n_b, Hkv, D))
+            vf = np.zeros((n_b, Hkv, D))
+            for h in range(Hkv):
+                kept = ks[b][h].shape[0]
+                kf[n_b - kept:, h] = orc.widen(ks[b][h])
+                vf[n_b - kept:, h] = orc.widen(vs[b][h])
+            o_ref, l_ref = orc.decode_attend(q[b], kf, vf, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
+            eo, el = np.abs(o[b] - o_ref), np.abs(l[b] - l_ref)
+            assert np.all(eo <= 1e-2 + np.abs(o_ref) * 2.0 ** -8) and eo.mean() <= 1e-3, (b, eo.max(), eo.mean())
+            assert el.max() <= 1e-2 and el.mean() <= 1e-3, (b, el.max())
+            worst = max(worst, eo.max())
+        print(f"decode C5: worst |dO| = {worst:.3e}")
+    finally:
+        c.close()
