@@ -33,6 +33,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+# HBM-side bytes of one prefill_mfma_kernel launch on the 128K workload, from the FETCH_SIZE and
+# WRITE_SIZE counter runs summarised in profiles/prefill_mfma_c4_128k_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": 30.39e9 + 4.43e9}
 
 
 def visible_pairs(w) -> int:
@@ -57,6 +60,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c4_128k_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode and streaming legs")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives or sharding); "
@@ -117,6 +122,12 @@ def main() -> int:
             sa.seg_kv_past_evict(ctx, h, 0, stream)
         sa.seg_attn_decode(ctx, q1, k1, v1, o1, l1, stream)
 
+    if args.calibration_copy:  # known traffic: 1 GiB read + 1 GiB written by one elementwise kernel
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -145,7 +156,8 @@ def main() -> int:
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "kernel_ms": round(kern_ms, 4), "traffic": None},
+                     "kernel_ms": round(kern_ms, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "algorithmic_bytes": w.batch * (2 * N * Hq * D * 2 + 2 * N * Hkv * D * 2 + N * Hq * 4)},
         "memory": {"resident_kv_bytes_after_step": resident, "dense_causal_kv_bytes": dense_kv,
                    "ratio": round(dense_kv / resident, 3),
                    "torch_peak_allocated_bytes": int(torch.cuda.max_memory_allocated())},
