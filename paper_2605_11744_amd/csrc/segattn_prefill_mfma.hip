@@ -47,8 +47,10 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 #define GLB_AS __attribute__((address_space(1)))
 
 constexpr int kStepKeys = 32;
-constexpr int kSlots = 5;
-constexpr float kLazyLog2 = 8.f;  // rescale only when a step's maximum exceeds the reference by 2^8
+constexpr int kSlots = 5;                 // LDS ring: steps j-1 .. j+kSlots-2 are resident or in flight
+constexpr int kAhead = kSlots - 4;        // whole steps of loads that may still be in flight at a sync
+constexpr float kLazyLimit = 256.f;  // a lane's 16-weight row sum above this triggers a rescale
+constexpr float kLazyLog2 = 8.f;     // masked steps: rescale when the maximum exceeds the reference by 2^8
 
 template <int D>
 struct StepGeom {
@@ -227,22 +229,30 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     ld_vp += (size_t)kStepKeys * ld_stride;
     ld_left -= kStepKeys;
   };
+  // s_waitcnt vmcnt(k * loads per step): at most k whole steps of this wave's loads stay in flight
+  auto wait_in_flight = [&](int k) {
+    constexpr int L = 2 * LPW;
+    static_assert(kAhead >= 1 && kAhead <= 6 && 6 * L < 64, "vmcnt is a 6-bit counter");
+#define SEGATTN_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
+    if (k <= 0) SEGATTN_VMCNT(0);
+    else if (k == 1) SEGATTN_VMCNT(1 * L);
+    else if (k == 2) SEGATTN_VMCNT(2 * L);
+    else if (k == 3) SEGATTN_VMCNT(3 * L);
+    else if (k == 4) SEGATTN_VMCNT(4 * L);
+    else if (k == 5) SEGATTN_VMCNT(5 * L);
+    else SEGATTN_VMCNT(6 * L);
+  };
   // Executed once per step j by every wave (in the prologue for j = 0, in the middle of step j
   // otherwise): the loads of steps <= j+2 have landed for every wave and every wave is done
   // reading the slot of step j-1, which now receives the loads of step j+4.
   auto sync_step = [&](int j) {
     const int in_flight = ld_js - 1 - (j + 2);  // whole steps that may stay outstanding
-    if (in_flight >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * LPW));
-    else if (in_flight == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPW));
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    wait_in_flight(in_flight);
     __builtin_amdgcn_s_barrier();
     if (ld_js < n) issue();
   };
 
-  issue();
-  if (1 < n) issue();
-  if (2 < n) issue();
-  if (3 < n) issue();
+  for (int i = 0; i < kSlots - 1 && i < n; ++i) issue();
 
   // ---- Q^T operands: Qr[qb][kc] = Q[row(qb, col)][16 kc + 8 hi .. +7], parked in accumulation
   //      registers (they are only ever MFMA operands) so that the vector registers stay free
@@ -284,10 +294,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
   }
 
   f32x16 O[QB][NB];
-  float m_ref[QB], l_run[QB];
+  float m_ref[QB], mc_ref[QB], l_run[QB];  // mc_ref = m_ref * c
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m_ref[qb] = -INFINITY;
+    mc_ref[qb] = -INFINITY;
     l_run[qb] = 0.f;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -354,15 +365,20 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
         S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, Kr[kc]), Qr[qb][kc],
                                                         kc == 0 ? zero : S[qb], 0, 0, 0);
   };
+  // One PV product O^T[qb][nb] += V^T(h2, nb) . P^T[qb][h2].  Inline asm with the accumulator
+  // pinned to accumulation registers: O^T is then never a vector-register value, while the
+  // S^T products above (compiled in VGPR form) deliver their result where the softmax reads it.
+  auto pv_one = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2, int nb, int qb) {
+    const bf16x8 va =
+        __builtin_bit_cast(bf16x8, __builtin_shufflevector(Vr[h2][nb][0], Vr[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7));
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(O[qb][nb]) : "v"(va), "v"(P[qb][h2]));
+  };
   auto pv_mma = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2) {
+    asm volatile("s_nop 4");  // P may have been written by the vector ALU just before
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const bf16x8 va =
-          __builtin_bit_cast(bf16x8, __builtin_shufflevector(Vr[h2][nb][0], Vr[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7));
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-        O[qb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, P[qb][h2], O[qb][nb], 0, 0, 0);
-    }
+      for (int qb = 0; qb < QB; ++qb) pv_one(Vr, P, h2, nb, qb);
   };
   auto compute_s = [&](int so, f32x16(&S)[QB]) {  // unpipelined S^T of the step in slot `so`
     i32x4 Kr[NC];
@@ -377,24 +393,19 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     pv_mma(Vr, P, 0);
     pv_mma(Vr, P, 1);
   };
-  // S^T accumulators -> vector registers, at this point of the program (the accumulation
-  // registers are then free for the next step's product)
+  // S^T accumulators (produced in vector registers: VGPR-form products) as plain floats
   auto s_fetch = [&](const f32x16(&S)[QB], float(&Sv)[QB][16]) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = S[qb][r];
-        asm volatile("" : "+v"(x));
-        Sv[qb][r] = x;
-      }
+      for (int r = 0; r < 16; ++r) Sv[qb][r] = S[qb][r];
   };
-  // P = exp2(S c - m_ref c) as bf16, its row sums (of the rounded values) and the row maxima of S
-  auto softmax = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB], float(&rmax)[QB]) {
+  // P = exp2(S c - m_ref c) as bf16 and its row sums (of the rounded values)
+  auto softmax = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB]) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const float mc = m_ref[qb] * c;
+      const float mc = mc_ref[qb];
       float ps = 0.f;
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
@@ -410,11 +421,13 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
         }
       }
       psum[qb] = ps;
-      float mx = fmaxf(S[qb][0], S[qb][1]);
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, S[qb][r]), S[qb][r + 1]);
-      rmax[qb] = mx;
     }
+  };
+  auto row_max = [&](const float(&S)[QB][16], int qb) {
+    float mx = fmaxf(S[qb][0], S[qb][1]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, S[qb][r]), S[qb][r + 1]);
+    return half_max(mx);
   };
   auto rescale = [&](int qb, float alpha) {  // rare: O^T and l of query block qb times alpha
     l_run[qb] *= alpha;
@@ -425,29 +438,29 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       for (int r = 0; r < 16; ++r) O[qb][nb][r] = acc_scale(O[qb][nb][r], alpha);
     acc_drain();
   };
-  // Validate the P just formed against the step's own maximum; rescale and redo if needed.
-  auto settle = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB], float(&rmax)[QB]) {
-    bool need[QB];
-    float mx[QB];
+  // Validate the P just formed (before anything uses it).  A lane's row sum can only exceed
+  // 2^8 if one of its weights does, i.e. if a score of this step exceeds the reference maximum
+  // by more than 2^8/... ; then the reference is raised to the step's true maximum, the
+  // accumulators are rescaled and this P is formed again.  exp2 can therefore not overflow
+  // into the accumulators, and the common path pays two compares.
+  auto settle = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB]) {
     bool any = false;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      mx[qb] = half_max(rmax[qb]);
-      need[qb] = mx[qb] > m_ref[qb] + tau;
-      any |= need[qb];
-    }
+    for (int qb = 0; qb < QB; ++qb) any |= !(psum[qb] <= kLazyLimit);
     if (__builtin_amdgcn_ballot_w64(any) != 0) {
       // The first P stays "used" on this path too, so that its computation is not sunk below
       // the branch (it has to overlap with the matrix products above).
       asm volatile("" ::"v"(P[0][0]), "v"(P[0][1]), "v"(P[1][0]), "v"(P[1][1]), "v"(psum[0]), "v"(psum[1]));
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        const float m_new = need[qb] ? mx[qb] : m_ref[qb];
-        const float alpha = need[qb] ? __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c) : 1.f;
+        const float mx = row_max(S, qb);
+        const float m_new = fmaxf(m_ref[qb], mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c);
         m_ref[qb] = m_new;
+        mc_ref[qb] = m_new * c;
         rescale(qb, alpha);
       }
-      softmax(S, P, psum, rmax);
+      softmax(S, P, psum);
     }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb];
@@ -465,10 +478,10 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
   // One pipelined step j >= 1.  On entry Kr holds the K operands of step j+1 (if do_s), Sc is
   // S^T of step j and Pp is P of step j-1.  The step forms S^T(j+1) -> Sn, adds PV of step j-1,
   // turns Sc into Pc, runs the step's sync in the middle and, if fetch_k, leaves the K operands
-  // of step j+2 in Kr.
+  // of step j+2 in Kr.  Generic version (any sync branch); the hot loop uses hot_step.
   auto fast_step = [&](int j, auto do_s, auto fetch_k, i32x4(&Kr)[NC], const float(&Sc)[QB][16],
                        float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) {
-    float psum[QB], rmax[QB];
+    float psum[QB];
     s16x4 Vr[2][NB][2];
     f32x16 Sacc[QB];
     v_load(so_m1, Vr);
@@ -478,39 +491,128 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     sync_step(j);
     if constexpr (decltype(fetch_k)::value) k_load(so_p2, Kr);
     pv_mma(Vr, Pp, 1);
-    softmax(Sc, Pc, psum, rmax);
+    softmax(Sc, Pc, psum);
     if constexpr (decltype(do_s)::value) s_fetch(Sacc, Sn);
     if constexpr (decltype(fetch_k)::value) k_wait(Kr);
-    settle(Sc, Pc, psum, rmax);
+    settle(Sc, Pc, psum);
   };
-  // The same step for the hot loop: one basic block up to the final check.  The sync is
-  // branch-free (exactly one step of loads stays in flight, the loads issued are a full step of
-  // the current span) and the instruction mix is laid out explicitly: matrix products
-  // interleaved with the softmax arithmetic that runs in their shadow.
+  // The same step for the hot loop, laid out by hand as 2*NC + 4*NB slots of one matrix product
+  // each; whatever else the step has to do is spread over the slots so that it issues in the
+  // shadow of the products (about six vector instructions fit under a 32x32x16 MFMA).  The
+  // sync is branch-free: exactly one step of loads stays in flight and the loads issued are a
+  // full step of the current span.
+  //   slots 0 .. 2NC-1        S^T(j+1) products; all V^T reads; exp2 of pair i in slot 2i
+  //   slots 2NC .. 2NC+2NB-1  PV(j-1), first 16 keys
+  //   (sync, then the K reads of step j+2, two per slot)
+  //   slots .. end            PV(j-1), last 16 keys
+  //   odd slots               convert pair i to bf16 and add it to the row sum
   auto hot_step = [&](i32x4(&Kr)[NC], const float(&Sc)[QB][16], float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2],
                       bf16x8(&Pc)[QB][2]) {
-    float psum[QB], rmax[QB];
+    constexpr int NS = 2 * NC, NP = 2 * NB;  // slots of the S^T product / of half a PV product
+    constexpr int NSLOT = NS + 2 * NP;
+    constexpr int EPS = 32 / NSLOT;          // softmax elements per slot (32 per lane and step)
+    static_assert(EPS * NSLOT == 32 && (EPS == 1 || EPS == 2), "slot layout");
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float psum[QB] = {0.f, 0.f};
     s16x4 Vr[2][NB][2];
     f32x16 Sacc[QB];
-    v_load(so_m1, Vr);
-    s_mma(Kr, Sacc);
-    softmax(Sc, Pc, psum, rmax);
-    v_wait(Vr);
-    pv_mma(Vr, Pp, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPW));
-    __builtin_amdgcn_s_barrier();
-    issue_hot();
-    k_load(so_p2, Kr);
-    pv_mma(Vr, Pp, 1);
+    int Pw[QB][8];  // P of the current step as 32-bit words: word 4 h2 + t of Pw[qb] = elements 8 h2 + 2t, +1
+    float ev[32];   // exp2 results on their way to the bf16 pairs (a few live at a time)
+    unsigned va[NB], ka[NKA];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) va[nb] = (unsigned)(size_t)lds + (unsigned)(voff[nb] + so_m1);
+#pragma unroll
+    for (int i = 0; i < NKA; ++i) ka[i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + so_p2);
+    // vector-ALU work of one slot: exp2 of EPS elements, and half of the conversion / row-sum
+    // work of an earlier pair, so that every slot carries the same four issue slots
+    auto valu_chunk = [&](int slot) {
+#pragma unroll
+      for (int u = 0; u < EPS; ++u) {
+        const int e = EPS * slot + u, qb = e / 16, r = e % 16;
+        ev[e] = __builtin_amdgcn_exp2f(fmaf(Sc[qb][r], c, -mc_ref[qb]));
+      }
+      // pair index handled now: its two exp2 were issued at least one slot ago
+      const int first_pair = (EPS == 1) ? (slot / 2 - 1) : (slot - 1);
+      if (first_pair >= 0) {
+        const int i = first_pair, qb = i / 8, w8 = i % 8;
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        if (EPS == 2 || slot % 2 == 0) {
+          const f32x2 ee = {ev[2 * i], ev[2 * i + 1]};
+          Pw[qb][w8] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
+        }
+        if (EPS == 2 || slot % 2 == 1)
+          psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][w8]), ones, psum[qb], false);
+      }
+    };
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int slot = 0; slot < NSLOT; ++slot) {
+      // ---- the slot's matrix product
+      if (slot < NS) {
+        const int kc = slot / 2, qb = slot % 2;
+        Sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, Kr[kc]), Qr[qb][kc],
+                                                           kc == 0 ? zero : Sacc[qb], 0, 0, 0);
+      } else {
+        const int t = slot - NS, h2 = t / NP, nb = (t % NP) / 2, qb = t % 2;
+        pv_one(Vr, Pp, h2, nb, qb);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- V^T reads (h2-major), spread over the S^T slots so that the four waves of the
+      //      workgroup, which run in lockstep, do not all hit the LDS in one burst
+      {
+        constexpr int VPS = (4 * NB + NS - 1) / NS;  // transposing reads per slot
+#pragma unroll
+        for (int u = 0; u < VPS; ++u) {
+          const int idx = VPS * slot + u;  // 0 .. 4 NB - 1: (h2, nb, half)
+          if (idx < 4 * NB) {
+            const int h2 = idx / (2 * NB), nb = (idx / 2) % NB, half = idx % 2;
+            if (half == 0)
+              asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                           : "=v"(Vr[h2][nb][0]) : "v"(va[nb]), "n"(16 * h2 * G::kRowBytes));
+            else
+              asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                           : "=v"(Vr[h2][nb][1]) : "v"(va[nb]), "n"((16 * h2 + 8) * G::kRowBytes));
+          }
+        }
+      }
+      // ---- after the S^T slots: V^T has arrived; sync; then the K reads of step j+2, one per slot
+      if (slot == NS - 1) {
+        v_wait(Vr);
+        SEGATTN_VMCNT(kAhead * 2 * LPW);
+        __builtin_amdgcn_s_barrier();
+        issue_hot();
+      }
+      if (slot >= NS && slot < NS + NC) {
+        const int kc = slot - NS;
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
+      }
+      valu_chunk(slot);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    {  // the last pair(s)
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      const int qb = QB - 1;
+      if (EPS == 1) {
+        const f32x2 ee = {ev[30], ev[31]};
+        Pw[qb][7] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
+        psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][7]), ones, psum[qb], false);
+      } else {
+        const f32x2 ee = {ev[30], ev[31]};
+        Pw[qb][7] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
+        psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][7]), ones, psum[qb], false);
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const i32x4 w4 = {Pw[qb][4 * h2], Pw[qb][4 * h2 + 1], Pw[qb][4 * h2 + 2], Pw[qb][4 * h2 + 3]};
+        Pc[qb][h2] = __builtin_bit_cast(bf16x8, w4);
+      }
     s_fetch(Sacc, Sn);
     k_wait(Kr);
-    // 2*NC + 4*NB matrix products; the softmax is about 3.5 vector instructions per element
-#pragma unroll
-    for (int i = 0; i < 2 * NC + 4 * NB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // five VALU
-    }
-    settle(Sc, Pc, psum, rmax);
+    settle(Sc, Pc, psum);
   };
   // An unpipelined step (slot so, span-local first key j0) with element masks: keys with
   // in-span index >= lim[qb] are invisible.
@@ -518,7 +620,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     f32x16 Sacc[QB];
     float S[QB][16];
     bf16x8 P[QB][2];
-    float psum[QB], rmax[QB];
+    float psum[QB];
     compute_s(so, Sacc);
     s_fetch(Sacc, S);
 #pragma unroll
@@ -540,10 +642,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
         const float m_new = need ? mx : m_ref[qb];
         const float alpha = need ? __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c) : 1.f;
         m_ref[qb] = m_new;
+        mc_ref[qb] = m_new * c;
         rescale(qb, alpha);
       }
     }
-    softmax(S, P, psum, rmax);
+    softmax(S, P, psum);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb];
     pv(so, P);
@@ -557,7 +660,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
   int j = 0;
   if (f > 0) {
     {  // step 0 without overlap: exact maximum as the first reference
-      float psum[QB], rmax[QB];
+      float psum[QB];
       f32x16 Sacc[QB];
       compute_s(so_0, Sacc);
       s_fetch(Sacc, Sa);
@@ -567,8 +670,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, Sa[qb][r]);
         m_ref[qb] = half_max(mx);
+        mc_ref[qb] = m_ref[qb] * c;
       }
-      softmax(Sa, Pb, psum, rmax);
+      softmax(Sa, Pb, psum);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) l_run[qb] = psum[qb];
       if (f > 1) {
@@ -586,6 +690,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     constexpr std::false_type no{};
     for (;;) {
       // hot pairs: the next two loads are plain full steps of the current span
+      // Nothing the compiler tracks may be pending on entry (a spill reload in the generic path
+      // would otherwise put a full vmcnt wait, which also drains our prefetch, into the loop).
+      __builtin_amdgcn_s_waitcnt(0x0F70);
       while (j + 3 < f && ld_js + 2 < ld_full_end) {
         hot_step(Kr, Sa, Sb, Pb, Pa);
         advance();
