@@ -336,7 +336,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   if (!ctx || !q || !k_new || !v_new || !out || !lse) return SEGATTN_EINVAL;
   if (!ctx->ready) return SEGATTN_ESTATE;
   const Problem &p = ctx->p;
-  long long max_window = 0;
+  long long max_window = 1, max_window_past = 1;
   bool any_full = false;
   for (int b = 0; b < p.B; ++b) {
     for (int h = 0; h < p.Hkv; ++h) {
@@ -348,7 +348,8 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
       } else {
         win = ((p.policy[h] & SEGATTN_TAIL) ? ctx->tail[b] : 0) + ctx->fill[b] + 1;
       }
-      if (win > max_window) max_window = win;
+      long long &mw = (p.policy[h] & SEGATTN_PAST) ? max_window_past : max_window;
+      if (win > mw) mw = win;
     }
     any_full |= ctx->fill[b] + 1 == p.S;
   }
@@ -370,7 +371,8 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   da.lse = lse;
   da.cache = ctx->cache;
   da.geom = ctx->g;
-  da.max_splits = (int)((max_window + kDecodeChunk - 1) / kDecodeChunk);
+  da.splits_past = (int)((max_window_past + kDecodeChunk - 1) / kDecodeChunk);
+  da.splits_other = (int)((max_window + kDecodeChunk - 1) / kDecodeChunk);
   if (launch_decode(p, da, p.B, st) != hipSuccess) return SEGATTN_EHIP;
   if (any_full && launch_cache_close(p, ctx->cache, ctx->g, 0, st) != hipSuccess) return SEGATTN_EHIP;
   for (int b = 0; b < p.B; ++b) {

@@ -3,13 +3,13 @@
 // conditioning on x_<t, C_{i-1}, R_{i-1}).  The work is HBM-bound (every visible K and V row
 // is read once per KV head and serves the g query heads of the group), so it is a split-K
 // reduction:
-//   decode_split_kernel    grid (split, b*Hkv): a workgroup streams one chunk of the window
+//   decode_split_kernel    one workgroup per (b, KV head, chunk of the window): it streams the chunk
 //                          with 16-byte coalesced loads (D/8 lanes per key row), forms the g
 //                          dot products per row with a DPP reduction inside each lane group,
 //                          keeps an online-softmax state per lane group, merges the groups
 //                          with wave shuffles and the four waves through LDS, and writes one
 //                          partial (m, l, acc[D]) per query head.
-//   decode_combine_kernel  one wave per (b, query head): merges the partials of all splits.
+//   decode_combine_kernel  one workgroup per (b, query head): merges the partials of all splits.
 #include "segattn_internal.h"
 
 namespace segattn {
@@ -47,18 +47,51 @@ __device__ inline void unpack8(const uint4 u, float (&f)[8]) {
   f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
 }
 
-template <int D, int GH>
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline float dot2_bf16(unsigned a, unsigned b, float c) {  // a.lo*b.lo + a.hi*b.hi + c
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+
+// blockIdx.x -> (split, b, kv): PAST heads first (they have up to splits_past splits), then the
+// others (at most splits_other), so that few workgroups find nothing to do.
+__device__ inline bool decode_block(const Problem &p, const DecodeArgs &a, int bid, int &split, int &b, int &kv) {
+  const int past_blocks = p.B * p.n_past * a.splits_past;
+  int hidx;
+  if (bid < past_blocks) {
+    split = bid % a.splits_past;
+    const int r = bid / a.splits_past;
+    hidx = r % p.n_past;
+    b = r / p.n_past;
+  } else {
+    const int y = bid - past_blocks;
+    const int n_other = p.Hkv - p.n_past;
+    split = y % a.splits_other;
+    const int r = y / a.splits_other;
+    hidx = p.n_past + r % n_other;
+    b = r / n_other;
+  }
+  kv = p.order[hidx];
+  return true;
+}
+
+// EXACT: fp32 weights and fp32 FMAs throughout (validation mode).  Otherwise the dot products
+// use v_dot2_f32_bf16 on the bf16 pairs as they come from memory, and the weights are rounded to
+// bf16 for the PV product (as in the prefill kernel; the row sums use the same rounded values).
+template <int D, int GH, bool EXACT>
 __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, const DecodeArgs a,
                                                           const int head_pass) {
   constexpr int LPR = D / 8;        // lanes per key row
   constexpr int GPW = 64 / LPR;     // key rows per wave-wide load
   constexpr int U = 4;              // rows in flight per lane group
-  const int b = blockIdx.y / p.Hkv, kv = blockIdx.y % p.Hkv;
+  int split, b, kv;
+  decode_block(p, a, blockIdx.x, split, b, kv);
   const int *meta = meta_ro(a.cache, a.geom, p, b, kv);
   int lo, seg_row0;
   window_of(p, kv, meta, lo, seg_row0);
   const int hi = seg_row0 + meta[META_FILL];
-  const int c0 = lo + blockIdx.x * a.geom.decode_chunk;
+  const int c0 = lo + split * a.geom.decode_chunk;
   if (c0 >= hi) return;
   const int c1 = min(hi, c0 + a.geom.decode_chunk);
 
@@ -67,10 +100,13 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
   const int head0 = kv * p.g + head_pass * GH;
   const float c = p.scale_log2e;
 
-  float qf[GH][8];
+  uint4 qp[GH];   // this lane's 8 query elements per head, as bf16 pairs
+  float qf[EXACT ? GH : 1][8];
 #pragma unroll
-  for (int h = 0; h < GH; ++h)
-    unpack8(*(const uint4 *)(a.q + ((long long)b * p.Hq + head0 + h) * D + li * 8), qf[h]);
+  for (int h = 0; h < GH; ++h) {
+    qp[h] = *(const uint4 *)(a.q + ((long long)b * p.Hq + head0 + h) * D + li * 8);
+    if (EXACT) unpack8(qp[h], qf[h]);
+  }
 
   float m_run[GH], l_run[GH], acc[GH][8];
 #pragma unroll
@@ -98,18 +134,26 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float kf[8];
-      unpack8(kr[u], kf);
+      if (EXACT) unpack8(kr[u], kf);
 #pragma unroll
       for (int h = 0; h < GH; ++h) {
         float d = 0.f;
+        if (EXACT) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) d = fmaf(qf[h][e], kf[e], d);
+          for (int e = 0; e < 8; ++e) d = fmaf(qf[h][e], kf[e], d);
+        } else {
+          d = dot2_bf16(qp[h].x, kr[u].x, d);
+          d = dot2_bf16(qp[h].y, kr[u].y, d);
+          d = dot2_bf16(qp[h].z, kr[u].z, d);
+          d = dot2_bf16(qp[h].w, kr[u].w, d);
+        }
         d = group_sum<LPR>(d);
         s[u][h] = row[u] < c1 ? d : -INFINITY;
       }
     }
     if (row[0] >= c1) continue;  // whole lane group past the end (rows ascend with u)
     float pw[U][GH];
+    unsigned pp[U / 2][GH];  // weights of rows (2i, 2i+1) as a bf16 pair
 #pragma unroll
     for (int h = 0; h < GH; ++h) {
       float mx = m_run[h];
@@ -119,23 +163,50 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
       const float mc = mx * c;
       float ps = 0.f;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        pw[u][h] = __builtin_amdgcn_exp2f(fmaf(s[u][h], c, -mc));
-        ps += pw[u][h];
+      for (int u = 0; u < U; ++u) pw[u][h] = __builtin_amdgcn_exp2f(fmaf(s[u][h], c, -mc));
+      if (EXACT) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) ps += pw[u][h];
+      } else {
+#pragma unroll
+        for (int i = 0; i < U / 2; ++i) {
+          const f32x2 two = {pw[2 * i][h], pw[2 * i + 1][h]};
+          pp[i][h] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
+          ps = dot2_bf16(pp[i][h], 0x3f803f80u, ps);
+        }
       }
       l_run[h] = l_run[h] * alpha + ps;
       m_run[h] = mx;
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
     }
+    if (EXACT) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float vf[8];
-      unpack8(vr[u], vf);
+      for (int u = 0; u < U; ++u) {
+        float vf[8];
+        unpack8(vr[u], vf);
 #pragma unroll
-      for (int h = 0; h < GH; ++h)
+        for (int h = 0; h < GH; ++h)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pw[u][h], vf[e], acc[h][e]);
+          for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pw[u][h], vf[e], acc[h][e]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < U / 2; ++i) {
+        // element e of rows 2i and 2i+1 side by side: low halves then high halves of each word
+        const unsigned w0[4] = {vr[2 * i].x, vr[2 * i].y, vr[2 * i].z, vr[2 * i].w};
+        const unsigned w1[4] = {vr[2 * i + 1].x, vr[2 * i + 1].y, vr[2 * i + 1].z, vr[2 * i + 1].w};
+        unsigned vpair[8];
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+          vpair[2 * wd] = __builtin_amdgcn_perm(w1[wd], w0[wd], 0x05040100u);
+          vpair[2 * wd + 1] = __builtin_amdgcn_perm(w1[wd], w0[wd], 0x07060302u);
+        }
+#pragma unroll
+        for (int h = 0; h < GH; ++h)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[h][e] = dot2_bf16(vpair[e], pp[i][h], acc[h][e]);
+      }
     }
   }
 
@@ -184,7 +255,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
       l += sm_l[w][h] * wgt;
       o += sm_acc[w][h][d] * wgt;
     }
-    float *slot = ws + (ws_slot_base(p, a.geom, b, head0 + h) + blockIdx.x) * (2 + D);
+    float *slot = ws + (ws_slot_base(p, a.geom, b, head0 + h) + split) * (2 + D);
     if (d == 0) {
       slot[0] = mx;
       slot[1] = l;
@@ -193,8 +264,11 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
   }
 }
 
+// One workgroup per (b, query head).  All threads find the global maximum over the splits; then
+// wave w accumulates the splits congruent to w mod 4 (lanes over the D outputs) and the four
+// partial sums meet in LDS.
 template <int D>
-__global__ __launch_bounds__(64) void decode_combine_kernel(const Problem p, const DecodeArgs a) {
+__global__ __launch_bounds__(256) void decode_combine_kernel(const Problem p, const DecodeArgs a) {
   const int b = blockIdx.x / p.Hq, head = blockIdx.x % p.Hq;
   const int kv = head / p.g;
   const int *meta = meta_ro(a.cache, a.geom, p, b, kv);
@@ -203,57 +277,64 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const Problem p, con
   const int hi = seg_row0 + meta[META_FILL];
   const int ns = (hi - lo + a.geom.decode_chunk - 1) / a.geom.decode_chunk;
   const float *ws = (const float *)(a.cache + a.geom.ws_off) + ws_slot_base(p, a.geom, b, head) * (2 + D);
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float c = p.scale_log2e;
-  // global max and denominator: lanes stride over the splits, then a wave reduction
+  constexpr int DPL = D / 64;
+  __shared__ float sm_max[4], sm_l[4], sm_o[4][D];
+
   float mx = -INFINITY;
-  for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, ws[(long long)s * (2 + D)]);
+  for (int s = tid; s < ns; s += 256) mx = fmaxf(mx, ws[(long long)s * (2 + D)]);
 #pragma unroll
   for (int sh = 1; sh < 64; sh <<= 1) mx = fmaxf(mx, __shfl_xor(mx, sh));
-  float l = 0.f;
-  for (int s = lane; s < ns; s += 64) {
-    const float *slot = ws + (long long)s * (2 + D);
-    l += slot[1] * __builtin_amdgcn_exp2f((slot[0] - mx) * c);
-  }
-#pragma unroll
-  for (int sh = 1; sh < 64; sh <<= 1) l += __shfl_xor(l, sh);
-  constexpr int DPL = D / 64;
-  float o[DPL];
+  if (lane == 0) sm_max[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
+
+  float l = 0.f, o[DPL];
 #pragma unroll
   for (int e = 0; e < DPL; ++e) o[e] = 0.f;
-  for (int s = 0; s < ns; ++s) {
+#pragma unroll 4
+  for (int s = wave; s < ns; s += 4) {
     const float *slot = ws + (long long)s * (2 + D);
     const float wgt = __builtin_amdgcn_exp2f((slot[0] - mx) * c);
+    l = fmaf(slot[1], wgt, l);
 #pragma unroll
     for (int e = 0; e < DPL; ++e) o[e] = fmaf(slot[2 + lane * DPL + e], wgt, o[e]);
   }
-  const float inv = 1.f / l;
-  const long long obase = ((long long)b * p.Hq + head) * D + lane * DPL;
+  if (lane == 0) sm_l[wave] = l;
 #pragma unroll
-  for (int e = 0; e < DPL; ++e) {
-    if (p.out_fp32) ((float *)a.out)[obase + e] = o[e] * inv;
-    else ((__bf16 *)a.out)[obase + e] = (__bf16)(o[e] * inv);
-  }
-  if (lane == 0) a.lse[(long long)b * p.Hq + head] = mx * p.scale + __logf(l);
+  for (int e = 0; e < DPL; ++e) sm_o[wave][lane * DPL + e] = o[e];
+  __syncthreads();
+  if (tid >= D) return;
+  l = (sm_l[0] + sm_l[1]) + (sm_l[2] + sm_l[3]);
+  const float od = (sm_o[0][tid] + sm_o[1][tid]) + (sm_o[2][tid] + sm_o[3][tid]);
+  const float r = od / l;
+  const long long oidx = ((long long)b * p.Hq + head) * D + tid;
+  if (p.out_fp32) ((float *)a.out)[oidx] = r;
+  else ((__bf16 *)a.out)[oidx] = (__bf16)r;
+  if (tid == 0) a.lse[(long long)b * p.Hq + head] = mx * p.scale + __logf(l);
 }
 
-template <int D>
+template <int D, bool EXACT>
 static hipError_t launch_split(const Problem &p, const DecodeArgs &a, hipStream_t st) {
-  const dim3 grid(a.max_splits, p.B * p.Hkv);
+  const long long blocks = (long long)p.B * ((long long)p.n_past * a.splits_past +
+                                             (long long)(p.Hkv - p.n_past) * a.splits_other);
+  const dim3 grid((unsigned)blocks);
   int gh = (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1;
   for (int pass = 0; pass < p.g / gh; ++pass) {
-    if (gh == 4) hipLaunchKernelGGL((decode_split_kernel<D, 4>), grid, dim3(256), 0, st, p, a, pass);
-    else if (gh == 2) hipLaunchKernelGGL((decode_split_kernel<D, 2>), grid, dim3(256), 0, st, p, a, pass);
-    else hipLaunchKernelGGL((decode_split_kernel<D, 1>), grid, dim3(256), 0, st, p, a, pass);
+    if (gh == 4) hipLaunchKernelGGL((decode_split_kernel<D, 4, EXACT>), grid, dim3(256), 0, st, p, a, pass);
+    else if (gh == 2) hipLaunchKernelGGL((decode_split_kernel<D, 2, EXACT>), grid, dim3(256), 0, st, p, a, pass);
+    else hipLaunchKernelGGL((decode_split_kernel<D, 1, EXACT>), grid, dim3(256), 0, st, p, a, pass);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(p.B * p.Hq), dim3(64), 0, st, p, a);
+  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(p.B * p.Hq), dim3(256), 0, st, p, a);
   return hipGetLastError();
 }
 
 hipError_t launch_decode(const Problem &p, const DecodeArgs &a, int, hipStream_t st) {
-  return p.D == 128 ? launch_split<128>(p, a, st) : launch_split<64>(p, a, st);
+  if (p.fp32_math) return p.D == 128 ? launch_split<128, true>(p, a, st) : launch_split<64, true>(p, a, st);
+  return p.D == 128 ? launch_split<128, false>(p, a, st) : launch_split<64, false>(p, a, st);
 }
 
 }  // namespace segattn

@@ -58,7 +58,8 @@ struct DecodeArgs {
   float *lse;
   unsigned char *cache;
   CacheGeom geom;
-  int max_splits;        // grid.x of the split kernel
+  int splits_past;       // chunks of the longest window among PAST heads (>= 1)
+  int splits_other;      // same among the other heads (>= 1)
 };
 
 struct CopyArgs {
