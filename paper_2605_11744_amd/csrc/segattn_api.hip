@@ -11,7 +11,10 @@ using namespace segattn;
 
 namespace {
 
-constexpr int kDecodeChunk = 512;
+#ifndef SEGATTN_DECODE_CHUNK
+#define SEGATTN_DECODE_CHUNK 512
+#endif
+constexpr int kDecodeChunk = SEGATTN_DECODE_CHUNK;  // key rows per split-K workgroup
 constexpr unsigned long long kAlign = 256;
 
 unsigned long long align_up(unsigned long long x) { return (x + kAlign - 1) / kAlign * kAlign; }

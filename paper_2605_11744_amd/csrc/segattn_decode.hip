@@ -12,6 +12,10 @@
 //   decode_combine_kernel  one workgroup per (b, query head): merges the partials of all splits.
 #include "segattn_internal.h"
 
+#ifndef SEGATTN_DECODE_U
+#define SEGATTN_DECODE_U 8
+#endif
+
 namespace segattn {
 
 __device__ inline const int *meta_ro(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b,
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
                                                           const int head_pass) {
   constexpr int LPR = D / 8;        // lanes per key row
   constexpr int GPW = 64 / LPR;     // key rows per wave-wide load
-  constexpr int U = 4;              // rows in flight per lane group
+  constexpr int U = SEGATTN_DECODE_U;  // rows in flight per lane group
   int split, b, kv;
   decode_block(p, a, blockIdx.x, split, b, kv);
   const int *meta = meta_ro(a.cache, a.geom, p, b, kv);

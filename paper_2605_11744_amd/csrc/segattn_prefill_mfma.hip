@@ -750,16 +750,25 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
   }
   if (pending) pv(so_m1, Pb);
 
-  // ---- epilogue: normalise, write O (row t, head, d) and LSE
+  // ---- epilogue: normalise, write LSE, and write O through LDS so that every store
+  // instruction covers whole 16-byte pieces of contiguous output rows.  A lane holds four
+  // consecutive d of one query row per accumulator quad; it drops them into the wave's own
+  // [32 rows][D] staging block (rows padded by 8 bytes against bank conflicts), and the wave
+  // reads the block back row-major.
   acc_drain();
+  __syncthreads();  // every wave is past its last read of the K/V ring
+  const bool wide = p.out_fp32 != 0;
+  const int es = wide ? 4 : 2;                 // bytes per output element
+  const int row_bytes = D * es + 8;
+  unsigned char *stage = smem + wave * (32 * (D * 4 + 8));
+  const int lanes_per_row = D * es / 16;       // 16-byte pieces per output row
+  const int rows_per_pass = 64 / lanes_per_row;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int t = tw0 + 32 * qb + col;
     const float l = half_sum(l_run[qb]);
-    if (t > last_row) continue;
     const float inv = 1.f / l;
-    if (hi == 0) w.lse[(long long)head * w.lse_head_stride + t] = m_ref[qb] * p.scale + __logf(l);
-    const long long orow = ((long long)t * p.Hq + head) * D;
+    if (hi == 0 && t <= last_row) w.lse[(long long)head * w.lse_head_stride + t] = m_ref[qb] * p.scale + __logf(l);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -767,13 +776,25 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
         const int d = 32 * nb + 8 * rg + 4 * hi;
         const f32x4 o = {acc_get(O[qb][nb][4 * rg + 0]) * inv, acc_get(O[qb][nb][4 * rg + 1]) * inv,
                          acc_get(O[qb][nb][4 * rg + 2]) * inv, acc_get(O[qb][nb][4 * rg + 3]) * inv};
-        if (p.out_fp32) {
-          *(f32x4 *)((float *)w.out + orow + d) = o;
+        unsigned char *dst = stage + col * row_bytes + d * es;
+        if (wide) {
+          *(uint2 *)dst = uint2{__float_as_uint(o[0]), __float_as_uint(o[1])};
+          *(uint2 *)(dst + 8) = uint2{__float_as_uint(o[2]), __float_as_uint(o[3])};
         } else {
-          const bf16x4 hq = __builtin_convertvector(o, bf16x4);
-          *(uint2 *)((unsigned short *)w.out + orow + d) = __builtin_bit_cast(uint2, hq);
+          *(uint2 *)dst = __builtin_bit_cast(uint2, __builtin_convertvector(o, bf16x4));
         }
       }
+    __syncthreads();
+    const int piece = lane % lanes_per_row;
+    for (int r = lane / lanes_per_row; r < 32; r += rows_per_pass) {
+      const int tr = tw0 + 32 * qb + r;
+      if (tr > last_row) break;
+      const unsigned char *src = stage + r * row_bytes + piece * 16;
+      const uint2 a0 = *(const uint2 *)src, a1 = *(const uint2 *)(src + 8);
+      unsigned char *gdst = (unsigned char *)w.out + (((long long)tr * p.Hq + head) * D) * es + piece * 16;
+      *(uint4 *)gdst = uint4{a0.x, a0.y, a1.x, a1.y};
+    }
+    __syncthreads();
   }
 }
 
