@@ -20,8 +20,11 @@ Readings taken where the paper is silent (each is repeated in the design notes):
 * The policy is a bit mask per KV head, TAIL = 1, PAST = 2; a head with both bits sees
   the *union of positions* (a key is never counted twice).  The query heads of a GQA
   group inherit the policy of their KV head, which is query head // group size.
-* "Past" here is every position before the current segment (minus `evicted` oldest
-  ones), not a top-k subset: the retrieval operator of Appendix D is outside this path.
+* "Past" is every position before the current segment (minus `evicted` oldest ones) by
+  default.  With `retrieved` given it is the paper's own form (Eq. 13, second case;
+  Appendix D "Output"): the R pool rows an index list names, as a set of distinct
+  positions before the segment.  How the list is chosen (top-k scoring, anchors, window
+  expansion of Appendix D) is not part of this file.
 * The tail is the last min(T, length of the previous segment) rows of the previous
   segment only; T <= S is required.  Segments start at multiples of S; only the last
   one may be short.
@@ -52,9 +55,10 @@ def widen(x: np.ndarray) -> np.ndarray:
 
 
 def visible_mask(p: int, n: int, seg_len: int, tail_len: int, policy: int,
-                 evicted: int = 0) -> np.ndarray:
+                 evicted: int = 0, retrieved=None) -> np.ndarray:
     """Boolean [n]: which key positions query position p may attend to (Eq. 12 mask,
-    Eq. 13 context).  Segment i = p // S starts at s = i*S."""
+    Eq. 13 context).  Segment i = p // S starts at s = i*S.  `retrieved`, if not None, is
+    the retrieved prefix of p's segment for a PAST head: distinct positions < s."""
     if not (0 <= tail_len <= seg_len):
         raise ValueError("need 0 <= tail_len <= seg_len")
     if not (0 <= p < n):
@@ -64,8 +68,16 @@ def visible_mask(p: int, n: int, seg_len: int, tail_len: int, policy: int,
     vis = (j >= s) & (j <= p)                      # own segment, causal (all cases of Eq. 13)
     if policy & POLICY_TAIL:                       # carried tail: last T rows of segment i-1
         vis |= (j >= max(0, s - tail_len)) & (j < s)
-    if policy & POLICY_PAST:                       # forward-only past: every earlier row kept
-        vis |= (j >= evicted) & (j < s)
+    if policy & POLICY_PAST:
+        if retrieved is None:                      # forward-only past: every earlier row kept
+            vis |= (j >= evicted) & (j < s)
+        else:                                      # forward-only past: the R retrieved rows
+            idx = np.asarray(retrieved, dtype=np.int64).reshape(-1)
+            if idx.size and (idx.min() < evicted or idx.max() >= s):
+                raise ValueError("retrieved position outside the pool of this segment")
+            if np.unique(idx).size != idx.size:
+                raise ValueError("retrieved positions must be distinct")
+            vis[idx] = True
     return vis
 
 
@@ -80,12 +92,15 @@ def _rows_arg(rows, n):
 
 def attend(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
            scale: Optional[float] = None, rows=None, evicted: Optional[Sequence[int]] = None,
-           return_probs: bool = False, max_block_bytes: int = 1 << 28):
+           return_probs: bool = False, max_block_bytes: int = 1 << 28, retrieved=None):
     """Segment-level attention for the query positions `rows` (default: all).
 
     q [B,N,Hq,D]; k, v [B,N,Hkv,D]; returns O [B,R,Hq,D] and LSE [B,Hq,R] in float64
     (and the probabilities [B,Hq,R,N] if return_probs).  evicted[h] = number of oldest
-    rows KV head h no longer holds (only PAST visibility is affected)."""
+    rows KV head h no longer holds (only PAST visibility is affected).  retrieved, if
+    given, maps (b, kv head, segment index) to the positions of that segment's retrieved
+    prefix; PAST heads then see those rows instead of the whole history (a missing key
+    means an empty prefix)."""
     q, k, v = widen(q), widen(k), widen(v)
     B, N, Hq, D = q.shape
     Hkv = k.shape[2]
@@ -106,9 +121,18 @@ def attend(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
         pol = int(kv_policy[kvh])
         for r0 in range(0, R, step):
             rr = rows[r0:r0 + step]
-            mask = np.stack([visible_mask(int(p), N, seg_len, tail_len, pol, ev[kvh]) for p in rr]) \
-                if rr.size else np.zeros((0, N), dtype=bool)
+            def mask_for(b):
+                if not rr.size:
+                    return np.zeros((0, N), dtype=bool)
+                if retrieved is None:
+                    return np.stack([visible_mask(int(p), N, seg_len, tail_len, pol, ev[kvh]) for p in rr])
+                return np.stack([visible_mask(int(p), N, seg_len, tail_len, pol, ev[kvh],
+                                              retrieved.get((b, kvh, int(p) // seg_len), ()))
+                                 for p in rr])
+            mask = mask_for(0)
             for b in range(B):
+                if retrieved is not None and b > 0:
+                    mask = mask_for(b)
                 kb, vb = k[b, :, kvh, :], v[b, :, kvh, :]
                 for h in range(kvh * g, (kvh + 1) * g):
                     z = (q[b, rr, h, :] @ kb.T) * scale          # dense scores, all N keys
@@ -127,20 +151,22 @@ def attend(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
 
 
 def decode_attend(q, k_ctx, v_ctx, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
-                  scale: Optional[float] = None, evicted: Optional[Sequence[int]] = None
-                  ) -> Tuple[np.ndarray, np.ndarray]:
+                  scale: Optional[float] = None, evicted: Optional[Sequence[int]] = None,
+                  retrieved=None) -> Tuple[np.ndarray, np.ndarray]:
     """One decoding step of one sequence (Eq. 2's conditioning on x_<t of the current
     segment, C_{i-1} and R_{i-1}).  q [Hq,D] is the query of the newest token; k_ctx,
     v_ctx [n,Hkv,D] hold the keys/values of all n tokens so far, the newest included.
     By the forward identity of Sec. 3.1 this is row n-1 of the prefill of the same n
-    tokens.  Returns O [Hq,D] and LSE [Hq]."""
+    tokens.  retrieved, if given, maps a KV head to the retrieved prefix of the open
+    segment.  Returns O [Hq,D] and LSE [Hq]."""
     q = widen(q)
     k_ctx, v_ctx = widen(k_ctx), widen(v_ctx)
     n = k_ctx.shape[0]
     qfull = np.zeros((1, n, q.shape[0], q.shape[1]))
     qfull[0, n - 1] = q
+    ret = None if retrieved is None else {(0, h, (n - 1) // seg_len): idx for h, idx in retrieved.items()}
     o, l = attend(qfull, k_ctx[None], v_ctx[None], seg_len=seg_len, tail_len=tail_len,
-                  kv_policy=kv_policy, scale=scale, rows=[n - 1], evicted=evicted)
+                  kv_policy=kv_policy, scale=scale, rows=[n - 1], evicted=evicted, retrieved=ret)
     return o[0, 0], l[0, :, 0]
 
 

@@ -31,6 +31,12 @@ MUTANTS = {
     "mask_added_as_zero": ("np.where(mask, z, -np.inf)", "np.where(mask, z, 0.0)"),
     "decode_uses_previous_row": ("rows=[n - 1], evicted=evicted", "rows=[max(n - 2, 0)], evicted=evicted"),
     "bf16_widen_shift": ("<< np.uint32(16)", "<< np.uint32(15)"),
+    "retrieved_list_ignored": ("            vis[idx] = True\n", "            pass\n"),
+    "retrieved_added_to_whole_history": ("        if retrieved is None:                      # forward-only", "        if True:                      # forward-only"),
+    "retrieved_of_previous_segment": ("retrieved.get((b, kvh, int(p) // seg_len), ())", "retrieved.get((b, kvh, int(p) // seg_len - 1), ())"),
+    "retrieved_of_first_sequence_for_all": ("retrieved.get((b, kvh, int(p) // seg_len), ())", "retrieved.get((0, kvh, int(p) // seg_len), ())"),
+    "retrieved_duplicates_accepted": ("if np.unique(idx).size != idx.size:", "if False:"),
+    "decode_retrieved_of_next_segment": ("{(0, h, (n - 1) // seg_len): idx", "{(0, h, n // seg_len): idx"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 
@@ -69,7 +75,7 @@ def test_planted_mistake_is_caught(mutant, monkeypatch):
     for name, fn, kwargs in _pin_calls():
         try:
             fn(**kwargs)
-        except (AssertionError, ValueError, IndexError, FloatingPointError):
+        except (AssertionError, ValueError, IndexError, FloatingPointError, pytest.fail.Exception):
             failed.append(name)
     assert failed, f"no pin notices the planted mistake '{mutant}'"
 

@@ -319,3 +319,99 @@ def test_rejects_bad_arguments():
         orc.attend(q, q[:, :, :1], q, seg_len=2, tail_len=1, kv_policy=[1])  # V shape
     with pytest.raises(ValueError):
         orc.attend(q, q, q, seg_len=2, tail_len=1, kv_policy=[1, 1], rows=[4])
+
+
+# ---------------------------------------------------------------- retrieved prefix
+# Eq. 13, second case: a long-range head attends to [K_ret ; K_seg]; Appendix D "Output": the
+# retrieved prefix is R gathered pool rows.  None of the references below touch the mask code.
+def gathered_rows(q, k, v, S, ret_of_seg, scale):
+    """Literal [gathered rows ; segment] with the textbook scalar loops: for the query at
+    in-segment offset t, keys = the gathered rows in list order, then segment rows 0..t."""
+    n, d = q.shape
+    out = np.zeros((n, d))
+    lse = np.zeros(n)
+    for p in range(n):
+        i, s = p // S, (p // S) * S
+        js = [int(j) for j in ret_of_seg.get(i, ())] + list(range(s, p + 1))
+        z = [scale * sum(q[p, c] * k[j, c] for c in range(d)) for j in js]
+        zm = max(z)
+        w = [math.exp(x - zm) for x in z]
+        tot = sum(w)
+        for c in range(d):
+            out[p, c] = sum(wi * v[j, c] for wi, j in zip(w, js)) / tot
+        lse[p] = zm + math.log(tot)
+    return out, lse
+
+
+def _random_retrieval(rng, n, S, R):
+    """For every segment after the first, R (or fewer) distinct earlier positions in random order."""
+    ret = {}
+    for i in range(1, (n + S - 1) // S):
+        s = i * S
+        ret[i] = rng.permutation(s)[:min(R, s)]
+    return ret
+
+
+@pytest.mark.parametrize("S,R,n", [(8, 3, 29), (8, 8, 40), (5, 11, 33), (16, 1, 50)])
+def test_retrieved_prefix_equals_literal_gather(S, R, n):
+    d, B, Hkv, g = 3, 2, 2, 2
+    rng = np.random.default_rng(300 + n)
+    q = rng.standard_normal((B, n, Hkv * g, d))
+    k, v = rng.standard_normal((B, n, Hkv, d)), rng.standard_normal((B, n, Hkv, d))
+    per = {(b, h): _random_retrieval(rng, n, S, R) for b in range(B) for h in range(Hkv)}
+    retrieved = {(b, h, i): idx for (b, h), r in per.items() for i, idx in r.items()}
+    o, l = orc.attend(q, k, v, seg_len=S, tail_len=2, kv_policy=[2, 2], retrieved=retrieved)
+    for b in range(B):
+        for hq in range(Hkv * g):
+            h = hq // g
+            oe, le = gathered_rows(q[b, :, hq], k[b, :, h], v[b, :, h], S, per[(b, h)], 1 / math.sqrt(d))
+            np.testing.assert_allclose(o[b, :, hq], oe, atol=1e-13)
+            np.testing.assert_allclose(l[b, hq], le, atol=1e-13)
+
+
+def test_retrieved_prefix_special_cases_reduce_to_the_other_policies():
+    """Retrieving every earlier row is the full-history head, retrieving the last T rows of the
+    previous segment is a local head, retrieving nothing is within-segment attention; a local
+    head ignores the list."""
+    n, d, S, T = 37, 4, 8, 3
+    q, k, v = _rand((1, n, 1, d), 310), _rand((1, n, 1, d), 311), _rand((1, n, 1, d), 312)
+    nseg = (n + S - 1) // S
+    def run(policy, retrieved=None):
+        return orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=[policy], retrieved=retrieved)
+    everything = {(0, 0, i): np.arange(i * S) for i in range(nseg)}
+    window = {(0, 0, i): np.arange(max(0, i * S - T), i * S) for i in range(nseg)}
+    for got, want in ((run(2, everything), run(2)), (run(2, window), run(1)), (run(2, {}), run(0)),
+                      (run(1, everything), run(1))):
+        np.testing.assert_allclose(got[0], want[0], atol=1e-13)
+        np.testing.assert_allclose(got[1], want[1], atol=1e-13)
+    lo = lambda p: (p // S) * S
+    oe, le = textbook_rows(q[0, :, 0], k[0, :, 0], v[0, :, 0], 1 / math.sqrt(d), lo, lambda p: p)
+    np.testing.assert_allclose(run(2, {})[0][0, :, 0], oe, atol=1e-13)
+
+
+def test_retrieved_prefix_with_zero_queries_is_mean_of_gathered_and_segment_values():
+    n, d, S = 20, 2, 6
+    k, v = _rand((1, n, 1, d), 320), _rand((1, n, 1, d), 321)
+    ret = {(0, 0, 1): [4, 0], (0, 0, 2): [11, 2, 7], (0, 0, 3): [17]}
+    o, l = orc.attend(np.zeros((1, n, 1, d)), k, v, seg_len=S, tail_len=0, kv_policy=[2], retrieved=ret)
+    for p in range(n):
+        i, s = p // S, (p // S) * S
+        js = list(ret.get((0, 0, i), [])) + list(range(s, p + 1))
+        np.testing.assert_allclose(o[0, p, 0], v[0, js, 0].mean(0), atol=1e-14)
+        assert abs(l[0, 0, p] - math.log(len(js))) < 1e-14
+
+
+def test_retrieved_prefix_decode_row_and_bad_lists():
+    n, d, S = 27, 4, 8
+    q, k, v = _rand((1, n, 2, d), 330), _rand((1, n, 1, d), 331), _rand((1, n, 1, d), 332)
+    ret = {(0, 0, i): np.random.default_rng(i).permutation(i * S)[:5] for i in range(1, 4)}
+    o, l = orc.attend(q, k, v, seg_len=S, tail_len=0, kv_policy=[2], retrieved=ret)
+    for m in (8, 9, 16, 27):
+        od, ld = orc.decode_attend(q[0, m - 1], k[0, :m], v[0, :m], seg_len=S, tail_len=0, kv_policy=[2],
+                                   retrieved={0: ret.get((0, 0, (m - 1) // S), ())})
+        np.testing.assert_allclose(od, o[0, m - 1], atol=1e-14)
+        np.testing.assert_allclose(ld, l[0, :, m - 1], atol=1e-14)
+    with pytest.raises(ValueError):   # a row of the segment itself is not in the pool yet
+        orc.attend(q, k, v, seg_len=S, tail_len=0, kv_policy=[2], retrieved={(0, 0, 1): [8]})
+    with pytest.raises(ValueError):   # the same row twice would double its weight
+        orc.attend(q, k, v, seg_len=S, tail_len=0, kv_policy=[2], retrieved={(0, 0, 1): [3, 3]})
