@@ -73,13 +73,19 @@ typedef struct {
   int32_t fp32_check;      /* 1: fp32 FMA arithmetic and fp32 `out` (validation mode)     */
   int32_t out_fp32;        /* 1: `out` is fp32 (the unrounded accumulator) also in bf16
                               MFMA mode; implied by fp32_check                            */
+  int32_t retrieved_capacity; /* 0: a PAST head attends to its whole pool.  R_max > 0:
+                              retrieval mode (Sec. 3.4 "Long-Range Channel"): a PAST head
+                              attends to [retrieved prefix ; own segment] (Eq. 13, second case),
+                              the prefix being the rows seg_kv_past_select() gathered, at most
+                              R_max of them; no head may then have both TAIL and PAST       */
 } segattn_config;
 
 /* ---- context --------------------------------------------------------------------------- */
 
 /* Bytes of device memory the cache arena needs for this configuration (0 if invalid).
- * Per TAIL/SEG head: (T + S) rows of K and of V; per PAST head: past_capacity rows; plus
- * per-(sequence, head) counters and the split-K workspace of the decode path. */
+ * Per TAIL/SEG head: (T + S) rows of K and of V; per PAST head: past_capacity rows (in
+ * retrieval mode also retrieved_capacity + S rows: retrieved prefix and a copy of the open
+ * segment); plus per-(sequence, head) counters and the split-K workspace of the decode path. */
 size_t segattn_cache_bytes(const segattn_config *cfg);
 
 /* Create a context over a caller-allocated arena (device, >= segattn_cache_bytes(), aligned
@@ -127,6 +133,20 @@ segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int
 segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void *k,
                                   const void *v, int64_t rows, void *stream);
 
+/* Retrieval mode only.  Retrieved prefix for the next segment (Appendix D "Output"): for every
+ * sequence and every PAST head gather the R pool rows idx names into the head's retrieved
+ * prefix.  idx: device int32 [B, n_past, R], n_past = the PAST heads in ascending KV-head
+ * order; entries are pool row numbers (absolute positions, or the order of
+ * seg_kv_past_append), distinct, each below the head's pool size and not evicted.  The
+ * prefix rows take the order of the list (softmax does not depend on it).  The prefix serves
+ * the segment that starts next (prefill calls and decode steps alike) and is dropped when
+ * that segment closes; without a call the prefix is empty.  R = 0 empties it.  Valid between
+ * segments only (ESTATE with an open segment); EINVAL if the context is not in retrieval
+ * mode or R > retrieved_capacity; ECAPACITY if R exceeds the visible pool rows of some
+ * sequence and head.  The lists are not read on the host: an out-of-range entry is clamped
+ * into the pool (never an out-of-bounds access), a repeated entry counts twice. */
+segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t R, void *stream);
+
 /* Hide the n_oldest oldest rows of one PAST head's pool from now on (all sequences).  Pure
  * bookkeeping: nothing is copied and the rows' storage is not reused.  If the head also has
  * the TAIL bit, rows inside the current tail window stay visible.  Evicting more rows than
@@ -142,8 +162,9 @@ segattn_status seg_kv_lengths(const segattn_ctx *ctx, int64_t *past, int32_t *ta
 
 /* Declare the cache contents after the caller has written K/V rows into the arena itself
  * (restore from a snapshot, benchmark set-up): host arrays closed_rows [B] = rows in closed
- * segments (a multiple of S), tail [B] (<= min(T, closed_rows)), seg_fill [B] (< S).
- * Row placement is given by segattn_cache_span(). */
+ * segments (a multiple of S), tail [B] (<= min(T, closed_rows)), seg_fill [B] (< S; 0 in
+ * retrieval mode).  Row placement is given by segattn_cache_span().  The retrieved prefix
+ * starts empty. */
 segattn_status seg_kv_set_lengths(segattn_ctx *ctx, const int64_t *closed_rows,
                                   const int32_t *tail, const int32_t *seg_fill, void *stream);
 
@@ -155,7 +176,8 @@ segattn_status segattn_cache_span(const segattn_ctx *ctx, int32_t b, int32_t kv_
                                   size_t *k_off, size_t *v_off, int64_t *cap_rows);
 
 /* Bytes of K/V rows currently held (visible or not yet dropped) over all sequences and
- * heads: the quantity Sec. 3.5 bounds by S + T per local head plus the pool of PAST heads. */
+ * heads: the quantity Sec. 3.5 bounds by S + T per local head plus the pool of PAST heads
+ * (in retrieval mode plus the retrieved prefix and the segment mirror of those heads). */
 size_t segattn_resident_bytes(const segattn_ctx *ctx);
 
 /* ---- decode ----------------------------------------------------------------------------- */

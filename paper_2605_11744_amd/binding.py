@@ -26,6 +26,7 @@ class segattn_config(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("seg_len", ctypes.c_int32), ("tail_len", ctypes.c_int32),
         ("past_capacity", ctypes.c_int64), ("kv_policy", ctypes.POINTER(ctypes.c_uint8)),
         ("scale", ctypes.c_float), ("fp32_check", ctypes.c_int32), ("out_fp32", ctypes.c_int32),
+        ("retrieved_capacity", ctypes.c_int32),
     ]
 
 
@@ -52,6 +53,7 @@ def lib() -> ctypes.CDLL:
             "seg_attn_fwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, i64, vp, vp, vp]),
             "seg_kv_commit": (ctypes.c_int, [vp, vp, vp, i32, vp]),
             "seg_kv_past_append": (ctypes.c_int, [vp, i32, vp, vp, i64, vp]),
+            "seg_kv_past_select": (ctypes.c_int, [vp, vp, i32, vp]),
             "seg_kv_past_evict": (ctypes.c_int, [vp, i32, i64, vp]),
             "seg_kv_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]),
             "seg_kv_set_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), vp]),
@@ -70,7 +72,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_evict",
+           "seg_attn_fwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_past_evict",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -90,11 +92,12 @@ def _check(st: int, where: str) -> None:
 
 def make_config(*, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seg_len: int,
                 tail_len: int, kv_policy: Sequence[int], past_capacity: int = 0, scale: float = 0.0,
-                fp32_check: bool = False, out_fp32: bool = False) -> segattn_config:
+                fp32_check: bool = False, out_fp32: bool = False,
+                retrieved_capacity: int = 0) -> segattn_config:
     pol = (ctypes.c_uint8 * len(kv_policy))(*[int(p) for p in kv_policy])
     cfg = segattn_config(batch, n_q_heads, n_kv_heads, head_dim, seg_len, tail_len, past_capacity,
                          ctypes.cast(pol, ctypes.POINTER(ctypes.c_uint8)), scale,
-                         int(fp32_check), int(out_fp32))
+                         int(fp32_check), int(out_fp32), int(retrieved_capacity))
     cfg._policy_keepalive = pol
     return cfg
 
@@ -140,6 +143,10 @@ def seg_kv_commit(ctx: int, k, v, m: int, stream=None) -> None:
 
 def seg_kv_past_append(ctx: int, kv_head: int, k, v, rows: int, stream=None) -> None:
     _check(lib().seg_kv_past_append(ctx, kv_head, _ptr(k), _ptr(v), rows, _ptr(stream)), "seg_kv_past_append")
+
+
+def seg_kv_past_select(ctx: int, idx, R: int, stream=None) -> None:
+    _check(lib().seg_kv_past_select(ctx, _ptr(idx), R, _ptr(stream)), "seg_kv_past_select")
 
 
 def seg_kv_past_evict(ctx: int, kv_head: int, n_oldest: int, stream=None) -> None:

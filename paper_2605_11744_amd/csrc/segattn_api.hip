@@ -55,14 +55,21 @@ bool build_problem(const segattn_config *cfg, bool need_cache, Problem &p) {
   if (need_cache && n_past > 0) {
     if (cfg->past_capacity < cfg->seg_len || cfg->past_capacity >= (1ll << 31) - 4096) return false;
   }
+  if (need_cache && cfg->retrieved_capacity != 0) {
+    if (cfg->retrieved_capacity < 0 || cfg->retrieved_capacity > (1 << 24) || n_past == 0) return false;
+    for (int h = 0; h < p.Hkv; ++h)
+      if (p.policy[h] == (SEGATTN_TAIL | SEGATTN_PAST)) return false;
+  }
   return true;
 }
 
 bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsigned long long &total) {
   memset(&g, 0, sizeof(g));
   g.pool_cap = p.n_past ? (unsigned long long)cfg->past_capacity : 0;
+  g.ret_cap = cfg->retrieved_capacity;
   g.decode_chunk = kDecodeChunk;
-  g.ws_splits_past = (int)((g.pool_cap + kDecodeChunk - 1) / kDecodeChunk);
+  const unsigned long long past_window = g.ret_cap ? (unsigned long long)g.ret_cap + p.S : g.pool_cap;
+  g.ws_splits_past = (int)((past_window + kDecodeChunk - 1) / kDecodeChunk);
   g.ws_splits_other = (p.T + p.S + kDecodeChunk - 1) / kDecodeChunk;
   g.rows_per_seq = (unsigned long long)p.n_past * g.pool_cap +
                    (unsigned long long)(p.Hkv - p.n_past) * (unsigned long long)(p.T + p.S);
@@ -73,7 +80,10 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
                                    ((unsigned long long)p.n_past * g.ws_splits_past +
                                     (unsigned long long)(p.Hkv - p.n_past) * g.ws_splits_other);
   g.kv_off = align_up(g.ws_off + slots * (2ull + p.D) * 4ull);
-  total = g.kv_off + (unsigned long long)p.B * g.rows_per_seq * 2ull * p.D * 2ull;
+  g.view_off = align_up(g.kv_off + (unsigned long long)p.B * g.rows_per_seq * 2ull * p.D * 2ull);
+  total = g.view_off;
+  if (g.ret_cap)
+    total += (unsigned long long)p.B * p.n_past * 2ull * (unsigned long long)(g.ret_cap + p.S) * p.D * 2ull;
   return total < (1ull << 46);
 }
 
@@ -89,6 +99,7 @@ struct segattn_ctx {
   std::vector<long long> closed;    // [B] rows in closed segments
   std::vector<int> tail, fill;      // [B]
   std::vector<long long> pool, lo;  // [B*Hkv] (PAST heads)
+  std::vector<int> ret;             // [B] rows of the retrieved prefix (retrieval mode)
   std::vector<int> staging;         // host image of the device counters for set_lengths
 };
 
@@ -122,6 +133,7 @@ segattn_status segattn_create(const segattn_config *cfg, void *cache_dev, size_t
   c->fill.assign(p.B, 0);
   c->pool.assign((size_t)p.B * p.Hkv, 0);
   c->lo.assign((size_t)p.B * p.Hkv, 0);
+  c->ret.assign(p.B, 0);
   *out_ctx = c;
   return SEGATTN_OK;
 }
@@ -137,6 +149,7 @@ segattn_status segattn_reset(segattn_ctx *ctx, void *stream) {
   std::fill(ctx->fill.begin(), ctx->fill.end(), 0);
   std::fill(ctx->pool.begin(), ctx->pool.end(), 0);
   std::fill(ctx->lo.begin(), ctx->lo.end(), 0);
+  std::fill(ctx->ret.begin(), ctx->ret.end(), 0);
   ctx->ready = true;
   return SEGATTN_OK;
 }
@@ -214,6 +227,7 @@ segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int
     if (ctx->fill[b] == p.S) {
       ctx->fill[b] = 0;
       ctx->tail[b] = p.T;
+      ctx->ret[b] = 0;
       ctx->closed[b] += p.S;
       for (int h = 0; h < p.Hkv; ++h)
         if (p.policy[h] & SEGATTN_PAST) ctx->pool[(size_t)b * p.Hkv + h] += p.S;
@@ -242,6 +256,29 @@ segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void 
   a.kv_head = kv_head;
   if (launch_cache_past_append(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
   for (int b = 0; b < p.B; ++b) ctx->pool[(size_t)b * p.Hkv + kv_head] += rows;
+  return SEGATTN_OK;
+}
+
+segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t R, void *stream) {
+  if (!ctx || R < 0 || (R > 0 && !idx)) return SEGATTN_EINVAL;
+  const Problem &p = ctx->p;
+  if (ctx->g.ret_cap == 0 || R > ctx->g.ret_cap) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  for (int b = 0; b < p.B; ++b) {
+    if (ctx->fill[b] != 0) return SEGATTN_ESTATE;
+    for (int h = 0; h < p.Hkv; ++h) {
+      const size_t i = (size_t)b * p.Hkv + h;
+      if ((p.policy[h] & SEGATTN_PAST) && R > ctx->pool[i] - ctx->lo[i]) return SEGATTN_ECAPACITY;
+    }
+  }
+  SelectArgs a;
+  memset(&a, 0, sizeof(a));
+  a.idx = idx;
+  a.cache = ctx->cache;
+  a.geom = ctx->g;
+  a.R = R;
+  if (launch_cache_select(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  for (int b = 0; b < p.B; ++b) ctx->ret[b] = R;
   return SEGATTN_OK;
 }
 
@@ -285,6 +322,7 @@ segattn_status seg_kv_set_lengths(segattn_ctx *ctx, const int64_t *closed_rows, 
   for (int b = 0; b < p.B; ++b) {
     if (closed_rows[b] < 0 || closed_rows[b] % p.S) return SEGATTN_EINVAL;
     if (seg_fill[b] < 0 || seg_fill[b] >= p.S) return SEGATTN_EINVAL;
+    if (ctx->g.ret_cap && seg_fill[b] != 0) return SEGATTN_EINVAL;
     if (tail[b] < 0 || tail[b] > p.T || tail[b] > closed_rows[b]) return SEGATTN_EINVAL;
     if (p.n_past && closed_rows[b] + seg_fill[b] > (long long)ctx->g.pool_cap) return SEGATTN_ECAPACITY;
   }
@@ -304,6 +342,7 @@ segattn_status seg_kv_set_lengths(segattn_ctx *ctx, const int64_t *closed_rows, 
     ctx->closed[b] = closed_rows[b];
     ctx->tail[b] = tail[b];
     ctx->fill[b] = seg_fill[b];
+    ctx->ret[b] = 0;
     for (int h = 0; h < p.Hkv; ++h) {
       ctx->pool[(size_t)b * p.Hkv + h] = (p.policy[h] & SEGATTN_PAST) ? closed_rows[b] : 0;
       ctx->lo[(size_t)b * p.Hkv + h] = 0;
@@ -328,7 +367,9 @@ size_t segattn_resident_bytes(const segattn_ctx *ctx) {
   unsigned long long rows = 0;
   for (int b = 0; b < p.B; ++b)
     for (int h = 0; h < p.Hkv; ++h) {
-      if (p.policy[h] & SEGATTN_PAST) rows += ctx->pool[(size_t)b * p.Hkv + h] + ctx->fill[b];
+      if (p.policy[h] & SEGATTN_PAST)
+        rows += ctx->pool[(size_t)b * p.Hkv + h] + ctx->fill[b] +
+                (ctx->g.ret_cap ? ctx->ret[b] + ctx->fill[b] : 0);
       else rows += ((p.policy[h] & SEGATTN_TAIL) ? ctx->tail[b] : 0) + ctx->fill[b];
     }
   return (size_t)(rows * 2ull * p.D * 2ull);
@@ -347,7 +388,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
       long long win;
       if (p.policy[h] & SEGATTN_PAST) {
         if (ctx->pool[i] + ctx->fill[b] + 1 > (long long)ctx->g.pool_cap) return SEGATTN_ECAPACITY;
-        win = ctx->pool[i] - ctx->lo[i] + ctx->fill[b] + 1;
+        win = (ctx->g.ret_cap ? ctx->ret[b] : ctx->pool[i] - ctx->lo[i]) + ctx->fill[b] + 1;
       } else {
         win = ((p.policy[h] & SEGATTN_TAIL) ? ctx->tail[b] : 0) + ctx->fill[b] + 1;
       }
@@ -383,6 +424,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
     if (ctx->fill[b] == p.S) {
       ctx->fill[b] = 0;
       ctx->tail[b] = p.T;
+      ctx->ret[b] = 0;
       ctx->closed[b] += p.S;
       for (int h = 0; h < p.Hkv; ++h)
         if (p.policy[h] & SEGATTN_PAST) ctx->pool[(size_t)b * p.Hkv + h] += p.S;

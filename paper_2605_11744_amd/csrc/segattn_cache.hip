@@ -1,7 +1,11 @@
 // Cross-segment state of libsegattn (Sec. 3.4): the carried KV tail C_i of local heads and the
 // append-only past pool of long-range heads, kept in one caller-owned arena.  All kernels
 // here are plain copies (HBM-bound) plus the per-(sequence, head) counters they maintain:
-//   counters[b][h] = { pool rows, tail rows, open-segment rows, first visible pool row }.
+//   counters[b][h] = { pool rows, tail rows, open-segment rows, first visible pool row,
+//                      rows of the retrieved prefix }.
+// In retrieval mode (Sec. 3.4 "Long-Range Channel", Appendix D "Output") a long-range head
+// attends to R gathered pool rows plus its own segment: cache_select_kernel gathers the rows into
+// the head's attention view, and every row appended to the open segment is mirrored there.
 // The host keeps a mirror of the counters for validation; the device copy is only ever
 // changed by these kernels, in stream order, so a sequence of calls can be graph-captured.
 #include "segattn_internal.h"
@@ -46,14 +50,26 @@ __global__ __launch_bounds__(256) void cache_append_kernel(const Problem p, cons
   const int r_begin = blockIdx.x * rows_per_block;
   const int r_end = min(n, r_begin + rows_per_block);
   const int c = threadIdx.x % CPR;
+  uint4 *km = nullptr, *vm = nullptr;  // mirror of the open segment in the attention view
+  if (uses_view(p, a.geom, h)) {
+    km = (uint4 *)(a.cache + view_k_off(p, a.geom, b, h)) + (long long)(a.geom.ret_cap + fill) * CPR;
+    vm = (uint4 *)(a.cache + view_v_off(p, a.geom, b, h)) + (long long)(a.geom.ret_cap + fill) * CPR;
+  }
   for (int r = r_begin + threadIdx.x / CPR; r < r_end; r += 256 / CPR) {
-    kd[(long long)(dst0 + r) * CPR + c] = ks[(long long)(src0 + r) * src_stride + c];
-    vd[(long long)(dst0 + r) * CPR + c] = vs[(long long)(src0 + r) * src_stride + c];
+    const uint4 kx = ks[(long long)(src0 + r) * src_stride + c];
+    const uint4 vx = vs[(long long)(src0 + r) * src_stride + c];
+    kd[(long long)(dst0 + r) * CPR + c] = kx;
+    vd[(long long)(dst0 + r) * CPR + c] = vx;
+    if (km) {
+      km[(long long)r * CPR + c] = kx;
+      vm[(long long)r * CPR + c] = vx;
+    }
   }
 }
 
 // Close the open segment of every (b,h) whose fill reaches S after adding `add` rows:
-// tail <- last T rows of the segment (non-PAST heads), pool += S (PAST heads), fill <- 0.
+// tail <- last T rows of the segment (non-PAST heads), pool += S (PAST heads), fill <- 0; in
+// retrieval mode the retrieved prefix belonged to the segment just closed and is dropped.
 // One workgroup per (b,h): it alone reads and writes that head's counters.
 template <int D>
 __global__ __launch_bounds__(256) void cache_close_kernel(const Problem p, unsigned char *cache,
@@ -82,6 +98,7 @@ __global__ __launch_bounds__(256) void cache_close_kernel(const Problem p, unsig
     meta[META_FILL] = 0;
     meta[META_TAIL] = p.T;
     if (past) meta[META_POOL] = pool + p.S;
+    meta[META_RET] = 0;
   }
 }
 
@@ -100,7 +117,12 @@ __global__ __launch_bounds__(64) void cache_decode_append_kernel(const Problem p
     const int c = is_v ? t - CPR : t;
     const uint4 *src = (const uint4 *)((is_v ? a.v : a.k) + ((long long)b * p.Hkv + h) * D);
     uint4 *dst = (uint4 *)(a.cache + (is_v ? v_block_off(p, a.geom, b, h) : k_block_off(p, a.geom, b, h)));
-    dst[(long long)row * CPR + c] = src[c];
+    const uint4 x = src[c];
+    dst[(long long)row * CPR + c] = x;
+    if (uses_view(p, a.geom, h)) {
+      uint4 *mir = (uint4 *)(a.cache + (is_v ? view_v_off(p, a.geom, b, h) : view_k_off(p, a.geom, b, h)));
+      mir[(long long)(a.geom.ret_cap + fill) * CPR + c] = x;
+    }
   }
   if (t == 0) meta[META_FILL] = fill + 1;
 }
@@ -142,6 +164,34 @@ __global__ void cache_evict_kernel(const Problem p, unsigned char *cache, const 
   long long lo_new = lo + n < limit ? lo + n : limit;
   if (lo_new < lo) lo_new = lo;
   meta[META_LO] = (int)lo_new;
+}
+
+// Retrieved prefix of every PAST head (Appendix D "Output"): pool rows idx[b][past head][0..R)
+// -> rows [ret_cap - R, ret_cap) of the head's attention view, in list order.  An index is
+// clamped into the pool, so a bad list cannot read outside the arena.  grid = (row chunks,
+// B * n_past); the first block of each (b, head) also records R.
+template <int D>
+__global__ __launch_bounds__(256) void cache_select_kernel(const Problem p, const SelectArgs a) {
+  constexpr int CPR = D / 8;
+  const int b = blockIdx.y / p.n_past, np = blockIdx.y % p.n_past;
+  const int h = p.order[np];  // PAST heads come first in `order`, by ascending head index
+  int *meta = meta_of(a.cache, a.geom, p, b, h);
+  const int pool = meta[META_POOL];
+  const int *idx = a.idx + ((long long)b * p.n_past + np) * a.R;
+  const uint4 *ks = (const uint4 *)(a.cache + k_block_off(p, a.geom, b, h));
+  const uint4 *vs = (const uint4 *)(a.cache + v_block_off(p, a.geom, b, h));
+  uint4 *kd = (uint4 *)(a.cache + view_k_off(p, a.geom, b, h)) + (long long)(a.geom.ret_cap - a.R) * CPR;
+  uint4 *vd = (uint4 *)(a.cache + view_v_off(p, a.geom, b, h)) + (long long)(a.geom.ret_cap - a.R) * CPR;
+  const int c = threadIdx.x % CPR;
+  for (int r = blockIdx.x * (256 / CPR) + threadIdx.x / CPR; r < a.R; r += gridDim.x * (256 / CPR)) {
+    int j = idx[r];
+    j = j < 0 ? 0 : (j >= pool ? pool - 1 : j);
+    if (pool > 0) {
+      kd[(long long)r * CPR + c] = ks[(long long)j * CPR + c];
+      vd[(long long)r * CPR + c] = vs[(long long)j * CPR + c];
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) meta[META_RET] = pool > 0 ? a.R : 0;
 }
 
 // ---- launchers ----------------------------------------------------------------------------
@@ -187,6 +237,16 @@ hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStre
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cache_pool_add_kernel, dim3((p.B + 63) / 64), dim3(64), 0, st, p, a.cache, a.geom,
                      a.kv_head, a.m);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st) {
+  const int rows_per_block = 256 / (p.D / 8);
+  int chunks = (a.R + rows_per_block - 1) / rows_per_block;
+  if (chunks < 1) chunks = 1;
+  const dim3 grid(chunks, p.B * p.n_past);
+  if (p.D == 128) hipLaunchKernelGGL(cache_select_kernel<128>, grid, dim3(256), 0, st, p, a);
+  else hipLaunchKernelGGL(cache_select_kernel<64>, grid, dim3(256), 0, st, p, a);
   return hipGetLastError();
 }
 

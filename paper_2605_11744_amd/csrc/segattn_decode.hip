@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
   decode_block(p, a, blockIdx.x, split, b, kv);
   const int *meta = meta_ro(a.cache, a.geom, p, b, kv);
   int lo, seg_row0;
-  window_of(p, kv, meta, lo, seg_row0);
+  window_of(p, a.geom, kv, meta, lo, seg_row0);
   const int hi = seg_row0 + meta[META_FILL];
   const int c0 = lo + split * a.geom.decode_chunk;
   if (c0 >= hi) return;
@@ -121,8 +121,8 @@ __global__ __launch_bounds__(256) void decode_split_kernel(const Problem p, cons
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
   }
 
-  const uint4 *kb = (const uint4 *)(a.cache + k_block_off(p, a.geom, b, kv)) + li;
-  const uint4 *vb = (const uint4 *)(a.cache + v_block_off(p, a.geom, b, kv)) + li;
+  const uint4 *kb = (const uint4 *)(a.cache + attn_k_off(p, a.geom, b, kv)) + li;
+  const uint4 *vb = (const uint4 *)(a.cache + attn_v_off(p, a.geom, b, kv)) + li;
   constexpr int ROWS_PER_ITER = 4 * GPW * U;  // rows a workgroup consumes per iteration
   for (int r0 = c0; r0 < c1; r0 += ROWS_PER_ITER) {
     uint4 kr[U], vr[U];
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const Problem p, co
   const int kv = head / p.g;
   const int *meta = meta_ro(a.cache, a.geom, p, b, kv);
   int lo, seg_row0;
-  window_of(p, kv, meta, lo, seg_row0);
+  window_of(p, a.geom, kv, meta, lo, seg_row0);
   const int hi = seg_row0 + meta[META_FILL];
   const int ns = (hi - lo + a.geom.decode_chunk - 1) / a.geom.decode_chunk;
   const float *ws = (const float *)(a.cache + a.geom.ws_off) + ws_slot_base(p, a.geom, b, head) * (2 + D);

@@ -9,18 +9,25 @@
 namespace segattn {
 
 constexpr int kMaxKvHeads = 128;
-constexpr int kMetaInts = 4;  // per (sequence, KV head): pool rows, tail rows, open-segment rows, first visible pool row
+// per (sequence, KV head): pool rows, tail rows, open-segment rows, first visible pool row,
+// rows of the retrieved prefix (retrieval mode), 3 unused
+constexpr int kMetaInts = 8;
 
-enum MetaSlot { META_POOL = 0, META_TAIL = 1, META_FILL = 2, META_LO = 3 };
+enum MetaSlot { META_POOL = 0, META_TAIL = 1, META_FILL = 2, META_LO = 3, META_RET = 4 };
 
 // Geometry of the cache arena, identical on host and device.
-//   [ counters : B*Hkv*4 int32 ][ decode workspace ][ K/V rows ]
+//   [ counters : B*Hkv*8 int32 ][ decode workspace ][ K/V rows ][ attention views ]
 // K/V rows of (b, h): K block of cap(h) rows, then V block of cap(h) rows, D bf16 each;
 // cap(h) = pool_cap for a PAST head, T + S otherwise.
+// Retrieval mode (ret_cap > 0): a PAST head attends to [retrieved prefix ; open segment]
+// instead of its pool, read from its attention view: K block of ret_cap + S rows, then the V
+// block; rows [ret_cap - R, ret_cap) hold the R retrieved rows, rows from ret_cap on mirror the
+// open segment (which is appended to the pool as well).
 struct CacheGeom {
-  unsigned long long meta_off, ws_off, kv_off;
+  unsigned long long meta_off, ws_off, kv_off, view_off;
   unsigned long long rows_per_seq;     // sum of cap(h) over heads
   unsigned long long pool_cap;         // rows per PAST head
+  int ret_cap;                         // rows of retrieved prefix a view can hold; 0: no views
   int ws_splits_past, ws_splits_other; // split-K slots per query head (PAST / other heads)
   int decode_chunk;                    // keys per split
 };
@@ -70,6 +77,13 @@ struct CopyArgs {
   int kv_head;           // past_append: target head; otherwise unused
 };
 
+struct SelectArgs {
+  const int *idx;        // [B, n_past, R] pool row numbers
+  unsigned char *cache;
+  CacheGeom geom;
+  int R;
+};
+
 // ---- helpers usable on host and device ----------------------------------------------------
 __host__ __device__ inline unsigned long long head_row_offset(const Problem &p, const CacheGeom &g,
                                                               int h) {
@@ -88,11 +102,33 @@ __host__ __device__ inline unsigned long long v_block_off(const Problem &p, cons
                                                           int h) {
   return k_block_off(p, g, b, h) + head_cap(p, g, h) * (unsigned long long)p.D * 2ull;
 }
-// First row of the visible window and first row of the open segment inside the (b,h) block.
-__host__ __device__ inline void window_of(const Problem &p, int h, const int *meta, int &lo,
-                                          int &seg_row0) {
+// Attention view of a PAST head in retrieval mode.
+__host__ __device__ inline unsigned long long view_k_off(const Problem &p, const CacheGeom &g, int b, int h) {
+  return g.view_off + ((unsigned long long)b * p.n_past + p.past_before[h]) * 2ull *
+                          (unsigned long long)(g.ret_cap + p.S) * (unsigned long long)p.D * 2ull;
+}
+__host__ __device__ inline unsigned long long view_v_off(const Problem &p, const CacheGeom &g, int b, int h) {
+  return view_k_off(p, g, b, h) + (unsigned long long)(g.ret_cap + p.S) * (unsigned long long)p.D * 2ull;
+}
+__host__ __device__ inline bool uses_view(const Problem &p, const CacheGeom &g, int h) {
+  return g.ret_cap > 0 && (p.policy[h] & SEGATTN_PAST);
+}
+// The block the attention kernels read for (b,h): the view in retrieval mode, else the K/V rows.
+__host__ __device__ inline unsigned long long attn_k_off(const Problem &p, const CacheGeom &g, int b, int h) {
+  return uses_view(p, g, h) ? view_k_off(p, g, b, h) : k_block_off(p, g, b, h);
+}
+__host__ __device__ inline unsigned long long attn_v_off(const Problem &p, const CacheGeom &g, int b, int h) {
+  return uses_view(p, g, h) ? view_v_off(p, g, b, h) : v_block_off(p, g, b, h);
+}
+// First row of the visible window and first row of the open segment inside the block that
+// attn_k_off / attn_v_off name.
+__host__ __device__ inline void window_of(const Problem &p, const CacheGeom &g, int h, const int *meta,
+                                          int &lo, int &seg_row0) {
   const int pol = p.policy[h];
-  if (pol & SEGATTN_PAST) {
+  if (uses_view(p, g, h)) {
+    lo = g.ret_cap - meta[META_RET];
+    seg_row0 = g.ret_cap;
+  } else if (pol & SEGATTN_PAST) {
     lo = meta[META_LO];
     seg_row0 = meta[META_POOL];
   } else {
@@ -112,6 +148,7 @@ hipError_t launch_cache_decode_append(const Problem &p, const CopyArgs &a, hipSt
 hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStream_t st);
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
                               long long n_oldest, hipStream_t st);
+hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st);
 int prefill_rows_per_workgroup(const Problem &p);
 
 }  // namespace segattn

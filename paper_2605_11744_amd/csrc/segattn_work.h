@@ -2,7 +2,8 @@
 // which (sequence, KV head, head sub-group, segment, query block), and where its keys live.
 //
 // A workgroup's keys form two spans: span 0 = the prefix the head's policy grants (carried
-// tail and/or past rows, Eq. 13; every row visible to every query of the workgroup) and
+// tail and/or past rows -- the whole pool or, in retrieval mode, the gathered rows of the
+// head's attention view -- Eq. 13; every row visible to every query of the workgroup) and
 // span 1 = the rows of the query's own segment (causal, Eq. 12's mask).
 #pragma once
 #include "segattn_internal.h"
@@ -85,13 +86,13 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   } else {  // CTX mode: prefix (and the committed part of the open segment) from the cache
     const int *meta = (const int *)(a.cache + a.geom.meta_off) + ((long long)b * p.Hkv + kv) * kMetaInts;
     int lo, seg_row0;
-    window_of(p, kv, meta, lo, seg_row0);
+    window_of(p, a.geom, kv, meta, lo, seg_row0);
     const int hi = seg_row0 + meta[META_FILL];
     const long long m = a.n_rows;
     w.n0 = hi - lo;
     w.n1 = (int)m;
-    w.k0 = (const unsigned short *)(a.cache + k_block_off(p, a.geom, b, kv)) + (long long)lo * p.D;
-    w.v0 = (const unsigned short *)(a.cache + v_block_off(p, a.geom, b, kv)) + (long long)lo * p.D;
+    w.k0 = (const unsigned short *)(a.cache + attn_k_off(p, a.geom, b, kv)) + (long long)lo * p.D;
+    w.v0 = (const unsigned short *)(a.cache + attn_v_off(p, a.geom, b, kv)) + (long long)lo * p.D;
     w.stride0 = p.D;
     w.k1 = a.k + (long long)b * m * kv_stride + (long long)kv * p.D;
     w.v1 = a.v + (long long)b * m * kv_stride + (long long)kv * p.D;

@@ -18,11 +18,13 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def config_of(w, *, fp32_check=False, out_fp32=False, past_capacity=0, batch=None, scale=0.0):
+def config_of(w, *, fp32_check=False, out_fp32=False, past_capacity=0, batch=None, scale=0.0,
+              retrieved_capacity=0):
     return sa.make_config(batch=w.batch if batch is None else batch, n_q_heads=w.n_q_heads,
                           n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, seg_len=w.seg_len,
                           tail_len=w.tail_len, kv_policy=w.kv_policy, past_capacity=past_capacity,
-                          scale=scale, fp32_check=fp32_check, out_fp32=out_fp32)
+                          scale=scale, fp32_check=fp32_check, out_fp32=out_fp32,
+                          retrieved_capacity=retrieved_capacity)
 
 
 def fwd_seq(w, q_bits, k_bits, v_bits, *, fp32_check=False, out_fp32=True, scale=0.0):
@@ -55,11 +57,12 @@ def assert_parity(o_gpu, l_gpu, o_ref, l_ref, *, fp32_check, what=""):
 class Cache:
     """A context over a torch-allocated arena."""
 
-    def __init__(self, w, *, past_capacity, fp32_check=False, out_fp32=True, batch=None, scale=0.0):
+    def __init__(self, w, *, past_capacity, fp32_check=False, out_fp32=True, batch=None, scale=0.0,
+                 retrieved_capacity=0):
         self.w = w
         self.B = w.batch if batch is None else batch
         self.cfg = config_of(w, fp32_check=fp32_check, out_fp32=out_fp32, past_capacity=past_capacity,
-                             batch=self.B, scale=scale)
+                             batch=self.B, scale=scale, retrieved_capacity=retrieved_capacity)
         self.odt = torch.float32 if (fp32_check or out_fp32) else torch.bfloat16
         self.bytes = sa.segattn_cache_bytes(self.cfg)
         assert self.bytes > 0
@@ -83,6 +86,13 @@ class Cache:
         sa.seg_kv_commit(self.ctx, k, v, m, self.stream)
         torch.cuda.synchronize()
         return to_f64(out), to_f64(lse)
+
+    def select(self, idx):
+        """idx: integer array [B, n_past, R] of pool rows; becomes the retrieved prefix."""
+        idx = np.ascontiguousarray(idx, dtype=np.int32)
+        t = torch.from_numpy(idx).cuda()
+        sa.seg_kv_past_select(self.ctx, t, idx.shape[2], self.stream)
+        torch.cuda.synchronize()
 
     def decode(self, q_bits, k_bits, v_bits):
         q, k, v = dev_bf16(q_bits), dev_bf16(k_bits), dev_bf16(v_bits)

@@ -89,6 +89,42 @@ def test_create_checks_arena_and_calls_check_state_and_pointers():
         sa.segattn_destroy(ctx)
 
 
+def test_retrieval_mode_configuration_and_select_validation():
+    """Retrieval mode (retrieved_capacity > 0): needs a PAST head, forbids TAIL|PAST, adds the
+    attention views to the arena; seg_kv_past_select checks mode, size and pool contents."""
+    plain = sa.segattn_cache_bytes(_cfg(kv_policy=[1, 2]))
+    with_views = sa.segattn_cache_bytes(_cfg(kv_policy=[1, 2], retrieved_capacity=32))
+    view_bytes = 2 * (32 + 64) * 128 * 2          # one PAST head: K and V of R_max + S rows
+    assert plain > 0 and view_bytes <= with_views - plain < view_bytes + 4096
+    for bad in (dict(kv_policy=[1, 3], retrieved_capacity=32), dict(kv_policy=[1, 0], retrieved_capacity=32),
+                dict(kv_policy=[1, 2], retrieved_capacity=-1)):
+        assert sa.segattn_cache_bytes(_cfg(**bad)) == 0
+    cfg = _cfg(kv_policy=[1, 2], retrieved_capacity=32)
+    ctx = sa.segattn_create(cfg, 4096, sa.segattn_cache_bytes(cfg))
+    try:
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_past_select(ctx, 4096, 4)             # nothing reset yet
+        assert e.value.status == sa.SEGATTN_ESTATE
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_past_select(ctx, 4096, 33)            # beyond retrieved_capacity
+        assert e.value.status == sa.SEGATTN_EINVAL
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_past_select(ctx, 0, 4)                # null list
+        assert e.value.status == sa.SEGATTN_EINVAL
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_set_lengths(ctx, [64], [16], [3])     # open segment cannot be declared here
+        assert e.value.status == sa.SEGATTN_EINVAL
+    finally:
+        sa.segattn_destroy(ctx)
+    ctx = sa.segattn_create(_cfg(), 4096, sa.segattn_cache_bytes(_cfg()))
+    try:
+        with pytest.raises(sa.SegattnError) as e:
+            sa.seg_kv_past_select(ctx, 4096, 4)             # context is not in retrieval mode
+        assert e.value.status == sa.SEGATTN_EINVAL
+    finally:
+        sa.segattn_destroy(ctx)
+
+
 def test_fwd_seq_validates_before_launching():
     cfg = _cfg()
     with pytest.raises(sa.SegattnError) as e:
