@@ -167,6 +167,7 @@ def main() -> int:
 
     if not args.no_extras:
         result["streaming"] = streaming_leg(sa, W, w, q, k, v, out, lse, flops)
+        result["retrieval"] = retrieval_leg(sa, W, w, q, k, v, out)
         del q, k, v, out, lse
         torch.cuda.empty_cache()
         result["decode"] = decode_leg(sa, W)
@@ -207,6 +208,62 @@ def streaming_leg(sa, W, w, q, k, v, out, lse, flops):
     ms = (time.perf_counter() - t0) * 1e3 / reps
     res = {"ms": round(ms, 3), "tflops_useful": round(flops / ms / 1e9, 2),
            "resident_kv_bytes": sa.segattn_resident_bytes(ctx), "arena_bytes": nbytes}
+    sa.segattn_destroy(ctx)
+    return res
+
+
+def retrieval_leg(sa, W, w, q, k, v, out, R=512):
+    """The paper's own long-range channel on the same 128K inputs (Sec. 3.4; Appendix F: R = 512):
+    PAST heads see R gathered pool rows + their segment instead of the whole history.  Per
+    segment: seg_kv_past_select (gather), seg_attn_fwd, seg_kv_commit.  The index lists are
+    seeded random distinct pool rows, drawn before the timed region (choosing them -- the top-k
+    scoring of Appendix D -- is not part of this path)."""
+    import torch
+    N, S, T = w.seq_len, w.seg_len, w.tail_len
+    policy = [2 if (p & 2) else p for p in w.kv_policy]       # long-range heads: retrieved prefix only
+    n_past = sum(1 for p in policy if p & 2)
+    cfg = sa.make_config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seg_len=S, tail_len=T, kv_policy=policy, past_capacity=N, retrieved_capacity=R)
+    nbytes = sa.segattn_cache_bytes(cfg)
+    arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ctx = sa.segattn_create(cfg, arena, nbytes)
+    stream = torch.cuda.current_stream().cuda_stream
+    lse_seg = torch.empty((w.batch, w.n_q_heads, S), dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(w.seed)
+    lists = {}
+    for s in range(S, N, S):
+        r = min(R, s)
+        lists[s] = torch.stack([torch.randperm(s, device="cuda", generator=g)[:r] for _ in range(w.batch * n_past)]) \
+            .to(torch.int32).view(w.batch, n_past, r).contiguous()
+    gq = w.n_q_heads // w.n_kv_heads
+    pairs = 0
+    for s in range(0, N, S):
+        m = min(S, N - s)
+        for p in policy:
+            prefix = min(R, s) if (p & 2) else (min(T, s) if (p & 1) else 0)
+            pairs += gq * (m * (m + 1) // 2 + m * prefix)
+    flops = 4 * w.head_dim * pairs * w.batch
+
+    def run():
+        sa.segattn_reset(ctx, stream)
+        for s in range(0, N, S):
+            m = min(S, N - s)
+            if s:
+                sa.seg_kv_past_select(ctx, lists[s], lists[s].shape[2], stream)
+            sa.seg_attn_fwd(ctx, q[:, s:s + m], k[:, s:s + m], v[:, s:s + m], m, out[:, s:s + m], lse_seg, stream)
+            sa.seg_kv_commit(ctx, k[:, s:s + m], v[:, s:s + m], m, stream)
+
+    run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 3
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / reps
+    res = {"R": R, "kv_policy": policy, "ms": round(ms, 3), "useful_flops": flops,
+           "tflops_useful": round(flops / ms / 1e9, 2), "resident_kv_bytes": sa.segattn_resident_bytes(ctx),
+           "arena_bytes": nbytes}
     sa.segattn_destroy(ctx)
     return res
 
