@@ -33,6 +33,8 @@ Readings taken where the paper is silent (each is repeated in the design notes):
 Everything is written over absolute token positions with an explicit boolean mask per
 query row, dense scores over all N keys, -inf where masked, and a plain softmax.
 Inputs are bf16 bit patterns (uint16) or floats; bf16 is widened exactly to fp64.
+attend_backward() is the gradient of the same definition (dQ, dK, dV), with gradient stopped
+where the paper stops it (past rows are forward-only; the carried tail is differentiable).
 All pins for this file live in tests/test_oracle_*.py; no function here is unpinned.
 """
 from __future__ import annotations
@@ -168,6 +170,66 @@ def decode_attend(q, k_ctx, v_ctx, *, seg_len: int, tail_len: int, kv_policy: Se
     o, l = attend(qfull, k_ctx[None], v_ctx[None], seg_len=seg_len, tail_len=tail_len,
                   kv_policy=kv_policy, scale=scale, rows=[n - 1], evicted=evicted, retrieved=ret)
     return o[0, 0], l[0, :, 0]
+
+
+def differentiable_mask(p: int, n: int, seg_len: int, tail_len: int, policy: int) -> np.ndarray:
+    """Boolean [n]: the keys of query position p through which gradient flows into K and V.
+    The own segment and, for a head with the TAIL bit, the carried tail C_{i-1} (the
+    differentiable interface state of Sec. 3.2: with truncation depth K >= 1 the loss of
+    segment i reaches the update that produced C_{i-1}).  Past rows reached only through the
+    PAST bit are forward-only (Lemma "No-gradient retrieval prefix", Appendix B): they shape
+    the softmax but receive no gradient."""
+    s = (p // seg_len) * seg_len
+    j = np.arange(n)
+    diff = (j >= s) & (j <= p)
+    if policy & POLICY_TAIL:
+        diff |= (j >= max(0, s - tail_len)) & (j < s)
+    return diff
+
+
+def attend_backward(q, k, v, dout, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
+                    scale: Optional[float] = None, evicted: Optional[Sequence[int]] = None,
+                    max_block_bytes: int = 1 << 28):
+    """Gradients of L = sum(O * dout) for O = attend(q, k, v) (Eq. 12 under the mask of Eq. 13),
+    with the stop-gradient placement of Definition "K-truncated consistent objective" and of
+    the no-gradient lemma: every visible key contributes to dQ; dK and dV collect only the
+    pairs of differentiable_mask().
+
+    With P = softmax(scale * Q K^T + M), dP = dout V^T, delta_i = sum_j P_ij dP_ij and
+    dS = P * (dP - delta):   dQ = scale * dS K,   dK = scale * (dS * G)^T Q,   dV = (P * G)^T dout,
+    G the 0/1 matrix of differentiable pairs.  q, dout [B,N,Hq,D]; k, v [B,N,Hkv,D]; returns
+    dQ [B,N,Hq,D], dK, dV [B,N,Hkv,D] in float64 (the g query heads of a group add up)."""
+    q, k, v, dout = widen(q), widen(k), widen(v), widen(dout)
+    B, N, Hq, D = q.shape
+    Hkv = k.shape[2]
+    if k.shape != (B, N, Hkv, D) or v.shape != k.shape or dout.shape != q.shape:
+        raise ValueError("shape mismatch")
+    if Hq % Hkv or len(kv_policy) != Hkv:
+        raise ValueError("bad head configuration")
+    g = Hq // Hkv
+    scale = 1.0 / np.sqrt(D) if scale is None else float(scale)
+    ev = [0] * Hkv if evicted is None else [int(e) for e in evicted]
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    step = max(1, int(max_block_bytes // (8 * max(N, 1))))
+    for kvh in range(Hkv):
+        pol = int(kv_policy[kvh])
+        for r0 in range(0, N, step):
+            rr = np.arange(r0, min(N, r0 + step))
+            mask = np.stack([visible_mask(int(p), N, seg_len, tail_len, pol, ev[kvh]) for p in rr])
+            grad = np.stack([differentiable_mask(int(p), N, seg_len, tail_len, pol) for p in rr])
+            for b in range(B):
+                kb, vb = k[b, :, kvh, :], v[b, :, kvh, :]
+                for h in range(kvh * g, (kvh + 1) * g):
+                    z = np.where(mask, (q[b, rr, h, :] @ kb.T) * scale, -np.inf)
+                    e = np.exp(z - z.max(axis=1, keepdims=True))
+                    pr = e / e.sum(axis=1, keepdims=True)
+                    dp = dout[b, rr, h, :] @ vb.T
+                    delta = (pr * dp).sum(axis=1, keepdims=True)
+                    ds = pr * (dp - delta)
+                    dq[b, rr, h, :] = scale * (ds @ kb)
+                    dk[b, :, kvh, :] += scale * ((ds * grad).T @ q[b, rr, h, :])
+                    dv[b, :, kvh, :] += (pr * grad).T @ dout[b, rr, h, :]
+    return dq, dk, dv
 
 
 def visible_pairs(n: int, seg_len: int, tail_len: int, policy: int, evicted: int = 0) -> int:

@@ -37,6 +37,14 @@ MUTANTS = {
     "retrieved_of_first_sequence_for_all": ("retrieved.get((b, kvh, int(p) // seg_len), ())", "retrieved.get((0, kvh, int(p) // seg_len), ())"),
     "retrieved_duplicates_accepted": ("if np.unique(idx).size != idx.size:", "if False:"),
     "decode_retrieved_of_next_segment": ("{(0, h, (n - 1) // seg_len): idx", "{(0, h, n // seg_len): idx"),
+    "bwd_gradient_into_past_rows": ("dk[b, :, kvh, :] += scale * ((ds * grad).T @ q[b, rr, h, :])", "dk[b, :, kvh, :] += scale * ((ds * mask).T @ q[b, rr, h, :])"),
+    "bwd_value_gradient_into_past_rows": ("(pr * grad).T @ dout[b, rr, h, :]", "(pr * mask).T @ dout[b, rr, h, :]"),
+    "bwd_tail_not_differentiable": ("        diff |= (j >= max(0, s - tail_len)) & (j < s)", "        pass"),
+    "bwd_delta_dropped": ("ds = pr * (dp - delta)", "ds = pr * dp"),
+    "bwd_dq_scale_dropped": ("dq[b, rr, h, :] = scale * (ds @ kb)", "dq[b, rr, h, :] = (ds @ kb)"),
+    "bwd_dk_uses_dout": ("((ds * grad).T @ q[b, rr, h, :])", "((ds * grad).T @ dout[b, rr, h, :])"),
+    "bwd_dp_from_keys": ("dp = dout[b, rr, h, :] @ vb.T", "dp = dout[b, rr, h, :] @ kb.T"),
+    "bwd_group_heads_overwrite": ("dv[b, :, kvh, :] += (pr * grad)", "dv[b, :, kvh, :] = (pr * grad)"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 

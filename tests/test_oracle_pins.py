@@ -415,3 +415,113 @@ def test_retrieved_prefix_decode_row_and_bad_lists():
         orc.attend(q, k, v, seg_len=S, tail_len=0, kv_policy=[2], retrieved={(0, 0, 1): [8]})
     with pytest.raises(ValueError):   # the same row twice would double its weight
         orc.attend(q, k, v, seg_len=S, tail_len=0, kv_policy=[2], retrieved={(0, 0, 1): [3, 3]})
+
+
+# ---------------------------------------------------------------- backward
+# Definition "K-truncated consistent objective" (Sec. 3.2) and the no-gradient lemma of
+# Appendix B: the carried tail is differentiable, past rows are constants.  The reference is a
+# scalar-loop forward in which the past rows come from separate, constant copies of K and V,
+# differentiated numerically; it shares nothing with the oracle's formulas.
+def split_forward_loss(q, k, v, k_const, v_const, gout, S, T, policy, scale):
+    """sum(O * gout) for one head; a key seen through the tail or the own segment is read from
+    (k, v), a key seen only through the PAST bit from (k_const, v_const)."""
+    n, d = q.shape
+    total = 0.0
+    for p in range(n):
+        s = (p // S) * S
+        keys = []
+        for j in range(0, p + 1):
+            in_seg = j >= s
+            in_tail = (policy & 1) and max(0, s - T) <= j < s
+            in_past = (policy & 2) and j < s
+            if in_seg or in_tail:
+                keys.append((k[j], v[j]))
+            elif in_past:
+                keys.append((k_const[j], v_const[j]))
+        z = np.array([scale * float(np.dot(q[p], kj)) for kj, _ in keys])
+        w = np.exp(z - z.max())
+        w /= w.sum()
+        o = sum(wi * vj for wi, (_, vj) in zip(w, keys))
+        total += float(np.dot(o, gout[p]))
+    return total
+
+
+def _numeric_grad(f, x, eps=1e-6):
+    gr = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + eps
+        fp = f()
+        x[i] = old - eps
+        fm = f()
+        x[i] = old
+        gr[i] = (fp - fm) / (2 * eps)
+    return gr
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+@pytest.mark.parametrize("S,T,n", [(4, 2, 11), (5, 5, 12), (16, 3, 9)])
+def test_backward_equals_numerical_gradient_with_past_rows_constant(policy, S, T, n):
+    d = 3
+    rng = np.random.default_rng(400 + 10 * policy + n)
+    q, k, v, go = (rng.standard_normal((n, d)) for _ in range(4))
+    kc, vc = k.copy(), v.copy()
+    scale = 0.7
+    f = lambda: split_forward_loss(q, k, v, kc, vc, go, S, T, policy, scale)
+    want = [_numeric_grad(f, x) for x in (q, k, v)]
+    got = orc.attend_backward(q[None, :, None], k[None, :, None], v[None, :, None], go[None, :, None],
+                              seg_len=S, tail_len=T, kv_policy=[policy], scale=scale)
+    for g_, w_ in zip(got, want):
+        np.testing.assert_allclose(g_[0, :, 0], w_, atol=2e-8)
+
+
+def test_backward_sums_the_query_heads_of_a_group_and_keeps_sequences_apart():
+    n, d, S, T, B, Hkv, g = 10, 2, 4, 2, 2, 2, 2
+    rng = np.random.default_rng(410)
+    q, go = rng.standard_normal((B, n, Hkv * g, d)), rng.standard_normal((B, n, Hkv * g, d))
+    k, v = rng.standard_normal((B, n, Hkv, d)), rng.standard_normal((B, n, Hkv, d))
+    pol = [1, 3]
+    dq, dk, dv = orc.attend_backward(q, k, v, go, seg_len=S, tail_len=T, kv_policy=pol)
+    for b in range(B):
+        for h in range(Hkv):
+            dk_sum, dv_sum = np.zeros((n, d)), np.zeros((n, d))
+            for hq in range(h * g, (h + 1) * g):
+                one = orc.attend_backward(q[b:b + 1, :, hq:hq + 1], k[b:b + 1, :, h:h + 1], v[b:b + 1, :, h:h + 1],
+                                          go[b:b + 1, :, hq:hq + 1], seg_len=S, tail_len=T, kv_policy=[pol[h]])
+                np.testing.assert_allclose(dq[b, :, hq], one[0][0, :, 0], atol=1e-14)
+                dk_sum += one[1][0, :, 0]
+                dv_sum += one[2][0, :, 0]
+            np.testing.assert_allclose(dk[b, :, h], dk_sum, atol=1e-13)
+            np.testing.assert_allclose(dv[b, :, h], dv_sum, atol=1e-13)
+
+
+def test_backward_closed_forms():
+    """(i) Uniform attention (Q = 0): dV_j = sum over the queries that see j of dout_i / |vis(i)|,
+    and sum_j dV_j = sum_i dout_i when every visible pair is differentiable.  (ii) dout = 0 gives
+    zero gradients.  (iii) Row blocking does not change the result.  (iv) Forward-only rows."""
+    n, d, S, T = 13, 3, 5, 2
+    rng = np.random.default_rng(420)
+    k, v, go = (rng.standard_normal((1, n, 1, d)) for _ in range(3))
+    q0 = np.zeros((1, n, 1, d))
+    dq, dk, dv = orc.attend_backward(q0, k, v, go, seg_len=S, tail_len=T, kv_policy=[1])
+    want = np.zeros((n, d))
+    for p in range(n):
+        vis = orc.visible_mask(p, n, S, T, 1)
+        want[vis] += go[0, p, 0] / vis.sum()
+    np.testing.assert_allclose(dv[0, :, 0], want, atol=1e-14)
+    np.testing.assert_allclose(dv.sum(axis=1), go.sum(axis=1), atol=1e-13)
+    q = rng.standard_normal((1, n, 1, d))
+    for gr in orc.attend_backward(q, k, v, np.zeros_like(go), seg_len=S, tail_len=T, kv_policy=[3]):
+        assert not gr.any()
+    a = orc.attend_backward(q, k, v, go, seg_len=S, tail_len=T, kv_policy=[3])
+    b = orc.attend_backward(q, k, v, go, seg_len=S, tail_len=T, kv_policy=[3], max_block_bytes=8 * n * 4)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, atol=1e-14)
+    # a PAST-only head: later segments read the rows of segment 0 forward-only, so those rows get
+    # exactly the gradient of the 5-token problem made of segment 0 alone
+    _, dk2, dv2 = orc.attend_backward(q, k, v, go, seg_len=S, tail_len=T, kv_policy=[2])
+    alone = orc.attend_backward(q[:, :S], k[:, :S], v[:, :S], go[:, :S], seg_len=S, tail_len=T, kv_policy=[0])
+    np.testing.assert_allclose(dk2[0, :S, 0], alone[1][0, :, 0], atol=1e-14)
+    np.testing.assert_allclose(dv2[0, :S, 0], alone[2][0, :, 0], atol=1e-14)
