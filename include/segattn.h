@@ -117,6 +117,24 @@ segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, cons
 segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const void *k,
                                 const void *v, int64_t n, void *out, float *lse, void *stream);
 
+/* ---- backward (training) ---------------------------------------------------------------- */
+
+/* Gradients of seg_attn_fwd_seq for truncated backpropagation over segments (Sec. 3.2,
+ * Definition "K-truncated consistent objective"): given dout = dL/dout [B,n,Hq,D] (bf16) and
+ * the forward's out and lse, writes dq [B,n,Hq,D] and dk, dv [B,n,Hkv,D] (bf16, or fp32 if
+ * cfg->out_fp32 or cfg->fp32_check; `out` has that same type).  Every visible key contributes to
+ * dq.  dk and dv collect the pairs inside a query's own segment and, for a head with the TAIL
+ * bit, its carried tail -- the differentiable interface state; rows a query reaches only through
+ * the PAST bit are forward-only and receive nothing (no-gradient lemma, Appendix B).  A window
+ * of K+1 segments passed as one sequence is therefore exactly the graph truncation depth K
+ * backpropagates through.  The g query heads of a group add up in dk, dv.  workspace: device,
+ * at least seg_attn_bwd_workspace_bytes(cfg, n) bytes, 256-byte aligned, overwritten. */
+size_t seg_attn_bwd_workspace_bytes(const segattn_config *cfg, int64_t n);
+segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const void *k,
+                                const void *v, const void *out, const float *lse,
+                                const void *dout, int64_t n, void *dq, void *dk, void *dv,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- cache operations -------------------------------------------------------------------- */
 
 /* Append m rows k,v [B,m,Hkv,D] to the open segment of every sequence.  When that makes the

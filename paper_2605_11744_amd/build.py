@@ -11,16 +11,17 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
 SOURCES = ("segattn_api.hip", "segattn_prefill_mfma.hip", "segattn_prefill_fp32.hip", "segattn_decode.hip",
-           "segattn_cache.hip")
+           "segattn_cache.hip", "segattn_bwd_fp32.hip", "segattn_bwd_mfma.hip")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # S^T products deliver their result in vector registers (where the softmax reads it); the
-    # output accumulators are pinned to accumulation registers by the kernel itself
-    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wno-unused-command-line-argument",
 )
+# Per-source extras.  Forward prefill kernel: its S^T products deliver their result in vector
+# registers (where the softmax reads it) and it pins the output accumulators to accumulation
+# registers itself.  Every other file keeps the compiler's default MFMA register form.
+EXTRA_FLAGS = {"segattn_prefill_mfma.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1")}
 
 
 def hipcc() -> str:
@@ -38,7 +39,7 @@ def build(verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
-        cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        cmd = [hipcc(), *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, ()), "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

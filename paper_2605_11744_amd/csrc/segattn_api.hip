@@ -198,6 +198,39 @@ segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const 
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
 }
 
+size_t seg_attn_bwd_workspace_bytes(const segattn_config *cfg, int64_t n) {
+  Problem p;
+  if (!build_problem(cfg, false, p) || n < 1 || n >= (1ll << 31) - 4096) return 0;
+  return (size_t)align_up((unsigned long long)p.B * p.Hq * (unsigned long long)n * 4ull);
+}
+
+segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const void *k, const void *v,
+                                const void *out, const float *lse, const void *dout, int64_t n, void *dq,
+                                void *dk, void *dv, void *workspace, size_t workspace_bytes, void *stream) {
+  Problem p;
+  if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return SEGATTN_EINVAL;
+  if (n < 1 || n >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
+  if (workspace_bytes < seg_attn_bwd_workspace_bytes(cfg, n) || ((uintptr_t)workspace % kAlign))
+    return SEGATTN_EINVAL;
+  BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.dout = (const unsigned short *)dout;
+  a.out = out;
+  a.lse = lse;
+  a.delta = (float *)workspace;
+  a.dq = dq;
+  a.dk = dk;
+  a.dv = dv;
+  a.n = (int)n;
+  const hipStream_t st = (hipStream_t)stream;
+  if (launch_bwd_delta(p, a, st) != hipSuccess) return SEGATTN_EHIP;
+  return hip_status(p.fp32_math ? launch_bwd_fp32(p, a, st) : launch_bwd_mfma(p, a, st));
+}
+
 segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int32_t m, void *stream) {
   if (!ctx || !k || !v || m < 1) return SEGATTN_EINVAL;
   if (!ctx->ready) return SEGATTN_ESTATE;

@@ -1,0 +1,411 @@
+// bf16 MFMA backward of segment-level attention for gfx950 (training with truncated
+// backpropagation over segments, Sec. 3.2).  Two kernels, no atomics, deterministic:
+//
+//   bwd_dq_kernel    a wave owns 32 query rows of one head and walks the keys it sees in steps of
+//                    32 (prefix span, then its own segment up to the diagonal):
+//                      S^T  = K . Q^T          P^T = exp2(S^T c - LSE)
+//                      dP^T = V . dO^T         dS^T = P^T (dP^T - delta)
+//                      dQ^T += K^T . dS^T      (every visible key contributes, past rows too)
+//   bwd_dkv_kernel   a wave owns 32 key rows of one KV head and walks the queries whose pair with
+//                    them is differentiable (same segment from the diagonal on; the next segment
+//                    if the keys are in its carried tail), for each query head of the group:
+//                      S  = Q . K^T            P  = exp2(S c - LSE)
+//                      dP = dO . V^T           dS = P (dP - delta)
+//                      dV^T += dO^T . P        dK^T += Q^T . dS
+//                    Rows a query reaches only through the PAST bit are forward-only (no-gradient
+//                    lemma, Appendix B): they never show up here.
+//
+// As in the forward kernel the products are arranged so that the accumulator layout of the
+// score tile (lane = its column, the lane's 16 registers = rows) is the B-operand layout of
+// the products that consume P and dS; the transposed A operands (K^T, dO^T, Q^T) come from
+// row-major LDS tiles with ds_read_b64_tr_b16.  Tiles are staged HBM -> registers -> LDS,
+// double-buffered, one barrier per step; rows are padded by 16 bytes against bank conflicts.
+// This file is compiled with the compiler's default MFMA register form (accumulators in
+// accumulation registers, placed by the register allocator); all products are builtins, so the
+// compiler tracks every MFMA hazard itself.
+#include <string.h>
+
+#include "segattn_work.h"
+
+namespace segattn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+#define LDS_AS __attribute__((address_space(3)))
+
+constexpr int kBwdStep = 32;
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int D>
+struct BwdTile {
+  static constexpr int kRowBytes = 2 * D + 16;
+  static constexpr int kBytes = kBwdStep * kRowBytes;
+  static constexpr int kChunks = D / 8;                 // 16-byte chunks per row
+  static constexpr int kLoads = kBwdStep * kChunks / 256;  // chunks per thread per tile
+};
+
+// acc += A . B
+__device__ inline void mma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+}
+
+// A operand of a transposed product from a row-major [32 x D] tile: for the 32-column block nb
+// and the 16-row half h2, k-slot e of half-wave hi is tile row 16 h2 + 8 (e/4) + 4 hi + e%4 (the
+// accumulator layout of the score tile) and the lane's operand row is tile column 32 nb + lane%32.
+template <int D>
+__device__ inline bf16x8 read_transposed(const unsigned char *tile, int lane, int nb, int h2) {
+  using T = BwdTile<D>;
+  const int hi = lane >> 5, i16 = lane & 15, g16 = (lane >> 4) & 1;
+  const int row = 4 * hi + (i16 >> 2) + 16 * h2;
+  const int colb = (32 * nb + 16 * g16 + 4 * (i16 & 3)) * 2;
+  const LDS_AS s16x4 *p0 = (const LDS_AS s16x4 *)(tile + row * T::kRowBytes + colb);
+  const LDS_AS s16x4 *p1 = (const LDS_AS s16x4 *)(tile + (row + 8) * T::kRowBytes + colb);
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)p0);
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)p1);
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// A operand of a row product: tile row lane%32, elements 16 kc + 8 (lane/32) .. +7
+template <int D>
+__device__ inline bf16x8 read_row(const unsigned char *tile, int lane, int kc) {
+  using T = BwdTile<D>;
+  return *(const bf16x8 *)(tile + (lane & 31) * T::kRowBytes + 32 * kc + 16 * (lane >> 5));
+}
+
+// Cooperative copy of rows [r0, r0+32) (clamped to r_last) of a row-major bf16 matrix with
+// `stride` elements between rows: global -> registers, registers -> LDS tile.
+template <int D>
+struct TileRegs {
+  uint4 x[BwdTile<D>::kLoads];
+};
+template <int D>
+__device__ inline void tile_fetch(TileRegs<D> &t, const unsigned short *base, long long stride, long long r0,
+                                  long long r_last, int tid) {
+  using T = BwdTile<D>;
+#pragma unroll
+  for (int i = 0; i < T::kLoads; ++i) {
+    const int c = tid + 256 * i;
+    long long r = r0 + c / T::kChunks;
+    r = r < r_last ? r : r_last;
+    t.x[i] = *(const uint4 *)(base + r * stride + (c % T::kChunks) * 8);
+  }
+}
+template <int D>
+__device__ inline void tile_store(const TileRegs<D> &t, unsigned char *tile, int tid) {
+  using T = BwdTile<D>;
+#pragma unroll
+  for (int i = 0; i < T::kLoads; ++i) {
+    const int c = tid + 256 * i;
+    *(uint4 *)(tile + (c / T::kChunks) * T::kRowBytes + (c % T::kChunks) * 16) = t.x[i];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dQ
+// ---------------------------------------------------------------------------------------------
+template <int D, int HS>
+__global__ __launch_bounds__(256, 1) void bwd_dq_kernel(const Problem p, const PrefillArgs pa, const BwdArgs a) {
+  using T = BwdTile<D>;
+  constexpr int NC = D / 16, NB = D / 32;
+  constexpr int RW = 32;             // query rows per wave
+  constexpr int BQ = (4 / HS) * RW;  // query rows per workgroup
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][T::kBytes];  // [buffer][K,V]
+
+  const WorkItem w = resolve(p, pa, blockIdx.x, BQ, HS);
+  if (!w.valid) return;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hi = lane >> 5, col = lane & 31;
+  const int head = w.kv * p.g + w.hsub * HS + (wave % HS);
+  const int tw0 = w.t0 + (wave / HS) * RW;
+  const int last_row = w.n1 - 1;
+  const float c = p.scale_log2e;
+  // global row of the segment's first token (b*N + s) and this lane's query row
+  const long long seg_row = (w.q - a.q) / ((long long)p.Hq * D);
+  int t = tw0 + col;
+  const bool row_ok = t <= last_row;
+  t = row_ok ? t : last_row;
+  const long long qoff = ((seg_row + t) * p.Hq + head) * D;
+  const long long stat = (w.lse - a.lse) + (long long)head * a.n + t;  // index into lse / delta
+  const float lse2 = a.lse[stat] * kLog2e, delta = a.delta[stat];
+
+  bf16x8 Qr[NC], Gr[NC];  // Q^T and dO^T operands: row `col`, elements 16 kc + 8 hi .. +7
+#pragma unroll
+  for (int kc = 0; kc < NC; ++kc) {
+    Qr[kc] = *(const bf16x8 *)(a.q + qoff + 16 * kc + 8 * hi);
+    Gr[kc] = *(const bf16x8 *)(a.dout + qoff + 16 * kc + 8 * hi);
+  }
+  f32x16 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+
+  const int n1_needed = (w.t0 + BQ < w.n1) ? (w.t0 + BQ) : w.n1;
+  const int nst0 = (w.n0 + kBwdStep - 1) / kBwdStep;
+  const int nst1 = (n1_needed + kBwdStep - 1) / kBwdStep;
+  const int nsteps = nst0 + nst1;
+  const int my_last = tw0 + RW - 1;  // keys of the own segment beyond this row are invisible to the wave
+
+  TileRegs<D> kr, vr;
+  auto fetch = [&](int j) {
+    if (j < nst0) {
+      tile_fetch<D>(kr, w.k0, w.stride0, (long long)j * kBwdStep, w.n0 - 1, tid);
+      tile_fetch<D>(vr, w.v0, w.stride0, (long long)j * kBwdStep, w.n0 - 1, tid);
+    } else {
+      tile_fetch<D>(kr, w.k1, w.stride1, (long long)(j - nst0) * kBwdStep, w.n1 - 1, tid);
+      tile_fetch<D>(vr, w.v1, w.stride1, (long long)(j - nst0) * kBwdStep, w.n1 - 1, tid);
+    }
+  };
+  fetch(0);
+  tile_store<D>(kr, smem[0][0], tid);
+  tile_store<D>(vr, smem[0][1], tid);
+  __syncthreads();
+  for (int j = 0; j < nsteps; ++j) {
+    const int cur = j & 1;
+    if (j + 1 < nsteps) fetch(j + 1);
+    const bool own = j >= nst0;
+    const int k0 = (own ? j - nst0 : j) * kBwdStep;           // first key of the step inside its span
+    const int span_len = own ? w.n1 : w.n0;
+    if (!own || k0 <= my_last) {
+      const unsigned char *kt = smem[cur][0], *vt = smem[cur][1];
+      f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 dP = S;
+#pragma unroll
+      for (int kc = 0; kc < NC; ++kc) {
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(kt, lane, kc), Qr[kc], S, 0, 0, 0);
+        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(vt, lane, kc), Gr[kc], dP, 0, 0, 0);
+      }
+      bf16x8 dS[2];
+      const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1;  // last visible key of the span
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        f32x8 e;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const int r = 8 * h2 + x;
+          const int key = k0 + 8 * (r / 4) + 4 * hi + r % 4;
+          const float pr = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2));
+          e[x] = key <= kmax ? pr * (dP[r] - delta) : 0.f;
+        }
+        dS[h2] = __builtin_convertvector(e, bf16x8);
+      }
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) mma_acc(acc[nb], read_transposed<D>(kt, lane, nb, h2), dS[h2]);
+    }
+    if (j + 1 < nsteps) {
+      tile_store<D>(kr, smem[cur ^ 1][0], tid);
+      tile_store<D>(vr, smem[cur ^ 1][1], tid);
+    }
+    __syncthreads();
+  }
+  if (!row_ok) return;
+  // dQ^T[d][q]: this lane holds, for its query row, d = 32 nb + 8 rg + 4 hi .. +3
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      const int d = 32 * nb + 8 * rg + 4 * hi;
+      const f32x4 o = {acc[nb][4 * rg + 0] * p.scale, acc[nb][4 * rg + 1] * p.scale,
+                       acc[nb][4 * rg + 2] * p.scale, acc[nb][4 * rg + 3] * p.scale};
+      if (p.out_fp32) *(f32x4 *)((float *)a.dq + qoff + d) = o;
+      else *(uint2 *)((unsigned short *)a.dq + qoff + d) = __builtin_bit_cast(uint2, __builtin_convertvector(o, bf16x4));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK, dV
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const BwdArgs a, const int blocks_per_seg,
+                                                         const int n_seg) {
+  using T = BwdTile<D>;
+  constexpr int NC = D / 16, NB = D / 32;
+  constexpr int BK = 128;  // key rows per workgroup
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][T::kBytes];  // [buffer][Q,dO]
+  __shared__ float stats[2][2][kBwdStep];                                       // [buffer][lse*log2e, delta]
+
+  // blockIdx -> (key block inside its segment, segment, kv head, b); blocks near the start of a
+  // segment have the most queries after them and come first
+  const int per = n_seg * p.Hkv * p.B;
+  const int kb = blockIdx.x / per;
+  int rest = blockIdx.x % per;
+  const int seg = rest % n_seg;
+  rest /= n_seg;
+  const int kv = rest % p.Hkv;
+  const int b = rest / p.Hkv;
+  const int pol = p.policy[kv];
+  const long long N = a.n;
+  const long long s0 = (long long)seg * p.S;
+  const long long seg_end = s0 + p.S < N ? s0 + p.S : N;
+  const long long j0 = s0 + (long long)kb * BK;
+  if (j0 >= seg_end) return;
+  const long long j_end = j0 + BK < seg_end ? j0 + BK : seg_end;  // keys of the workgroup: [j0, j_end)
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hi = lane >> 5, col = lane & 31;
+  const float c = p.scale_log2e;
+  // this lane's key row (clamped for loads; stores are guarded)
+  const long long jw0 = j0 + 32 * wave;
+  long long jk = jw0 + col;
+  const bool key_ok = jk < j_end;
+  jk = key_ok ? jk : j_end - 1;
+  const long long koff = ((b * N + jk) * p.Hkv + kv) * D;
+  bf16x8 Kr[NC], Vr[NC];
+#pragma unroll
+  for (int kc = 0; kc < NC; ++kc) {
+    Kr[kc] = *(const bf16x8 *)(a.k + koff + 16 * kc + 8 * hi);
+    Vr[kc] = *(const bf16x8 *)(a.v + koff + 16 * kc + 8 * hi);
+  }
+  f32x16 dKa[NB], dVa[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dKa[nb][r] = 0.f;
+      dVa[nb][r] = 0.f;
+    }
+
+  // queries: own segment from row j0 on; then, for keys in the carried tail of the next segment,
+  // all rows of that segment (one contiguous row range)
+  const long long q_begin = j0;
+  long long next_end = seg_end;
+  const long long tail_lo = seg_end - p.T;  // keys >= tail_lo are in the next segment's tail
+  if ((pol & SEGATTN_TAIL) && seg_end == s0 + p.S && j_end > tail_lo && seg_end < N)
+    next_end = seg_end + p.S < N ? seg_end + p.S : N;
+  const int steps_per_head = (int)((next_end - q_begin + kBwdStep - 1) / kBwdStep);
+  const int nsteps = steps_per_head * p.g;
+  const long long q_stride = (long long)p.Hq * D;
+
+  TileRegs<D> qr, gr;
+  float st_reg = 0.f;
+  auto fetch = [&](int it) {
+    const int hq = kv * p.g + it / steps_per_head;
+    const long long i0 = q_begin + (long long)(it % steps_per_head) * kBwdStep;
+    const unsigned short *qb = a.q + ((b * N) * p.Hq + hq) * D;
+    const unsigned short *gb = a.dout + ((b * N) * p.Hq + hq) * D;
+    tile_fetch<D>(qr, qb, q_stride, i0, next_end - 1, tid);
+    tile_fetch<D>(gr, gb, q_stride, i0, next_end - 1, tid);
+    if (tid < 2 * kBwdStep) {
+      long long i = i0 + (tid & 31);
+      i = i < next_end ? i : next_end - 1;
+      const long long idx = ((long long)b * p.Hq + hq) * N + i;
+      st_reg = tid < kBwdStep ? a.lse[idx] * kLog2e : a.delta[idx];
+    }
+  };
+  auto stash = [&](int buf) {
+    tile_store<D>(qr, smem[buf][0], tid);
+    tile_store<D>(gr, smem[buf][1], tid);
+    if (tid < 2 * kBwdStep) stats[buf][tid >> 5][tid & 31] = st_reg;
+  };
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int it = 0; it < nsteps; ++it) {
+    const int cur = it & 1;
+    if (it + 1 < nsteps) fetch(it + 1);
+    const long long i0 = q_begin + (long long)(it % steps_per_head) * kBwdStep;
+    // the wave takes part if some query of the step is at or after its first key and it has keys
+    if (jw0 < j_end && i0 + kBwdStep - 1 >= jw0) {
+      const unsigned char *qt = smem[cur][0], *gt = smem[cur][1];
+      f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 dP = S;
+#pragma unroll
+      for (int kc = 0; kc < NC; ++kc) {
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(qt, lane, kc), Kr[kc], S, 0, 0, 0);
+        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(gt, lane, kc), Vr[kc], dP, 0, 0, 0);
+      }
+      bf16x8 Pb[2], dSb[2];
+      const long long jq = jw0 + col;  // this lane's key (unclamped)
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        f32x8 e, f;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const int r = 8 * h2 + x;
+          const int rr = 8 * (r / 4) + 4 * hi + r % 4;  // query row inside the step
+          const long long i = i0 + rr;
+          // differentiable pair: same segment and causal, or next segment and key in its tail
+          const bool ok = jq < j_end && i < next_end && (i < seg_end ? i >= jq : jq >= tail_lo);
+          const float pr = __builtin_amdgcn_exp2f(fmaf(S[r], c, -stats[cur][0][rr]));
+          e[x] = ok ? pr : 0.f;
+          f[x] = ok ? pr * (dP[r] - stats[cur][1][rr]) : 0.f;
+        }
+        Pb[h2] = __builtin_convertvector(e, bf16x8);
+        dSb[h2] = __builtin_convertvector(f, bf16x8);
+      }
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          mma_acc(dVa[nb], read_transposed<D>(gt, lane, nb, h2), Pb[h2]);
+          mma_acc(dKa[nb], read_transposed<D>(qt, lane, nb, h2), dSb[h2]);
+        }
+    }
+    if (it + 1 < nsteps) stash(cur ^ 1);
+    __syncthreads();
+  }
+  if (!key_ok) return;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      const int d = 32 * nb + 8 * rg + 4 * hi;
+      const f32x4 gk = {dKa[nb][4 * rg + 0] * p.scale, dKa[nb][4 * rg + 1] * p.scale,
+                        dKa[nb][4 * rg + 2] * p.scale, dKa[nb][4 * rg + 3] * p.scale};
+      const f32x4 gv = {dVa[nb][4 * rg + 0], dVa[nb][4 * rg + 1], dVa[nb][4 * rg + 2],
+                        dVa[nb][4 * rg + 3]};
+      if (p.out_fp32) {
+        *(f32x4 *)((float *)a.dk + koff + d) = gk;
+        *(f32x4 *)((float *)a.dv + koff + d) = gv;
+      } else {
+        *(uint2 *)((unsigned short *)a.dk + koff + d) = __builtin_bit_cast(uint2, __builtin_convertvector(gk, bf16x4));
+        *(uint2 *)((unsigned short *)a.dv + koff + d) = __builtin_bit_cast(uint2, __builtin_convertvector(gv, bf16x4));
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launch
+// ---------------------------------------------------------------------------------------------
+static int bwd_heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1; }
+
+template <int D>
+static hipError_t launch_bwd_d(const Problem &p, const BwdArgs &a, hipStream_t st) {
+  const int hs = bwd_heads_per_wg(p);
+  const int rows = (4 / hs) * 32;
+  PrefillArgs pa;
+  memset(&pa, 0, sizeof(pa));
+  pa.q = a.q;
+  pa.k = a.k;
+  pa.v = a.v;
+  pa.out = a.dq;
+  pa.lse = const_cast<float *>(a.lse);
+  pa.cache = nullptr;
+  pa.n_rows = a.n;
+  pa.n_seg = (a.n + p.S - 1) / p.S;
+  const long long seg_rows = a.n < p.S ? a.n : p.S;
+  pa.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
+  const long long grid_q = (long long)p.B * p.Hkv * (p.g / hs) * pa.n_seg * pa.q_blocks_per_seg;
+  const int blocks_per_seg = (int)((seg_rows + 127) / 128);
+  const long long grid_k = (long long)p.B * p.Hkv * pa.n_seg * blocks_per_seg;
+  if (grid_q <= 0 || grid_q > 0x7fffffffLL || grid_k > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (hs == 4) hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  else if (hs == 2) hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  else hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bwd_dkv_kernel<D>, dim3((unsigned)grid_k), dim3(256), 0, st, p, a, blocks_per_seg, pa.n_seg);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st) {
+  return p.D == 128 ? launch_bwd_d<128>(p, a, st) : launch_bwd_d<64>(p, a, st);
+}
+
+}  // namespace segattn

@@ -77,6 +77,16 @@ struct CopyArgs {
   int kv_head;           // past_append: target head; otherwise unused
 };
 
+// Arguments of the backward kernels (whole-sequence form, positions absolute as in SEQ mode).
+struct BwdArgs {
+  const unsigned short *q, *k, *v, *dout;  // bf16
+  const void *out;                         // forward output: bf16, or fp32 if Problem::out_fp32
+  const float *lse;                        // [B,Hq,n]
+  float *delta;                            // [B,Hq,n] workspace: sum_d dO*O
+  void *dq, *dk, *dv;                      // bf16, or fp32 if Problem::out_fp32
+  int n;
+};
+
 struct SelectArgs {
   const int *idx;        // [B, n_past, R] pool row numbers
   unsigned char *cache;
@@ -149,6 +159,9 @@ hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStre
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
                               long long n_oldest, hipStream_t st);
 hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st);
+hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);
+hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);
+hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st);
 int prefill_rows_per_workgroup(const Problem &p);
 
 }  // namespace segattn

@@ -32,7 +32,7 @@ POLICY_PAST = 2
 
 BASE_SEED = 20260511
 _ROWS_PER_BLOCK = 4096
-_TENSOR_Q, _TENSOR_K, _TENSOR_V, _TENSOR_AUX = 0, 1, 2, 3
+_TENSOR_Q, _TENSOR_K, _TENSOR_V, _TENSOR_AUX, _TENSOR_DOUT = 0, 1, 2, 3, 4
 
 
 @dataclasses.dataclass(frozen=True)
@@ -156,6 +156,13 @@ def prefill_inputs(w: Workload, seq_len: Optional[int] = None):
                     outlier_channel_scale(w))
     v = normal_bf16(w.seed, _TENSOR_V, w.batch, n, w.n_kv_heads, w.head_dim)
     return q, k, v
+
+
+def grad_inputs(w: Workload, seq_len: Optional[int] = None) -> np.ndarray:
+    """Upstream gradient dL/dO for the backward pass: bf16 bit patterns of N(0,1) draws,
+    [B,N,Hq,D], from a stream of its own."""
+    n = w.seq_len if seq_len is None else seq_len
+    return normal_bf16(w.seed, _TENSOR_DOUT, w.batch, n, w.n_q_heads, w.head_dim)
 
 
 def decode_lengths(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
