@@ -170,6 +170,7 @@ def main() -> int:
         result["retrieval"] = retrieval_leg(sa, W, w, q, k, v, out)
         del q, k, v, out, lse
         torch.cuda.empty_cache()
+        result["backward"] = backward_leg(sa, W, w)
         result["decode"] = decode_leg(sa, W)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(W, w, qb, kb, vb)
@@ -266,6 +267,50 @@ def retrieval_leg(sa, W, w, q, k, v, out, R=512):
            "arena_bytes": nbytes}
     sa.segattn_destroy(ctx)
     return res
+
+
+def backward_leg(sa, W, w, batch=4):
+    """Training window of truncation depth K = 1 (Sec. 3.2; Appendix F: S = 4096, so 8K tokens):
+    two segments per sequence with the 128K workload's heads and policy; forward once, then
+    seg_attn_bwd_seq timed.  Useful FLOPs: 2D each for S, dP and dQ per visible pair plus 2D each
+    for dV and dK per differentiable pair (own segment and carried tail)."""
+    import torch
+    S, T, D, Hq, Hkv = w.seg_len, w.tail_len, w.head_dim, w.n_q_heads, w.n_kv_heads
+    n = 2 * S
+    cfg = sa.make_config(batch=batch, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, seg_len=S, tail_len=T,
+                         kv_policy=w.kv_policy)
+    g = torch.Generator(device="cuda").manual_seed(w.seed + 7)
+    mk = lambda h: torch.randn((batch, n, h, D), device="cuda", generator=g).to(torch.bfloat16)
+    q, k, v, go = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+    out, lse = torch.empty_like(q), torch.empty((batch, Hq, n), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    nws = sa.seg_attn_bwd_workspace_bytes(cfg, n)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    sa.seg_attn_fwd_seq(cfg, q, k, v, n, out, lse, st)
+    run = lambda: sa.seg_attn_bwd_seq(cfg, q, k, v, out, lse, go, n, dq, dk, dv, ws, nws, st)
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    gq = Hq // Hkv
+    vis = diff = 0
+    for pol in w.kv_policy:
+        for s in range(0, n, S):
+            own = S * (S + 1) // 2
+            tail = S * min(T, s) if pol & 1 else 0
+            vis += gq * (own + (S * s if pol & 2 else tail))
+            diff += gq * (own + tail)
+    flops = batch * (6 * D * vis + 4 * D * diff)
+    return {"workload": f"2 segments of {S} (truncation depth 1), batch {batch}, heads and policy of {w.name}",
+            "ms": round(ms, 3), "useful_flops": flops, "tflops_useful": round(flops / ms / 1e9, 2),
+            "frac_of_bf16_mfma_peak": round(flops / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
 
 
 def decode_leg(sa, W):

@@ -83,9 +83,10 @@ struct TileRegs {
   uint4 x[BwdTile<D>::kLoads];
 };
 template <int D>
-__device__ inline void tile_fetch(TileRegs<D> &t, const unsigned short *base, long long stride, long long r0,
-                                  long long r_last, int tid) {
+__device__ inline TileRegs<D> tile_fetch(const unsigned short *base, long long stride, long long r0,
+                                         long long r_last, int tid) {
   using T = BwdTile<D>;
+  TileRegs<D> t;
 #pragma unroll
   for (int i = 0; i < T::kLoads; ++i) {
     const int c = tid + 256 * i;
@@ -93,6 +94,7 @@ __device__ inline void tile_fetch(TileRegs<D> &t, const unsigned short *base, lo
     r = r < r_last ? r : r_last;
     t.x[i] = *(const uint4 *)(base + r * stride + (c % T::kChunks) * 8);
   }
+  return t;
 }
 template <int D>
 __device__ inline void tile_store(const TileRegs<D> &t, unsigned char *tile, int tid) {
@@ -150,27 +152,33 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_kernel(const Problem p, const P
   const int nsteps = nst0 + nst1;
   const int my_last = tw0 + RW - 1;  // keys of the own segment beyond this row are invisible to the wave
 
-  TileRegs<D> kr, vr;
-  auto fetch = [&](int j) {
-    if (j < nst0) {
-      tile_fetch<D>(kr, w.k0, w.stride0, (long long)j * kBwdStep, w.n0 - 1, tid);
-      tile_fetch<D>(vr, w.v0, w.stride0, (long long)j * kBwdStep, w.n0 - 1, tid);
-    } else {
-      tile_fetch<D>(kr, w.k1, w.stride1, (long long)(j - nst0) * kBwdStep, w.n1 - 1, tid);
-      tile_fetch<D>(vr, w.v1, w.stride1, (long long)(j - nst0) * kBwdStep, w.n1 - 1, tid);
-    }
+  // tiles of step j (clamped to the last step, whose re-fetch is not used)
+  auto fetch_k = [&](int j) {
+    j = j < nsteps ? j : nsteps - 1;
+    const bool s1 = j >= nst0;
+    return tile_fetch<D>(s1 ? w.k1 : w.k0, s1 ? w.stride1 : w.stride0, (long long)(s1 ? j - nst0 : j) * kBwdStep,
+                         (s1 ? w.n1 : w.n0) - 1, tid);
   };
-  fetch(0);
-  tile_store<D>(kr, smem[0][0], tid);
-  tile_store<D>(vr, smem[0][1], tid);
+  auto fetch_v = [&](int j) {
+    j = j < nsteps ? j : nsteps - 1;
+    const bool s1 = j >= nst0;
+    return tile_fetch<D>(s1 ? w.v1 : w.v0, s1 ? w.stride1 : w.stride0, (long long)(s1 ? j - nst0 : j) * kBwdStep,
+                         (s1 ? w.n1 : w.n0) - 1, tid);
+  };
+  {
+    const TileRegs<D> kr = fetch_k(0), vr = fetch_v(0);
+    tile_store<D>(kr, smem[0][0], tid);
+    tile_store<D>(vr, smem[0][1], tid);
+  }
   __syncthreads();
+  (void)my_last;
   for (int j = 0; j < nsteps; ++j) {
     const int cur = j & 1;
-    if (j + 1 < nsteps) fetch(j + 1);
+    const TileRegs<D> kr = fetch_k(j + 1), vr = fetch_v(j + 1);
     const bool own = j >= nst0;
     const int k0 = (own ? j - nst0 : j) * kBwdStep;           // first key of the step inside its span
     const int span_len = own ? w.n1 : w.n0;
-    if (!own || k0 <= my_last) {
+    {
       const unsigned char *kt = smem[cur][0], *vt = smem[cur][1];
       f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       f32x16 dP = S;
@@ -188,8 +196,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_kernel(const Problem p, const P
         for (int x = 0; x < 8; ++x) {
           const int r = 8 * h2 + x;
           const int key = k0 + 8 * (r / 4) + 4 * hi + r % 4;
-          const float pr = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2));
-          e[x] = key <= kmax ? pr * (dP[r] - delta) : 0.f;
+          // a masked pair gets exponent -inf: its weight is exactly 0, without a branch
+          const float pr = __builtin_amdgcn_exp2f(key <= kmax ? fmaf(S[r], c, -lse2) : -INFINITY);
+          e[x] = pr * (dP[r] - delta);
         }
         dS[h2] = __builtin_convertvector(e, bf16x8);
       }
@@ -198,10 +207,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_kernel(const Problem p, const P
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) mma_acc(acc[nb], read_transposed<D>(kt, lane, nb, h2), dS[h2]);
     }
-    if (j + 1 < nsteps) {
-      tile_store<D>(kr, smem[cur ^ 1][0], tid);
-      tile_store<D>(vr, smem[cur ^ 1][1], tid);
-    }
+    tile_store<D>(kr, smem[cur ^ 1][0], tid);
+    tile_store<D>(vr, smem[cur ^ 1][1], tid);
     __syncthreads();
   }
   if (!row_ok) return;
@@ -228,7 +235,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   constexpr int NC = D / 16, NB = D / 32;
   constexpr int BK = 128;  // key rows per workgroup
   __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][T::kBytes];  // [buffer][Q,dO]
-  __shared__ float stats[2][2][kBwdStep];                                       // [buffer][lse*log2e, delta]
+  __shared__ __attribute__((aligned(16))) float stats[2][2][kBwdStep];                                       // [buffer][lse*log2e, delta]
 
   // blockIdx -> (key block inside its segment, segment, kv head, b); blocks near the start of a
   // segment have the most queries after them and come first
@@ -282,36 +289,43 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   const int nsteps = steps_per_head * p.g;
   const long long q_stride = (long long)p.Hq * D;
 
-  TileRegs<D> qr, gr;
-  float st_reg = 0.f;
-  auto fetch = [&](int it) {
+  // per-lane bounds of the differentiable queries, as offsets from q_begin: rows [q_lo, q_lim).
+  // Own segment: causal, i >= key.  Next segment: every row, if the key is in its carried tail.
+  const long long jq = jw0 + col;
+  const int q_lo = (int)(jq - q_begin);
+  const int q_lim = jq < j_end ? (int)((jq >= tail_lo ? next_end : seg_end) - q_begin) : 0;
+
+  auto fetch_tile = [&](const unsigned short *base, int it) {
+    it = it < nsteps ? it : nsteps - 1;  // the re-fetch after the last step is not used
     const int hq = kv * p.g + it / steps_per_head;
     const long long i0 = q_begin + (long long)(it % steps_per_head) * kBwdStep;
-    const unsigned short *qb = a.q + ((b * N) * p.Hq + hq) * D;
-    const unsigned short *gb = a.dout + ((b * N) * p.Hq + hq) * D;
-    tile_fetch<D>(qr, qb, q_stride, i0, next_end - 1, tid);
-    tile_fetch<D>(gr, gb, q_stride, i0, next_end - 1, tid);
-    if (tid < 2 * kBwdStep) {
-      long long i = i0 + (tid & 31);
-      i = i < next_end ? i : next_end - 1;
-      const long long idx = ((long long)b * p.Hq + hq) * N + i;
-      st_reg = tid < kBwdStep ? a.lse[idx] * kLog2e : a.delta[idx];
-    }
+    return tile_fetch<D>(base + ((b * N) * p.Hq + hq) * D, q_stride, i0, next_end - 1, tid);
   };
-  auto stash = [&](int buf) {
-    tile_store<D>(qr, smem[buf][0], tid);
-    tile_store<D>(gr, smem[buf][1], tid);
-    if (tid < 2 * kBwdStep) stats[buf][tid >> 5][tid & 31] = st_reg;
+  auto fetch_stat = [&](int it) {
+    it = it < nsteps ? it : nsteps - 1;
+    const int hq = kv * p.g + it / steps_per_head;
+    long long i = q_begin + (long long)(it % steps_per_head) * kBwdStep + (tid & 31);
+    i = i < next_end ? i : next_end - 1;
+    const long long idx = ((long long)b * p.Hq + hq) * N + i;
+    float x = 0.f;
+    if (tid < kBwdStep) x = a.lse[idx] * kLog2e;
+    else if (tid < 2 * kBwdStep) x = a.delta[idx];
+    return x;
   };
-  fetch(0);
-  stash(0);
+  {
+    const TileRegs<D> qr = fetch_tile(a.q, 0), gr = fetch_tile(a.dout, 0);
+    const float sr = fetch_stat(0);
+    tile_store<D>(qr, smem[0][0], tid);
+    tile_store<D>(gr, smem[0][1], tid);
+    if (tid < 2 * kBwdStep) stats[0][tid >> 5][tid & 31] = sr;
+  }
   __syncthreads();
   for (int it = 0; it < nsteps; ++it) {
     const int cur = it & 1;
-    if (it + 1 < nsteps) fetch(it + 1);
-    const long long i0 = q_begin + (long long)(it % steps_per_head) * kBwdStep;
-    // the wave takes part if some query of the step is at or after its first key and it has keys
-    if (jw0 < j_end && i0 + kBwdStep - 1 >= jw0) {
+    const TileRegs<D> qr = fetch_tile(a.q, it + 1), gr = fetch_tile(a.dout, it + 1);
+    const float sr = fetch_stat(it + 1);
+    const int i_rel0 = (it % steps_per_head) * kBwdStep;
+    {
       const unsigned char *qt = smem[cur][0], *gt = smem[cur][1];
       f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       f32x16 dP = S;
@@ -321,7 +335,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
         dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(gt, lane, kc), Vr[kc], dP, 0, 0, 0);
       }
       bf16x8 Pb[2], dSb[2];
-      const long long jq = jw0 + col;  // this lane's key (unclamped)
+      f32x4 lse4[4], del4[4];  // row statistics of the lane's 16 query rows: rows 8 g + 4 hi .. +3
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        lse4[g4] = *(const f32x4 *)&stats[cur][0][8 * g4 + 4 * hi];
+        del4[g4] = *(const f32x4 *)&stats[cur][1][8 * g4 + 4 * hi];
+      }
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
         f32x8 e, f;
@@ -329,12 +348,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
         for (int x = 0; x < 8; ++x) {
           const int r = 8 * h2 + x;
           const int rr = 8 * (r / 4) + 4 * hi + r % 4;  // query row inside the step
-          const long long i = i0 + rr;
-          // differentiable pair: same segment and causal, or next segment and key in its tail
-          const bool ok = jq < j_end && i < next_end && (i < seg_end ? i >= jq : jq >= tail_lo);
-          const float pr = __builtin_amdgcn_exp2f(fmaf(S[r], c, -stats[cur][0][rr]));
-          e[x] = ok ? pr : 0.f;
-          f[x] = ok ? pr * (dP[r] - stats[cur][1][rr]) : 0.f;
+          const int i_rel = i_rel0 + rr;
+          const bool ok = (i_rel >= q_lo) & (i_rel < q_lim);
+          // a masked pair gets exponent -inf: its weight is exactly 0, without a branch
+          const float pr = __builtin_amdgcn_exp2f(ok ? fmaf(S[r], c, -lse4[r / 4][r % 4]) : -INFINITY);
+          e[x] = pr;
+          f[x] = pr * (dP[r] - del4[r / 4][r % 4]);
         }
         Pb[h2] = __builtin_convertvector(e, bf16x8);
         dSb[h2] = __builtin_convertvector(f, bf16x8);
@@ -347,7 +366,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
           mma_acc(dKa[nb], read_transposed<D>(qt, lane, nb, h2), dSb[h2]);
         }
     }
-    if (it + 1 < nsteps) stash(cur ^ 1);
+    tile_store<D>(qr, smem[cur ^ 1][0], tid);
+    tile_store<D>(gr, smem[cur ^ 1][1], tid);
+    if (tid < 2 * kBwdStep) stats[cur ^ 1][tid >> 5][tid & 31] = sr;
     __syncthreads();
   }
   if (!key_ok) return;
