@@ -35,6 +35,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
 
 constexpr int kBwdStep = 32;
@@ -51,6 +52,18 @@ struct BwdTile {
 // acc += A . B
 __device__ inline void mma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+}
+
+// Move four dwords into accumulation registers; the result is used as an MFMA operand only.
+__device__ inline bf16x8 park(const uint4 v) {
+  int a0, a1, a2, a3;
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a0) : "v"(v.x));
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a1) : "v"(v.y));
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a2) : "v"(v.z));
+  asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a3) : "v"(v.w));
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  const i32x4 q4 = {a0, a1, a2, a3};
+  return __builtin_bit_cast(bf16x8, q4);
 }
 
 // A operand of a transposed product from a row-major [32 x D] tile: for the 32-column block nb
@@ -263,11 +276,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   const bool key_ok = jk < j_end;
   jk = key_ok ? jk : j_end - 1;
   const long long koff = ((b * N + jk) * p.Hkv + kv) * D;
+  // K^T and V^T operands of this lane's key: only ever MFMA operands, so they are parked in
+  // accumulation registers and the vector registers stay free for operand prefetch
   bf16x8 Kr[NC], Vr[NC];
 #pragma unroll
   for (int kc = 0; kc < NC; ++kc) {
-    Kr[kc] = *(const bf16x8 *)(a.k + koff + 16 * kc + 8 * hi);
-    Vr[kc] = *(const bf16x8 *)(a.v + koff + 16 * kc + 8 * hi);
+    Kr[kc] = park(*(const uint4 *)(a.k + koff + 16 * kc + 8 * hi));
+    Vr[kc] = park(*(const uint4 *)(a.v + koff + 16 * kc + 8 * hi));
   }
   f32x16 dKa[NB], dVa[NB];
 #pragma unroll
@@ -295,52 +310,122 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   const int q_lo = (int)(jq - q_begin);
   const int q_lim = jq < j_end ? (int)((jq >= tail_lo ? next_end : seg_end) - q_begin) : 0;
 
-  auto fetch_tile = [&](const unsigned short *base, int it) {
-    it = it < nsteps ? it : nsteps - 1;  // the re-fetch after the last step is not used
-    const int hq = kv * p.g + it / steps_per_head;
-    const long long i0 = q_begin + (long long)(it % steps_per_head) * kBwdStep;
-    return tile_fetch<D>(base + ((b * N) * p.Hq + hq) * D, q_stride, i0, next_end - 1, tid);
-  };
-  auto fetch_stat = [&](int it) {
-    it = it < nsteps ? it : nsteps - 1;
-    const int hq = kv * p.g + it / steps_per_head;
-    long long i = q_begin + (long long)(it % steps_per_head) * kBwdStep + (tid & 31);
-    i = i < next_end ? i : next_end - 1;
-    const long long idx = ((long long)b * p.Hq + hq) * N + i;
-    float x = 0.f;
-    if (tid < kBwdStep) x = a.lse[idx] * kLog2e;
-    else if (tid < 2 * kBwdStep) x = a.delta[idx];
-    return x;
-  };
-  {
-    const TileRegs<D> qr = fetch_tile(a.q, 0), gr = fetch_tile(a.dout, 0);
-    const float sr = fetch_stat(0);
-    tile_store<D>(qr, smem[0][0], tid);
-    tile_store<D>(gr, smem[0][1], tid);
-    if (tid < 2 * kBwdStep) stats[0][tid >> 5][tid & 31] = sr;
+  // Wave-uniform bounds: a step whose 32 queries all lie in [q_lo_max, q_lim_min) needs no masks.
+  const int q_lo_max = (int)(jw0 + 31 - q_begin);
+  int q_lim_min = q_lim;
+#pragma unroll
+  for (int sh = 32; sh >= 1; sh >>= 1) q_lim_min = min(q_lim_min, __shfl_xor(q_lim_min, sh));
+  q_lim_min = __builtin_amdgcn_readfirstlane(q_lim_min);
+
+  // Fetch cursor: tiles are fetched in step order (query head major), one call per step; calls
+  // beyond the last step repeat it (their data is never used).
+  int f_head = 0, f_step = 0;
+  const long long head0_q = ((b * N) * p.Hq + (long long)kv * p.g) * D;   // element offset of (b, row 0, first head)
+  const long long head0_s = ((long long)b * p.Hq + (long long)kv * p.g) * N;
+  int f_row[T::kLoads], f_col[T::kLoads];
+#pragma unroll
+  for (int i = 0; i < T::kLoads; ++i) {
+    f_row[i] = (tid + 256 * i) / T::kChunks;
+    f_col[i] = ((tid + 256 * i) % T::kChunks) * 8;
   }
+  const int last_rel = (int)(next_end - 1 - q_begin);
+  // (a macro rather than a lambda: register arrays handed to a lambda by reference end up in
+  // scratch memory)
+  u32x4 nq[T::kLoads], ng[T::kLoads];  // tile rows in flight: Q and dO (native vectors: they stay in registers)
+  float ns = 0.f;                      // and this thread's row statistic
+#define SEGATTN_BWD_FETCH_NEXT()                                                                      \
+  do {                                                                                                \
+    const int r0_ = f_step * kBwdStep;                                                                \
+    const unsigned short *qb_ = a.q + head0_q + (long long)f_head * D + q_begin * q_stride;           \
+    const unsigned short *gb_ = a.dout + head0_q + (long long)f_head * D + q_begin * q_stride;        \
+    _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                        \
+      int r_ = r0_ + f_row[i_];                                                                       \
+      r_ = r_ < last_rel ? r_ : last_rel;                                                             \
+      nq[i_] = *(const u32x4 *)(qb_ + (long long)r_ * q_stride + f_col[i_]);                          \
+      ng[i_] = *(const u32x4 *)(gb_ + (long long)r_ * q_stride + f_col[i_]);                          \
+    }                                                                                                 \
+    if (tid < 2 * kBwdStep) {                                                                         \
+      int r_ = r0_ + (tid & 31);                                                                      \
+      r_ = r_ < last_rel ? r_ : last_rel;                                                             \
+      const long long idx_ = head0_s + (long long)f_head * N + q_begin + r_;                          \
+      ns = tid < kBwdStep ? a.lse[idx_] * kLog2e : a.delta[idx_];                                     \
+    }                                                                                                 \
+    if (!(f_head == p.g - 1 && f_step == steps_per_head - 1)) {                                       \
+      f_step += 1;                                                                                    \
+      if (f_step == steps_per_head) {                                                                 \
+        f_step = 0;                                                                                   \
+        f_head += 1;                                                                                  \
+      }                                                                                               \
+    }                                                                                                 \
+  } while (0)
+#define SEGATTN_BWD_STASH(buf)                                                                        \
+  do {                                                                                                \
+    _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                        \
+      const int off_ = f_row[i_] * T::kRowBytes + f_col[i_] * 2;                                      \
+      *(u32x4 *)(smem[buf][0] + off_) = nq[i_];                                                       \
+      *(u32x4 *)(smem[buf][1] + off_) = ng[i_];                                                       \
+    }                                                                                                 \
+    if (tid < 2 * kBwdStep) stats[buf][tid >> 5][tid & 31] = ns;                                      \
+  } while (0)
+
+  // Software pipeline over the steps.  During step `it` the tile of step it+1 is written to the
+  // other LDS buffer (fetched into registers one step earlier) and the tile of step it+2 is
+  // fetched from HBM; one barrier in the middle of the step publishes tile it+1, after which the
+  // row operands of step it+1 are read under the last products of step `it`.
+  SEGATTN_BWD_FETCH_NEXT();
+  SEGATTN_BWD_STASH(0);
+  SEGATTN_BWD_FETCH_NEXT();
   __syncthreads();
+  bf16x8 qa[NC], ga[NC];  // row operands of the current step
+#pragma unroll
+  for (int kc = 0; kc < NC; ++kc) {
+    qa[kc] = read_row<D>(smem[0][0], lane, kc);
+    ga[kc] = read_row<D>(smem[0][1], lane, kc);
+  }
+  int i_rel0 = 0;  // first query of the step, relative to q_begin
   for (int it = 0; it < nsteps; ++it) {
     const int cur = it & 1;
-    const TileRegs<D> qr = fetch_tile(a.q, it + 1), gr = fetch_tile(a.dout, it + 1);
-    const float sr = fetch_stat(it + 1);
-    const int i_rel0 = (it % steps_per_head) * kBwdStep;
-    {
-      const unsigned char *qt = smem[cur][0], *gt = smem[cur][1];
-      f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 dP = S;
+    const unsigned char *qt = smem[cur][0], *gt = smem[cur][1];
+    SEGATTN_BWD_STASH(cur ^ 1);
+    SEGATTN_BWD_FETCH_NEXT();
+    __builtin_amdgcn_sched_barrier(0);
+    // S, dP; behind them the transposed operands of the first 16 queries and the row statistics
+    f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 dP = S;
 #pragma unroll
-      for (int kc = 0; kc < NC; ++kc) {
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(qt, lane, kc), Kr[kc], S, 0, 0, 0);
-        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(gt, lane, kc), Vr[kc], dP, 0, 0, 0);
-      }
-      bf16x8 Pb[2], dSb[2];
-      f32x4 lse4[4], del4[4];  // row statistics of the lane's 16 query rows: rows 8 g + 4 hi .. +3
+    for (int kc = 0; kc < NC; ++kc) {
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kc], Kr[kc], S, 0, 0, 0);
+      dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[kc], Vr[kc], dP, 0, 0, 0);
+    }
+    bf16x8 gt0[NB], qt0[NB], gt1[NB], qt1[NB];
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        lse4[g4] = *(const f32x4 *)&stats[cur][0][8 * g4 + 4 * hi];
-        del4[g4] = *(const f32x4 *)&stats[cur][1][8 * g4 + 4 * hi];
+    for (int nb = 0; nb < NB; ++nb) {
+      gt0[nb] = read_transposed<D>(gt, lane, nb, 0);
+      qt0[nb] = read_transposed<D>(qt, lane, nb, 0);
+    }
+    f32x4 lse4[4], del4[4];  // row statistics of the lane's 16 query rows: rows 8 g + 4 hi .. +3
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      lse4[g4] = *(const f32x4 *)&stats[cur][0][8 * g4 + 4 * hi];
+      del4[g4] = *(const f32x4 *)&stats[cur][1][8 * g4 + 4 * hi];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 Pb[2], dSb[2];
+    if (i_rel0 >= q_lo_max && i_rel0 + kBwdStep <= q_lim_min) {  // every pair of the tile counts
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        f32x8 e, f;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const int r = 8 * h2 + x;
+          const float pr = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse4[r / 4][r % 4]));
+          e[x] = pr;
+          f[x] = pr * (dP[r] - del4[r / 4][r % 4]);
+        }
+        Pb[h2] = __builtin_convertvector(e, bf16x8);
+        dSb[h2] = __builtin_convertvector(f, bf16x8);
       }
+    } else {
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
         f32x8 e, f;
@@ -358,19 +443,38 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
         Pb[h2] = __builtin_convertvector(e, bf16x8);
         dSb[h2] = __builtin_convertvector(f, bf16x8);
       }
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          mma_acc(dVa[nb], read_transposed<D>(gt, lane, nb, h2), Pb[h2]);
-          mma_acc(dKa[nb], read_transposed<D>(qt, lane, nb, h2), dSb[h2]);
-        }
     }
-    tile_store<D>(qr, smem[cur ^ 1][0], tid);
-    tile_store<D>(gr, smem[cur ^ 1][1], tid);
-    if (tid < 2 * kBwdStep) stats[cur ^ 1][tid >> 5][tid & 31] = sr;
-    __syncthreads();
+    i_rel0 += kBwdStep;
+    if (i_rel0 >= steps_per_head * kBwdStep) i_rel0 = 0;
+    __builtin_amdgcn_sched_barrier(0);
+    // first 16 queries into dV^T, dK^T; behind them the transposed operands of the other 16
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      gt1[nb] = read_transposed<D>(gt, lane, nb, 1);
+      qt1[nb] = read_transposed<D>(qt, lane, nb, 1);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      mma_acc(dVa[nb], gt0[nb], Pb[0]);
+      mma_acc(dKa[nb], qt0[nb], dSb[0]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();  // tile it+1 is in LDS for everyone; nobody reads tile `it` any more
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kc = 0; kc < NC; ++kc) {
+      qa[kc] = read_row<D>(smem[cur ^ 1][0], lane, kc);
+      ga[kc] = read_row<D>(smem[cur ^ 1][1], lane, kc);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      mma_acc(dVa[nb], gt1[nb], Pb[1]);
+      mma_acc(dKa[nb], qt1[nb], dSb[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
+#undef SEGATTN_BWD_FETCH_NEXT
+#undef SEGATTN_BWD_STASH
   if (!key_ok) return;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
