@@ -19,7 +19,8 @@
 // score tile (lane = its column, the lane's 16 registers = rows) is the B-operand layout of
 // the products that consume P and dS; the transposed A operands (K^T, dO^T, Q^T) come from
 // row-major LDS tiles with ds_read_b64_tr_b16.  Tiles are staged HBM -> registers -> LDS,
-// double-buffered, one barrier per step; rows are padded by 16 bytes against bank conflicts.
+// double-buffered, one barrier per step; the 16-byte chunks of a row are XOR-swizzled against
+// bank conflicts.
 // This file is compiled with the compiler's default MFMA register form (accumulators in
 // accumulation registers, placed by the register allocator); all products are builtins, so the
 // compiler tracks every MFMA hazard itself.
@@ -41,12 +42,23 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBwdStep = 32;
 constexpr float kLog2e = 1.4426950408889634f;
 
+// A [32 x D] bf16 tile in LDS: dense rows, the 16-byte chunks of a row XOR-swizzled with a
+// function of the row chosen so that both access patterns are free of bank conflicts: the row
+// reads (16 lanes = 16 consecutive rows at one logical chunk) and the transposing reads (16
+// lanes = 4 consecutive rows x 32 contiguous bytes).
 template <int D>
 struct BwdTile {
-  static constexpr int kRowBytes = 2 * D + 16;
+  static constexpr int kRowBytes = 2 * D;
   static constexpr int kBytes = kBwdStep * kRowBytes;
   static constexpr int kChunks = D / 8;                 // 16-byte chunks per row
   static constexpr int kLoads = kBwdStep * kChunks / 256;  // chunks per thread per tile
+  __device__ static constexpr int swz(int row) {
+    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    const int a = row >> 1;  // 128-byte rows: two rows share a 64-bank line
+    return ((a & 1) << 2) | (((a >> 2) & 1) << 1) | ((a >> 1) & 1);
+  }
+  // byte offset of logical chunk `chunk` of row `row`
+  __device__ static constexpr int at(int row, int chunk) { return row * kRowBytes + ((chunk ^ swz(row)) << 4); }
 };
 
 // acc += A . B
@@ -74,9 +86,9 @@ __device__ inline bf16x8 read_transposed(const unsigned char *tile, int lane, in
   using T = BwdTile<D>;
   const int hi = lane >> 5, i16 = lane & 15, g16 = (lane >> 4) & 1;
   const int row = 4 * hi + (i16 >> 2) + 16 * h2;
-  const int colb = (32 * nb + 16 * g16 + 4 * (i16 & 3)) * 2;
-  const LDS_AS s16x4 *p0 = (const LDS_AS s16x4 *)(tile + row * T::kRowBytes + colb);
-  const LDS_AS s16x4 *p1 = (const LDS_AS s16x4 *)(tile + (row + 8) * T::kRowBytes + colb);
+  const int chunk = 4 * nb + 2 * g16 + ((i16 & 3) >> 1), half = 8 * (i16 & 1);
+  const LDS_AS s16x4 *p0 = (const LDS_AS s16x4 *)(tile + T::at(row, chunk) + half);
+  const LDS_AS s16x4 *p1 = (const LDS_AS s16x4 *)(tile + T::at(row + 8, chunk) + half);
   const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)p0);
   const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)p1);
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -86,7 +98,7 @@ __device__ inline bf16x8 read_transposed(const unsigned char *tile, int lane, in
 template <int D>
 __device__ inline bf16x8 read_row(const unsigned char *tile, int lane, int kc) {
   using T = BwdTile<D>;
-  return *(const bf16x8 *)(tile + (lane & 31) * T::kRowBytes + 32 * kc + 16 * (lane >> 5));
+  return *(const bf16x8 *)(tile + T::at(lane & 31, 2 * kc + (lane >> 5)));
 }
 
 // Cooperative copy of rows [r0, r0+32) (clamped to r_last) of a row-major bf16 matrix with
@@ -115,7 +127,7 @@ __device__ inline void tile_store(const TileRegs<D> &t, unsigned char *tile, int
 #pragma unroll
   for (int i = 0; i < T::kLoads; ++i) {
     const int c = tid + 256 * i;
-    *(uint4 *)(tile + (c / T::kChunks) * T::kRowBytes + (c % T::kChunks) * 16) = t.x[i];
+    *(uint4 *)(tile + T::at(c / T::kChunks, c % T::kChunks)) = t.x[i];
   }
 }
 
@@ -361,7 +373,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
 #define SEGATTN_BWD_STASH(buf)                                                                        \
   do {                                                                                                \
     _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                        \
-      const int off_ = f_row[i_] * T::kRowBytes + f_col[i_] * 2;                                      \
+      const int off_ = T::at(f_row[i_], f_col[i_] / 8);                                               \
       *(u32x4 *)(smem[buf][0] + off_) = nq[i_];                                                       \
       *(u32x4 *)(smem[buf][1] + off_) = ng[i_];                                                       \
     }                                                                                                 \
