@@ -33,6 +33,7 @@ Readings taken where the paper is silent (each is repeated in the design notes):
 Everything is written over absolute token positions with an explicit boolean mask per
 query row, dense scores over all N keys, -inf where masked, and a plain softmax.
 Inputs are bf16 bit patterns (uint16) or floats; bf16 is widened exactly to fp64.
+rope_rotate() / attend_reindexed() are the RoPE re-indexing of Appendix E written literally.
 attend_backward() is the gradient of the same definition (dQ, dK, dV), with gradient stopped
 where the paper stops it (past rows are forward-only; the carried tail is differentiable).
 All pins for this file live in tests/test_oracle_*.py; no function here is unpinned.
@@ -230,6 +231,71 @@ def attend_backward(q, k, v, dout, *, seg_len: int, tail_len: int, kv_policy: Se
                     dk[b, :, kvh, :] += scale * ((ds * grad).T @ q[b, rr, h, :])
                     dv[b, :, kvh, :] += (pr * grad).T @ dout[b, rr, h, :]
     return dq, dk, dv
+
+
+def rope_rotate(x, positions, theta: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding of x [..., rows, heads, D] at integer `positions` [rows]
+    (standard RoPE, which Appendix E reuses): channel pair (i, i + D/2), i < D/2, is turned by
+    the angle position * theta^(-2i/D):  y_i = x_i cos - x_{i+D/2} sin,  y_{i+D/2} = x_i sin +
+    x_{i+D/2} cos.  The pairing (first half with second half, as the LLaMA backbones the paper
+    uses do) and the base theta are readings: the paper states neither."""
+    x = widen(x)
+    D = x.shape[-1]
+    half = D // 2
+    pos = np.asarray(positions, dtype=np.float64).reshape(-1)
+    if x.shape[-3] != pos.size or D % 2:
+        raise ValueError("positions do not match the rows of x")
+    inv_freq = float(theta) ** (-np.arange(half, dtype=np.float64) * 2.0 / D)
+    ang = pos[:, None] * inv_freq[None, :]                       # [rows, D/2]
+    cos, sin = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]  # broadcast over heads
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * cos - b * sin, a * sin + b * cos], axis=-1)
+
+
+def attend_reindexed(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
+                     theta: float = 10000.0, scale: Optional[float] = None, retrieved=None):
+    """Segment-level attention with the RoPE re-indexing of Appendix E, written literally:
+    q, k are *unrotated*; for every segment and KV head the prefix the head sees (carried tail,
+    whole history, or the retrieved list, in list order) gets key positions 0..P-1 and the
+    segment's queries and keys get positions P..P+m-1; values are not rotated.  Returns O
+    [B,N,Hq,D] and LSE [B,Hq,N] in float64.  retrieved as in attend()."""
+    q, k, v = widen(q), widen(k), widen(v)
+    B, N, Hq, D = q.shape
+    Hkv = k.shape[2]
+    g = Hq // Hkv
+    scale = 1.0 / np.sqrt(D) if scale is None else float(scale)
+    out = np.zeros((B, N, Hq, D))
+    lse = np.zeros((B, Hq, N))
+    for b in range(B):
+        for kvh in range(Hkv):
+            pol = int(kv_policy[kvh])
+            for i, s in enumerate(range(0, N, seg_len)):
+                m = min(seg_len, N - s)
+                if (pol & POLICY_PAST) and retrieved is not None:
+                    pref = np.asarray(retrieved.get((b, kvh, i), ()), dtype=np.int64).reshape(-1)
+                elif pol & POLICY_PAST:
+                    pref = np.arange(0, s)
+                elif pol & POLICY_TAIL:
+                    pref = np.arange(max(0, s - tail_len), s)
+                else:
+                    pref = np.arange(0, 0)
+                P = pref.size
+                kp = rope_rotate(k[b, pref, kvh:kvh + 1, :], np.arange(P), theta)[:, 0]       # prefix keys
+                ks = rope_rotate(k[b, s:s + m, kvh:kvh + 1, :], P + np.arange(m), theta)[:, 0]  # segment keys
+                kc = np.concatenate([kp, ks])
+                vc = np.concatenate([v[b, pref, kvh, :], v[b, s:s + m, kvh, :]])
+                for h in range(kvh * g, (kvh + 1) * g):
+                    qs = rope_rotate(q[b, s:s + m, h:h + 1, :], P + np.arange(m), theta)[:, 0]
+                    z = (qs @ kc.T) * scale
+                    allowed = np.concatenate([np.ones((m, P), dtype=bool),
+                                              np.tril(np.ones((m, m), dtype=bool))], axis=1)
+                    z = np.where(allowed, z, -np.inf)
+                    zmax = z.max(axis=1, keepdims=True)
+                    e = np.exp(z - zmax)
+                    den = e.sum(axis=1, keepdims=True)
+                    out[b, s:s + m, h, :] = (e / den) @ vc
+                    lse[b, h, s:s + m] = (zmax + np.log(den))[:, 0]
+    return out, lse
 
 
 def visible_pairs(n: int, seg_len: int, tail_len: int, policy: int, evicted: int = 0) -> int:

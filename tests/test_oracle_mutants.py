@@ -45,6 +45,11 @@ MUTANTS = {
     "bwd_dk_uses_dout": ("((ds * grad).T @ q[b, rr, h, :])", "((ds * grad).T @ dout[b, rr, h, :])"),
     "bwd_dp_from_keys": ("dp = dout[b, rr, h, :] @ vb.T", "dp = dout[b, rr, h, :] @ kb.T"),
     "bwd_group_heads_overwrite": ("dv[b, :, kvh, :] += (pr * grad)", "dv[b, :, kvh, :] = (pr * grad)"),
+    "rope_interleaved_pairs_sign": ("np.concatenate([a * cos - b * sin, a * sin + b * cos], axis=-1)", "np.concatenate([a * cos + b * sin, -a * sin + b * cos], axis=-1)"),
+    "rope_frequency_exponent": ("* 2.0 / D)", "* 1.0 / D)"),
+    "reindex_segment_starts_at_zero": ("ks = rope_rotate(k[b, s:s + m, kvh:kvh + 1, :], P + np.arange(m), theta)[:, 0]", "ks = rope_rotate(k[b, s:s + m, kvh:kvh + 1, :], np.arange(m), theta)[:, 0]"),
+    "reindex_queries_not_shifted": ("qs = rope_rotate(q[b, s:s + m, h:h + 1, :], P + np.arange(m), theta)[:, 0]", "qs = rope_rotate(q[b, s:s + m, h:h + 1, :], np.arange(m), theta)[:, 0]"),
+    "reindex_values_rotated": ("vc = np.concatenate([v[b, pref, kvh, :], v[b, s:s + m, kvh, :]])", "vc = np.concatenate([rope_rotate(v[b, pref, kvh:kvh + 1, :], np.arange(P), theta)[:, 0], v[b, s:s + m, kvh, :]])"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 

@@ -525,3 +525,76 @@ def test_backward_closed_forms():
     alone = orc.attend_backward(q[:, :S], k[:, :S], v[:, :S], go[:, :S], seg_len=S, tail_len=T, kv_policy=[0])
     np.testing.assert_allclose(dk2[0, :S, 0], alone[1][0, :, 0], atol=1e-14)
     np.testing.assert_allclose(dv2[0, :S, 0], alone[2][0, :, 0], atol=1e-14)
+
+
+# ---------------------------------------------------------------- RoPE re-indexing (Appendix E)
+def test_rope_hand_values_and_textbook_properties():
+    # D = 2: one pair, frequency theta^0 = 1: rotation of (x0, x1) by `position` radians
+    x = np.array([[[[1.0, 0.0]]], [[[0.0, 2.0]]], [[[3.0, 4.0]]]]).reshape(3, 1, 2)
+    y = orc.rope_rotate(x, [0, 1, 2], theta=10000.0)
+    np.testing.assert_allclose(y[0, 0], [1.0, 0.0], atol=1e-15)                       # position 0: identity
+    np.testing.assert_allclose(y[1, 0], [-2 * math.sin(1), 2 * math.cos(1)], atol=1e-15)
+    np.testing.assert_allclose(y[2, 0], [3 * math.cos(2) - 4 * math.sin(2), 3 * math.sin(2) + 4 * math.cos(2)], atol=1e-15)
+    # D = 4, theta = 100: pairs (0,2) at frequency 1 and (1,3) at frequency 100^(-1/2) = 0.1
+    x4 = np.array([1.0, 2.0, 3.0, 4.0]).reshape(1, 1, 4)
+    y4 = orc.rope_rotate(x4, [5], theta=100.0)[0, 0]
+    want = [math.cos(5) - 3 * math.sin(5), 2 * math.cos(0.5) - 4 * math.sin(0.5),
+            math.sin(5) + 3 * math.cos(5), 2 * math.sin(0.5) + 4 * math.cos(0.5)]
+    np.testing.assert_allclose(y4, want, atol=1e-14)
+    # norm preserved; inner products depend on the position difference only
+    rng = np.random.default_rng(500)
+    a, b = rng.standard_normal((1, 1, 16)), rng.standard_normal((1, 1, 16))
+    np.testing.assert_allclose(np.linalg.norm(orc.rope_rotate(a, [12345])), np.linalg.norm(a), rtol=1e-13)
+    d1 = float(orc.rope_rotate(a, [70])[0, 0] @ orc.rope_rotate(b, [50])[0, 0])
+    d2 = float(orc.rope_rotate(a, [1020])[0, 0] @ orc.rope_rotate(b, [1000])[0, 0])
+    d3 = float(orc.rope_rotate(a, [71])[0, 0] @ orc.rope_rotate(b, [50])[0, 0])
+    assert abs(d1 - d2) < 1e-12 and abs(d1 - d3) > 1e-3
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+def test_reindexed_positions_equal_absolute_positions_for_contiguous_prefixes(policy):
+    """A prefix that is a contiguous run of tokens ending at the segment start keeps every
+    query-key distance under re-indexing, so Appendix E's positions give exactly standard RoPE
+    with absolute positions followed by the unrotated-path attention."""
+    n, d, S, T = 29, 8, 8, 3
+    rng = np.random.default_rng(510 + policy)
+    q, k, v = rng.standard_normal((1, n, 2, d)), rng.standard_normal((1, n, 1, d)), rng.standard_normal((1, n, 1, d))
+    o1, l1 = orc.attend_reindexed(q, k, v, seg_len=S, tail_len=T, kv_policy=[policy], theta=50.0)
+    qa, ka = orc.rope_rotate(q, np.arange(n), 50.0), orc.rope_rotate(k, np.arange(n), 50.0)
+    o2, l2 = orc.attend(qa, ka, v, seg_len=S, tail_len=T, kv_policy=[policy])
+    np.testing.assert_allclose(o1, o2, atol=1e-12)
+    np.testing.assert_allclose(l1, l2, atol=1e-12)
+
+
+def test_reindexed_retrieved_prefix_is_the_literal_concatenation():
+    """Retrieved rows take positions 0..R-1 in list order and the segment R..R+m-1 (Appendix E,
+    P = R), checked against scalar loops; unlike a contiguous prefix this is *not* what absolute
+    positions would give."""
+    n, d, S, theta = 20, 4, 6, 30.0
+    rng = np.random.default_rng(520)
+    q, k, v = rng.standard_normal((n, d)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    ret = {(0, 0, 1): [4, 0, 2], (0, 0, 2): [11, 3], (0, 0, 3): [17, 1, 9, 5]}
+    o, l = orc.attend_reindexed(q[None, :, None], k[None, :, None], v[None, :, None], seg_len=S, tail_len=0,
+                                kv_policy=[2], theta=theta, retrieved=ret)
+    def rot(x, pos):
+        h = d // 2
+        y = np.zeros(d)
+        for i in range(h):
+            a = pos * theta ** (-2.0 * i / d)
+            y[i] = x[i] * math.cos(a) - x[i + h] * math.sin(a)
+            y[i + h] = x[i] * math.sin(a) + x[i + h] * math.cos(a)
+        return y
+    for p in range(n):
+        i, s = p // S, (p // S) * S
+        pref = list(ret.get((0, 0, i), []))
+        P = len(pref)
+        keys = [rot(k[j], u) for u, j in enumerate(pref)] + [rot(k[j], P + j - s) for j in range(s, p + 1)]
+        vals = [v[j] for j in pref] + [v[j] for j in range(s, p + 1)]
+        qq = rot(q[p], P + p - s)
+        z = np.array([float(qq @ kk) / math.sqrt(d) for kk in keys])
+        w = np.exp(z - z.max())
+        np.testing.assert_allclose(o[0, p, 0], (w / w.sum()) @ np.array(vals), atol=1e-13)
+        assert abs(l[0, 0, p] - (z.max() + math.log(w.sum()))) < 1e-13
+    qa, ka = orc.rope_rotate(q[None, :, None], np.arange(n), theta), orc.rope_rotate(k[None, :, None], np.arange(n), theta)
+    o_abs, _ = orc.attend(qa, ka, v[None, :, None], seg_len=S, tail_len=0, kv_policy=[2], retrieved=ret)
+    assert np.abs(o_abs - o).max() > 1e-3
