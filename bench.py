@@ -168,6 +168,7 @@ def main() -> int:
     if not args.no_extras:
         result["streaming"] = streaming_leg(sa, W, w, q, k, v, out, lse, flops)
         result["retrieval"] = retrieval_leg(sa, W, w, q, k, v, out)
+        result["rope"] = rope_leg(sa, W, w, q, k)
         del q, k, v, out, lse
         torch.cuda.empty_cache()
         result["backward"] = backward_leg(sa, W, w)
@@ -267,6 +268,28 @@ def retrieval_leg(sa, W, w, q, k, v, out, R=512):
            "arena_bytes": nbytes}
     sa.segattn_destroy(ctx)
     return res
+
+
+def rope_leg(sa, W, w, q, k):
+    """seg_rope_apply over the whole 128K prompt (q and k rotated in place by absolute position,
+    Appendix E): every element read and written once, HBM-bound."""
+    import torch
+    cfg = sa.make_config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seg_len=w.seg_len, tail_len=w.tail_len, kv_policy=w.kv_policy, rope_theta=500000.0)
+    st = torch.cuda.current_stream().cuda_stream
+    sa.seg_rope_apply(cfg, q, k, w.seq_len, None, st)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        sa.seg_rope_apply(cfg, q, k, w.seq_len, None, st)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = 2 * (q.numel() + k.numel()) * 2
+    return {"ms": round(ms, 4), "bytes": nbytes, "achieved_GBps": round(nbytes / ms / 1e6, 1),
+            "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
 
 
 def backward_leg(sa, W, w, batch=4):

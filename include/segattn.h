@@ -78,6 +78,10 @@ typedef struct {
                               attends to [retrieved prefix ; own segment] (Eq. 13, second case),
                               the prefix being the rows seg_kv_past_select() gathered, at most
                               R_max of them; no head may then have both TAIL and PAST       */
+  float rope_theta;        /* 0: positions are not the library's business.  > 0: base of the
+                              rotary embedding (Appendix E): seg_rope_apply() rotates by it, and
+                              in retrieval mode the gathered K rows are re-rotated (see
+                              seg_kv_past_select)                                              */
 } segattn_config;
 
 /* ---- context --------------------------------------------------------------------------- */
@@ -116,6 +120,19 @@ segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, cons
  * fp32 if cfg->out_fp32 or cfg->fp32_check), lse [B,Hq,n].  cfg->past_capacity is ignored. */
 segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const void *k,
                                 const void *v, int64_t n, void *out, float *lse, void *stream);
+
+/* ---- positions --------------------------------------------------------------------------- */
+
+/* RoPE re-indexing for prefix concatenation (Sec. 3.4, Appendix E).  Rotates q [B,rows,Hq,D] and
+ * k [B,rows,Hkv,D] in place: row t of sequence b by the position pos0[b] + t, channel pair
+ * (i, i + D/2) by position * theta^(-2i/D), theta = cfg->rope_theta (> 0).  pos0: device int64 [B]
+ * or NULL (all zero).  Rotating every token by its absolute position before seg_attn_fwd* /
+ * seg_kv_commit / seg_attn_decode reproduces the paper's re-indexed positions (prefix 0..P-1,
+ * segment P..P+m-1) exactly for the carried tail and for a whole-history prefix, because RoPE
+ * scores depend on position differences only; a retrieved prefix is turned to the positions
+ * just before its segment by seg_kv_past_select.  Values are never rotated. */
+segattn_status seg_rope_apply(const segattn_config *cfg, void *q, void *k, int64_t rows,
+                              const int64_t *pos0, void *stream);
 
 /* ---- backward (training) ---------------------------------------------------------------- */
 
@@ -162,7 +179,11 @@ segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void 
  * segments only (ESTATE with an open segment); EINVAL if the context is not in retrieval
  * mode or R > retrieved_capacity; ECAPACITY if R exceeds the visible pool rows of some
  * sequence and head.  The lists are not read on the host: an out-of-range entry is clamped
- * into the pool (never an out-of-bounds access), a repeated entry counts twice. */
+ * into the pool (never an out-of-bounds access), a repeated entry counts twice.
+ * With rope_theta > 0 the pool is taken to hold keys rotated by their absolute position (pool
+ * row number = position, as seg_rope_apply + seg_kv_commit leave them) and list entry r is
+ * re-rotated to position s - R + r, s the position at which the next segment starts: the
+ * positions 0..R-1 / R..R+m-1 of Appendix E up to a common shift. */
 segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t R, void *stream);
 
 /* Hide the n_oldest oldest rows of one PAST head's pool from now on (all sequences).  Pure

@@ -26,7 +26,7 @@ class segattn_config(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("seg_len", ctypes.c_int32), ("tail_len", ctypes.c_int32),
         ("past_capacity", ctypes.c_int64), ("kv_policy", ctypes.POINTER(ctypes.c_uint8)),
         ("scale", ctypes.c_float), ("fp32_check", ctypes.c_int32), ("out_fp32", ctypes.c_int32),
-        ("retrieved_capacity", ctypes.c_int32),
+        ("retrieved_capacity", ctypes.c_int32), ("rope_theta", ctypes.c_float),
     ]
 
 
@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
             "segattn_reset": (ctypes.c_int, [vp, vp]),
             "seg_attn_fwd": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, vp, vp]),
             "seg_attn_fwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, i64, vp, vp, vp]),
+            "seg_rope_apply": (ctypes.c_int, [cfgp, vp, vp, i64, vp, vp]),
             "seg_attn_bwd_workspace_bytes": (sz, [cfgp, i64]),
             "seg_attn_bwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]),
             "seg_kv_commit": (ctypes.c_int, [vp, vp, vp, i32, vp]),
@@ -74,7 +75,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_past_evict",
+           "seg_attn_fwd_seq", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_past_evict",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -95,11 +96,11 @@ def _check(st: int, where: str) -> None:
 def make_config(*, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seg_len: int,
                 tail_len: int, kv_policy: Sequence[int], past_capacity: int = 0, scale: float = 0.0,
                 fp32_check: bool = False, out_fp32: bool = False,
-                retrieved_capacity: int = 0) -> segattn_config:
+                retrieved_capacity: int = 0, rope_theta: float = 0.0) -> segattn_config:
     pol = (ctypes.c_uint8 * len(kv_policy))(*[int(p) for p in kv_policy])
     cfg = segattn_config(batch, n_q_heads, n_kv_heads, head_dim, seg_len, tail_len, past_capacity,
                          ctypes.cast(pol, ctypes.POINTER(ctypes.c_uint8)), scale,
-                         int(fp32_check), int(out_fp32), int(retrieved_capacity))
+                         int(fp32_check), int(out_fp32), int(retrieved_capacity), float(rope_theta))
     cfg._policy_keepalive = pol
     return cfg
 
@@ -137,6 +138,10 @@ def seg_attn_fwd(ctx: int, q, k, v, m: int, out, lse, stream=None) -> None:
 def seg_attn_fwd_seq(cfg: segattn_config, q, k, v, n: int, out, lse, stream=None) -> None:
     _check(lib().seg_attn_fwd_seq(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), n, _ptr(out), _ptr(lse),
                                   _ptr(stream)), "seg_attn_fwd_seq")
+
+
+def seg_rope_apply(cfg: segattn_config, q, k, rows: int, pos0=None, stream=None) -> None:
+    _check(lib().seg_rope_apply(ctypes.byref(cfg), _ptr(q), _ptr(k), rows, _ptr(pos0), _ptr(stream)), "seg_rope_apply")
 
 
 def seg_attn_bwd_workspace_bytes(cfg: segattn_config, n: int) -> int:

@@ -27,6 +27,7 @@ bool build_problem(const segattn_config *cfg, bool need_cache, Problem &p) {
   if (cfg->seg_len < 1 || cfg->tail_len < 0 || cfg->tail_len > cfg->seg_len) return false;
   if ((long long)cfg->seg_len + cfg->tail_len >= (1ll << 30)) return false;
   if (!(cfg->scale >= 0.f) || isinf(cfg->scale)) return false;
+  if (!(cfg->rope_theta >= 0.f) || isinf(cfg->rope_theta)) return false;
   memset(&p, 0, sizeof(p));
   p.B = cfg->batch;
   p.Hq = cfg->n_q_heads;
@@ -89,9 +90,14 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
 
 segattn_status hip_status(hipError_t e) { return e == hipSuccess ? SEGATTN_OK : SEGATTN_EHIP; }
 
+void fill_inv_freq(double (&t)[64], int D, float theta) {
+  for (int i = 0; i < 64; ++i) t[i] = i < D / 2 ? pow((double)theta, -2.0 * i / D) : 0.0;
+}
+
 }  // namespace
 
 struct segattn_ctx {
+  float rope_theta;
   Problem p;
   CacheGeom g;
   unsigned char *cache;
@@ -125,6 +131,7 @@ segattn_status segattn_create(const segattn_config *cfg, void *cache_dev, size_t
   segattn_ctx *c = new (std::nothrow) segattn_ctx();
   if (!c) return SEGATTN_EINVAL;
   c->p = p;
+  c->rope_theta = cfg->rope_theta;
   c->g = g;
   c->cache = (unsigned char *)cache_dev;
   c->ready = false;
@@ -196,6 +203,21 @@ segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const 
   const long long seg_rows = n < p.S ? n : p.S;
   a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
+}
+
+segattn_status seg_rope_apply(const segattn_config *cfg, void *q, void *k, int64_t rows, const int64_t *pos0,
+                              void *stream) {
+  Problem p;
+  if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
+  if (!q || !k || rows < 1 || rows >= (1ll << 31) - 4096 || !(cfg->rope_theta > 0.f)) return SEGATTN_EINVAL;
+  RopeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (unsigned short *)q;
+  a.k = (unsigned short *)k;
+  a.pos0 = (const long long *)pos0;
+  a.rows = (int)rows;
+  fill_inv_freq(a.inv_freq, p.D, cfg->rope_theta);
+  return hip_status(launch_rope_apply(p, a, (hipStream_t)stream));
 }
 
 size_t seg_attn_bwd_workspace_bytes(const segattn_config *cfg, int64_t n) {
@@ -310,6 +332,8 @@ segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t 
   a.cache = ctx->cache;
   a.geom = ctx->g;
   a.R = R;
+  a.rope = ctx->rope_theta > 0.f;
+  if (a.rope) fill_inv_freq(a.inv_freq, p.D, ctx->rope_theta);
   if (launch_cache_select(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
   for (int b = 0; b < p.B; ++b) ctx->ret[b] = R;
   return SEGATTN_OK;

@@ -8,9 +8,34 @@
 // the head's attention view, and every row appended to the open segment is mirrored there.
 // The host keeps a mirror of the counters for validation; the device copy is only ever
 // changed by these kernels, in stream order, so a sequence of calls can be graph-captured.
+#include <math.h>
+
 #include "segattn_internal.h"
 
 namespace segattn {
+
+// Turn 8 channel pairs (lo: channels i0..i0+7, hi: their partners i0+D/2..) by `delta` positions.
+__device__ inline void rerotate8(uint4 &lo, uint4 &hi, double delta, const double *inv_freq, int i0) {
+  unsigned *lw = (unsigned *)&lo, *hw = (unsigned *)&hi;
+  const double two_pi = 6.283185307179586476925286766559;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    unsigned lo_out = 0, hi_out = 0;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const float x = __uint_as_float(e ? (lw[w] & 0xffff0000u) : (lw[w] << 16));
+      const float y = __uint_as_float(e ? (hw[w] & 0xffff0000u) : (hw[w] << 16));
+      const double ang = delta * inv_freq[i0 + 2 * w + e];
+      float sn, cs;
+      sincosf((float)(ang - two_pi * rint(ang / two_pi)), &sn, &cs);
+      const __bf16 ya = (__bf16)(x * cs - y * sn), yb = (__bf16)(x * sn + y * cs);
+      lo_out |= (unsigned)__builtin_bit_cast(unsigned short, ya) << (16 * e);
+      hi_out |= (unsigned)__builtin_bit_cast(unsigned short, yb) << (16 * e);
+    }
+    lw[w] = lo_out;
+    hw[w] = hi_out;
+  }
+}
 
 __device__ inline int *meta_of(unsigned char *cache, const CacheGeom &g, const Problem &p, int b, int h) {
   return (int *)(cache + g.meta_off) + ((long long)b * p.Hkv + h) * kMetaInts;
@@ -187,8 +212,18 @@ __global__ __launch_bounds__(256) void cache_select_kernel(const Problem p, cons
     int j = idx[r];
     j = j < 0 ? 0 : (j >= pool ? pool - 1 : j);
     if (pool > 0) {
-      kd[(long long)r * CPR + c] = ks[(long long)j * CPR + c];
       vd[(long long)r * CPR + c] = vs[(long long)j * CPR + c];
+      if (!a.rope) {
+        kd[(long long)r * CPR + c] = ks[(long long)j * CPR + c];
+      } else if (c < CPR / 2) {
+        // RoPE re-indexing of a retrieved prefix (Appendix E): the pool holds K rotated by the
+        // token's absolute position j; list entry r moves to position pool - R + r, i.e. the R
+        // rows become the R tokens just before the segment that starts at position `pool`.
+        uint4 lo = ks[(long long)j * CPR + c], hi = ks[(long long)j * CPR + c + CPR / 2];
+        rerotate8(lo, hi, (double)(pool - a.R + r - j), a.inv_freq, 8 * c);
+        kd[(long long)r * CPR + c] = lo;
+        kd[(long long)r * CPR + c + CPR / 2] = hi;
+      }
     }
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) meta[META_RET] = pool > 0 ? a.R : 0;

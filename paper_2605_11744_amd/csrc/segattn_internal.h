@@ -92,6 +92,15 @@ struct SelectArgs {
   unsigned char *cache;
   CacheGeom geom;
   int R;
+  int rope;              // re-rotate the gathered K rows to the positions just before the segment
+  double inv_freq[64];   // theta^(-2i/D), i < D/2
+};
+
+struct RopeArgs {
+  unsigned short *q, *k;     // rotated in place
+  const long long *pos0;     // device [B]: position of row 0 of every sequence, or nullptr (all 0)
+  int rows;
+  double inv_freq[64];
 };
 
 // ---- helpers usable on host and device ----------------------------------------------------
@@ -159,6 +168,7 @@ hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStre
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
                               long long n_oldest, hipStream_t st);
 hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st);
+hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st);
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st);

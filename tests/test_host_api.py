@@ -45,7 +45,7 @@ def test_cache_bytes_accounts_for_rows_counters_and_workspace():
 @pytest.mark.parametrize("bad", [
     dict(head_dim=96), dict(n_q_heads=7), dict(tail_len=65), dict(seg_len=0), dict(batch=0),
     dict(kv_policy=[1, 4]), dict(past_capacity=32), dict(tail_len=-1), dict(scale=-1.0),
-    dict(n_kv_heads=0, n_q_heads=0, kv_policy=[]),
+    dict(n_kv_heads=0, n_q_heads=0, kv_policy=[]), dict(rope_theta=-1.0),
 ])
 def test_invalid_configurations_are_rejected(bad):
     cfg = _cfg(**bad)
