@@ -33,6 +33,9 @@ Readings taken where the paper is silent (each is repeated in the design notes):
 Everything is written over absolute token positions with an explicit boolean mask per
 query row, dense scores over all N keys, -inf where masked, and a plain softmax.
 Inputs are bf16 bit patterns (uint16) or floats; bf16 is widened exactly to fp64.
+retrieve_indices() is the retrieval operator of Appendix D under stated readings of its
+unstated parameters: PARITY UNPINNED against the paper (it prints no values, k, anchor count,
+window or fallback); its pins check the reading against its own literal description.
 rope_rotate() / attend_reindexed() are the RoPE re-indexing of Appendix E written literally.
 attend_backward() is the gradient of the same definition (dQ, dK, dV), with gradient stopped
 where the paper stops it (past rows are forward-only; the carried tail is differentiable).
@@ -296,6 +299,72 @@ def attend_reindexed(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequenc
                     out[b, s:s + m, h, :] = (e / den) @ vc
                     lse[b, h, s:s + m] = (zmax + np.log(den))[:, 0]
     return out, lse
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 (ties to even) of float64 values, returned as float64."""
+    u = np.asarray(x, dtype=np.float64).astype(np.float32).view(np.uint32)
+    # the float32 step can only matter on an exact bf16 tie of the float64 value; inputs here are
+    # means of a few bf16 numbers, which float32 holds exactly
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)) << np.uint32(16)
+    return r.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def retrieval_summaries(q_prev, *, n_queries: int, pool_window: int, tail_avg: int) -> np.ndarray:
+    """Query summaries of Appendix D ("Query construction") for one sequence: from the last
+    L = min(n_queries, m) query rows of the previous segment q_prev [m, H, D], (i) the means of
+    consecutive windows of pool_window rows (sliding-window mean pooling with stride = window; a
+    shorter last window averages what it has) and (ii) the mean of the last min(tail_avg, L)
+    rows.  Returns [n_sum, H, D].  Window length, stride and tail length are readings: the paper
+    names the two ingredients only."""
+    q_prev = widen(q_prev)
+    m = q_prev.shape[0]
+    L = min(int(n_queries), m)
+    last = q_prev[m - L:]
+    out = [last[a:a + pool_window].mean(axis=0) for a in range(0, L, pool_window)]
+    out.append(last[L - min(int(tail_avg), L):].mean(axis=0))
+    return np.stack(out)
+
+
+def retrieve_indices(q_prev, k_pool, *, R: int, n_queries: int, pool_window: int, tail_avg: int,
+                     n_anchors: int, win_before: int, win_after: int, evicted: int = 0,
+                     return_scores: bool = False):
+    """Top-k retrieval operator of Appendix D for one sequence and one KV head, as read here.
+
+    q_prev [m, g, D]: previous-segment queries of the g query heads of the group; k_pool [n, D]:
+    the head's pool.  Scoring: dot products between every summary (rounded to bf16, the form in
+    which the kernel's matrix cores take them) and every pool key; a row's score is its best
+    over the summaries.  Anchors: the n_anchors rows with the highest scores (ties: lower row
+    first) -- the same rows as "per-summary top-k, de-duplicate, keep the highest-scoring
+    anchors" for any k >= n_anchors.  Window expansion: anchors in descending score order each
+    add rows a-win_before .. a+win_after (clipped to the pool, ascending, skipping rows already
+    in) until R rows are in.  Padding: if fewer than R, the earliest pool rows not yet in.
+    Result: the min(R, n - evicted) rows, sorted ascending."""
+    q_prev, k_pool = widen(q_prev), widen(k_pool)
+    n = k_pool.shape[0]
+    summ = round_bf16(retrieval_summaries(q_prev, n_queries=n_queries, pool_window=pool_window,
+                                          tail_avg=tail_avg))
+    sig = summ.reshape(-1, summ.shape[-1])                  # all summaries of all heads of the group
+    scores = (sig @ k_pool.T).max(axis=0)                   # [n]
+    scores[:evicted] = -np.inf
+    want = min(int(R), n - evicted)
+    order = sorted(range(evicted, n), key=lambda r: (-scores[r], r))[:n_anchors]
+    chosen = []
+    inside = set()
+    for a_ in order:
+        for r in range(max(evicted, a_ - win_before), min(n, a_ + win_after + 1)):
+            if len(chosen) < want and r not in inside:
+                inside.add(r)
+                chosen.append(r)
+    r = evicted
+    while len(chosen) < want:
+        if r not in inside:
+            inside.add(r)
+            chosen.append(r)
+        r += 1
+    res = np.array(sorted(chosen), dtype=np.int64)
+    return (res, scores) if return_scores else res
 
 
 def visible_pairs(n: int, seg_len: int, tail_len: int, policy: int, evicted: int = 0) -> int:

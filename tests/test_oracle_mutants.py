@@ -50,6 +50,14 @@ MUTANTS = {
     "reindex_segment_starts_at_zero": ("ks = rope_rotate(k[b, s:s + m, kvh:kvh + 1, :], P + np.arange(m), theta)[:, 0]", "ks = rope_rotate(k[b, s:s + m, kvh:kvh + 1, :], np.arange(m), theta)[:, 0]"),
     "reindex_queries_not_shifted": ("qs = rope_rotate(q[b, s:s + m, h:h + 1, :], P + np.arange(m), theta)[:, 0]", "qs = rope_rotate(q[b, s:s + m, h:h + 1, :], np.arange(m), theta)[:, 0]"),
     "reindex_values_rotated": ("vc = np.concatenate([v[b, pref, kvh, :], v[b, s:s + m, kvh, :]])", "vc = np.concatenate([rope_rotate(v[b, pref, kvh:kvh + 1, :], np.arange(P), theta)[:, 0], v[b, s:s + m, kvh, :]])"),
+    "retrieval_tail_average_missing": ("    out.append(last[L - min(int(tail_avg), L):].mean(axis=0))\n", ""),
+    "retrieval_windows_from_segment_start": ("    last = q_prev[m - L:]", "    last = q_prev[:L]"),
+    "retrieval_score_is_mean_over_summaries": ("scores = (sig @ k_pool.T).max(axis=0)", "scores = (sig @ k_pool.T).mean(axis=0)"),
+    "retrieval_anchor_order_ascending": ("key=lambda r: (-scores[r], r))[:n_anchors]", "key=lambda r: (scores[r], r))[:n_anchors]"),
+    "retrieval_window_not_clipped_left": ("for r in range(max(evicted, a_ - win_before), min(n, a_ + win_after + 1)):", "for r in range(a_ - win_before, min(n, a_ + win_after + 1)):"),
+    "retrieval_window_one_short": ("min(n, a_ + win_after + 1)):", "min(n, a_ + win_after)):"),
+    "retrieval_pads_with_latest": ("    r = evicted\n    while len(chosen) < want:\n        if r not in inside:\n            inside.add(r)\n            chosen.append(r)\n        r += 1", "    r = n - 1\n    while len(chosen) < want:\n        if r not in inside:\n            inside.add(r)\n            chosen.append(r)\n        r -= 1"),
+    "retrieval_result_unsorted": ("res = np.array(sorted(chosen), dtype=np.int64)", "res = np.array(chosen, dtype=np.int64)"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 

@@ -598,3 +598,74 @@ def test_reindexed_retrieved_prefix_is_the_literal_concatenation():
     qa, ka = orc.rope_rotate(q[None, :, None], np.arange(n), theta), orc.rope_rotate(k[None, :, None], np.arange(n), theta)
     o_abs, _ = orc.attend(qa, ka, v[None, :, None], seg_len=S, tail_len=0, kv_policy=[2], retrieved=ret)
     assert np.abs(o_abs - o).max() > 1e-3
+
+
+# ---------------------------------------------------------------- retrieval operator (Appendix D)
+# The paper states the steps but none of the sizes, so these pins tie the oracle's reading to
+# the literal description of the steps, not to printed values ("parity unpinned" w.r.t. the paper).
+RET = dict(n_queries=6, pool_window=2, tail_avg=2, n_anchors=2, win_before=1, win_after=1)
+
+
+def test_retrieval_summaries_by_hand():
+    q = np.arange(1.0, 9.0).reshape(8, 1, 1)                 # rows 1..8, one head, D = 1
+    s = orc.retrieval_summaries(q, n_queries=6, pool_window=4, tail_avg=3)
+    # last 6 rows: 3..8 -> windows (3,4,5,6) and (7,8); tail mean of (6,7,8)
+    np.testing.assert_allclose(s[:, 0, 0], [4.5, 7.5, 7.0])
+    s = orc.retrieval_summaries(q[:3], n_queries=6, pool_window=2, tail_avg=5)   # fewer rows than L_q
+    np.testing.assert_allclose(s[:, 0, 0], [1.5, 3.0, 2.0])
+
+
+def literal_appendix_d(q_prev, k_pool, R, k_top, p):
+    """Appendix D step by step: per summary take the top-k rows, de-duplicate the union, keep the
+    n_anchors highest-scoring ones as anchors, expand, de-duplicate / sort, pad with the earliest
+    rows.  Scores and window rules as in the oracle's docstring; plain Python sets and sorts."""
+    summ = orc.round_bf16(orc.retrieval_summaries(q_prev, n_queries=p["n_queries"], pool_window=p["pool_window"],
+                                                  tail_avg=p["tail_avg"]))
+    sig = summ.reshape(-1, summ.shape[-1])
+    n = k_pool.shape[0]
+    per = [[float(np.dot(sg, k_pool[r])) for r in range(n)] for sg in sig]
+    union = set()
+    for sc in per:
+        union |= set(sorted(range(n), key=lambda r: (-sc[r], r))[:k_top])
+    best = {r: max(sc[r] for sc in per) for r in union}
+    anchors = sorted(union, key=lambda r: (-best[r], r))[:p["n_anchors"]]
+    picked = []
+    for a_ in anchors:
+        for r in range(max(0, a_ - p["win_before"]), min(n, a_ + p["win_after"] + 1)):
+            if r not in picked and len(picked) < min(R, n):
+                picked.append(r)
+    r = 0
+    while len(picked) < min(R, n):
+        if r not in picked:
+            picked.append(r)
+        r += 1
+    return sorted(picked)
+
+
+@pytest.mark.parametrize("seed,n,R,k_top", [(1, 40, 8, 2), (2, 64, 10, 5), (3, 17, 12, 3), (4, 9, 20, 2), (5, 50, 3, 4)])
+def test_retrieve_indices_equals_literal_steps(seed, n, R, k_top):
+    rng = np.random.default_rng(600 + seed)
+    q_prev = orc.round_bf16(rng.standard_normal((11, 2, 8)))
+    k_pool = orc.round_bf16(rng.standard_normal((n, 8)))
+    got = orc.retrieve_indices(q_prev, k_pool, R=R, **RET)
+    assert list(got) == literal_appendix_d(q_prev, k_pool, R, k_top, RET)
+    assert len(got) == min(R, n) and len(set(got)) == len(got) and list(got) == sorted(got)
+
+
+def test_retrieve_indices_planted_rows_and_fallback():
+    """Keys equal to a multiple of the (single) summary direction win; windows of 3 rows around
+    two anchors give 6 rows, the earliest rows pad to R = 9; evicted rows are never returned."""
+    d, n = 4, 30
+    q_prev = np.tile(np.array([1.0, 0.0, 0.0, 0.0]), (6, 1, 1))            # every summary = e0
+    k_pool = np.zeros((n, d))
+    k_pool[:, 1] = 1.0
+    k_pool[20, 0], k_pool[11, 0] = 5.0, 3.0
+    got = orc.retrieve_indices(q_prev, k_pool, R=9, **RET)
+    assert list(got) == [0, 1, 2, 10, 11, 12, 19, 20, 21]
+    got = orc.retrieve_indices(q_prev, k_pool, R=4, **RET)                  # best anchor first, then truncation
+    assert list(got) == [10, 19, 20, 21]
+    got = orc.retrieve_indices(q_prev, k_pool, R=9, evicted=11, **RET)     # row 11 itself is the first kept row
+    assert list(got) == [11, 12, 13, 14, 15, 16, 19, 20, 21]
+    k_pool[29, 0] = 9.0                                                     # window clipped at the pool end
+    got = orc.retrieve_indices(q_prev, k_pool, R=5, **RET)
+    assert list(got) == [19, 20, 21, 28, 29]
