@@ -186,6 +186,38 @@ segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void 
  * positions 0..R-1 / R..R+m-1 of Appendix E up to a common shift. */
 segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t R, void *stream);
 
+/* Sizes of the top-k retrieval operator (Appendix D).  The paper names the steps and gives
+ * L_q in [24, 64] and R = 512 (Appendix F); every other size is the caller's choice. */
+typedef struct {
+  int32_t n_queries;   /* L_q >= 1: the last L_q query rows of the previous segment are used     */
+  int32_t pool_window; /* >= 1: sliding-window mean pooling, window = stride = this many rows     */
+  int32_t tail_avg;    /* >= 1: one more summary, the mean of the last tail_avg rows              */
+  int32_t n_anchors;   /* 1..32: rows with the highest scores                                      */
+  int32_t win_before;  /* >= 0: an anchor a contributes rows a - win_before .. a + win_after       */
+  int32_t win_after;   /* >= 0                                                                     */
+} segattn_retrieval;
+
+/* Bytes of device workspace seg_kv_retrieve needs for this context (0 if the sizes are invalid:
+ * the summaries of one KV group, ceil(L_q / pool_window) + 1 per query head, must not exceed 64). */
+size_t seg_kv_retrieve_workspace_bytes(const segattn_ctx *ctx, const segattn_retrieval *r);
+
+/* Top-k retrieval operator (Appendix D): choose, for every sequence and every PAST head, the R
+ * pool rows that form the retrieved prefix, and write them to idx_out (device int32
+ * [B, n_past, R], ascending) in the form seg_kv_past_select takes.  q_prev: device bf16
+ * [B, m, Hq, D], the queries of the previous segment (m >= 1).  Steps, as read here: query
+ * summaries = means of consecutive pool_window-row windows of the last L_q rows plus the mean of
+ * the last tail_avg rows, for every query head of the group, rounded to bf16; score of a pool
+ * row = its best dot product with a summary over the visible pool (one bandwidth-bound pass over
+ * the head's K rows); anchors = the n_anchors best rows (ties: lower row), which is what
+ * per-summary top-k, de-duplication and anchor choice yield for any k >= n_anchors; anchors in
+ * descending score order add their windows (clipped, rows already in skipped) until R rows are
+ * in; the earliest visible rows pad to R.  ECAPACITY if some pool holds fewer than R visible
+ * rows; EINVAL on bad sizes, a context without PAST heads, or a pool capacity above 2^20 rows.
+ * workspace: device, >= seg_kv_retrieve_workspace_bytes(), 256-byte aligned, overwritten. */
+segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, const void *q_prev,
+                               int32_t m, int32_t R, int32_t *idx_out, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
 /* Hide the n_oldest oldest rows of one PAST head's pool from now on (all sequences).  Pure
  * bookkeeping: nothing is copied and the rows' storage is not reused.  If the head also has
  * the TAIL bit, rows inside the current tail window stay visible.  Evicting more rows than

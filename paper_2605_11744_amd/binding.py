@@ -30,6 +30,11 @@ class segattn_config(ctypes.Structure):
     ]
 
 
+class segattn_retrieval(ctypes.Structure):
+    _fields_ = [("n_queries", ctypes.c_int32), ("pool_window", ctypes.c_int32), ("tail_avg", ctypes.c_int32),
+                ("n_anchors", ctypes.c_int32), ("win_before", ctypes.c_int32), ("win_after", ctypes.c_int32)]
+
+
 _lib = None
 
 
@@ -58,6 +63,8 @@ def lib() -> ctypes.CDLL:
             "seg_kv_past_append": (ctypes.c_int, [vp, i32, vp, vp, i64, vp]),
             "seg_kv_past_select": (ctypes.c_int, [vp, vp, i32, vp]),
             "seg_kv_past_evict": (ctypes.c_int, [vp, i32, i64, vp]),
+            "seg_kv_retrieve_workspace_bytes": (sz, [vp, ctypes.POINTER(segattn_retrieval)]),
+            "seg_kv_retrieve": (ctypes.c_int, [vp, ctypes.POINTER(segattn_retrieval), vp, i32, i32, vp, vp, sz, vp]),
             "seg_kv_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]),
             "seg_kv_set_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), vp]),
             "segattn_cache_span": (ctypes.c_int, [vp, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(i64)]),
@@ -75,7 +82,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_past_evict",
+           "seg_attn_fwd_seq", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -165,6 +172,21 @@ def seg_kv_past_append(ctx: int, kv_head: int, k, v, rows: int, stream=None) -> 
 
 def seg_kv_past_select(ctx: int, idx, R: int, stream=None) -> None:
     _check(lib().seg_kv_past_select(ctx, _ptr(idx), R, _ptr(stream)), "seg_kv_past_select")
+
+
+def make_retrieval(*, n_queries: int, pool_window: int, tail_avg: int, n_anchors: int, win_before: int,
+                   win_after: int) -> segattn_retrieval:
+    return segattn_retrieval(n_queries, pool_window, tail_avg, n_anchors, win_before, win_after)
+
+
+def seg_kv_retrieve_workspace_bytes(ctx: int, r: segattn_retrieval) -> int:
+    return int(lib().seg_kv_retrieve_workspace_bytes(ctx, ctypes.byref(r)))
+
+
+def seg_kv_retrieve(ctx: int, r: segattn_retrieval, q_prev, m: int, R: int, idx_out, workspace,
+                    workspace_bytes: int, stream=None) -> None:
+    _check(lib().seg_kv_retrieve(ctx, ctypes.byref(r), _ptr(q_prev), m, R, _ptr(idx_out), _ptr(workspace),
+                                 workspace_bytes, _ptr(stream)), "seg_kv_retrieve")
 
 
 def seg_kv_past_evict(ctx: int, kv_head: int, n_oldest: int, stream=None) -> None:

@@ -339,6 +339,70 @@ segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t 
   return SEGATTN_OK;
 }
 
+namespace {
+constexpr int kRetrieveChunk = 4096, kRetrieveCand = 32;
+bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &nsp, int &n_chunks,
+                      unsigned long long &off_val, unsigned long long &off_idx, unsigned long long &total) {
+  if (!ctx || !r || ctx->p.n_past == 0) return false;
+  if (r->n_queries < 1 || r->pool_window < 1 || r->tail_avg < 1 || r->n_anchors < 1 || r->n_anchors > kRetrieveCand)
+    return false;
+  if (r->win_before < 0 || r->win_after < 0 || r->win_before > (1 << 20) || r->win_after > (1 << 20)) return false;
+  if (ctx->g.pool_cap > (1ull << 20)) return false;
+  const long long n_sum = (long long)(r->n_queries + r->pool_window - 1) / r->pool_window + 1;
+  if (n_sum * ctx->p.g > 64) return false;
+  nsp = (int)((n_sum * ctx->p.g + 31) / 32 * 32);
+  n_chunks = (int)((ctx->g.pool_cap + kRetrieveChunk - 1) / kRetrieveChunk);
+  const unsigned long long heads = (unsigned long long)ctx->p.B * ctx->p.n_past;
+  off_val = align_up(heads * nsp * ctx->p.D * 2ull);
+  off_idx = align_up(off_val + heads * n_chunks * kRetrieveCand * 4ull);
+  total = align_up(off_idx + heads * n_chunks * kRetrieveCand * 4ull);
+  return true;
+}
+}  // namespace
+
+size_t seg_kv_retrieve_workspace_bytes(const segattn_ctx *ctx, const segattn_retrieval *r) {
+  int nsp, n_chunks;
+  unsigned long long a, b, total;
+  return retrieval_layout(ctx, r, nsp, n_chunks, a, b, total) ? (size_t)total : 0;
+}
+
+segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, const void *q_prev, int32_t m,
+                               int32_t R, int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+  int nsp, n_chunks;
+  unsigned long long off_val, off_idx, total;
+  if (!retrieval_layout(ctx, r, nsp, n_chunks, off_val, off_idx, total)) return SEGATTN_EINVAL;
+  if (!q_prev || !idx_out || !workspace || m < 1 || R < 1 || R > (1 << 20)) return SEGATTN_EINVAL;
+  if (workspace_bytes < total || ((uintptr_t)workspace % kAlign)) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  const Problem &p = ctx->p;
+  for (int b = 0; b < p.B; ++b)
+    for (int h = 0; h < p.Hkv; ++h) {
+      const size_t i = (size_t)b * p.Hkv + h;
+      if ((p.policy[h] & SEGATTN_PAST) && R > ctx->pool[i] - ctx->lo[i]) return SEGATTN_ECAPACITY;
+    }
+  RetrieveArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q_prev = (const unsigned short *)q_prev;
+  a.cache = ctx->cache;
+  a.geom = ctx->g;
+  a.summaries = (unsigned short *)workspace;
+  a.cand_val = (float *)((unsigned char *)workspace + off_val);
+  a.cand_idx = (int *)((unsigned char *)workspace + off_idx);
+  a.idx_out = idx_out;
+  a.m = m;
+  a.R = R;
+  a.nsp = nsp;
+  a.n_chunks = n_chunks;
+  a.n_queries = r->n_queries;
+  a.pool_window = r->pool_window;
+  a.tail_avg = r->tail_avg;
+  a.n_anchors = r->n_anchors;
+  a.win_before = r->win_before;
+  a.win_after = r->win_after;
+  return hip_status(launch_retrieve(p, a, (hipStream_t)stream));
+}
+
 segattn_status seg_kv_past_evict(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest, void *stream) {
   if (!ctx || n_oldest < 0 || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;
   const Problem &p = ctx->p;

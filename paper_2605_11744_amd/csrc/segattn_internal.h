@@ -96,6 +96,19 @@ struct SelectArgs {
   double inv_freq[64];   // theta^(-2i/D), i < D/2
 };
 
+// Arguments of the retrieval operator kernels.
+struct RetrieveArgs {
+  const unsigned short *q_prev;  // [B, m, Hq, D] queries of the previous segment
+  unsigned char *cache;
+  CacheGeom geom;
+  unsigned short *summaries;     // workspace: [B, n_past, nsp, D] bf16
+  float *cand_val;               // workspace: [B, n_past, n_chunks, 32]
+  int *cand_idx;                 // workspace: same shape
+  int *idx_out;                  // [B, n_past, R]
+  int m, R, nsp, n_chunks;
+  int n_queries, pool_window, tail_avg, n_anchors, win_before, win_after;
+};
+
 struct RopeArgs {
   unsigned short *q, *k;     // rotated in place
   const long long *pos0;     // device [B]: position of row 0 of every sequence, or nullptr (all 0)
@@ -168,6 +181,7 @@ hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStre
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
                               long long n_oldest, hipStream_t st);
 hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st);
+hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t st);
 hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st);
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);
