@@ -173,6 +173,7 @@ def main() -> int:
         torch.cuda.empty_cache()
         result["backward"] = backward_leg(sa, W, w)
         result["decode"] = decode_leg(sa, W)
+        result["retrieve"] = retrieve_leg(sa, W)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(W, w, qb, kb, vb)
     print(json.dumps(result))
@@ -334,6 +335,52 @@ def backward_leg(sa, W, w, batch=4):
     return {"workload": f"2 segments of {S} (truncation depth 1), batch {batch}, heads and policy of {w.name}",
             "ms": round(ms, 3), "useful_flops": flops, "tflops_useful": round(flops / ms / 1e9, 2),
             "frac_of_bf16_mfma_peak": round(flops / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+
+
+def retrieve_leg(sa, W):
+    """Top-k retrieval operator (Appendix D) on the decode workload's caches: B = 64 sequences,
+    two long-range heads each with k_b * 4096 pool rows (random bf16 rows, seeded lengths), R = 512,
+    L_q = 32.  The scoring scan reads every pool K row once: HBM-bound."""
+    import torch
+    w = W.C5
+    k_done, _ = W.decode_lengths(w)
+    B, Hq, Hkv, D, S, T = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seg_len, w.tail_len
+    policy = [2 if (p & 2) else p for p in w.kv_policy]
+    cfg = sa.make_config(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, seg_len=S, tail_len=T,
+                         kv_policy=policy, past_capacity=w.max_context, retrieved_capacity=512)
+    nbytes = sa.segattn_cache_bytes(cfg)
+    arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(w.seed + 3)
+    view = arena[: nbytes // 2 * 2].view(torch.bfloat16)
+    step = 1 << 26
+    for i in range(0, view.numel(), step):
+        n = min(step, view.numel() - i)
+        view[i:i + n] = torch.randn(n, device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    ctx = sa.segattn_create(cfg, arena, nbytes)
+    st = torch.cuda.current_stream().cuda_stream
+    sa.seg_kv_set_lengths(ctx, [int(x) * S for x in k_done], [T] * B, [0] * B, st)
+    r = sa.make_retrieval(n_queries=32, pool_window=8, tail_avg=4, n_anchors=16, win_before=8, win_after=23)
+    nws = sa.seg_kv_retrieve_workspace_bytes(ctx, r)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    n_past = sum(1 for p in policy if p & 2)
+    idx = torch.empty((B, n_past, 512), dtype=torch.int32, device="cuda")
+    q_prev = torch.randn((B, 32, Hq, D), device="cuda", generator=g).to(torch.bfloat16)
+    run = lambda: sa.seg_kv_retrieve(ctx, r, q_prev, 32, 512, idx, ws, nws, st)
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    k_bytes = int(sum(int(x) * S for x in k_done)) * n_past * D * 2
+    sa.segattn_destroy(ctx)
+    return {"workload": "pools of c5_decode_b64 (2 long-range heads), R=512, L_q=32, 16 anchors x 32-row windows",
+            "ms": round(ms, 4), "k_bytes_scanned": k_bytes, "achieved_GBps": round(k_bytes / ms / 1e6, 1),
+            "frac_of_hbm_peak": round(k_bytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
 
 
 def decode_leg(sa, W):

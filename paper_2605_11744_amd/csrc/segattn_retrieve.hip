@@ -24,10 +24,10 @@ namespace segattn {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kChunkRows = 4096;   // pool rows per scoring workgroup
 constexpr int kMaxAnchors = 32;
-constexpr int kMaxPieces = 160;    // disjoint row ranges of one result
 
 __device__ inline const int *rmeta(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b, int h) {
   return (const int *)(cache + g.meta_off) + ((long long)b * p.Hkv + h) * kMetaInts;
@@ -68,14 +68,15 @@ __device__ inline void block_best(float &v, int &i, float *sm_v, int *sm_i) {
 //      repeats summary 0, which cannot change a maximum).  One workgroup per (b, PAST head).
 template <int D>
 __global__ __launch_bounds__(256) void retrieve_summaries_kernel(const Problem p, const RetrieveArgs a) {
+  constexpr int CH = D / 8;  // a thread forms 8 channels of one summary
   const int b = blockIdx.x / p.n_past, np = blockIdx.x % p.n_past;
   const int kv = p.order[np];
   const int L = a.n_queries < a.m ? a.n_queries : a.m;
   const int n_win = (L + a.pool_window - 1) / a.pool_window;
   const int n_sum = n_win + 1;
   unsigned short *dst = a.summaries + ((long long)b * p.n_past + np) * a.nsp * D;
-  for (int item = threadIdx.x; item < a.nsp * D; item += 256) {
-    const int s = item / D, d = item % D;
+  for (int item = threadIdx.x; item < a.nsp * CH; item += 256) {
+    const int s = item / CH, c = item % CH;
     const int sr = s < p.g * n_sum ? s : 0;           // padding rows repeat summary 0
     const int hq = kv * p.g + sr / n_sum, w = sr % n_sum;
     int r0, r1;                                        // rows [r0, r1) of the last L rows
@@ -86,21 +87,39 @@ __global__ __launch_bounds__(256) void retrieve_summaries_kernel(const Problem p
       r0 = L - (a.tail_avg < L ? a.tail_avg : L);
       r1 = L;
     }
-    float acc = 0.f;
-    for (int r = r0; r < r1; ++r)
-      acc += __uint_as_float((unsigned)a.q_prev[(((long long)b * a.m + (a.m - L + r)) * p.Hq + hq) * D + d] << 16);
-    dst[item] = __builtin_bit_cast(unsigned short, (__bf16)(acc / (float)(r1 - r0)));
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const unsigned short *src = a.q_prev + (((long long)b * a.m + (a.m - L)) * p.Hq + hq) * D + 8 * c;
+    const long long stride = (long long)p.Hq * D;
+#pragma unroll 4
+    for (int r = r0; r < r1; ++r) {
+      const uint4 x = *(const uint4 *)(src + r * stride);
+      const unsigned xw[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] += __uint_as_float(xw[e] << 16);
+        acc[2 * e + 1] += __uint_as_float(xw[e] & 0xffff0000u);
+      }
+    }
+    const float inv_n = (float)(r1 - r0);
+    unsigned o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const __bf16 lo16 = (__bf16)(acc[2 * e] / inv_n), hi16 = (__bf16)(acc[2 * e + 1] / inv_n);
+      o[e] = (unsigned)__builtin_bit_cast(unsigned short, lo16) | ((unsigned)__builtin_bit_cast(unsigned short, hi16) << 16);
+    }
+    *(uint4 *)(dst + (long long)s * D + 8 * c) = uint4{o[0], o[1], o[2], o[3]};
   }
 }
 
 // ---- scoring + per-chunk candidates.  grid (chunks, B * n_past), 4 waves; a wave scores 32 rows
-//      at a time: S[summary][row] = Sigma . K^T, A = summaries (registers), B = K rows straight
-//      from HBM in operand layout (lane = row, 16-byte pieces); the lane's 16 accumulator
-//      registers are 16 summaries of its row, so the maximum over summaries is local.
+//      at a time: S[summary][row] = Sigma . K^T, A = summaries (registers), B = K rows in operand
+//      layout (lane = row); the lane's 16 accumulator registers are 16 summaries of its row, so
+//      the maximum over summaries is local.
 template <int D, int NT>  // NT = NSP / 32 summary tiles
 __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, const RetrieveArgs a) {
   constexpr int NC = D / 16;
   __shared__ float sc[kChunkRows];
+  __shared__ __attribute__((aligned(16))) unsigned char stage[4][32 * 2 * D];  // one K tile per wave
   __shared__ float sm_v[4];
   __shared__ int sm_i[4];
   const int b = blockIdx.y / p.n_past, np = blockIdx.y % p.n_past;
@@ -124,13 +143,39 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
   for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int kc = 0; kc < NC; ++kc) A[t][kc] = *(const bf16x8 *)(sg + (long long)(32 * t + col) * D + 16 * kc + 8 * hi);
-  const unsigned short *kb = (const unsigned short *)(a.cache + k_block_off(p, a.geom, b, kv));
+  // K rows travel HBM -> registers with fully coalesced 1 KB wave loads (32 rows of a tile are
+  // contiguous in the pool), are dropped into a wave-private LDS tile with the 16-byte chunks of
+  // a row XOR-swizzled by the row, and come back in operand layout (lane = row).  The loads of
+  // the next tile are in flight while the current one is scored.
+  constexpr int RPL = 1024 / (2 * D);        // rows per 1 KB load
+  constexpr int NL = 32 / RPL;               // loads per tile
+  constexpr int CH = D / 8;                  // 16-byte chunks per row
+  const unsigned char *kb = a.cache + k_block_off(p, a.geom, b, kv);
+  auto swz = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
+  const long long last_byte_row = (long long)(pool - 1);
+  u32x4 cur[NL], nxt[NL];
+  auto fetch = [&](u32x4(&dst)[NL], int t0) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      long long row = (long long)c0 + t0 + RPL * i + lane / CH;
+      row = row < last_byte_row ? row : last_byte_row;  // clamp: stays inside the pool
+      dst[i] = *(const u32x4 *)(kb + row * (2 * D) + (lane % CH) * 16);
+    }
+  };
+  unsigned char *tile = stage[wave];
+  fetch(cur, wave * 32);
   for (int t0 = wave * 32; t0 < kChunkRows; t0 += 128) {
-    const int row = c0 + t0 + col;
-    const int rc = row < pool ? row : pool - 1;  // clamp: stays inside the pool
+    if (t0 + 128 < kChunkRows) fetch(nxt, t0 + 128);
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int r = RPL * i + lane / CH, c = lane % CH;
+      *(u32x4 *)(tile + r * (2 * D) + ((c ^ swz(r)) << 4)) = cur[i];
+    }
     bf16x8 K[NC];
 #pragma unroll
-    for (int kc = 0; kc < NC; ++kc) K[kc] = *(const bf16x8 *)(kb + (long long)rc * D + 16 * kc + 8 * hi);
+    for (int kc = 0; kc < NC; ++kc)
+      K[kc] = *(const bf16x8 *)(tile + col * (2 * D) + (((2 * kc + hi) ^ swz(col)) << 4));
+    const int row = c0 + t0 + col;
     float best = -INFINITY;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -142,6 +187,8 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
     }
     best = fmaxf(best, __shfl_xor(best, 32));  // the other 16 summaries of each tile
     if (hi == 0) sc[t0 + col] = (row >= lo && row < pool) ? best : -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) cur[i] = nxt[i];
   }
   __syncthreads();
   // the chunk's best n_anchors rows: every thread owns 16 scores; n_anchors rounds of a
@@ -173,11 +220,19 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
 }
 
 // ---- merge the candidates of all chunks, expand, pad, emit.  One workgroup per (b, PAST head).
+// The chosen rows are kept as sorted, disjoint, merged row ranges, one per lane of wave 0 (at
+// most one range per anchor window plus the padding prefix); the expansion itself is sequential
+// in the anchors' score order, but every step on the range list is a constant number of
+// wave-wide operations (ballot to locate, shuffle to insert or delete).
+constexpr int kCandLds = 4096;  // candidates held in LDS; beyond that they are re-read from memory
+
 __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, const RetrieveArgs a) {
   __shared__ float sm_v[4];
   __shared__ int sm_i[4];
   __shared__ int anchors[kMaxAnchors];
-  __shared__ int p_lo[kMaxPieces], p_hi[kMaxPieces], p_before[kMaxPieces + 1];
+  __shared__ float lc_v[kCandLds];
+  __shared__ int lc_i[kCandLds];
+  __shared__ int p_lo[64], p_before[65];
   __shared__ int n_pieces;
   const int b = blockIdx.x / p.n_past, np = blockIdx.x % p.n_past;
   const int kv = p.order[np];
@@ -185,7 +240,16 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
   const int pool = meta[META_POOL], lo = meta[META_LO];
   const int tid = threadIdx.x;
   const long long base = ((long long)b * p.n_past + np) * a.n_chunks * kMaxAnchors;
-  const int n_cand = a.n_chunks * kMaxAnchors;
+  // live candidates: n_anchors per chunk
+  const int n_cand = a.n_chunks * a.n_anchors;
+  const bool in_lds = n_cand <= kCandLds;
+  if (in_lds)
+    for (int c = tid; c < n_cand; c += 256) {
+      const long long src = base + (long long)(c / a.n_anchors) * kMaxAnchors + c % a.n_anchors;
+      lc_v[c] = a.cand_val[src];
+      lc_i[c] = a.cand_idx[src];
+    }
+  __syncthreads();
   // anchors: n_anchors rounds of arg-max over the candidates (value desc, row asc); a candidate
   // is retired by remembering the last winner: the order is total, so "strictly after the last
   // winner" selects the next one without writing anything
@@ -196,12 +260,18 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
     float v = -INFINITY;
     int i = 0x7fffffff;
     for (int c = tid; c < n_cand; c += 256) {
-      if ((c % kMaxAnchors) >= a.n_anchors) continue;
-      const float w = a.cand_val[base + c];
-      const int j = a.cand_idx[base + c];
+      float w;
+      int j;
+      if (in_lds) {
+        w = lc_v[c];
+        j = lc_i[c];
+      } else {
+        const long long src = base + (long long)(c / a.n_anchors) * kMaxAnchors + c % a.n_anchors;
+        w = a.cand_val[src];
+        j = a.cand_idx[src];
+      }
       if (w == -INFINITY) continue;
-      if (better(w, j, last_v, last_i)) continue;  // already taken (or is the last winner's better)
-      if (w == last_v && j == last_i) continue;
+      if (better(w, j, last_v, last_i) || (w == last_v && j == last_i)) continue;  // taken already
       if (better(w, j, v, i)) {
         v = w;
         i = j;
@@ -217,44 +287,53 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
   __syncthreads();
   const int visible = pool - lo;
   const int want = a.R < visible ? a.R : visible;
-  if (tid == 0) {
-    // pieces: disjoint row ranges kept sorted by start
-    int np_ = 0, count = 0;
-    auto insert = [&](int s, int e) {  // insert [s, e) keeping the list sorted
-      int k = np_;
-      while (k > 0 && p_lo[k - 1] > s) {
-        p_lo[k] = p_lo[k - 1];
-        p_hi[k] = p_hi[k - 1];
-        --k;
-      }
-      p_lo[k] = s;
-      p_hi[k] = e;
-      ++np_;
-    };
+  if (tid < 64) {
+    const int lane = tid;
+    int plo = 0x7fffffff, phi = 0x7fffffff;  // range `lane` of the sorted list (unused lanes: +inf)
+    int n = 0, count = 0;
     auto add_range = [&](int s, int e) {  // rows of [s, e) not yet in, ascending, until `want`
       int cur = s;
-      while (cur < e && count < want && np_ < kMaxPieces) {
-        // skip over a piece that contains cur
-        int k = 0;
-        bool inside = false;
-        int next_start = e;
-        for (k = 0; k < np_; ++k) {
-          if (p_lo[k] <= cur && cur < p_hi[k]) {
-            inside = true;
-            break;
-          }
-          if (p_lo[k] > cur) {
-            next_start = p_lo[k] < e ? p_lo[k] : e;
-            break;
-          }
-        }
-        if (inside) {
-          cur = p_hi[k];
+      while (cur < e && count < want) {
+        const unsigned long long inside = __builtin_amdgcn_ballot_w64(plo <= cur && cur < phi);
+        if (inside) {  // cur lies in a range: continue behind it
+          cur = __builtin_amdgcn_readlane(phi, (int)__builtin_ctzll(inside));
           continue;
+        }
+        const unsigned long long later = __builtin_amdgcn_ballot_w64(lane < n && plo > cur);
+        const int kn = later ? (int)__builtin_ctzll(later) : n;  // first range behind cur
+        int next_start = e;
+        if (later) {
+          const int ns = __builtin_amdgcn_readlane(plo, kn);
+          next_start = ns < e ? ns : e;
         }
         int take = next_start - cur;
         if (take > want - count) take = want - count;
-        insert(cur, cur + take);
+        int j;  // the range that now ends at cur + take
+        if (kn > 0 && __builtin_amdgcn_readlane(phi, kn - 1) == cur) {  // grows the range before it
+          j = kn - 1;
+          if (lane == j) phi = cur + take;
+        } else {  // new range at position kn: ranges kn.. move up one lane
+          const int ulo = __shfl_up(plo, 1), uhi = __shfl_up(phi, 1);
+          if (lane > kn) {
+            plo = ulo;
+            phi = uhi;
+          } else if (lane == kn) {
+            plo = cur;
+            phi = cur + take;
+          }
+          j = kn;
+          n += 1;
+        }
+        if (j + 1 < n && __builtin_amdgcn_readlane(plo, j + 1) == cur + take) {  // touches the next: merge
+          const int nhi = __builtin_amdgcn_readlane(phi, j + 1);
+          const int dlo = __shfl_down(plo, 1), dhi = __shfl_down(phi, 1);
+          if (lane == j) phi = nhi;
+          else if (lane > j) {
+            plo = lane + 1 < 64 ? dlo : 0x7fffffff;
+            phi = lane + 1 < 64 ? dhi : 0x7fffffff;
+          }
+          n -= 1;
+        }
         count += take;
         cur += take;
       }
@@ -266,17 +345,21 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
       add_range(s, e);
     }
     add_range(lo, pool);  // padding: the earliest visible rows not yet in
-    int before = 0;
-    for (int k = 0; k < np_; ++k) {
-      p_before[k] = before;
-      before += p_hi[k] - p_lo[k];
+    // rows before each range (exclusive prefix sum of the lengths)
+    int len = lane < n ? phi - plo : 0, incl = len;
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) {
+      const int up = __shfl_up(incl, sh);
+      if (lane >= sh) incl += up;
     }
-    p_before[np_] = before;
-    n_pieces = np_;
+    p_lo[lane] = plo;
+    p_before[lane] = incl - len;
+    if (lane == 63) p_before[64] = incl;
+    if (lane == 0) n_pieces = n;
   }
   __syncthreads();
   int *out = a.idx_out + ((long long)b * p.n_past + np) * a.R;
-  const int total = p_before[n_pieces];
+  const int total = p_before[64];
   for (int o = tid; o < a.R; o += 256) {
     int val = 0;
     if (o < total) {
@@ -284,7 +367,7 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
       while (k + 1 < n_pieces && p_before[k + 1] <= o) ++k;
       val = p_lo[k] + (o - p_before[k]);
     } else if (total > 0) {
-      val = p_hi[n_pieces - 1] - 1;  // unreachable when R <= visible rows (checked on the host)
+      val = pool - 1;  // unreachable when R <= visible rows (checked on the host)
     }
     out[o] = val;
   }
