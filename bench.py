@@ -216,11 +216,11 @@ def streaming_leg(sa, W, w, q, k, v, out, lse, flops):
 
 
 def retrieval_leg(sa, W, w, q, k, v, out, R=512):
-    """The paper's own long-range channel on the same 128K inputs (Sec. 3.4; Appendix F: R = 512):
-    PAST heads see R gathered pool rows + their segment instead of the whole history.  Per
-    segment: seg_kv_past_select (gather), seg_attn_fwd, seg_kv_commit.  The index lists are
-    seeded random distinct pool rows, drawn before the timed region (choosing them -- the top-k
-    scoring of Appendix D -- is not part of this path)."""
+    """The paper's own long-range channel on the same 128K inputs (Sec. 3.4; Appendix F: R = 512,
+    L_q in [24, 64]): PAST heads see R retrieved pool rows + their segment instead of the whole
+    history.  Per segment: seg_kv_retrieve (Appendix D: scores over the pool, anchors, windows),
+    seg_kv_past_select (gather), seg_attn_fwd, seg_kv_commit.  Sizes the paper leaves open:
+    8-row pooling windows, 4-row tail average, 16 anchors with 32-row windows."""
     import torch
     N, S, T = w.seq_len, w.seg_len, w.tail_len
     policy = [2 if (p & 2) else p for p in w.kv_policy]       # long-range heads: retrieved prefix only
@@ -232,12 +232,10 @@ def retrieval_leg(sa, W, w, q, k, v, out, R=512):
     ctx = sa.segattn_create(cfg, arena, nbytes)
     stream = torch.cuda.current_stream().cuda_stream
     lse_seg = torch.empty((w.batch, w.n_q_heads, S), dtype=torch.float32, device="cuda")
-    g = torch.Generator(device="cuda").manual_seed(w.seed)
-    lists = {}
-    for s in range(S, N, S):
-        r = min(R, s)
-        lists[s] = torch.stack([torch.randperm(s, device="cuda", generator=g)[:r] for _ in range(w.batch * n_past)]) \
-            .to(torch.int32).view(w.batch, n_past, r).contiguous()
+    rp = sa.make_retrieval(n_queries=32, pool_window=8, tail_avg=4, n_anchors=16, win_before=8, win_after=23)
+    nws = sa.seg_kv_retrieve_workspace_bytes(ctx, rp)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    idx = torch.empty((w.batch, n_past, R), dtype=torch.int32, device="cuda")
     gq = w.n_q_heads // w.n_kv_heads
     pairs = 0
     for s in range(0, N, S):
@@ -247,26 +245,32 @@ def retrieval_leg(sa, W, w, q, k, v, out, R=512):
             pairs += gq * (m * (m + 1) // 2 + m * prefix)
     flops = 4 * w.head_dim * pairs * w.batch
 
-    def run():
+    def run(with_retrieval=True):
         sa.segattn_reset(ctx, stream)
         for s in range(0, N, S):
             m = min(S, N - s)
-            if s:
-                sa.seg_kv_past_select(ctx, lists[s], lists[s].shape[2], stream)
+            if s and with_retrieval:
+                sa.seg_kv_retrieve(ctx, rp, q[:, s - S:s], S, R, idx, ws, nws, stream)
+                sa.seg_kv_past_select(ctx, idx, R, stream)
             sa.seg_attn_fwd(ctx, q[:, s:s + m], k[:, s:s + m], v[:, s:s + m], m, out[:, s:s + m], lse_seg, stream)
             sa.seg_kv_commit(ctx, k[:, s:s + m], v[:, s:s + m], m, stream)
 
-    run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    reps = 3
-    for _ in range(reps):
-        run()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / reps
+    def timed(flag):
+        run(flag)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 3
+        for _ in range(reps):
+            run(flag)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    ms = timed(True)
+    ms_no_prefix = timed(False)
     res = {"R": R, "kv_policy": policy, "ms": round(ms, 3), "useful_flops": flops,
-           "tflops_useful": round(flops / ms / 1e9, 2), "resident_kv_bytes": sa.segattn_resident_bytes(ctx),
-           "arena_bytes": nbytes}
+           "tflops_useful": round(flops / ms / 1e9, 2),
+           "ms_retrieve_and_select": round(ms - ms_no_prefix, 3),
+           "resident_kv_bytes": sa.segattn_resident_bytes(ctx), "arena_bytes": nbytes}
     sa.segattn_destroy(ctx)
     return res
 

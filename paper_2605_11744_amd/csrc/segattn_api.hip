@@ -340,7 +340,12 @@ segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t 
 }
 
 namespace {
-constexpr int kRetrieveChunk = 4096, kRetrieveCand = 32;
+constexpr int kRetrieveCand = 32;
+// pool rows per scoring workgroup: small chunks when (sequences x long-range heads) are few
+int retrieve_chunk_rows(const segattn_ctx *ctx) {
+  const unsigned long long big = (ctx->g.pool_cap + 4095) / 4096 * ctx->p.B * ctx->p.n_past;
+  return big >= 1024 ? 4096 : 1024;
+}
 bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &nsp, int &n_chunks,
                       unsigned long long &off_val, unsigned long long &off_idx, unsigned long long &total) {
   if (!ctx || !r || ctx->p.n_past == 0) return false;
@@ -351,7 +356,8 @@ bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &n
   const long long n_sum = (long long)(r->n_queries + r->pool_window - 1) / r->pool_window + 1;
   if (n_sum * ctx->p.g > 64) return false;
   nsp = (int)((n_sum * ctx->p.g + 31) / 32 * 32);
-  n_chunks = (int)((ctx->g.pool_cap + kRetrieveChunk - 1) / kRetrieveChunk);
+  const int chunk = retrieve_chunk_rows(ctx);
+  n_chunks = (int)((ctx->g.pool_cap + chunk - 1) / chunk);
   const unsigned long long heads = (unsigned long long)ctx->p.B * ctx->p.n_past;
   off_val = align_up(heads * nsp * ctx->p.D * 2ull);
   off_idx = align_up(off_val + heads * n_chunks * kRetrieveCand * 4ull);
@@ -394,6 +400,7 @@ segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, con
   a.R = R;
   a.nsp = nsp;
   a.n_chunks = n_chunks;
+  a.chunk_rows = retrieve_chunk_rows(ctx);
   a.n_queries = r->n_queries;
   a.pool_window = r->pool_window;
   a.tail_avg = r->tail_avg;

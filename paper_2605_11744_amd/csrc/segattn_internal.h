@@ -105,7 +105,7 @@ struct RetrieveArgs {
   float *cand_val;               // workspace: [B, n_past, n_chunks, 32]
   int *cand_idx;                 // workspace: same shape
   int *idx_out;                  // [B, n_past, R]
-  int m, R, nsp, n_chunks;
+  int m, R, nsp, n_chunks, chunk_rows;
   int n_queries, pool_window, tail_avg, n_anchors, win_before, win_after;
 };
 

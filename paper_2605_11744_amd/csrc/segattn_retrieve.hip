@@ -12,7 +12,8 @@
 //                        matrix cores so that the scan stays bandwidth-bound
 //   top-k / anchors      the n_anchors rows with the highest scores, ties to the lower row.  (For
 //                        any k >= n_anchors these are the anchors that "per-summary top-k,
-//                        de-duplicate, keep the best" yields.)  Two levels: every 4096-row chunk
+//                        de-duplicate, keep the best" yields.)  Two levels: every chunk of 1024
+//                        or 4096 rows (small chunks when few heads have to fill the chip)
 //                        keeps its own best n_anchors next to the scores in LDS -- scores never
 //                        go to HBM -- and one workgroup per head merges the candidates
 //   window expansion     anchors in descending score order add rows a - win_before .. a + win_after
@@ -26,7 +27,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kChunkRows = 4096;   // pool rows per scoring workgroup
 constexpr int kMaxAnchors = 32;
 
 __device__ inline const int *rmeta(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b, int h) {
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void retrieve_summaries_kernel(const Problem p
 //      at a time: S[summary][row] = Sigma . K^T, A = summaries (registers), B = K rows in operand
 //      layout (lane = row); the lane's 16 accumulator registers are 16 summaries of its row, so
 //      the maximum over summaries is local.
-template <int D, int NT>  // NT = NSP / 32 summary tiles
+template <int D, int NT, int kChunkRows>  // NT = NSP / 32 summary tiles; pool rows per workgroup
 __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, const RetrieveArgs a) {
   constexpr int NC = D / 16;
   __shared__ float sc[kChunkRows];
@@ -381,13 +381,19 @@ hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t 
   if (e != hipSuccess) return e;
   const dim3 grid(a.n_chunks, p.B * p.n_past);
   const int nt = a.nsp / 32;
+#define SEGATTN_SCORE(DD, NTT)                                                                            \
+  do {                                                                                                    \
+    if (a.chunk_rows == 1024) hipLaunchKernelGGL((retrieve_score_kernel<DD, NTT, 1024>), grid, dim3(256), 0, st, p, a); \
+    else hipLaunchKernelGGL((retrieve_score_kernel<DD, NTT, 4096>), grid, dim3(256), 0, st, p, a);         \
+  } while (0)
   if (p.D == 128) {
-    if (nt == 1) hipLaunchKernelGGL((retrieve_score_kernel<128, 1>), grid, dim3(256), 0, st, p, a);
-    else hipLaunchKernelGGL((retrieve_score_kernel<128, 2>), grid, dim3(256), 0, st, p, a);
+    if (nt == 1) SEGATTN_SCORE(128, 1);
+    else SEGATTN_SCORE(128, 2);
   } else {
-    if (nt == 1) hipLaunchKernelGGL((retrieve_score_kernel<64, 1>), grid, dim3(256), 0, st, p, a);
-    else hipLaunchKernelGGL((retrieve_score_kernel<64, 2>), grid, dim3(256), 0, st, p, a);
+    if (nt == 1) SEGATTN_SCORE(64, 1);
+    else SEGATTN_SCORE(64, 2);
   }
+#undef SEGATTN_SCORE
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(retrieve_select_kernel, heads, dim3(256), 0, st, p, a);
