@@ -18,9 +18,9 @@ HIPCC_FLAGS = (
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 )
-# Per-source extras.  Forward prefill kernel: its S^T products deliver their result in vector
-# registers (where the softmax reads it) and it pins the output accumulators to accumulation
-# registers itself.  Every other file keeps the compiler's default MFMA register form.
+# Per-source extras.  Forward prefill kernel: every matrix product delivers its result in vector
+# registers, where the softmax reads it (the kernel fits in 256 of them per wave).  Every other
+# file keeps the compiler's default MFMA register form.
 EXTRA_FLAGS = {"segattn_prefill_mfma.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1")}
 
 

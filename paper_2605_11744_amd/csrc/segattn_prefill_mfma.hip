@@ -1,9 +1,9 @@
 // bf16 MFMA prefill kernel of libsegattn: segment-level causal attention (Eq. 12 with the
 // per-head context of Eq. 13, Appendix C) for gfx950.
 //
-// Workgroup = 4 waves, one wave per SIMD, up to 512 registers per lane.  HS query heads of one
-// GQA group share the staged K/V rows; each wave owns one head and 64 consecutive query rows
-// (two 32-column MFMA blocks).  Keys are consumed in steps of 32:
+// Workgroup = 8 waves (two per SIMD, 256 registers each) for head_dim 128, 4 waves for head_dim
+// 64.  HS query heads of one GQA group share the staged K/V rows; each wave owns one head and
+// 32 (head_dim 128) or 64 consecutive query rows.  Keys are consumed in steps of 32:
 //
 //   S^T[key][query] = K_step . Q^T      v_mfma_f32_32x32x16_bf16, A = K rows read from LDS
 //   P = exp2(S^T c - m c)               per query, m a running reference maximum
@@ -59,7 +59,6 @@ struct StepGeom {
   static constexpr int kTensorBytes = kStepKeys * kRowBytes;   // K (or V) rows of one step
   static constexpr int kSlotBytes = 2 * kTensorBytes;
   static constexpr int kInstr = kTensorBytes / 1024;           // wave-wide 1 KB loads per tensor
-  static constexpr int kInstrPerWave = kInstr / 4;
   static constexpr int kRowsPerInstr = 1024 / kRowBytes;
   static constexpr int kRowsPer256 = 256 / kRowBytes;          // rows sharing one 64-bank window
   // K rows are read 16 lanes = 16 consecutive rows at one logical chunk: XOR-ing the low three
@@ -80,38 +79,23 @@ __device__ inline float half_sum(float x) {
   return __int_as_float(sw[0]) + __int_as_float(sw[1]);
 }
 
-// The output accumulators live in accumulation registers (AGPRs): the matrix cores read and
-// write them there directly and the vector registers stay free for the softmax.  The few
-// places that touch them with the vector ALU go through these helpers.
-__device__ inline float acc_zero() {
-  float x;
-  asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(x));
-  return x;
-}
-__device__ inline float acc_scale(float x, float alpha) {  // x * alpha, x and the result in AGPRs
-  float t;
-  asm volatile("v_accvgpr_read_b32 %1, %0\n\ts_nop 1\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1"
-               : "+a"(x), "=&v"(t)
-               : "v"(alpha));
-  return x;
-}
-__device__ inline float acc_get(float x) {
-  float t;
-  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(x));
-  return t;
-}
-// MFMA results must have left the pipeline before the helpers above read them.
-__device__ inline void acc_drain() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
-
-template <int D, int HS>
-__global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, const PrefillArgs a) {
-  using G = StepGeom<D>;
-  constexpr int QB = 2;             // 32-query blocks per wave
+// QB = 32-query blocks per wave, NW = waves per workgroup.  (D, QB, NW) = (128, 1, 8): two
+// waves per SIMD share the issue slots -- while one is blocked behind a matrix product or a
+// wait the other issues its softmax -- at the price of reading every K/V operand from LDS for
+// half as many products.  All products are compiler builtins in VGPR form (the file is built
+// with -amdgpu-mfma-vgpr-form): the compiler sees every MFMA hazard.  An earlier version kept
+// O^T in accumulation registers through inline-asm products; wherever the register allocator
+// then moved O^T at a control-flow merge, the move could read an accumulator whose product
+// was still in the pipeline, and results depended on register allocation.
+template <int D, int HS, int QB, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(const Problem p, const PrefillArgs a) {
+  using G = StepGeom<D>;  // NW = waves per workgroup; NW * QB = 4 leaves room for two workgroups per CU
   constexpr int RW = 32 * QB;       // query rows per wave
-  constexpr int BQ = (4 / HS) * RW; // query rows per workgroup
+  constexpr int BQ = (NW / HS) * RW; // query rows per workgroup
   constexpr int NC = D / 16;        // k-chunks of the QK^T product
   constexpr int NB = D / 32;        // 32-row blocks of O^T
-  constexpr int LPW = G::kInstrPerWave;
+  constexpr int LPW = G::kInstr / NW;  // wave-wide 1 KB loads per tensor, step and wave
+  static_assert(LPW >= 1, "too many waves for this tile");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const WorkItem w = resolve(p, a, blockIdx.x, BQ, HS);
@@ -254,9 +238,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 
   for (int i = 0; i < kSlots - 1 && i < n; ++i) issue();
 
-  // ---- Q^T operands: Qr[qb][kc] = Q[row(qb, col)][16 kc + 8 hi .. +7], parked in accumulation
-  //      registers (they are only ever MFMA operands) so that the vector registers stay free
-  //      for the softmax and for operand prefetch.
+  // ---- Q^T operands: Qr[qb][kc] = Q[row(qb, col)][16 kc + 8 hi .. +7]
   bf16x8 Qr[QB][NC];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -266,13 +248,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 #pragma unroll
     for (int kc = 0; kc < NC; ++kc) {
       const i32x4 v = __builtin_bit_cast(i32x4, *(const uint4 *)(qrow + 16 * kc));
-      int a0, a1, a2, a3;
-      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a0) : "v"(v[0]));
-      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a1) : "v"(v[1]));
-      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a2) : "v"(v[2]));
-      asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a3) : "v"(v[3]));
-      const i32x4 q4 = {a0, a1, a2, a3};
-      Qr[qb][kc] = __builtin_bit_cast(bf16x8, q4);
+      Qr[qb][kc] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
@@ -303,7 +279,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) O[qb][nb][r] = acc_zero();
+      for (int r = 0; r < 16; ++r) O[qb][nb][r] = 0.f;
   }
 
   // ---- operand fetch from LDS.  Inline asm: the order and the waits are ours (the compiler
@@ -365,16 +341,13 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
         S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, Kr[kc]), Qr[qb][kc],
                                                         kc == 0 ? zero : S[qb], 0, 0, 0);
   };
-  // One PV product O^T[qb][nb] += V^T(h2, nb) . P^T[qb][h2].  Inline asm with the accumulator
-  // pinned to accumulation registers: O^T is then never a vector-register value, while the
-  // S^T products above (compiled in VGPR form) deliver their result where the softmax reads it.
+  // One PV product O^T[qb][nb] += V^T(h2, nb) . P^T[qb][h2]
   auto pv_one = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2, int nb, int qb) {
     const bf16x8 va =
         __builtin_bit_cast(bf16x8, __builtin_shufflevector(Vr[h2][nb][0], Vr[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7));
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(O[qb][nb]) : "v"(va), "v"(P[qb][h2]));
+    O[qb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, P[qb][h2], O[qb][nb], 0, 0, 0);
   };
   auto pv_mma = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2) {
-    asm volatile("s_nop 4");  // P may have been written by the vector ALU just before
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -431,12 +404,10 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
   };
   auto rescale = [&](int qb, float alpha) {  // rare: O^T and l of query block qb times alpha
     l_run[qb] *= alpha;
-    acc_drain();
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) O[qb][nb][r] = acc_scale(O[qb][nb][r], alpha);
-    acc_drain();
+      for (int r = 0; r < 16; ++r) O[qb][nb][r] = O[qb][nb][r] * alpha;
   };
   // Validate the P just formed (before anything uses it).  A lane's row sum can only exceed
   // 2^8 if one of its weights does, i.e. if a score of this step exceeds the reference maximum
@@ -450,7 +421,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     if (__builtin_amdgcn_ballot_w64(any) != 0) {
       // The first P stays "used" on this path too, so that its computation is not sunk below
       // the branch (it has to overlap with the matrix products above).
-      asm volatile("" ::"v"(P[0][0]), "v"(P[0][1]), "v"(P[1][0]), "v"(P[1][1]), "v"(psum[0]), "v"(psum[1]));
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) asm volatile("" ::"v"(P[qb][0]), "v"(P[qb][1]), "v"(psum[qb]));
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const float mx = row_max(S, qb);
@@ -508,17 +480,18 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
   //   odd slots               convert pair i to bf16 and add it to the row sum
   auto hot_step = [&](i32x4(&Kr)[NC], const float(&Sc)[QB][16], float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2],
                       bf16x8(&Pc)[QB][2]) {
-    constexpr int NS = 2 * NC, NP = 2 * NB;  // slots of the S^T product / of half a PV product
+    constexpr int NS = QB * NC, NP = QB * NB;  // slots of the S^T product / of half a PV product
     constexpr int NSLOT = NS + 2 * NP;
-    constexpr int EPS = 32 / NSLOT;          // softmax elements per slot (32 per lane and step)
-    static_assert(EPS * NSLOT == 32 && (EPS == 1 || EPS == 2), "slot layout");
+    constexpr int NE = 16 * QB;                // softmax elements per lane and step
+    constexpr int EPS = NE / NSLOT;            // of them per slot
+    static_assert(EPS * NSLOT == NE && (EPS == 1 || EPS == 2), "slot layout");
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    float psum[QB] = {0.f, 0.f};
+    float psum[QB] = {};
     s16x4 Vr[2][NB][2];
     f32x16 Sacc[QB];
     int Pw[QB][8];  // P of the current step as 32-bit words: word 4 h2 + t of Pw[qb] = elements 8 h2 + 2t, +1
-    float ev[32];   // exp2 results on their way to the bf16 pairs (a few live at a time)
+    float ev[NE];   // exp2 results on their way to the bf16 pairs (a few live at a time)
     unsigned va[NB], ka[NKA];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) va[nb] = (unsigned)(size_t)lds + (unsigned)(voff[nb] + so_m1);
@@ -550,11 +523,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     for (int slot = 0; slot < NSLOT; ++slot) {
       // ---- the slot's matrix product
       if (slot < NS) {
-        const int kc = slot / 2, qb = slot % 2;
+        const int kc = slot / QB, qb = slot % QB;
         Sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, Kr[kc]), Qr[qb][kc],
                                                            kc == 0 ? zero : Sacc[qb], 0, 0, 0);
       } else {
-        const int t = slot - NS, h2 = t / NP, nb = (t % NP) / 2, qb = t % 2;
+        const int t = slot - NS, h2 = t / NP, nb = (t % NP) / QB, qb = t % QB;
         pv_one(Vr, Pp, h2, nb, qb);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -593,15 +566,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     {  // the last pair(s)
       typedef float f32x2 __attribute__((ext_vector_type(2)));
       const int qb = QB - 1;
-      if (EPS == 1) {
-        const f32x2 ee = {ev[30], ev[31]};
-        Pw[qb][7] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
-        psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][7]), ones, psum[qb], false);
-      } else {
-        const f32x2 ee = {ev[30], ev[31]};
-        Pw[qb][7] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
-        psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][7]), ones, psum[qb], false);
-      }
+      const f32x2 ee = {ev[NE - 2], ev[NE - 1]};
+      Pw[qb][7] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
+      psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][7]), ones, psum[qb], false);
     }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
@@ -654,10 +621,13 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 
   // =========================== main sequence ===========================
   sync_step(0);
-  float Sa[QB][16], Sb[QB][16];
-  bf16x8 Pa[QB][2], Pb[QB][2];
-  i32x4 Kr[NC];
+  // (all defined from the start: on some paths through the step schedule one of each pair is
+  // never written, and a value that is undefined on one path may not be merged with one that is)
+  float Sa[QB][16] = {}, Sb[QB][16] = {};
+  bf16x8 Pa[QB][2] = {}, Pb[QB][2] = {};
+  i32x4 Kr[NC] = {};
   int j = 0;
+  bool pend_in_a = false;
   if (f > 0) {
     {  // step 0 without overlap: exact maximum as the first reference
       float psum[QB];
@@ -725,20 +695,15 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
       fast_step(j, no, no, Kr, Sa, Sb, Pb, Pa);
       advance();
     }
-    if (rest == 3 || rest == 1) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        Pb[qb][0] = Pa[qb][0];
-        Pb[qb][1] = Pa[qb][1];
-      }
-    }
+    pend_in_a = rest == 3 || rest == 1;  // an odd number of steps since the hot loop: the last P is in Pa
     if (rest > 0) j += rest;
   }
-  // here j == f, so_0 is the slot of step j and, if f > 0, P(f-1) waits in Pb
+  // here j == f, so_0 is the slot of step j and, if f > 0, P(f-1) waits in Pb (or Pa)
   bool pending = f > 0;
   for (; j < n; ++j) {
     if (pending) {
-      pv(so_m1, Pb);
+      if (pend_in_a) pv(so_m1, Pa);
+      else pv(so_m1, Pb);
       pending = false;
     }
     if (j < j_active_end) {
@@ -748,19 +713,21 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
     if (j > 0) sync_step(j);
     advance();
   }
-  if (pending) pv(so_m1, Pb);
+  if (pending) {
+    if (pend_in_a) pv(so_m1, Pa);
+    else pv(so_m1, Pb);
+  }
 
   // ---- epilogue: normalise, write LSE, and write O through LDS so that every store
   // instruction covers whole 16-byte pieces of contiguous output rows.  A lane holds four
   // consecutive d of one query row per accumulator quad; it drops them into the wave's own
   // [32 rows][D] staging block (rows padded by 8 bytes against bank conflicts), and the wave
   // reads the block back row-major.
-  acc_drain();
   __syncthreads();  // every wave is past its last read of the K/V ring
   const bool wide = p.out_fp32 != 0;
   const int es = wide ? 4 : 2;                 // bytes per output element
   const int row_bytes = D * es + 8;
-  unsigned char *stage = smem + wave * (32 * (D * 4 + 8));
+  unsigned char *stage = smem + wave * (32 * (D * es + 8));
   const int lanes_per_row = D * es / 16;       // 16-byte pieces per output row
   const int rows_per_pass = 64 / lanes_per_row;
 #pragma unroll
@@ -774,8 +741,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_kernel(const Problem p, c
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         const int d = 32 * nb + 8 * rg + 4 * hi;
-        const f32x4 o = {acc_get(O[qb][nb][4 * rg + 0]) * inv, acc_get(O[qb][nb][4 * rg + 1]) * inv,
-                         acc_get(O[qb][nb][4 * rg + 2]) * inv, acc_get(O[qb][nb][4 * rg + 3]) * inv};
+        const f32x4 o = {O[qb][nb][4 * rg + 0] * inv, O[qb][nb][4 * rg + 1] * inv,
+                         O[qb][nb][4 * rg + 2] * inv, O[qb][nb][4 * rg + 3] * inv};
         unsigned char *dst = stage + col * row_bytes + d * es;
         if (wide) {
           *(uint2 *)dst = uint2{__float_as_uint(o[0]), __float_as_uint(o[1])};
@@ -805,22 +772,32 @@ hipError_t launch_prefill_fp32(const Problem &p, const PrefillArgs &a, long long
 
 static int heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1; }
 
-int prefill_rows_per_workgroup(const Problem &p) {
-  if (p.fp32_math) return 64;
-  return (4 / heads_per_wg(p)) * 64;
+// D = 128: 32 query rows per wave, eight waves (two per SIMD) that share the K/V tiles.
+// D = 64: 64 query rows per wave, four waves (the tiles are too small to split their loads
+// over eight).
+static int mfma_rows(const Problem &p) {
+  const int hs = heads_per_wg(p);
+  return p.D == 128 ? (8 / hs) * 32 : (4 / hs) * 64;
 }
 
-template <int D, int HS>
+int prefill_rows_per_workgroup(const Problem &p) {
+  if (p.fp32_math) return 64;
+  return mfma_rows(p);
+}
+
+template <int D, int HS, int QB, int NW>
 static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a, long long grid, hipStream_t st) {
-  constexpr int lds = kSlots * StepGeom<D>::kSlotBytes;
-  auto kern = prefill_mfma_kernel<D, HS>;
+  constexpr int ring = kSlots * StepGeom<D>::kSlotBytes;
+  constexpr int epilogue = NW * 32 * (D * 4 + 8);  // fp32 output staging, one block per wave
+  constexpr int lds = ring > epilogue ? ring : epilogue;
+  auto kern = prefill_mfma_kernel<D, HS, QB, NW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), lds, st, p, a);
   return hipGetLastError();
 }
 
@@ -831,13 +808,13 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (fp32) return launch_prefill_fp32(p, a, grid, st);
   if (p.D == 128) {
-    if (hs == 4) return launch_mfma<128, 4>(p, a, grid, st);
-    if (hs == 2) return launch_mfma<128, 2>(p, a, grid, st);
-    return launch_mfma<128, 1>(p, a, grid, st);
+    if (hs == 4) return launch_mfma<128, 4, 1, 8>(p, a, grid, st);
+    if (hs == 2) return launch_mfma<128, 2, 1, 8>(p, a, grid, st);
+    return launch_mfma<128, 1, 1, 8>(p, a, grid, st);
   }
-  if (hs == 4) return launch_mfma<64, 4>(p, a, grid, st);
-  if (hs == 2) return launch_mfma<64, 2>(p, a, grid, st);
-  return launch_mfma<64, 1>(p, a, grid, st);
+  if (hs == 4) return launch_mfma<64, 4, 2, 4>(p, a, grid, st);
+  if (hs == 2) return launch_mfma<64, 2, 2, 4>(p, a, grid, st);
+  return launch_mfma<64, 1, 2, 4>(p, a, grid, st);
 }
 
 }  // namespace segattn
