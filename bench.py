@@ -168,6 +168,7 @@ def main() -> int:
     if not args.no_extras:
         result["streaming"] = streaming_leg(sa, W, w, q, k, v, out, lse, flops)
         result["retrieval"] = retrieval_leg(sa, W, w, q, k, v, out)
+        result["ragged"] = ragged_leg(sa, W, w, q, k, v, out)
         result["rope"] = rope_leg(sa, W, w, q, k)
         del q, k, v, out, lse
         torch.cuda.empty_cache()
@@ -273,6 +274,44 @@ def retrieval_leg(sa, W, w, q, k, v, out, R=512):
            "resident_kv_bytes": sa.segattn_resident_bytes(ctx), "arena_bytes": nbytes}
     sa.segattn_destroy(ctx)
     return res
+
+
+def ragged_leg(sa, W, w, q, k, v, out):
+    """A packed batch of prompts of different lengths in one launch (seg_attn_fwd_varlen): the
+    128K tokens of the main workload cut into 12 sequences of 2K..32K tokens (a long-context
+    evaluation mix: many short prompts, a few long ones), same heads, segment and policy."""
+    import torch
+    lens = [32768, 24576, 20000, 16384, 12288, 8192, 6000, 4096, 3000, 2048, 1000, 720]
+    assert sum(lens) == w.seq_len
+    S, T = w.seg_len, w.tail_len
+    gq = w.n_q_heads // w.n_kv_heads
+    pairs = 0
+    for n in lens:
+        for s in range(0, n, S):
+            m = min(S, n - s)
+            for p in w.kv_policy:
+                prefix = s if (p & 2) else (min(T, s) if (p & 1) else 0)
+                pairs += gq * (m * (m + 1) // 2 + m * prefix)
+    flops = 4 * w.head_dim * pairs
+    cu = torch.tensor([0] + list(__import__("itertools").accumulate(lens)), dtype=torch.int32, device="cuda")
+    cfg = sa.make_config(batch=len(lens), n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seg_len=S, tail_len=T, kv_policy=list(w.kv_policy))
+    lse = torch.empty((w.n_q_heads, w.seq_len), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run():
+        sa.seg_attn_fwd_varlen(cfg, q[0], k[0], v[0], cu, w.seq_len, max(lens), out[0], lse, stream)
+
+    run()
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / reps
+    return {"sequences": len(lens), "lengths": lens, "ms": round(ms, 3), "useful_flops": flops,
+            "tflops_useful": round(flops / ms / 1e9, 2)}
 
 
 def rope_leg(sa, W, w, q, k):

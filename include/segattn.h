@@ -121,6 +121,23 @@ segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, cons
 segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const void *k,
                                 const void *v, int64_t n, void *out, float *lse, void *stream);
 
+/* Packed ragged batch (sequences of different lengths, no padding): q [total,Hq,D], k,v
+ * [total,Hkv,D], out [total,Hq,D], lse [Hq,total]; sequence b = rows cu_seqlens[b] ..
+ * cu_seqlens[b+1]-1 with its own segment grid (segments start at multiples of S inside the
+ * sequence).  cu_seqlens: DEVICE int32 [cfg->batch + 1], ascending, cu_seqlens[0] = 0; total and
+ * max_seqlen (the longest sequence, which sizes the launch) are host values.  An empty sequence
+ * is allowed.  Otherwise as seg_attn_fwd_seq. */
+segattn_status seg_attn_fwd_varlen(const segattn_config *cfg, const void *q, const void *k,
+                                   const void *v, const int32_t *cu_seqlens, int64_t total,
+                                   int64_t max_seqlen, void *out, float *lse, void *stream);
+
+/* Policy array of one layer from the paper's head/layer sets (Sec. 3.4): KV heads in
+ * long_heads are long-range heads, the others local (TAIL); a long-range head is PAST in a layer
+ * of L_long and within-segment only (SEG) elsewhere.  Host only: long_heads [n_long] KV-head
+ * indices, policy_out [n_kv_heads].  EINVAL on a bad index. */
+segattn_status segattn_layer_policy(int32_t n_kv_heads, const int32_t *long_heads, int32_t n_long,
+                                    int32_t layer_in_l_long, uint8_t *policy_out);
+
 /* ---- positions --------------------------------------------------------------------------- */
 
 /* RoPE re-indexing for prefix concatenation (Sec. 3.4, Appendix E).  Rotates q [B,rows,Hq,D] and
@@ -224,6 +241,14 @@ segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, con
  * the pool holds hides all of them. */
 segattn_status seg_kv_past_evict(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest,
                                  void *stream);
+
+/* Budget form of the same eviction (an extension: the paper's pool grows without eviction,
+ * Sec. 3.4): per sequence, hide the oldest rows of the head's pool until at most max_rows
+ * remain visible (a sequence holding fewer is left alone).  Called after each commit it keeps
+ * a sliding budget of the most recent max_rows rows.  Rows of the current tail window of a
+ * TAIL|PAST head stay visible even if max_rows is smaller. */
+segattn_status seg_kv_past_keep_recent(segattn_ctx *ctx, int32_t kv_head, int64_t max_rows,
+                                       void *stream);
 
 /* Host copies of the cache counters (any pointer may be NULL): past [B,Hkv] = visible pool
  * rows of PAST heads (closed segments only; 0 for other heads), tail [B] = rows in the

@@ -156,6 +156,22 @@ def attend(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
     return out, lse
 
 
+def attend_packed(q, k, v, cu_seqlens, **kw):
+    """A ragged batch packed without padding: q [total,Hq,D], k, v [total,Hkv,D]; sequence b is
+    rows cu_seqlens[b] .. cu_seqlens[b+1]-1 and is processed on its own (its segments start at
+    multiples of S counted from its first row; nothing crosses a sequence boundary -- the
+    sequences of a batch are independent samples in Eq. 12-13).  Returns O [total,Hq,D] and
+    LSE [Hq,total]; keyword arguments as for attend()."""
+    total, Hq, D = q.shape
+    out, lse = np.zeros((total, Hq, D)), np.zeros((Hq, total))
+    for b in range(len(cu_seqlens) - 1):
+        lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        if hi > lo:
+            o, l = attend(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], **kw)
+            out[lo:hi], lse[:, lo:hi] = o[0], l[0]
+    return out, lse
+
+
 def decode_attend(q, k_ctx, v_ctx, *, seg_len: int, tail_len: int, kv_policy: Sequence[int],
                   scale: Optional[float] = None, evicted: Optional[Sequence[int]] = None,
                   retrieved=None) -> Tuple[np.ndarray, np.ndarray]:

@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
             "segattn_reset": (ctypes.c_int, [vp, vp]),
             "seg_attn_fwd": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, vp, vp]),
             "seg_attn_fwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, i64, vp, vp, vp]),
+            "seg_attn_fwd_varlen": (ctypes.c_int, [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, vp]),
+            "segattn_layer_policy": (ctypes.c_int, [i32, ctypes.POINTER(i32), i32, i32, ctypes.POINTER(ctypes.c_uint8)]),
             "seg_rope_apply": (ctypes.c_int, [cfgp, vp, vp, i64, vp, vp]),
             "seg_attn_bwd_workspace_bytes": (sz, [cfgp, i64]),
             "seg_attn_bwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]),
@@ -63,6 +65,7 @@ def lib() -> ctypes.CDLL:
             "seg_kv_past_append": (ctypes.c_int, [vp, i32, vp, vp, i64, vp]),
             "seg_kv_past_select": (ctypes.c_int, [vp, vp, i32, vp]),
             "seg_kv_past_evict": (ctypes.c_int, [vp, i32, i64, vp]),
+            "seg_kv_past_keep_recent": (ctypes.c_int, [vp, i32, i64, vp]),
             "seg_kv_retrieve_workspace_bytes": (sz, [vp, ctypes.POINTER(segattn_retrieval)]),
             "seg_kv_retrieve": (ctypes.c_int, [vp, ctypes.POINTER(segattn_retrieval), vp, i32, i32, vp, vp, sz, vp]),
             "seg_kv_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]),
@@ -82,7 +85,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict",
+           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -147,6 +150,20 @@ def seg_attn_fwd_seq(cfg: segattn_config, q, k, v, n: int, out, lse, stream=None
                                   _ptr(stream)), "seg_attn_fwd_seq")
 
 
+def seg_attn_fwd_varlen(cfg: segattn_config, q, k, v, cu_seqlens, total: int, max_seqlen: int, out, lse,
+                        stream=None) -> None:
+    _check(lib().seg_attn_fwd_varlen(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), total,
+                                     max_seqlen, _ptr(out), _ptr(lse), _ptr(stream)), "seg_attn_fwd_varlen")
+
+
+def segattn_layer_policy(n_kv_heads: int, long_heads: Sequence[int], layer_in_l_long: bool):
+    lh = (ctypes.c_int32 * max(1, len(long_heads)))(*[int(h) for h in long_heads])
+    out = (ctypes.c_uint8 * n_kv_heads)()
+    _check(lib().segattn_layer_policy(n_kv_heads, lh, len(long_heads), int(bool(layer_in_l_long)), out),
+           "segattn_layer_policy")
+    return list(out)
+
+
 def seg_rope_apply(cfg: segattn_config, q, k, rows: int, pos0=None, stream=None) -> None:
     _check(lib().seg_rope_apply(ctypes.byref(cfg), _ptr(q), _ptr(k), rows, _ptr(pos0), _ptr(stream)), "seg_rope_apply")
 
@@ -191,6 +208,10 @@ def seg_kv_retrieve(ctx: int, r: segattn_retrieval, q_prev, m: int, R: int, idx_
 
 def seg_kv_past_evict(ctx: int, kv_head: int, n_oldest: int, stream=None) -> None:
     _check(lib().seg_kv_past_evict(ctx, kv_head, n_oldest, _ptr(stream)), "seg_kv_past_evict")
+
+
+def seg_kv_past_keep_recent(ctx: int, kv_head: int, max_rows: int, stream=None) -> None:
+    _check(lib().seg_kv_past_keep_recent(ctx, kv_head, max_rows, _ptr(stream)), "seg_kv_past_keep_recent")
 
 
 def seg_kv_lengths(ctx: int, batch: int, n_kv_heads: int):

@@ -205,6 +205,43 @@ segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const 
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
 }
 
+segattn_status seg_attn_fwd_varlen(const segattn_config *cfg, const void *q, const void *k, const void *v,
+                                   const int32_t *cu_seqlens, int64_t total, int64_t max_seqlen, void *out,
+                                   float *lse, void *stream) {
+  Problem p;
+  if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
+  if (!q || !k || !v || !out || !lse || !cu_seqlens) return SEGATTN_EINVAL;
+  if (max_seqlen < 1 || total < max_seqlen || total >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
+  PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.out = out;
+  a.lse = lse;
+  a.cache = nullptr;
+  a.cu_seqlens = cu_seqlens;
+  a.total_rows = total;
+  a.n_rows = (int)max_seqlen;
+  a.n_seg = (int)((max_seqlen + p.S - 1) / p.S);
+  const int rows = prefill_rows_per_workgroup(p);
+  const long long seg_rows = max_seqlen < p.S ? max_seqlen : p.S;
+  a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
+  return hip_status(launch_prefill(p, a, (hipStream_t)stream));
+}
+
+segattn_status segattn_layer_policy(int32_t n_kv_heads, const int32_t *long_heads, int32_t n_long,
+                                    int32_t layer_in_l_long, uint8_t *policy_out) {
+  if (n_kv_heads < 1 || n_kv_heads > kMaxKvHeads || n_long < 0 || (n_long > 0 && !long_heads) || !policy_out)
+    return SEGATTN_EINVAL;
+  for (int h = 0; h < n_kv_heads; ++h) policy_out[h] = SEGATTN_TAIL;
+  for (int i = 0; i < n_long; ++i) {
+    if (long_heads[i] < 0 || long_heads[i] >= n_kv_heads) return SEGATTN_EINVAL;
+    policy_out[long_heads[i]] = layer_in_l_long ? SEGATTN_PAST : SEGATTN_SEG;
+  }
+  return SEGATTN_OK;
+}
+
 segattn_status seg_rope_apply(const segattn_config *cfg, void *q, void *k, int64_t rows, const int64_t *pos0,
                               void *stream) {
   Problem p;
@@ -410,22 +447,36 @@ segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, con
   return hip_status(launch_retrieve(p, a, (hipStream_t)stream));
 }
 
-segattn_status seg_kv_past_evict(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest, void *stream) {
-  if (!ctx || n_oldest < 0 || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;
+// n_oldest >= 0 with keep < 0: hide that many more rows; keep >= 0: hide what exceeds `keep`
+// visible rows.  The host mirror follows the device counters.
+static segattn_status evict_rows(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest, int64_t keep, void *stream) {
+  if (!ctx || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;
   const Problem &p = ctx->p;
   if (!(p.policy[kv_head] & SEGATTN_PAST)) return SEGATTN_EINVAL;
   if (!ctx->ready) return SEGATTN_ESTATE;
-  if (launch_cache_evict(p, ctx->cache, ctx->g, kv_head, n_oldest, (hipStream_t)stream) != hipSuccess)
+  if (launch_cache_evict(p, ctx->cache, ctx->g, kv_head, n_oldest, keep, (hipStream_t)stream) != hipSuccess)
     return SEGATTN_EHIP;
   for (int b = 0; b < p.B; ++b) {
     const size_t i = (size_t)b * p.Hkv + kv_head;
     long long limit = ctx->pool[i];
+    long long n = n_oldest;
+    if (keep >= 0) n = limit - ctx->lo[i] > keep ? limit - ctx->lo[i] - keep : 0;
     if (p.policy[kv_head] & SEGATTN_TAIL) limit -= ctx->tail[b];
-    long long lo_new = ctx->lo[i] + n_oldest < limit ? ctx->lo[i] + n_oldest : limit;
+    long long lo_new = ctx->lo[i] + n < limit ? ctx->lo[i] + n : limit;
     if (lo_new < ctx->lo[i]) lo_new = ctx->lo[i];
     ctx->lo[i] = lo_new;
   }
   return SEGATTN_OK;
+}
+
+segattn_status seg_kv_past_evict(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest, void *stream) {
+  if (n_oldest < 0) return SEGATTN_EINVAL;
+  return evict_rows(ctx, kv_head, n_oldest, -1, stream);
+}
+
+segattn_status seg_kv_past_keep_recent(segattn_ctx *ctx, int32_t kv_head, int64_t max_rows, void *stream) {
+  if (max_rows < 0) return SEGATTN_EINVAL;
+  return evict_rows(ctx, kv_head, 0, max_rows, stream);
 }
 
 segattn_status seg_kv_lengths(const segattn_ctx *ctx, int64_t *past, int32_t *tail, int32_t *seg_fill) {

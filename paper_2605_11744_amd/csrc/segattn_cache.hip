@@ -178,13 +178,15 @@ __global__ void cache_pool_add_kernel(const Problem p, unsigned char *cache, con
 
 // Hide the n oldest pool rows of one PAST head; rows of the current tail window stay visible
 // when the head also has the TAIL bit.
+// keep < 0: hide n more rows; keep >= 0: hide as many as leave at most `keep` rows visible.
 __global__ void cache_evict_kernel(const Problem p, unsigned char *cache, const CacheGeom g, const int h,
-                                   const long long n) {
+                                   long long n, const long long keep) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= p.B) return;
   int *meta = meta_of(cache, g, p, b, h);
   const long long lo = meta[META_LO];
   long long limit = meta[META_POOL];
+  if (keep >= 0) n = limit - lo > keep ? limit - lo - keep : 0;
   if (p.policy[h] & SEGATTN_TAIL) limit -= meta[META_TAIL];
   long long lo_new = lo + n < limit ? lo + n : limit;
   if (lo_new < lo) lo_new = lo;
@@ -286,9 +288,9 @@ hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_
 }
 
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
-                              long long n_oldest, hipStream_t st) {
+                              long long n_oldest, long long keep, hipStream_t st) {
   hipLaunchKernelGGL(cache_evict_kernel, dim3((p.B + 63) / 64), dim3(64), 0, st, p, cache, g, kv_head,
-                     n_oldest);
+                     n_oldest, keep);
   return hipGetLastError();
 }
 

@@ -54,7 +54,9 @@ struct PrefillArgs {
   float *lse;
   unsigned char *cache;  // arena base or nullptr
   CacheGeom geom;
-  int n_rows;            // N (SEQ) or m (CTX)
+  int n_rows;            // N (SEQ; the longest sequence of a packed batch) or m (CTX)
+  const int *cu_seqlens; // SEQ mode, packed ragged batch: device [B+1] row offsets, else nullptr
+  long long total_rows;  // rows of the packed batch (lse is [Hq, total_rows] then)
   int n_seg;             // segments covered by the launch (1 in CTX mode)
   int q_blocks_per_seg;  // ceil(min(S, n_rows) / rows per workgroup)
 };
@@ -179,7 +181,7 @@ hipError_t launch_cache_close(const Problem &p, unsigned char *cache, const Cach
 hipError_t launch_cache_decode_append(const Problem &p, const CopyArgs &a, hipStream_t st);
 hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStream_t st);
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
-                              long long n_oldest, hipStream_t st);
+                              long long n_oldest, long long keep, hipStream_t st);
 hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st);
 hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t st);
 hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st);

@@ -26,8 +26,13 @@
 // of 5 step slots, three steps ahead of their use; the 16-byte chunks of a row are XOR-
 // swizzled by the loading lanes so that both the row-wise K reads and the transposing V reads
 // are free of bank conflicts.  Steps that need an element mask (the diagonal of the query's
-// own segment, the ragged end of a span) take a plain unpipelined path; steps wholly outside
-// a wave's visible range are skipped.
+// own segment, the ragged end of a span, a step past the wave's last query that other waves of
+// the workgroup still need) run the same pipelined step with the mask applied to S^T first, and
+// the loader keeps a constant number of loads in flight to the very end (it fetches the last
+// step again once it runs out), so one kind of step with one fixed wait covers the whole key
+// range.  Paths outside that step matter more than their share of the arithmetic suggests: a
+// register spilled there is reloaded through the same counter the K/V prefetch uses, and
+// waiting for it drains the prefetch queue.
 #include <type_traits>
 
 #include "segattn_work.h"
@@ -47,10 +52,12 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 #define GLB_AS __attribute__((address_space(1)))
 
 constexpr int kStepKeys = 32;
-constexpr int kSlots = 5;                 // LDS ring: steps j-1 .. j+kSlots-2 are resident or in flight
+#ifndef SEGATTN_PREFILL_SLOTS
+#define SEGATTN_PREFILL_SLOTS 5
+#endif
+constexpr int kSlots = SEGATTN_PREFILL_SLOTS;                 // LDS ring: steps j-1 .. j+kSlots-2 are resident or in flight
 constexpr int kAhead = kSlots - 4;        // whole steps of loads that may still be in flight at a sync
 constexpr float kLazyLimit = 256.f;  // a lane's 16-weight row sum above this triggers a rescale
-constexpr float kLazyLog2 = 8.f;     // masked steps: rescale when the maximum exceeds the reference by 2^8
 
 template <int D>
 struct StepGeom {
@@ -72,6 +79,14 @@ __device__ inline float half_max(float x) {  // max over lanes l and l^32
   const int xi = __float_as_int(x);
   const auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
   return fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
+}
+__device__ inline int uniform_i32(int x) { return __builtin_amdgcn_readfirstlane(x); }
+template <typename T>
+__device__ inline T *uniform_ptr(T *ptr) {
+  const unsigned long long u = (unsigned long long)ptr;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
+  return (T *)(((unsigned long long)hi << 32) | lo);
 }
 __device__ inline float half_sum(float x) {
   const int xi = __float_as_int(x);
@@ -98,8 +113,20 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   static_assert(LPW >= 1, "too many waves for this tile");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-  const WorkItem w = resolve(p, a, blockIdx.x, BQ, HS);
+  WorkItem w = resolve(p, a, blockIdx.x, BQ, HS);
   if (!w.valid) return;
+  // Everything in the work item is the same for the whole workgroup; some of it comes from memory
+  // (sequence offsets, cache counters) through vector loads.  Pin it to scalar registers so that
+  // the loader's pointers and every loop bound derived from it stay out of the vector file.
+  w.n0 = uniform_i32(w.n0);
+  w.n1 = uniform_i32(w.n1);
+  w.t0 = uniform_i32(w.t0);
+  w.stride0 = uniform_i32((int)w.stride0);
+  w.stride1 = uniform_i32((int)w.stride1);
+  w.k0 = uniform_ptr(w.k0);
+  w.v0 = uniform_ptr(w.v0);
+  w.k1 = uniform_ptr(w.k1);
+  w.v1 = uniform_ptr(w.v1);
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -109,7 +136,6 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   const int tw0 = w.t0 + (wave / HS) * RW;  // first query row of this wave
   const int last_row = w.n1 - 1;
   const float c = p.scale_log2e;
-  const float tau = kLazyLog2 / c;
 
   // ---- step schedule (workgroup) and this wave's share of it
   const int n1_needed = (w.t0 + BQ < w.n1) ? (w.t0 + BQ) : w.n1;
@@ -123,38 +149,39 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     const int full1 = (tw0 + 1) / kStepKeys;  // span-1 steps whose keys all precede every query
     f = nst0 + (full1 < nst1 ? full1 : nst1);
   }
-  int j_active_end;  // steps at or beyond this one start after the wave's last query
-  {
-    const int last_q = tw0 + RW - 1;
-    const int s1 = last_q / kStepKeys + 1;
-    j_active_end = nst0 + (s1 < nst1 ? s1 : nst1);
-  }
 
   // ---- HBM -> LDS.  Load i of a wave covers LDS bytes [(wave*LPW+i)*1024, +1024) of a tensor:
   //      row r = (wave*LPW+i)*rowsPerInstr + lane/chunks, chunk slot lane%chunks, which receives
   //      global chunk (slot ^ swizzle(r)).  For a full step the lane's byte offset from the
   //      step's first row is a per-span constant (off_k / off_v).
-  int ld_row[LPW];
-  unsigned ld_ck[LPW], ld_cv[LPW];  // byte offset of the global chunk inside its row (K / V swizzle)
-#pragma unroll
-  for (int i = 0; i < LPW; ++i) {
-    const int r = (wave * LPW + i) * G::kRowsPerInstr + lane / G::kChunks;
-    const int slot_chunk = lane % G::kChunks;
-    ld_row[i] = r;
-    ld_ck[i] = (unsigned)((slot_chunk ^ G::swz_k(r)) * 16);
-    ld_cv[i] = (unsigned)((slot_chunk ^ G::swz_v(r)) * 16);
-  }
   unsigned off_k[LPW], off_v[LPW];
   LDS_AS unsigned char *const lds = (LDS_AS unsigned char *)smem;
   constexpr int kRing = kSlots * G::kSlotBytes;
-  auto next_slot = [](int off) { return off + G::kSlotBytes == kRing ? 0 : off + G::kSlotBytes; };
+  auto next_slot = [](int off) __attribute__((always_inline)) { return off + G::kSlotBytes == kRing ? 0 : off + G::kSlotBytes; };
 
-  // loader state: the next step to fetch, where its rows start, how many rows its span has left
+  // loader state: the step the next loads fetch, where its rows start, how many rows its span
+  // has left.  The loader never stops: once the last step has been fetched it keeps fetching
+  // that step again (into slots nobody reads any more), so the number of loads in flight at a
+  // sync is the same constant at every step and the waits need no case analysis.
   int ld_js = 0, ld_span = -1, ld_left = 0, ld_slot = 0;
-  int ld_full_end = 0;  // first step of the current span (or n) that is not a plain full step
+  int ld_full_end = 0;  // first step at or after ld_js that is not a plain full step of the loader's span
   const unsigned char *ld_kp = nullptr, *ld_vp = nullptr;
   unsigned ld_stride = 0;
-  auto enter_span = [&](int s1) {
+  // Lane offsets of the step's loads (recomputed from the lane index where needed rather than
+  // kept in registers through the loop); rows past a ragged end are clamped.
+  auto set_offsets = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+      const int row = (wave * LPW + i) * G::kRowsPerInstr + lane / G::kChunks;
+      const int slot_chunk = lane % G::kChunks;
+      const int r = (ld_left >= kStepKeys || row < ld_left) ? row : ld_left - 1;
+      off_k[i] = (unsigned)r * ld_stride + (unsigned)((slot_chunk ^ G::swz_k(row)) * 16);
+      off_v[i] = (unsigned)r * ld_stride + (unsigned)((slot_chunk ^ G::swz_v(row)) * 16);
+    }
+  };
+  // (No lambda below is reached through two different closures: merged call sites would turn
+  // the captured state into memory accessed through a pointer chosen at run time.)
+  auto span_scalars = [&](int s1) __attribute__((always_inline)) {
     ld_span = s1;
     ld_kp = (const unsigned char *)(s1 ? w.k1 : w.k0);
     ld_vp = (const unsigned char *)(s1 ? w.v1 : w.v0);
@@ -162,44 +189,10 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     ld_stride = (unsigned)((s1 ? w.stride1 : w.stride0) * 2);
     ld_full_end = (s1 ? nst0 : 0) + ld_left / kStepKeys;
     if (ld_full_end > n) ld_full_end = n;
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-      off_k[i] = (unsigned)ld_row[i] * ld_stride + ld_ck[i];
-      off_v[i] = (unsigned)ld_row[i] * ld_stride + ld_cv[i];
-    }
   };
-  enter_span(nst0 > 0 ? 0 : 1);
-  auto issue = [&]() {  // enqueue the loads of step ld_js (< n) into its ring slot, then advance
-    LDS_AS unsigned char *dst = lds + ld_slot + wave * (LPW * 1024);
-    if (ld_left >= kStepKeys) {
-#pragma unroll
-      for (int i = 0; i < LPW; ++i) {
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_kp + off_k[i]), (LDS_AS void *)(dst + i * 1024), 16, 0,
-                                         0);
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + off_v[i]),
-                                         (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
-      }
-    } else {  // ragged end of the span: rows past it are clamped (and masked by the consumer)
-#pragma unroll
-      for (int i = 0; i < LPW; ++i) {
-        const int r = ld_row[i] < ld_left ? ld_row[i] : ld_left - 1;
-        const unsigned ro = (unsigned)r * ld_stride;
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_kp + (ro + ld_ck[i])), (LDS_AS void *)(dst + i * 1024),
-                                         16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + (ro + ld_cv[i])),
-                                         (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
-      }
-    }
-    ld_js += 1;
-    ld_slot = next_slot(ld_slot);
-    ld_kp += (size_t)kStepKeys * ld_stride;
-    ld_vp += (size_t)kStepKeys * ld_stride;
-    ld_left -= kStepKeys;
-    if (ld_span == 0 && ld_js == nst0) enter_span(1);
-  };
-  // Branch-free variant for the hot loop: a full step of the current span, no span switch after it
-  // (the caller guarantees ld_js + 1 < ld_full_end).
-  auto issue_hot = [&]() {
+  span_scalars(nst0 > 0 ? 0 : 1);
+  set_offsets();
+  auto issue_loads = [&]() __attribute__((always_inline)) {  // enqueue the loads of the loader's step into the next ring slot
     LDS_AS unsigned char *dst = lds + ld_slot + wave * (LPW * 1024);
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
@@ -207,36 +200,52 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + off_v[i]),
                                        (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
     }
-    ld_js += 1;
     ld_slot = next_slot(ld_slot);
+  };
+  // Branch-free advance for the hot loop: the caller guarantees that the next step is a plain
+  // full step of the same span (ld_js + 1 < ld_full_end).
+  auto loader_advance_plain = [&]() __attribute__((always_inline)) {
+    ld_js += 1;
     ld_kp += (size_t)kStepKeys * ld_stride;
     ld_vp += (size_t)kStepKeys * ld_stride;
     ld_left -= kStepKeys;
   };
-  // s_waitcnt vmcnt(k * loads per step): at most k whole steps of this wave's loads stay in flight
-  auto wait_in_flight = [&](int k) {
-    constexpr int L = 2 * LPW;
-    static_assert(kAhead >= 1 && kAhead <= 6 && 6 * L < 64, "vmcnt is a 6-bit counter");
-#define SEGATTN_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
-    if (k <= 0) SEGATTN_VMCNT(0);
-    else if (k == 1) SEGATTN_VMCNT(1 * L);
-    else if (k == 2) SEGATTN_VMCNT(2 * L);
-    else if (k == 3) SEGATTN_VMCNT(3 * L);
-    else if (k == 4) SEGATTN_VMCNT(4 * L);
-    else if (k == 5) SEGATTN_VMCNT(5 * L);
-    else SEGATTN_VMCNT(6 * L);
+  auto loader_advance = [&]() __attribute__((always_inline)) {  // move on to the next step, if there is one (uniform branches)
+    ld_js += 1;
+    if (ld_js < n) {
+      const bool to_span1 = ld_span == 0 && ld_js == nst0;
+      if (to_span1) {
+        ld_span = 1;
+        ld_kp = (const unsigned char *)w.k1;
+        ld_vp = (const unsigned char *)w.v1;
+        ld_left = w.n1;
+        ld_stride = (unsigned)(w.stride1 * 2);
+        ld_full_end = nst0 + ld_left / kStepKeys;
+        if (ld_full_end > n) ld_full_end = n;
+      } else {
+        ld_kp += (size_t)kStepKeys * ld_stride;
+        ld_vp += (size_t)kStepKeys * ld_stride;
+        ld_left -= kStepKeys;
+      }
+      if (to_span1 || ld_left < kStepKeys) set_offsets();
+    }
   };
+  // s_waitcnt vmcnt: at most kAhead whole steps of this wave's loads stay in flight
+  static_assert(kAhead >= 1 && kAhead * 2 * LPW < 64, "vmcnt is a 6-bit counter");
+#define SEGATTN_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
   // Executed once per step j by every wave (in the prologue for j = 0, in the middle of step j
   // otherwise): the loads of steps <= j+2 have landed for every wave and every wave is done
-  // reading the slot of step j-1, which now receives the loads of step j+4.
-  auto sync_step = [&](int j) {
-    const int in_flight = ld_js - 1 - (j + 2);  // whole steps that may stay outstanding
-    wait_in_flight(in_flight);
+  // reading the slot of step j-1, which now receives the loads of step j+kSlots-1.
+  auto sync_step = [&]() __attribute__((always_inline)) {
+    SEGATTN_VMCNT(kAhead * 2 * LPW);
     __builtin_amdgcn_s_barrier();
-    if (ld_js < n) issue();
+    issue_loads();
   };
 
-  for (int i = 0; i < kSlots - 1 && i < n; ++i) issue();
+  for (int i = 0; i < kSlots - 1; ++i) {
+    issue_loads();
+    loader_advance();
+  }
 
   // ---- Q^T operands: Qr[qb][kc] = Q[row(qb, col)][16 kc + 8 hi .. +7]
   bf16x8 Qr[QB][NC];
@@ -285,7 +294,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // ---- operand fetch from LDS.  Inline asm: the order and the waits are ours (the compiler
   //      would make a transposing read wait for every outstanding global->LDS load).
   // K operand of k-chunk kc for the step in the slot at byte offset `so`
-  auto k_load = [&](int so, i32x4(&Kr)[NC]) {
+  auto k_load = [&](int so, i32x4(&Kr)[NC]) __attribute__((always_inline)) {
     unsigned ka[NKA];
 #pragma unroll
     for (int i = 0; i < NKA; ++i) ka[i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + so);
@@ -293,7 +302,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     for (int kc = 0; kc < NC; ++kc)
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
   };
-  auto k_wait = [&](i32x4(&Kr)[NC]) {
+  auto k_wait = [&](i32x4(&Kr)[NC]) __attribute__((always_inline)) {
     if constexpr (NC == 8) {
       asm volatile("s_waitcnt lgkmcnt(0)"
                    : "+v"(Kr[0]), "+v"(Kr[1]), "+v"(Kr[2]), "+v"(Kr[3]), "+v"(Kr[4]), "+v"(Kr[5]), "+v"(Kr[6]),
@@ -305,7 +314,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // V^T operand: k-slot e of half-wave hi in chunk h2 is key 16 h2 + 8 (e/4) + 4 hi + e%4 (the
   // accumulator layout of S^T), so V^T is fetched for exactly those keys: two transposing reads
   // of 4 keys each per (h2, 32-row block nb).
-  auto v_load = [&](int so, s16x4(&Vr)[2][NB][2]) {
+  auto v_load = [&](int so, s16x4(&Vr)[2][NB][2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const unsigned va = (unsigned)(size_t)lds + (unsigned)(voff[nb] + so);
@@ -318,7 +327,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       }
     }
   };
-  auto v_wait = [&](s16x4(&Vr)[2][NB][2]) {
+  auto v_wait = [&](s16x4(&Vr)[2][NB][2]) __attribute__((always_inline)) {
     if constexpr (NB == 4) {
       asm volatile("s_waitcnt lgkmcnt(0)"
                    : "+v"(Vr[0][0][0]), "+v"(Vr[0][0][1]), "+v"(Vr[0][1][0]), "+v"(Vr[0][1][1]), "+v"(Vr[0][2][0]),
@@ -332,7 +341,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     }
   };
   // ---- matrix products
-  auto s_mma = [&](const i32x4(&Kr)[NC], f32x16(&S)[QB]) {
+  auto s_mma = [&](const i32x4(&Kr)[NC], f32x16(&S)[QB]) __attribute__((always_inline)) {
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kc = 0; kc < NC; ++kc)
@@ -342,24 +351,24 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
                                                         kc == 0 ? zero : S[qb], 0, 0, 0);
   };
   // One PV product O^T[qb][nb] += V^T(h2, nb) . P^T[qb][h2]
-  auto pv_one = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2, int nb, int qb) {
+  auto pv_one = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2, int nb, int qb) __attribute__((always_inline)) {
     const bf16x8 va =
         __builtin_bit_cast(bf16x8, __builtin_shufflevector(Vr[h2][nb][0], Vr[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7));
     O[qb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, P[qb][h2], O[qb][nb], 0, 0, 0);
   };
-  auto pv_mma = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2) {
+  auto pv_mma = [&](const s16x4(&Vr)[2][NB][2], const bf16x8(&P)[QB][2], int h2) __attribute__((always_inline)) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) pv_one(Vr, P, h2, nb, qb);
   };
-  auto compute_s = [&](int so, f32x16(&S)[QB]) {  // unpipelined S^T of the step in slot `so`
+  auto compute_s = [&](int so, f32x16(&S)[QB]) __attribute__((always_inline)) {  // unpipelined S^T of the step in slot `so`
     i32x4 Kr[NC];
     k_load(so, Kr);
     k_wait(Kr);
     s_mma(Kr, S);
   };
-  auto pv = [&](int so, const bf16x8(&P)[QB][2]) {  // unpipelined O^T += V^T P^T
+  auto pv = [&](int so, const bf16x8(&P)[QB][2]) __attribute__((always_inline)) {  // unpipelined O^T += V^T P^T
     s16x4 Vr[2][NB][2];
     v_load(so, Vr);
     v_wait(Vr);
@@ -367,14 +376,14 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     pv_mma(Vr, P, 1);
   };
   // S^T accumulators (produced in vector registers: VGPR-form products) as plain floats
-  auto s_fetch = [&](const f32x16(&S)[QB], float(&Sv)[QB][16]) {
+  auto s_fetch = [&](const f32x16(&S)[QB], float(&Sv)[QB][16]) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) Sv[qb][r] = S[qb][r];
   };
   // P = exp2(S c - m_ref c) as bf16 and its row sums (of the rounded values)
-  auto softmax = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB]) {
+  auto softmax = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB]) __attribute__((always_inline)) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -396,13 +405,13 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       psum[qb] = ps;
     }
   };
-  auto row_max = [&](const float(&S)[QB][16], int qb) {
+  auto row_max = [&](const float(&S)[QB][16], int qb) __attribute__((always_inline)) {
     float mx = fmaxf(S[qb][0], S[qb][1]);
 #pragma unroll
     for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, S[qb][r]), S[qb][r + 1]);
     return half_max(mx);
   };
-  auto rescale = [&](int qb, float alpha) {  // rare: O^T and l of query block qb times alpha
+  auto rescale = [&](int qb, float alpha) __attribute__((always_inline)) {  // rare: O^T and l of query block qb times alpha
     l_run[qb] *= alpha;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -414,7 +423,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // by more than 2^8/... ; then the reference is raised to the step's true maximum, the
   // accumulators are rescaled and this P is formed again.  exp2 can therefore not overflow
   // into the accumulators, and the common path pays two compares.
-  auto settle = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB]) {
+  auto settle = [&](const float(&S)[QB][16], bf16x8(&P)[QB][2], float(&psum)[QB]) __attribute__((always_inline)) {
     bool any = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) any |= !(psum[qb] <= kLazyLimit);
@@ -440,35 +449,35 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
 
   // ring offsets of steps j-1, j, j+1, j+2
   int so_m1 = 0, so_0 = 0, so_p1 = G::kSlotBytes, so_p2 = 2 * G::kSlotBytes;
-  auto advance = [&]() {
+  auto advance = [&]() __attribute__((always_inline)) {
     so_m1 = so_0;
     so_0 = so_p1;
     so_p1 = so_p2;
     so_p2 = next_slot(so_p2);
   };
 
-  // One pipelined step j >= 1.  On entry Kr holds the K operands of step j+1 (if do_s), Sc is
-  // S^T of step j and Pp is P of step j-1.  The step forms S^T(j+1) -> Sn, adds PV of step j-1,
-  // turns Sc into Pc, runs the step's sync in the middle and, if fetch_k, leaves the K operands
-  // of step j+2 in Kr.  Generic version (any sync branch); the hot loop uses hot_step.
-  auto fast_step = [&](int j, auto do_s, auto fetch_k, i32x4(&Kr)[NC], const float(&Sc)[QB][16],
-                       float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) {
-    float psum[QB];
-    s16x4 Vr[2][NB][2];
-    f32x16 Sacc[QB];
-    v_load(so_m1, Vr);
-    if constexpr (decltype(do_s)::value) s_mma(Kr, Sacc);
-    v_wait(Vr);
-    pv_mma(Vr, Pp, 0);
-    sync_step(j);
-    if constexpr (decltype(fetch_k)::value) k_load(so_p2, Kr);
-    pv_mma(Vr, Pp, 1);
-    softmax(Sc, Pc, psum);
-    if constexpr (decltype(do_s)::value) s_fetch(Sacc, Sn);
-    if constexpr (decltype(fetch_k)::value) k_wait(Kr);
-    settle(Sc, Pc, psum);
+  // Element mask of step j: the lane's query (row tw0 + 32 qb + col of the segment) sees the keys
+  // of a span-1 step up to its own row and the keys of a span-0 step up to the span's end.
+  auto mask_step = [&](float(&S)[QB][16], int j) __attribute__((always_inline)) {
+    const bool s1 = j >= nst0;
+    const int j0 = (s1 ? j - nst0 : j) * kStepKeys;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      int t = tw0 + 32 * qb + col;
+      t = t < last_row ? t : last_row;
+      const int lim = (s1 ? t + 1 : w.n0) - j0 - 4 * hi;  // first invisible key, relative to the lane's keys
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (8 * (r >> 2) + (r & 3) >= lim) S[qb][r] = -INFINITY;
+    }
   };
-  // The same step for the hot loop, laid out by hand as 2*NC + 4*NB slots of one matrix product
+  // One pipelined step j >= 1.  On entry Kr holds the K operands of step j+1, Sc is S^T of step
+  // j and Pp is P of step j-1.  The step forms S^T(j+1) -> Sn, adds PV of step j-1, turns Sc
+  // into Pc, runs the step's sync in the middle and leaves the K operands of step j+2 in Kr.
+  // Beyond the last step the operands are those of a step fetched again: finite and unused.
+  // MASKED: keys of step j with in-span index >= the lane's limit are invisible (the diagonal
+  // of the query's own segment, the ragged end of a span, steps past the wave's last query).
+  // Laid out by hand as 2*NC + 4*NB slots of one matrix product
   // each; whatever else the step has to do is spread over the slots so that it issues in the
   // shadow of the products (about six vector instructions fit under a 32x32x16 MFMA).  The
   // sync is branch-free: exactly one step of loads stays in flight and the loads issued are a
@@ -478,8 +487,9 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   //   (sync, then the K reads of step j+2, two per slot)
   //   slots .. end            PV(j-1), last 16 keys
   //   odd slots               convert pair i to bf16 and add it to the row sum
-  auto hot_step = [&](i32x4(&Kr)[NC], const float(&Sc)[QB][16], float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2],
-                      bf16x8(&Pc)[QB][2]) {
+  auto hot_step = [&](auto masked, auto plain, int j, i32x4(&Kr)[NC], float(&Sc)[QB][16], float(&Sn)[QB][16],
+                      const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) __attribute__((always_inline)) {
+    if constexpr (decltype(masked)::value) mask_step(Sc, j);
     constexpr int NS = QB * NC, NP = QB * NB;  // slots of the S^T product / of half a PV product
     constexpr int NSLOT = NS + 2 * NP;
     constexpr int NE = 16 * QB;                // softmax elements per lane and step
@@ -499,7 +509,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     for (int i = 0; i < NKA; ++i) ka[i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + so_p2);
     // vector-ALU work of one slot: exp2 of EPS elements, and half of the conversion / row-sum
     // work of an earlier pair, so that every slot carries the same four issue slots
-    auto valu_chunk = [&](int slot) {
+    auto valu_chunk = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
       for (int u = 0; u < EPS; ++u) {
         const int e = EPS * slot + u, qb = e / 16, r = e % 16;
@@ -552,9 +562,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       // ---- after the S^T slots: V^T has arrived; sync; then the K reads of step j+2, one per slot
       if (slot == NS - 1) {
         v_wait(Vr);
-        SEGATTN_VMCNT(kAhead * 2 * LPW);
-        __builtin_amdgcn_s_barrier();
-        issue_hot();
+        sync_step();
       }
       if (slot >= NS && slot < NS + NC) {
         const int kc = slot - NS;
@@ -580,143 +588,71 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     s_fetch(Sacc, Sn);
     k_wait(Kr);
     settle(Sc, Pc, psum);
+    if constexpr (decltype(plain)::value) loader_advance_plain();
+    else loader_advance();
   };
-  // An unpipelined step (slot so, span-local first key j0) with element masks: keys with
-  // in-span index >= lim[qb] are invisible.
-  auto slow_step = [&](int so, bool s1, int j0) {
-    f32x16 Sacc[QB];
-    float S[QB][16];
-    bf16x8 P[QB][2];
-    float psum[QB];
-    compute_s(so, Sacc);
-    s_fetch(Sacc, S);
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      int t = tw0 + 32 * qb + col;
-      t = t < last_row ? t : last_row;
-      const int lim = s1 ? t + 1 : w.n0;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = j0 + 8 * (r >> 2) + 4 * hi + (r & 3);
-        if (key >= lim) S[qb][r] = -INFINITY;
-      }
-      float mx = S[qb][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[qb][r]);
-      mx = half_max(mx);
-      const bool need = mx > m_ref[qb] + tau;  // true on the very first step (m_ref = -inf, mx finite)
-      if (__builtin_amdgcn_ballot_w64(need) != 0) {
-        const float m_new = need ? mx : m_ref[qb];
-        const float alpha = need ? __builtin_amdgcn_exp2f((m_ref[qb] - m_new) * c) : 1.f;
-        m_ref[qb] = m_new;
-        mc_ref[qb] = m_new * c;
-        rescale(qb, alpha);
-      }
-    }
-    softmax(S, P, psum);
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_run[qb] += psum[qb];
-    pv(so, P);
-  };
-
   // =========================== main sequence ===========================
-  sync_step(0);
-  // (all defined from the start: on some paths through the step schedule one of each pair is
-  // never written, and a value that is undefined on one path may not be merged with one that is)
+  sync_step();
+  loader_advance();
   float Sa[QB][16] = {}, Sb[QB][16] = {};
   bf16x8 Pa[QB][2] = {}, Pb[QB][2] = {};
   i32x4 Kr[NC] = {};
-  int j = 0;
-  bool pend_in_a = false;
-  if (f > 0) {
-    {  // step 0 without overlap: exact maximum as the first reference
-      float psum[QB];
-      f32x16 Sacc[QB];
-      compute_s(so_0, Sacc);
-      s_fetch(Sacc, Sa);
+  {  // step 0 without overlap: exact maximum as the first reference (every query sees key 0 of
+     // its first step)
+    float psum[QB];
+    f32x16 Sacc[QB];
+    compute_s(so_0, Sacc);
+    s_fetch(Sacc, Sa);
+    if (f == 0) mask_step(Sa, 0);
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float mx = Sa[qb][0];
+    for (int qb = 0; qb < QB; ++qb) {
+      float mx = Sa[qb][0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, Sa[qb][r]);
-        m_ref[qb] = half_max(mx);
-        mc_ref[qb] = m_ref[qb] * c;
-      }
-      softmax(Sa, Pb, psum);
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) l_run[qb] = psum[qb];
-      if (f > 1) {
-        compute_s(so_p1, Sacc);
-        s_fetch(Sacc, Sa);
-      }
-      if (f > 2) {  // K operands of step 2 for the product formed in step 1
-        k_load(so_p2, Kr);
-        k_wait(Kr);
-      }
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, Sa[qb][r]);
+      m_ref[qb] = half_max(mx);
+      mc_ref[qb] = m_ref[qb] * c;
     }
-    j = 1;
-    advance();
-    constexpr std::true_type yes{};
-    constexpr std::false_type no{};
-    for (;;) {
-      // hot pairs: the next two loads are plain full steps of the current span
-      // Nothing the compiler tracks may be pending on entry (a spill reload in the generic path
-      // would otherwise put a full vmcnt wait, which also drains our prefetch, into the loop).
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      while (j + 3 < f && ld_js + 2 < ld_full_end) {
-        hot_step(Kr, Sa, Sb, Pb, Pa);
-        advance();
-        hot_step(Kr, Sb, Sa, Pa, Pb);
-        advance();
-        j += 2;
-      }
-      if (!(j + 3 < f)) break;
-      // steps j and j+1 both form the next S^T and fetch the K operands after it
-      fast_step(j, yes, yes, Kr, Sa, Sb, Pb, Pa);
+    softmax(Sa, Pb, psum);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] = psum[qb];
+    compute_s(so_p1, Sacc);
+    s_fetch(Sacc, Sa);
+    k_load(so_p2, Kr);  // K operands of step 2 for the product formed in step 1
+    k_wait(Kr);
+  }
+  int j = 1;
+  advance();
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  // here and at the top of every iteration below: Sa = S^T(j), Pb = P(j-1), Kr = K operands of j+1
+  while (j < n) {
+    // pairs of steps that need no mask while the loader stays inside plain full steps of its span
+    while (j + 1 < f && ld_js + 2 < ld_full_end) {
+      hot_step(no, yes, j, Kr, Sa, Sb, Pb, Pa);
       advance();
-      fast_step(j + 1, yes, yes, Kr, Sb, Sa, Pa, Pb);
+      hot_step(no, yes, j + 1, Kr, Sb, Sa, Pa, Pb);
       advance();
       j += 2;
     }
-    const int rest = f - j;  // 0..3 pipelined steps left; Kr holds K(j+1) if rest >= 2
-    if (rest == 3) {
-      fast_step(j, yes, yes, Kr, Sa, Sb, Pb, Pa);
-      advance();
-      fast_step(j + 1, yes, no, Kr, Sb, Sa, Pa, Pb);
-      advance();
-      fast_step(j + 2, no, no, Kr, Sa, Sb, Pb, Pa);
-      advance();
-    } else if (rest == 2) {
-      fast_step(j, yes, no, Kr, Sa, Sb, Pb, Pa);
-      advance();
-      fast_step(j + 1, no, no, Kr, Sb, Sa, Pa, Pb);
-      advance();
-    } else if (rest == 1) {
-      fast_step(j, no, no, Kr, Sa, Sb, Pb, Pa);
-      advance();
-    }
-    pend_in_a = rest == 3 || rest == 1;  // an odd number of steps since the hot loop: the last P is in Pa
-    if (rest > 0) j += rest;
-  }
-  // here j == f, so_0 is the slot of step j and, if f > 0, P(f-1) waits in Pb (or Pa)
-  bool pending = f > 0;
-  for (; j < n; ++j) {
-    if (pending) {
-      if (pend_in_a) pv(so_m1, Pa);
-      else pv(so_m1, Pb);
-      pending = false;
-    }
-    if (j < j_active_end) {
-      const bool s1 = j >= nst0;
-      slow_step(so_0, s1, (s1 ? j - nst0 : j) * kStepKeys);
-    }
-    if (j > 0) sync_step(j);
+    if (j >= n) break;
+    // any other step (the loader is at a span switch, a ragged step or its last step, or the
+    // step needs a mask): the masked step with the loader's general advance; a mask that hides
+    // nothing is harmless.  Its results move back into (Sa, Pb) so that the roles stay fixed
+    // (choosing between the two register sets at run time would put them in memory).
+    hot_step(yes, no, j, Kr, Sa, Sb, Pb, Pa);
     advance();
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Sa[qb][r] = Sb[qb][r];
+      Pb[qb][0] = Pa[qb][0];
+      Pb[qb][1] = Pa[qb][1];
+    }
+    ++j;
   }
-  if (pending) {
-    if (pend_in_a) pv(so_m1, Pa);
-    else pv(so_m1, Pb);
-  }
+  // so_m1 is the slot of step n-1, whose P waits in Pb
+  pv(so_m1, Pb);
+  SEGATTN_VMCNT(0);  // the loader's surplus loads have landed: the ring may be reused
 
   // ---- epilogue: normalise, write LSE, and write O through LDS so that every store
   // instruction covers whole 16-byte pieces of contiguous output rows.  A lane holds four
@@ -775,9 +711,12 @@ static int heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2
 // D = 128: 32 query rows per wave, eight waves (two per SIMD) that share the K/V tiles.
 // D = 64: 64 query rows per wave, four waves (the tiles are too small to split their loads
 // over eight).
+#ifndef SEGATTN_PREFILL_NW128
+#define SEGATTN_PREFILL_NW128 8
+#endif
 static int mfma_rows(const Problem &p) {
   const int hs = heads_per_wg(p);
-  return p.D == 128 ? (8 / hs) * 32 : (4 / hs) * 64;
+  return p.D == 128 ? (SEGATTN_PREFILL_NW128 / hs) * 32 : (4 / hs) * 64;
 }
 
 int prefill_rows_per_workgroup(const Problem &p) {
@@ -808,9 +747,9 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (fp32) return launch_prefill_fp32(p, a, grid, st);
   if (p.D == 128) {
-    if (hs == 4) return launch_mfma<128, 4, 1, 8>(p, a, grid, st);
-    if (hs == 2) return launch_mfma<128, 2, 1, 8>(p, a, grid, st);
-    return launch_mfma<128, 1, 1, 8>(p, a, grid, st);
+    if (hs == 4) return launch_mfma<128, 4, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);
+    if (hs == 2) return launch_mfma<128, 2, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);
+    return launch_mfma<128, 1, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);
   }
   if (hs == 4) return launch_mfma<64, 4, 2, 4>(p, a, grid, st);
   if (hs == 2) return launch_mfma<64, 2, 2, 4>(p, a, grid, st);

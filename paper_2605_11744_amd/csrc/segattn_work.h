@@ -65,24 +65,32 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   w.t0 = qblk * rows_per_wg;
   const long long kv_stride = (long long)p.Hkv * p.D;
   if (a.cache == nullptr) {  // SEQ mode: prefix read from k/v by absolute position
-    const long long N = a.n_rows;
+    // dense batch: sequence b occupies rows [b*N, (b+1)*N); packed ragged batch: rows
+    // [cu[b], cu[b+1]) and lse is [Hq, total rows]
+    long long N = a.n_rows, base = (long long)b * N, lse_base = (long long)b * p.Hq * N, lse_stride = N;
+    if (a.cu_seqlens) {
+      base = a.cu_seqlens[b];
+      N = a.cu_seqlens[b + 1] - base;
+      lse_base = base;
+      lse_stride = a.total_rows;
+    }
     const long long s = (long long)seg * p.S;
-    const long long m_i = (N - s < p.S) ? (N - s) : p.S;
+    const long long m_i = (N - s < p.S) ? (N - s) : p.S;  // <= 0 beyond the end of a short sequence
     long long lo = s;
     if (pol & SEGATTN_PAST) lo = 0;
     else if (pol & SEGATTN_TAIL) lo = (s - p.T > 0) ? s - p.T : 0;
     w.n0 = (int)(s - lo);
     w.n1 = (int)m_i;
-    w.k0 = a.k + ((long long)b * N + lo) * kv_stride + (long long)kv * p.D;
-    w.v0 = a.v + ((long long)b * N + lo) * kv_stride + (long long)kv * p.D;
-    w.k1 = a.k + ((long long)b * N + s) * kv_stride + (long long)kv * p.D;
-    w.v1 = a.v + ((long long)b * N + s) * kv_stride + (long long)kv * p.D;
+    w.k0 = a.k + (base + lo) * kv_stride + (long long)kv * p.D;
+    w.v0 = a.v + (base + lo) * kv_stride + (long long)kv * p.D;
+    w.k1 = a.k + (base + s) * kv_stride + (long long)kv * p.D;
+    w.v1 = a.v + (base + s) * kv_stride + (long long)kv * p.D;
     w.stride0 = w.stride1 = kv_stride;
-    w.q = a.q + ((long long)b * N + s) * p.Hq * p.D;
+    w.q = a.q + (base + s) * p.Hq * p.D;
     const long long osz = p.out_fp32 ? 4 : 2;
-    w.out = (unsigned char *)a.out + ((long long)b * N + s) * p.Hq * p.D * osz;
-    w.lse = a.lse + (long long)b * p.Hq * N + s;
-    w.lse_head_stride = N;
+    w.out = (unsigned char *)a.out + (base + s) * p.Hq * p.D * osz;
+    w.lse = a.lse + lse_base + s;
+    w.lse_head_stride = lse_stride;
   } else {  // CTX mode: prefix (and the committed part of the open segment) from the cache
     const int *meta = (const int *)(a.cache + a.geom.meta_off) + ((long long)b * p.Hkv + kv) * kMetaInts;
     int lo, seg_row0;

@@ -154,6 +154,34 @@ def test_evict_hides_oldest_pool_rows():
         c.close()
 
 
+def test_keep_recent_holds_a_sliding_budget_of_pool_rows():
+    """seg_kv_past_keep_recent after every commit: the PAST head sees at most `budget` rows before
+    its segment; the oracle models that as evicted = s - budget per segment."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    S, budget = 64, 100
+    w = W.small("budget", index=231, seq_len=320, seg_len=S, tail_len=16, n_q_heads=4, n_kv_heads=2,
+                head_dim=128, kv_policy=[2, 3], batch=2)
+    q, k, v = W.prefill_inputs(w)
+    c = G.Cache(w, past_capacity=320)
+    try:
+        for s in range(0, 320, S):
+            o, l = c.fwd(q[:, s:s + S], k[:, s:s + S], v[:, s:s + S])
+            ev = max(0, s - budget)
+            o_ref, l_ref = _oracle(w, q, k, v, rows=np.arange(s, s + S), evicted=[ev, ev])
+            G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what=f"budget, segment at {s}")
+            sa.seg_kv_past_keep_recent(c.ctx, 0, budget, c.stream)
+            sa.seg_kv_past_keep_recent(c.ctx, 1, budget, c.stream)
+        past, _, _ = sa.seg_kv_lengths(c.ctx, 2, 2)
+        assert past == [[budget, budget], [budget, budget]]
+        sa.seg_kv_past_keep_recent(c.ctx, 1, 3, c.stream)      # the tail window (16 rows) stays
+        sa.seg_kv_past_keep_recent(c.ctx, 0, 3, c.stream)
+        past, _, _ = sa.seg_kv_lengths(c.ctx, 2, 2)
+        assert past == [[3, 16], [3, 16]]
+    finally:
+        c.close()
+
+
 def test_past_append_explicit_rows_act_as_prefix():
     """Rows handed to seg_kv_past_append become the long-range prefix of the next segment
     (Eq. 13, second case, with gathered rows in place of the whole history)."""

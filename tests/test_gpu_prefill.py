@@ -47,3 +47,31 @@ def test_fwd_seq_c1_full(fp32_check):
     o_ref, l_ref = _oracle(w, q, k, v)
     o, l = G.fwd_seq(w, q, k, v, fp32_check=fp32_check)
     G.assert_parity(o, l, o_ref, l_ref, fp32_check=fp32_check, what="C1")
+
+
+@pytest.mark.parametrize("fp32_check", [True, False])
+def test_packed_ragged_batch_matches_per_sequence_oracle(fp32_check):
+    """seg_attn_fwd_varlen: sequences of different lengths packed without padding, each with its own
+    segment grid; the oracle is run sequence by sequence."""
+    import gpu_util as G
+    lens = [300, 1, 0, 513, 128, 77]
+    S, T = 128, 32
+    w = W.small("ragged", index=140, seq_len=sum(lens), seg_len=S, tail_len=T, n_q_heads=8, n_kv_heads=4,
+                head_dim=128, kv_policy=[1, 3, 0, 2])
+    q, k, v = W.prefill_inputs(w)                       # [1, total, H, D]: one stream, cut into sequences
+    total = sum(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cfg = G.config_of(w, fp32_check=fp32_check, out_fp32=True, batch=len(lens))
+    qd, kd, vd = G.dev_bf16(q[0]), G.dev_bf16(k[0]), G.dev_bf16(v[0])
+    out = torch.full((total, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((8, total), float("nan"), dtype=torch.float32, device="cuda")
+    G.sa.seg_attn_fwd_varlen(cfg, qd, kd, vd, torch.from_numpy(cu).cuda(), total, max(lens), out, lse,
+                           torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    o_gpu, l_gpu = G.to_f64(out), G.to_f64(lse)
+    o_ref, l_ref = orc.attend_packed(q[0], k[0], v[0], cu, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
+    for b, n in enumerate(lens):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        if n:
+            G.assert_parity(o_gpu[lo:hi], l_gpu[:, lo:hi], o_ref[lo:hi], l_ref[:, lo:hi], fp32_check=fp32_check,
+                            what=f"ragged sequence {b} (n={n})")

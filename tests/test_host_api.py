@@ -134,3 +134,13 @@ def test_fwd_seq_validates_before_launching():
         sa.seg_attn_fwd_seq(cfg, 4096, 4096, 4096, 0, 4096, 4096)
     assert e.value.status == sa.SEGATTN_EINVAL
     assert sa.strerror(sa.SEGATTN_ECAPACITY).startswith("past pool")
+
+
+def test_layer_policy_follows_the_head_and_layer_sets():
+    """Sec. 3.4: local heads carry the tail in every layer; long-range heads read the past in the
+    layers of L_long and only their own segment elsewhere."""
+    assert sa.segattn_layer_policy(8, [0, 5], True) == [2, 1, 1, 1, 1, 2, 1, 1]
+    assert sa.segattn_layer_policy(8, [0, 5], False) == [0, 1, 1, 1, 1, 0, 1, 1]
+    assert sa.segattn_layer_policy(4, [], True) == [1, 1, 1, 1]
+    with pytest.raises(sa.SegattnError):
+        sa.segattn_layer_policy(4, [4], True)

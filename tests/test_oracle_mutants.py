@@ -58,6 +58,8 @@ MUTANTS = {
     "retrieval_window_one_short": ("min(n, a_ + win_after + 1)):", "min(n, a_ + win_after)):"),
     "retrieval_pads_with_latest": ("    r = evicted\n    while len(chosen) < want:\n        if r not in inside:\n            inside.add(r)\n            chosen.append(r)\n        r += 1", "    r = n - 1\n    while len(chosen) < want:\n        if r not in inside:\n            inside.add(r)\n            chosen.append(r)\n        r -= 1"),
     "retrieval_result_unsorted": ("res = np.array(sorted(chosen), dtype=np.int64)", "res = np.array(chosen, dtype=np.int64)"),
+    "packed_segment_grid_runs_through_the_pack": ("            o, l = attend(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], **kw)\n            out[lo:hi], lse[:, lo:hi] = o[0], l[0]", "            o, l = attend(q[None, :hi], k[None, :hi], v[None, :hi], **kw)\n            out[lo:hi], lse[:, lo:hi] = o[0, lo:], l[0, :, lo:]"),
+    "packed_lse_of_first_head_for_all": ("out[lo:hi], lse[:, lo:hi] = o[0], l[0]", "out[lo:hi], lse[:, lo:hi] = o[0], l[0, :1]"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 

@@ -669,3 +669,42 @@ def test_retrieve_indices_planted_rows_and_fallback():
     k_pool[29, 0] = 9.0                                                     # window clipped at the pool end
     got = orc.retrieve_indices(q_prev, k_pool, R=5, **RET)
     assert list(got) == [19, 20, 21, 28, 29]
+
+
+def test_packed_batch_keeps_sequences_apart_and_restarts_the_segment_grid():
+    """A packed ragged batch is a set of independent samples: equal lengths reproduce the dense
+    batch; a sequence's result does not change when its neighbours do; and the segment grid starts
+    again at each sequence's first row (a one-segment sequence is plain causal attention whatever
+    precedes it in the pack)."""
+    rng = np.random.default_rng(77)
+    Hq, Hkv, D, S, T = 4, 2, 8, 5, 2
+    kw = dict(seg_len=S, tail_len=T, kv_policy=[1, 3])
+    n = 12
+    q, k, v = (rng.standard_normal((3, n, h, D)) for h in (Hq, Hkv, Hkv))
+    o_d, l_d = orc.attend(q, k, v, **kw)
+    cu = np.arange(4) * n
+    o_p, l_p = orc.attend_packed(q.reshape(3 * n, Hq, D), k.reshape(3 * n, Hkv, D), v.reshape(3 * n, Hkv, D), cu, **kw)
+    np.testing.assert_array_equal(o_p.reshape(3, n, Hq, D), o_d)
+    np.testing.assert_array_equal(l_p.reshape(Hq, 3, n).transpose(1, 0, 2), l_d)
+
+    lens = [7, 0, 4, 11]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    tot = int(cu[-1])
+    q, k, v = (rng.standard_normal((tot, h, D)) for h in (Hq, Hkv, Hkv))
+    o1, l1 = orc.attend_packed(q, k, v, cu, **kw)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for x in (q2, k2, v2):
+        x[:7] += 1.0            # disturb sequence 0 only
+    o2, l2 = orc.attend_packed(q2, k2, v2, cu, **kw)
+    np.testing.assert_array_equal(o1[7:], o2[7:])
+    np.testing.assert_array_equal(l1[:, 7:], l2[:, 7:])
+    assert np.abs(o1[:7] - o2[:7]).max() > 1e-3
+    # sequence 2 (4 rows < S) sits at packed rows 7..10, across a multiple of S of the pack: it
+    # must be plain causal softmax attention over its own rows
+    lo = 7
+    for t in range(4):
+        for h in range(Hq):
+            sc = (k[lo:lo + t + 1, h // 2] @ q[lo + t, h]) / math.sqrt(D)
+            pr = np.exp(sc - sc.max())
+            pr /= pr.sum()
+            np.testing.assert_allclose(o1[lo + t, h], pr @ v[lo:lo + t + 1, h // 2], rtol=0, atol=1e-12)
