@@ -528,6 +528,7 @@ static hipError_t launch_bwd_d(const Problem &p, const BwdArgs &a, hipStream_t s
   pa.n_seg = (a.n + p.S - 1) / p.S;
   const long long seg_rows = a.n < p.S ? a.n : p.S;
   pa.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
+  pa.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * pa.n_seg);
   const long long grid_q = (long long)p.B * p.Hkv * (p.g / hs) * pa.n_seg * pa.q_blocks_per_seg;
   const int blocks_per_seg = (int)((seg_rows + 127) / 128);
   const long long grid_k = (long long)p.B * p.Hkv * pa.n_seg * blocks_per_seg;

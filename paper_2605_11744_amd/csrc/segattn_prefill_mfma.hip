@@ -740,11 +740,33 @@ static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a, long long 
   return hipGetLastError();
 }
 
-hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st) {
+// Stride of the group shuffle in resolve(): the smallest number >= groups/8 that is coprime to
+// the number of groups.
+int prefill_pair_stride(long long groups) {
+  if (groups <= 1) return 1;
+  auto gcd = [](long long x, long long y) {
+    while (y) {
+      const long long t = x % y;
+      x = y;
+      y = t;
+    }
+    return x;
+  };
+  long long s = groups / 8 > 0 ? groups / 8 : 1;
+  while (gcd(s, groups) != 1) ++s;
+  return (int)s;
+}
+
+hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t st) {
   const bool fp32 = p.fp32_math != 0;
   const int hs = fp32 ? 1 : heads_per_wg(p);
-  const long long grid = (long long)p.B * p.Hkv * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
+  const long long grid = (long long)p.B * p.Hkv * (p.g / hs) * a_in.n_seg * a_in.q_blocks_per_seg;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  PrefillArgs a = a_in;
+  a.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * a.n_seg);
+#ifdef SEGATTN_NO_SHUFFLE
+  a.pair_stride = 1;
+#endif
   if (fp32) return launch_prefill_fp32(p, a, grid, st);
   if (p.D == 128) {
     if (hs == 4) return launch_mfma<128, 4, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);

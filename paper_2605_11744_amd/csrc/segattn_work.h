@@ -24,9 +24,9 @@ struct WorkItem {
   bool valid;
 };
 
-// blockIdx -> (sequence, KV head, head sub-group, segment, query block), longest work first:
-// all PAST workgroups by descending absolute query block, then the others by descending
-// in-segment query block.
+// blockIdx -> (sequence, KV head, head sub-group, segment, query block): all PAST workgroups by
+// descending absolute query block (longest work first), then the others grouped so that the
+// query blocks sharing K/V rows run together on one XCD.
 __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int bid, int rows_per_wg,
                                    int heads_per_wg) {
   WorkItem w;
@@ -46,10 +46,28 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     hidx = rest % p.n_past;
     b = rest / p.n_past;
   } else {
-    const int y = bid - (int)past_items;
-    const int per = p.B * n_other * nhs * a.n_seg;
-    qblk = nqb - 1 - y / per;
-    int rest = y % per;
+    // Heads without the PAST bit: the query blocks of one (sequence, head, segment) read the same
+    // few MB of K/V, so they should run at the same time behind the same L2.  Workgroups go to the
+    // 8 XCDs (one L2 each) round-robin by index: XCD x = bid % 8 takes the bids x, x+8, ... in
+    // order.  Give each XCD a contiguous range of the list ordered by (segment, sequence, head,
+    // head sub-group) and, inside one of those, by descending query block.
+    const long long items = (long long)gridDim.x - past_items;
+    const int x = bid & 7;
+    long long start = 0, first = 0;
+#pragma unroll
+    for (int xx = 0; xx < 8; ++xx) {
+      const long long o = (xx - past_items) & 7;  // first list position served by XCD xx
+      const long long cnt = o < items ? (items - o + 7) >> 3 : 0;
+      if (xx < x) start += cnt;
+      if (xx == x) first = past_items + o;
+    }
+    const long long L = start + ((bid - first) >> 3);
+    qblk = nqb - 1 - (int)(L % nqb);
+    // Consecutive groups differ little in length for a dense batch but a lot for a ragged one (a
+    // whole range of them can be empty): a multiplicative shuffle of the group index (stride
+    // coprime to the group count, about an eighth of it) deals each XCD an even sample.
+    const long long groups = items / nqb;
+    int rest = (int)((L / nqb) * (a.pair_stride > 0 ? a.pair_stride : 1) % groups);
     hs = rest % nhs;
     rest /= nhs;
     hidx = p.n_past + rest % n_other;
