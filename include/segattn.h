@@ -109,7 +109,10 @@ segattn_status segattn_reset(segattn_ctx *ctx, void *stream);
  * in-segment offset fill+t, where fill is the number of rows already committed to the open
  * segment; it sees the head's prefix held in the cache, those fill rows, and rows 0..t of k/v.
  * Requires 1 <= m and fill + m <= S for every sequence (ESTATE otherwise).  Reads the cache,
- * does not change it: follow with seg_kv_commit() on the same stream. */
+ * does not change it: follow with seg_kv_commit() on the same stream.
+ * (All prefill entry points, head_dim 128: the library runs workgroups of eight or of four waves
+ * depending on how much work the launch has; the environment variable SEGATTN_PREFILL_WAVES=4|8,
+ * read at every launch, forces one of them.  Results do not depend on it beyond rounding.) */
 segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, const void *v,
                             int32_t m, void *out, float *lse, void *stream);
 

@@ -179,8 +179,6 @@ segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, cons
   a.geom = ctx->g;
   a.n_rows = m;
   a.n_seg = 1;
-  const int rows = prefill_rows_per_workgroup(p);
-  a.q_blocks_per_seg = (m + rows - 1) / rows;
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
 }
 
@@ -199,9 +197,6 @@ segattn_status seg_attn_fwd_seq(const segattn_config *cfg, const void *q, const 
   a.cache = nullptr;
   a.n_rows = (int)n;
   a.n_seg = (int)((n + p.S - 1) / p.S);
-  const int rows = prefill_rows_per_workgroup(p);
-  const long long seg_rows = n < p.S ? n : p.S;
-  a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
 }
 
@@ -224,9 +219,6 @@ segattn_status seg_attn_fwd_varlen(const segattn_config *cfg, const void *q, con
   a.total_rows = total;
   a.n_rows = (int)max_seqlen;
   a.n_seg = (int)((max_seqlen + p.S - 1) / p.S);
-  const int rows = prefill_rows_per_workgroup(p);
-  const long long seg_rows = max_seqlen < p.S ? max_seqlen : p.S;
-  a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
 }
 

@@ -58,7 +58,7 @@ struct PrefillArgs {
   const int *cu_seqlens; // SEQ mode, packed ragged batch: device [B+1] row offsets, else nullptr
   long long total_rows;  // rows of the packed batch (lse is [Hq, total_rows] then)
   int n_seg;             // segments covered by the launch (1 in CTX mode)
-  int q_blocks_per_seg;  // ceil(min(S, n_rows) / rows per workgroup)
+  int q_blocks_per_seg;  // ceil(min(S, n_rows) / rows per workgroup); set by the launcher
   int pair_stride;       // spreads the (segment, sequence, head) groups of non-PAST heads over the XCDs (0 = 1)
 };
 
@@ -189,7 +189,6 @@ hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st);
-int prefill_rows_per_workgroup(const Problem &p);
 int prefill_pair_stride(long long groups);
 
 }  // namespace segattn

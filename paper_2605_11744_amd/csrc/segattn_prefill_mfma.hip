@@ -33,6 +33,8 @@
 // range.  Paths outside that step matter more than their share of the arithmetic suggests: a
 // register spilled there is reloaded through the same counter the K/V prefetch uses, and
 // waiting for it drains the prefetch queue.
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "segattn_work.h"
@@ -708,22 +710,6 @@ hipError_t launch_prefill_fp32(const Problem &p, const PrefillArgs &a, long long
 
 static int heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1; }
 
-// D = 128: 32 query rows per wave, eight waves (two per SIMD) that share the K/V tiles.
-// D = 64: 64 query rows per wave, four waves (the tiles are too small to split their loads
-// over eight).
-#ifndef SEGATTN_PREFILL_NW128
-#define SEGATTN_PREFILL_NW128 8
-#endif
-static int mfma_rows(const Problem &p) {
-  const int hs = heads_per_wg(p);
-  return p.D == 128 ? (SEGATTN_PREFILL_NW128 / hs) * 32 : (4 / hs) * 64;
-}
-
-int prefill_rows_per_workgroup(const Problem &p) {
-  if (p.fp32_math) return 64;
-  return mfma_rows(p);
-}
-
 template <int D, int HS, int QB, int NW>
 static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a, long long grid, hipStream_t st) {
   constexpr int ring = kSlots * StepGeom<D>::kSlotBytes;
@@ -757,21 +743,55 @@ int prefill_pair_stride(long long groups) {
   return (int)s;
 }
 
+// Waves per workgroup for head_dim 128 (each wave owns one head x 32 query rows; D = 64 always
+// runs four waves of 64 rows).  Eight waves -- 64 rows per head, one workgroup per CU, two waves
+// per SIMD -- move half as many K/V bytes per query row and are the choice whenever there is
+// enough work to fill the chip.  Four waves -- 32 rows per head, two workgroups fit a CU -- double
+// the number of workgroups: right when the long (PAST) workgroups of a launch would otherwise
+// leave CUs idle, which is the case for a segment-by-segment prefill (one segment has 64-row
+// blocks for only half of the CUs, and they carry nearly all of the work).
+// SEGATTN_PREFILL_WAVES=4|8 in the environment overrides the choice (used by the tests to run
+// both variants on small inputs).
+static int waves_d128(const Problem &p, const PrefillArgs &a, int hs) {
+  if (const char *e = getenv("SEGATTN_PREFILL_WAVES")) {  // read at every launch: tests switch it
+    const int v = atoi(e);
+    if (v == 4 || v == 8) return v;
+  }
+  static const int n_cu = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    return cus;
+  }();
+  const long long seg_rows = a.n_rows < p.S ? a.n_rows : p.S;
+  const int rows8 = (8 / hs) * 32;
+  const long long blocks8 = (long long)a.n_seg * ((seg_rows + rows8 - 1) / rows8);
+  const long long heads = (long long)p.B * (p.n_past > 0 ? p.n_past : p.Hkv) * (p.g / hs);
+  return heads * blocks8 < n_cu ? 4 : 8;
+}
+
 hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t st) {
   const bool fp32 = p.fp32_math != 0;
   const int hs = fp32 ? 1 : heads_per_wg(p);
-  const long long grid = (long long)p.B * p.Hkv * (p.g / hs) * a_in.n_seg * a_in.q_blocks_per_seg;
-  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int nw = p.D == 128 ? waves_d128(p, a_in, hs) : 4;
+  const int rows = fp32 ? 64 : (p.D == 128 ? (nw / hs) * 32 : (4 / hs) * 64);
   PrefillArgs a = a_in;
+  const long long seg_rows = a.n_rows < p.S ? a.n_rows : p.S;
+  a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
+  const long long grid = (long long)p.B * p.Hkv * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
+  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   a.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * a.n_seg);
-#ifdef SEGATTN_NO_SHUFFLE
-  a.pair_stride = 1;
-#endif
   if (fp32) return launch_prefill_fp32(p, a, grid, st);
   if (p.D == 128) {
-    if (hs == 4) return launch_mfma<128, 4, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);
-    if (hs == 2) return launch_mfma<128, 2, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);
-    return launch_mfma<128, 1, 1, SEGATTN_PREFILL_NW128>(p, a, grid, st);
+    if (nw == 8) {
+      if (hs == 4) return launch_mfma<128, 4, 1, 8>(p, a, grid, st);
+      if (hs == 2) return launch_mfma<128, 2, 1, 8>(p, a, grid, st);
+      return launch_mfma<128, 1, 1, 8>(p, a, grid, st);
+    }
+    if (hs == 4) return launch_mfma<128, 4, 1, 4>(p, a, grid, st);
+    if (hs == 2) return launch_mfma<128, 2, 1, 4>(p, a, grid, st);
+    return launch_mfma<128, 1, 1, 4>(p, a, grid, st);
   }
   if (hs == 4) return launch_mfma<64, 4, 2, 4>(p, a, grid, st);
   if (hs == 2) return launch_mfma<64, 2, 2, 4>(p, a, grid, st);

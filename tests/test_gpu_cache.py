@@ -23,11 +23,18 @@ STREAM_CASES = [
 ]
 
 
+@pytest.mark.parametrize("waves", ["auto", "4", "8"])
 @pytest.mark.parametrize("fp32_check", [True, False])
 @pytest.mark.parametrize("case", range(len(STREAM_CASES)))
-def test_streaming_prefill_equals_oracle(case, fp32_check):
+def test_streaming_prefill_equals_oracle(case, fp32_check, waves, monkeypatch):
     import gpu_util as G
     kw, chunks = STREAM_CASES[case]
+    if waves != "auto":
+        if fp32_check or kw["head_dim"] != 128:
+            pytest.skip("the wave count only exists in the head_dim-128 MFMA kernel")
+        monkeypatch.setenv("SEGATTN_PREFILL_WAVES", waves)
+    else:
+        monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
     w = W.small(f"stream{case}", index=200 + case, **kw)
     q, k, v = W.prefill_inputs(w)
     o_ref, l_ref = _oracle(w, q, k, v)

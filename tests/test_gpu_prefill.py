@@ -28,10 +28,22 @@ SMALL = [
 ]
 
 
+@pytest.fixture(params=["auto", "4", "8"])
+def waves(request, monkeypatch):
+    """Workgroup shape of the head_dim-128 MFMA kernel: the library's own choice, or forced."""
+    if request.param == "auto":
+        monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
+    else:
+        monkeypatch.setenv("SEGATTN_PREFILL_WAVES", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("fp32_check", [True, False])
 @pytest.mark.parametrize("case", range(len(SMALL)))
-def test_fwd_seq_small(case, fp32_check):
+def test_fwd_seq_small(case, fp32_check, waves):
     import gpu_util as G
+    if waves != "auto" and (fp32_check or SMALL[case]["head_dim"] != 128):
+        pytest.skip("the wave count only exists in the head_dim-128 MFMA kernel")
     w = W.small(f"small{case}", index=100 + case, **SMALL[case])
     q, k, v = W.prefill_inputs(w)
     o_ref, l_ref = _oracle(w, q, k, v)
@@ -50,10 +62,12 @@ def test_fwd_seq_c1_full(fp32_check):
 
 
 @pytest.mark.parametrize("fp32_check", [True, False])
-def test_packed_ragged_batch_matches_per_sequence_oracle(fp32_check):
+def test_packed_ragged_batch_matches_per_sequence_oracle(fp32_check, waves):
     """seg_attn_fwd_varlen: sequences of different lengths packed without padding, each with its own
     segment grid; the oracle is run sequence by sequence."""
     import gpu_util as G
+    if waves != "auto" and fp32_check:
+        pytest.skip("the wave count only exists in the head_dim-128 MFMA kernel")
     lens = [300, 1, 0, 513, 128, 77]
     S, T = 128, 32
     w = W.small("ragged", index=140, seq_len=sum(lens), seg_len=S, tail_len=T, n_q_heads=8, n_kv_heads=4,
