@@ -767,7 +767,9 @@ static int waves_d128(const Problem &p, const PrefillArgs &a, int hs) {
   const long long seg_rows = a.n_rows < p.S ? a.n_rows : p.S;
   const int rows8 = (8 / hs) * 32;
   const long long blocks8 = (long long)a.n_seg * ((seg_rows + rows8 - 1) / rows8);
-  const long long heads = (long long)p.B * (p.n_past > 0 ? p.n_past : p.Hkv) * (p.g / hs);
+  // PAST heads carry the long key ranges unless they attend to a retrieved prefix of bounded size
+  const bool long_past = p.n_past > 0 && !(a.cache != nullptr && a.geom.ret_cap > 0);
+  const long long heads = (long long)p.B * (long_past ? p.n_past : p.Hkv) * (p.g / hs);
   return heads * blocks8 < n_cu ? 4 : 8;
 }
 

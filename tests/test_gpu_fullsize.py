@@ -122,3 +122,37 @@ def test_decode_c5_full_batch():
         print(f"decode C5: worst |dO| = {worst:.3e}")
     finally:
         c.close()
+
+
+def test_ragged_batch_full_size_sampled_rows():
+    """The packed batch bench.py times (the 128K tokens of the main workload cut into 12 sequences of
+    720 .. 32768 tokens, one seg_attn_fwd_varlen launch, bf16 output): rows at the start and end of
+    every sequence, around its segment boundaries and at random, against the oracle run on that
+    sequence alone; and everything written and finite."""
+    import gpu_util as G
+    w = W.C4
+    lens = [32768, 24576, 20000, 16384, 12288, 8192, 6000, 4096, 3000, 2048, 1000, 720]
+    assert sum(lens) == w.seq_len
+    q, k, v = W.prefill_inputs(w)                       # [1, total, H, D]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cfg = G.config_of(w, out_fp32=False, batch=len(lens))
+    qd, kd, vd = G.dev_bf16(q[0]), G.dev_bf16(k[0]), G.dev_bf16(v[0])
+    out = torch.full((w.seq_len, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((w.n_q_heads, w.seq_len), float("nan"), dtype=torch.float32, device="cuda")
+    G.sa.seg_attn_fwd_varlen(cfg, qd, kd, vd, torch.from_numpy(cu).cuda(), w.seq_len, max(lens), out, lse,
+                             torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    rng = np.random.default_rng(w.seed + 21)
+    S = w.seg_len
+    for b, n in enumerate(lens):
+        lo = int(cu[b])
+        fixed = {0, 1, 63, 64, n - 1, n - 2, n // 2, S - 1, S, S + 1, (n // S) * S - 1, (n // S) * S}
+        rows = sorted({r for r in fixed if 0 <= r < n} | set(int(x) for x in rng.integers(0, n, 6)))
+        rows = np.array(rows, dtype=np.int64)
+        w_b = W.small(f"ragged{b}", index=0, seq_len=n, seg_len=S, tail_len=w.tail_len, n_q_heads=w.n_q_heads,
+                      n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, kv_policy=list(w.kv_policy))
+        idx = torch.from_numpy(rows + lo).cuda()
+        o_gpu = G.to_f64(out.index_select(0, idx))[None]
+        l_gpu = G.to_f64(lse.index_select(1, idx))[None]
+        _check_rows(w_b, q[:, lo:lo + n], k[:, lo:lo + n], v[:, lo:lo + n], o_gpu, l_gpu, rows, True)
