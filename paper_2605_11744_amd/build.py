@@ -11,17 +11,19 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
 SOURCES = ("segattn_api.hip", "segattn_prefill_mfma.hip", "segattn_prefill_fp32.hip", "segattn_decode.hip",
-           "segattn_cache.hip", "segattn_bwd_fp32.hip", "segattn_bwd_mfma.hip", "segattn_rope.hip", "segattn_retrieve.hip")
+           "segattn_cache.hip", "segattn_bwd_fp32.hip", "segattn_bwd_dq.hip", "segattn_bwd_mfma.hip", "segattn_rope.hip", "segattn_retrieve.hip")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 )
-# Per-source extras.  Forward prefill kernel: every matrix product delivers its result in vector
-# registers, where the softmax reads it (the kernel fits in 256 of them per wave).  Every other
-# file keeps the compiler's default MFMA register form.
-EXTRA_FLAGS = {"segattn_prefill_mfma.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1")}
+# Per-source extras.  Forward prefill kernel and the dQ kernel of the backward: every matrix product
+# delivers its result in vector registers, where the softmax reads it (each kernel fits in 256 of
+# them per wave, two waves per SIMD).  Every other file keeps the compiler's default MFMA register
+# form.
+EXTRA_FLAGS = {"segattn_prefill_mfma.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1"),
+               "segattn_bwd_dq.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1")}
 
 
 def hipcc() -> str:

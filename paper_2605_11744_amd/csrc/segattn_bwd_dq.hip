@@ -1,0 +1,199 @@
+// dQ kernel of the bf16 MFMA backward of segment-level attention (see segattn_bwd_mfma.hip for
+// the scheme).  A wave owns 32 query rows of one head and walks the keys it sees in steps of 32
+// (prefix span, then its own segment up to the diagonal):
+//   S^T  = K . Q^T          P^T = exp2(S^T c - LSE)
+//   dP^T = V . dO^T         dS^T = P^T (dP^T - delta)
+//   dQ^T += K^T . dS^T      (every visible key contributes, past rows too)
+// Built with the compiler's VGPR form of the matrix products (-amdgpu-mfma-vgpr-form): the whole
+// state of a wave -- Q^T and dO^T operands, the dQ^T accumulators, the score tiles -- fits 256
+// vector registers, so two workgroups share a CU and one fills the other's stalls (each step is
+// a chain products -> exponentials -> products with a barrier at its end).
+#include <string.h>
+
+#include "segattn_bwd_tiles.h"
+
+namespace segattn {
+
+// ---------------------------------------------------------------------------------------------
+// dQ
+// ---------------------------------------------------------------------------------------------
+template <int D, int HS>
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p, const PrefillArgs pa, const BwdArgs a) {
+  using T = BwdTile<D>;
+  constexpr int NC = D / 16, NB = D / 32;
+  constexpr int RW = 32;             // query rows per wave
+  constexpr int BQ = (4 / HS) * RW;  // query rows per workgroup
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][T::kBytes];  // [buffer][K,V]
+
+  WorkItem w = resolve(p, pa, blockIdx.x, BQ, HS);
+  if (!w.valid) return;
+  pin_uniform(w);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hi = lane >> 5, col = lane & 31;
+  const int head = w.kv * p.g + w.hsub * HS + (wave % HS);
+  const int tw0 = w.t0 + (wave / HS) * RW;
+  const int last_row = w.n1 - 1;
+  const float c = p.scale_log2e;
+  // global row of the segment's first token (b*N + s) and this lane's query row
+  const long long seg_row = (w.q - a.q) / ((long long)p.Hq * D);
+  int t = tw0 + col;
+  const bool row_ok = t <= last_row;
+  t = row_ok ? t : last_row;
+  const long long qoff = ((seg_row + t) * p.Hq + head) * D;
+  const long long stat = (w.lse - a.lse) + (long long)head * a.n + t;  // index into lse / delta
+  const float lse2 = a.lse[stat] * kLog2e, delta = a.delta[stat];
+
+  bf16x8 Qr[NC], Gr[NC];  // Q^T and dO^T operands: row `col`, elements 16 kc + 8 hi .. +7
+#pragma unroll
+  for (int kc = 0; kc < NC; ++kc) {
+    Qr[kc] = *(const bf16x8 *)(a.q + qoff + 16 * kc + 8 * hi);
+    Gr[kc] = *(const bf16x8 *)(a.dout + qoff + 16 * kc + 8 * hi);
+  }
+  f32x16 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+
+  const int n1_needed = (w.t0 + BQ < w.n1) ? (w.t0 + BQ) : w.n1;
+  const int nst0 = (w.n0 + kBwdStep - 1) / kBwdStep;
+  const int nst1 = (n1_needed + kBwdStep - 1) / kBwdStep;
+  const int nsteps = nst0 + nst1;
+  const int my_last = tw0 + RW - 1;  // keys of the own segment beyond this row are invisible to the wave
+
+  // Tiles of step j (clamped to the last step, whose re-fetch is not used): global -> registers.
+  // A scalar base per step plus a 32-bit lane offset fixed for the kernel (both spans have the
+  // same row stride here: the backward pass reads K/V by absolute position); only the last step
+  // of a span can reach past its end, and only then are the lane's rows clamped.
+  const unsigned row_bytes = (unsigned)(w.stride1 * 2);
+  int f_row[T::kLoads];
+  unsigned f_col2[T::kLoads], f_off[T::kLoads];
+#pragma unroll
+  for (int i = 0; i < T::kLoads; ++i) {
+    f_row[i] = (tid + 256 * i) / T::kChunks;
+    f_col2[i] = (unsigned)((tid + 256 * i) % T::kChunks) * 16;
+    f_off[i] = (unsigned)f_row[i] * row_bytes + f_col2[i];
+  }
+  u32x4 kr[T::kLoads], vr[T::kLoads];
+#define SEGATTN_BWD_FETCH_KV(jj)                                                                      \
+  do {                                                                                                \
+    int j_ = (jj);                                                                                    \
+    j_ = j_ < nsteps ? j_ : nsteps - 1;                                                               \
+    const bool s1_ = j_ >= nst0;                                                                      \
+    const int jl_ = s1_ ? j_ - nst0 : j_;                                                             \
+    const int left_ = (s1_ ? w.n1 : w.n0) - jl_ * kBwdStep;                                           \
+    const unsigned long long so_ = (unsigned long long)jl_ * kBwdStep * row_bytes;                    \
+    const unsigned char *kb_ = (const unsigned char *)(s1_ ? w.k1 : w.k0) + so_;                      \
+    const unsigned char *vb_ = (const unsigned char *)(s1_ ? w.v1 : w.v0) + so_;                      \
+    if (left_ >= kBwdStep) {                                                                          \
+      _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                      \
+        kr[i_] = *(const u32x4 *)(kb_ + f_off[i_]);                                                   \
+        vr[i_] = *(const u32x4 *)(vb_ + f_off[i_]);                                                   \
+      }                                                                                               \
+    } else {                                                                                          \
+      _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                      \
+        const int r_ = f_row[i_] < left_ ? f_row[i_] : left_ - 1;                                     \
+        const unsigned o_ = (unsigned)r_ * row_bytes + f_col2[i_];                                    \
+        kr[i_] = *(const u32x4 *)(kb_ + o_);                                                          \
+        vr[i_] = *(const u32x4 *)(vb_ + o_);                                                          \
+      }                                                                                               \
+    }                                                                                                 \
+  } while (0)
+#define SEGATTN_BWD_STORE_KV(buf)                                                                     \
+  do {                                                                                                \
+    _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                        \
+      const int off_ = T::at(f_row[i_], (int)(f_col2[i_] / 16));                                      \
+      *(u32x4 *)(smem[buf][0] + off_) = kr[i_];                                                       \
+      *(u32x4 *)(smem[buf][1] + off_) = vr[i_];                                                       \
+    }                                                                                                 \
+  } while (0)
+  SEGATTN_BWD_FETCH_KV(0);
+  SEGATTN_BWD_STORE_KV(0);
+  __syncthreads();
+  (void)my_last;
+  for (int j = 0; j < nsteps; ++j) {
+    const int cur = j & 1;
+    SEGATTN_BWD_FETCH_KV(j + 1);
+    const bool own = j >= nst0;
+    const int k0 = (own ? j - nst0 : j) * kBwdStep;           // first key of the step inside its span
+    const int span_len = own ? w.n1 : w.n0;
+    {
+      const unsigned char *kt = smem[cur][0], *vt = smem[cur][1];
+      f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 dP = S;
+#pragma unroll
+      for (int kc = 0; kc < NC; ++kc) {
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(kt, lane, kc), Qr[kc], S, 0, 0, 0);
+        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(vt, lane, kc), Gr[kc], dP, 0, 0, 0);
+      }
+      bf16x8 dS[2];
+      const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1;  // last visible key of the span
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        f32x8 e;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const int r = 8 * h2 + x;
+          const int key = k0 + 8 * (r / 4) + 4 * hi + r % 4;
+          // a masked pair gets exponent -inf: its weight is exactly 0, without a branch
+          const float pr = __builtin_amdgcn_exp2f(key <= kmax ? fmaf(S[r], c, -lse2) : -INFINITY);
+          e[x] = pr * (dP[r] - delta);
+        }
+        dS[h2] = __builtin_convertvector(e, bf16x8);
+      }
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) mma_acc(acc[nb], read_transposed<D>(kt, lane, nb, h2), dS[h2]);
+    }
+    SEGATTN_BWD_STORE_KV(cur ^ 1);
+    __syncthreads();
+  }
+#undef SEGATTN_BWD_FETCH_KV
+#undef SEGATTN_BWD_STORE_KV
+  if (!row_ok) return;
+  // dQ^T[d][q]: this lane holds, for its query row, d = 32 nb + 8 rg + 4 hi .. +3
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      const int d = 32 * nb + 8 * rg + 4 * hi;
+      const f32x4 o = {acc[nb][4 * rg + 0] * p.scale, acc[nb][4 * rg + 1] * p.scale,
+                       acc[nb][4 * rg + 2] * p.scale, acc[nb][4 * rg + 3] * p.scale};
+      if (p.out_fp32) *(f32x4 *)((float *)a.dq + qoff + d) = o;
+      else *(uint2 *)((unsigned short *)a.dq + qoff + d) = __builtin_bit_cast(uint2, __builtin_convertvector(o, bf16x4));
+    }
+}
+
+static int bwd_heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1; }
+
+template <int D>
+static hipError_t launch_dq(const Problem &p, const BwdArgs &a, hipStream_t st) {
+  const int hs = bwd_heads_per_wg(p);
+  const int rows = (4 / hs) * 32;
+  PrefillArgs pa;
+  memset(&pa, 0, sizeof(pa));
+  pa.q = a.q;
+  pa.k = a.k;
+  pa.v = a.v;
+  pa.out = a.dq;
+  pa.lse = const_cast<float *>(a.lse);
+  pa.cache = nullptr;
+  pa.n_rows = a.n;
+  pa.n_seg = (a.n + p.S - 1) / p.S;
+  const long long seg_rows = a.n < p.S ? a.n : p.S;
+  pa.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
+  pa.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * pa.n_seg);
+  const long long grid_q = (long long)p.B * p.Hkv * (p.g / hs) * pa.n_seg * pa.q_blocks_per_seg;
+  if (grid_q <= 0 || grid_q > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (hs == 4) hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  else if (hs == 2) hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  else hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dq(const Problem &p, const BwdArgs &a, hipStream_t st) {
+  return p.D == 128 ? launch_dq<128>(p, a, st) : launch_dq<64>(p, a, st);
+}
+
+}  // namespace segattn

@@ -188,6 +188,7 @@ hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t 
 hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st);
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);
+hipError_t launch_bwd_dq(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st);
 int prefill_pair_stride(long long groups);
 

@@ -82,14 +82,6 @@ __device__ inline float half_max(float x) {  // max over lanes l and l^32
   const auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
   return fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
 }
-__device__ inline int uniform_i32(int x) { return __builtin_amdgcn_readfirstlane(x); }
-template <typename T>
-__device__ inline T *uniform_ptr(T *ptr) {
-  const unsigned long long u = (unsigned long long)ptr;
-  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
-  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
-  return (T *)(((unsigned long long)hi << 32) | lo);
-}
 __device__ inline float half_sum(float x) {
   const int xi = __float_as_int(x);
   const auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
@@ -117,18 +109,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
 
   WorkItem w = resolve(p, a, blockIdx.x, BQ, HS);
   if (!w.valid) return;
-  // Everything in the work item is the same for the whole workgroup; some of it comes from memory
-  // (sequence offsets, cache counters) through vector loads.  Pin it to scalar registers so that
-  // the loader's pointers and every loop bound derived from it stay out of the vector file.
-  w.n0 = uniform_i32(w.n0);
-  w.n1 = uniform_i32(w.n1);
-  w.t0 = uniform_i32(w.t0);
-  w.stride0 = uniform_i32((int)w.stride0);
-  w.stride1 = uniform_i32((int)w.stride1);
-  w.k0 = uniform_ptr(w.k0);
-  w.v0 = uniform_ptr(w.v0);
-  w.k1 = uniform_ptr(w.k1);
-  w.v1 = uniform_ptr(w.v1);
+  pin_uniform(w);
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;

@@ -133,6 +133,30 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   return w;
 }
 
+__device__ inline int uniform_i32(int x) { return __builtin_amdgcn_readfirstlane(x); }
+template <typename T>
+__device__ inline T *uniform_ptr(T *ptr) {
+  const unsigned long long u = (unsigned long long)ptr;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
+  return (T *)(((unsigned long long)hi << 32) | lo);
+}
+// Everything in a work item is the same for the whole workgroup, but some of it comes from memory
+// (sequence offsets, cache counters) through vector loads.  Pin the sizes and the K/V pointers to
+// scalar registers so that loader pointers and loop bounds derived from them stay out of the
+// vector file.
+__device__ inline void pin_uniform(WorkItem &w) {
+  w.n0 = uniform_i32(w.n0);
+  w.n1 = uniform_i32(w.n1);
+  w.t0 = uniform_i32(w.t0);
+  w.stride0 = uniform_i32((int)w.stride0);
+  w.stride1 = uniform_i32((int)w.stride1);
+  w.k0 = uniform_ptr(w.k0);
+  w.v0 = uniform_ptr(w.v0);
+  w.k1 = uniform_ptr(w.k1);
+  w.v1 = uniform_ptr(w.v1);
+}
+
 __device__ inline float bf16_bits_to_f32(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
 
 }  // namespace segattn
