@@ -18,12 +18,15 @@ HIPCC_FLAGS = (
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 )
-# Per-source extras.  Forward prefill kernel and the dQ kernel of the backward: every matrix product
-# delivers its result in vector registers, where the softmax reads it (each kernel fits in 256 of
-# them per wave, two waves per SIMD).  Every other file keeps the compiler's default MFMA register
-# form.
-EXTRA_FLAGS = {"segattn_prefill_mfma.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1"),
-               "segattn_bwd_dq.hip": ("-mllvm", "-amdgpu-mfma-vgpr-form=1")}
+# Per-source extras.  The forward prefill kernel and both backward kernels are built with the
+# VGPR form of the matrix products: a product delivers its result in vector registers, where the
+# softmax / dS arithmetic reads it, instead of in accumulation registers that have to be copied
+# out first.  The forward and dQ kernels fit 256 vector registers per wave (two waves per SIMD);
+# the dK/dV kernel keeps its K and V operands in accumulation registers, which the products can
+# read directly.  Every other file keeps the compiler's default form.
+_VGPR_FORM = ("-mllvm", "-amdgpu-mfma-vgpr-form=1")
+EXTRA_FLAGS = {"segattn_prefill_mfma.hip": _VGPR_FORM, "segattn_bwd_dq.hip": _VGPR_FORM,
+               "segattn_bwd_mfma.hip": _VGPR_FORM}
 
 
 def hipcc() -> str:

@@ -83,19 +83,19 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p, const P
     const int jl_ = s1_ ? j_ - nst0 : j_;                                                             \
     const int left_ = (s1_ ? w.n1 : w.n0) - jl_ * kBwdStep;                                           \
     const unsigned long long so_ = (unsigned long long)jl_ * kBwdStep * row_bytes;                    \
-    const unsigned char *kb_ = (const unsigned char *)(s1_ ? w.k1 : w.k0) + so_;                      \
-    const unsigned char *vb_ = (const unsigned char *)(s1_ ? w.v1 : w.v0) + so_;                      \
+    const GLB_AS unsigned char *kb_ = (const GLB_AS unsigned char *)(s1_ ? w.k1 : w.k0) + so_;        \
+    const GLB_AS unsigned char *vb_ = (const GLB_AS unsigned char *)(s1_ ? w.v1 : w.v0) + so_;        \
     if (left_ >= kBwdStep) {                                                                          \
       _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                      \
-        kr[i_] = *(const u32x4 *)(kb_ + f_off[i_]);                                                   \
-        vr[i_] = *(const u32x4 *)(vb_ + f_off[i_]);                                                   \
+        kr[i_] = *(const GLB_AS u32x4 *)(kb_ + f_off[i_]);                                            \
+        vr[i_] = *(const GLB_AS u32x4 *)(vb_ + f_off[i_]);                                            \
       }                                                                                               \
     } else {                                                                                          \
       _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                      \
         const int r_ = f_row[i_] < left_ ? f_row[i_] : left_ - 1;                                     \
         const unsigned o_ = (unsigned)r_ * row_bytes + f_col2[i_];                                    \
-        kr[i_] = *(const u32x4 *)(kb_ + o_);                                                          \
-        vr[i_] = *(const u32x4 *)(vb_ + o_);                                                          \
+        kr[i_] = *(const GLB_AS u32x4 *)(kb_ + o_);                                                   \
+        vr[i_] = *(const GLB_AS u32x4 *)(vb_ + o_);                                                   \
       }                                                                                               \
     }                                                                                                 \
   } while (0)
@@ -127,19 +127,35 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p, const P
         dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(vt, lane, kc), Gr[kc], dP, 0, 0, 0);
       }
       bf16x8 dS[2];
-      const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1;  // last visible key of the span
+      // a step whose 32 keys are visible to all 32 queries of the wave needs no masks: keys of the
+      // prefix span short of its ragged end, keys of the own segment up to the wave's first row
+      const bool all_visible = own ? (k0 + kBwdStep - 1 <= tw0 && tw0 + RW - 1 <= last_row) : (k0 + kBwdStep <= span_len);
+      if (all_visible) {
 #pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) {
-        f32x8 e;
+        for (int h2 = 0; h2 < 2; ++h2) {
+          f32x8 e;
 #pragma unroll
-        for (int x = 0; x < 8; ++x) {
-          const int r = 8 * h2 + x;
-          const int key = k0 + 8 * (r / 4) + 4 * hi + r % 4;
-          // a masked pair gets exponent -inf: its weight is exactly 0, without a branch
-          const float pr = __builtin_amdgcn_exp2f(key <= kmax ? fmaf(S[r], c, -lse2) : -INFINITY);
-          e[x] = pr * (dP[r] - delta);
+          for (int x = 0; x < 8; ++x) {
+            const int r = 8 * h2 + x;
+            e[x] = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2)) * (dP[r] - delta);
+          }
+          dS[h2] = __builtin_convertvector(e, bf16x8);
         }
-        dS[h2] = __builtin_convertvector(e, bf16x8);
+      } else {
+        const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1;  // last visible key of the span
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          f32x8 e;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) {
+            const int r = 8 * h2 + x;
+            const int key = k0 + 8 * (r / 4) + 4 * hi + r % 4;
+            // a masked pair gets exponent -inf: its weight is exactly 0, without a branch
+            const float pr = __builtin_amdgcn_exp2f(key <= kmax ? fmaf(S[r], c, -lse2) : -INFINITY);
+            e[x] = pr * (dP[r] - delta);
+          }
+          dS[h2] = __builtin_convertvector(e, bf16x8);
+        }
       }
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2)

@@ -21,9 +21,12 @@
 // row-major LDS tiles with ds_read_b64_tr_b16.  Tiles are staged HBM -> registers -> LDS,
 // double-buffered, one barrier per step; the 16-byte chunks of a row are XOR-swizzled against
 // bank conflicts.
-// This file is compiled with the compiler's default MFMA register form (accumulators in
-// accumulation registers, placed by the register allocator); all products are builtins, so the
-// compiler tracks every MFMA hazard itself.
+// This file and segattn_bwd_dq.hip are compiled with the VGPR form of the matrix products
+// (-amdgpu-mfma-vgpr-form): S and dP arrive in vector registers, where the exponentials read them.
+// In the dK/dV kernel the K and V operands sit in accumulation registers (park()), which a product
+// reads directly; with the default form the compiler also kept S and dP there and moved two
+// accumulator blocks back and forth every step to make room (96 register moves per 32 products).
+// All products are builtins, so the compiler tracks every MFMA hazard itself.
 #include <string.h>
 
 #include "segattn_bwd_tiles.h"
