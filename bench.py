@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c4_128k_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode and streaming legs")
+    ap.add_argument("--only", choices=("backward", "decode", "retrieve"),
+                    help="profiling aid: run just this leg (none of them needs the 128K inputs) and print it alone")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -80,6 +82,11 @@ def main() -> int:
     sa.lib()  # fails loudly if libsegattn.so has not been built
     torch.cuda.set_device(0)
     w = W.WORKLOADS[args.workload]
+    if args.only:
+        leg = {"backward": lambda: backward_leg(sa, W, w), "decode": lambda: decode_leg(sa, W),
+               "retrieve": lambda: retrieve_leg(sa, W)}[args.only]
+        print(json.dumps({args.only: leg()}))
+        return 0
     N, Hq, Hkv, D, S, T = w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seg_len, w.tail_len
     stream = torch.cuda.current_stream().cuda_stream
 
