@@ -26,13 +26,13 @@
 // of 5 step slots, three steps ahead of their use; the 16-byte chunks of a row are XOR-
 // swizzled by the loading lanes so that both the row-wise K reads and the transposing V reads
 // are free of bank conflicts.  Steps that need an element mask (the diagonal of the query's
-// own segment, the ragged end of a span, a step past the wave's last query that other waves of
-// the workgroup still need) run the same pipelined step with the mask applied to S^T first, and
-// the loader keeps a constant number of loads in flight to the very end (it fetches the last
-// step again once it runs out), so one kind of step with one fixed wait covers the whole key
-// range.  Paths outside that step matter more than their share of the arithmetic suggests: a
-// register spilled there is reloaded through the same counter the K/V prefetch uses, and
-// waiting for it drains the prefetch queue.
+// own segment, the ragged end of a span) run the same pipelined step with the mask applied to
+// S^T first, and the loader keeps a constant number of loads in flight to the very end (it
+// fetches the last step again once it runs out), so one kind of step with one fixed wait covers
+// the whole key range; a wave that has passed its last query only keeps loading and meeting at
+// the barriers until the other waves of the workgroup are done.  Paths outside that step matter
+// more than their share of the arithmetic suggests: a register spilled there is reloaded
+// through the same counter the K/V prefetch uses, and waiting for it drains the prefetch queue.
 #include <stdlib.h>
 
 #include <type_traits>
@@ -131,6 +131,11 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   } else {
     const int full1 = (tw0 + 1) / kStepKeys;  // span-1 steps whose keys all precede every query
     f = nst0 + (full1 < nst1 ? full1 : nst1);
+  }
+  int n_act;  // steps at or beyond this one start after the wave's last query: nothing to compute
+  {
+    const int s1 = (tw0 + RW - 1) / kStepKeys + 1;
+    n_act = nst0 + (s1 < nst1 ? s1 : nst1);
   }
 
   // ---- HBM -> LDS.  Load i of a wave covers LDS bytes [(wave*LPW+i)*1024, +1024) of a tensor:
@@ -459,7 +464,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // into Pc, runs the step's sync in the middle and leaves the K operands of step j+2 in Kr.
   // Beyond the last step the operands are those of a step fetched again: finite and unused.
   // MASKED: keys of step j with in-span index >= the lane's limit are invisible (the diagonal
-  // of the query's own segment, the ragged end of a span, steps past the wave's last query).
+  // of the query's own segment, the ragged end of a span).
   // Laid out by hand as 2*NC + 4*NB slots of one matrix product
   // each; whatever else the step has to do is spread over the slots so that it issues in the
   // shadow of the products (about six vector instructions fit under a 32x32x16 MFMA).  The
@@ -608,7 +613,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
   // here and at the top of every iteration below: Sa = S^T(j), Pb = P(j-1), Kr = K operands of j+1
-  while (j < n) {
+  while (j < n_act) {
     // pairs of steps that need no mask while the loader stays inside plain full steps of its span
     while (j + 1 < f && ld_js + 2 < ld_full_end) {
       hot_step(no, yes, j, Kr, Sa, Sb, Pb, Pa);
@@ -617,7 +622,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       advance();
       j += 2;
     }
-    if (j >= n) break;
+    if (j >= n_act) break;
     // any other step (the loader is at a span switch, a ragged step or its last step, or the
     // step needs a mask): the masked step with the loader's general advance; a mask that hides
     // nothing is harmless.  Its results move back into (Sa, Pb) so that the roles stay fixed
@@ -633,8 +638,14 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     }
     ++j;
   }
-  // so_m1 is the slot of step n-1, whose P waits in Pb
+  // so_m1 is the slot of the wave's last step, whose P waits in Pb
   pv(so_m1, Pb);
+  // steps that only other waves of the workgroup need (a workgroup with several 32-row blocks per
+  // head ends on the diagonal of its last block): keep loading and meeting at the barriers
+  for (; j < n; ++j) {
+    sync_step();
+    loader_advance();
+  }
   SEGATTN_VMCNT(0);  // the loader's surplus loads have landed: the ring may be reused
 
   // ---- epilogue: normalise, write LSE, and write O through LDS so that every store
