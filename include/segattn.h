@@ -172,6 +172,17 @@ segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const 
                                 const void *dout, int64_t n, void *dq, void *dk, void *dv,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same backward pass for a packed ragged batch (layout and cu_seqlens as for
+ * seg_attn_fwd_varlen: q, out, dout, dq [total,Hq,D]; k, v, dk, dv [total,Hkv,D]; lse [Hq,total]);
+ * every sequence is differentiated on its own, as one window of consecutive segments.
+ * workspace: device, >= seg_attn_bwd_varlen_workspace_bytes(cfg, total), 256-byte aligned. */
+size_t seg_attn_bwd_varlen_workspace_bytes(const segattn_config *cfg, int64_t total);
+segattn_status seg_attn_bwd_varlen(const segattn_config *cfg, const void *q, const void *k,
+                                   const void *v, const void *out, const float *lse,
+                                   const void *dout, const int32_t *cu_seqlens, int64_t total,
+                                   int64_t max_seqlen, void *dq, void *dk, void *dv,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- cache operations -------------------------------------------------------------------- */
 
 /* Append m rows k,v [B,m,Hkv,D] to the open segment of every sequence.  When that makes the

@@ -252,6 +252,19 @@ def attend_backward(q, k, v, dout, *, seg_len: int, tail_len: int, kv_policy: Se
     return dq, dk, dv
 
 
+def attend_backward_packed(q, k, v, dout, cu_seqlens, **kw):
+    """attend_backward for a packed ragged batch (layout as attend_packed): every sequence is
+    differentiated on its own; nothing flows across a sequence boundary.  q, dout [total,Hq,D];
+    k, v [total,Hkv,D]; returns dQ, dK, dV in the same layouts."""
+    dq, dk, dv = np.zeros(q.shape), np.zeros(k.shape), np.zeros(v.shape)
+    for b in range(len(cu_seqlens) - 1):
+        lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        if hi > lo:
+            gq, gk, gv = attend_backward(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], dout[None, lo:hi], **kw)
+            dq[lo:hi], dk[lo:hi], dv[lo:hi] = gq[0], gk[0], gv[0]
+    return dq, dk, dv
+
+
 def rope_rotate(x, positions, theta: float = 10000.0) -> np.ndarray:
     """Rotary position embedding of x [..., rows, heads, D] at integer `positions` [rows]
     (standard RoPE, which Appendix E reuses): channel pair (i, i + D/2), i < D/2, is turned by

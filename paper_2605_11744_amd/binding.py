@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
             "seg_rope_apply": (ctypes.c_int, [cfgp, vp, vp, i64, vp, vp]),
             "seg_attn_bwd_workspace_bytes": (sz, [cfgp, i64]),
             "seg_attn_bwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]),
+            "seg_attn_bwd_varlen_workspace_bytes": (sz, [cfgp, i64]),
+            "seg_attn_bwd_varlen": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]),
             "seg_kv_commit": (ctypes.c_int, [vp, vp, vp, i32, vp]),
             "seg_kv_past_append": (ctypes.c_int, [vp, i32, vp, vp, i64, vp]),
             "seg_kv_past_select": (ctypes.c_int, [vp, vp, i32, vp]),
@@ -85,7 +87,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
+           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -177,6 +179,17 @@ def seg_attn_bwd_seq(cfg: segattn_config, q, k, v, out, lse, dout, n: int, dq, d
     _check(lib().seg_attn_bwd_seq(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), n,
                                   _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), workspace_bytes, _ptr(stream)),
            "seg_attn_bwd_seq")
+
+
+def seg_attn_bwd_varlen_workspace_bytes(cfg: segattn_config, total: int) -> int:
+    return int(lib().seg_attn_bwd_varlen_workspace_bytes(ctypes.byref(cfg), total))
+
+
+def seg_attn_bwd_varlen(cfg: segattn_config, q, k, v, out, lse, dout, cu_seqlens, total: int, max_seqlen: int,
+                        dq, dk, dv, workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().seg_attn_bwd_varlen(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout),
+                                     _ptr(cu_seqlens), total, max_seqlen, _ptr(dq), _ptr(dk), _ptr(dv),
+                                     _ptr(workspace), workspace_bytes, _ptr(stream)), "seg_attn_bwd_varlen")
 
 
 def seg_kv_commit(ctx: int, k, v, m: int, stream=None) -> None:

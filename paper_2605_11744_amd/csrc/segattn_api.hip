@@ -282,6 +282,43 @@ segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const 
   return hip_status(p.fp32_math ? launch_bwd_fp32(p, a, st) : launch_bwd_mfma(p, a, st));
 }
 
+size_t seg_attn_bwd_varlen_workspace_bytes(const segattn_config *cfg, int64_t total) {
+  Problem p;
+  if (!build_problem(cfg, false, p) || total < 1 || total >= (1ll << 31) - 4096) return 0;
+  return (size_t)align_up((unsigned long long)p.Hq * (unsigned long long)total * 4ull);
+}
+
+segattn_status seg_attn_bwd_varlen(const segattn_config *cfg, const void *q, const void *k, const void *v,
+                                   const void *out, const float *lse, const void *dout,
+                                   const int32_t *cu_seqlens, int64_t total, int64_t max_seqlen, void *dq,
+                                   void *dk, void *dv, void *workspace, size_t workspace_bytes, void *stream) {
+  Problem p;
+  if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace || !cu_seqlens)
+    return SEGATTN_EINVAL;
+  if (max_seqlen < 1 || total < max_seqlen || total >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
+  if (workspace_bytes < seg_attn_bwd_varlen_workspace_bytes(cfg, total) || ((uintptr_t)workspace % kAlign))
+    return SEGATTN_EINVAL;
+  BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.dout = (const unsigned short *)dout;
+  a.out = out;
+  a.lse = lse;
+  a.delta = (float *)workspace;
+  a.dq = dq;
+  a.dk = dk;
+  a.dv = dv;
+  a.n = (int)max_seqlen;
+  a.cu_seqlens = cu_seqlens;
+  a.total = total;
+  const hipStream_t st = (hipStream_t)stream;
+  if (launch_bwd_delta(p, a, st) != hipSuccess) return SEGATTN_EHIP;
+  return hip_status(p.fp32_math ? launch_bwd_fp32(p, a, st) : launch_bwd_mfma(p, a, st));
+}
+
 segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int32_t m, void *stream) {
   if (!ctx || !k || !v || m < 1) return SEGATTN_EINVAL;
   if (!ctx->ready) return SEGATTN_ESTATE;

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p, const P
   const bool row_ok = t <= last_row;
   t = row_ok ? t : last_row;
   const long long qoff = ((seg_row + t) * p.Hq + head) * D;
-  const long long stat = (w.lse - a.lse) + (long long)head * a.n + t;  // index into lse / delta
+  const long long stat = (w.lse - a.lse) + (long long)head * w.lse_head_stride + t;  // index into lse / delta
   const float lse2 = a.lse[stat] * kLog2e, delta = a.delta[stat];
 
   bf16x8 Qr[NC], Gr[NC];  // Q^T and dO^T operands: row `col`, elements 16 kc + 8 hi .. +7
@@ -196,6 +196,8 @@ static hipError_t launch_dq(const Problem &p, const BwdArgs &a, hipStream_t st) 
   pa.lse = const_cast<float *>(a.lse);
   pa.cache = nullptr;
   pa.n_rows = a.n;
+  pa.cu_seqlens = a.cu_seqlens;
+  pa.total_rows = a.total;
   pa.n_seg = (a.n + p.S - 1) / p.S;
   const long long seg_rows = a.n < p.S ? a.n : p.S;
   pa.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);

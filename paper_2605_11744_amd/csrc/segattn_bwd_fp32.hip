@@ -25,9 +25,10 @@ __device__ inline float wave_sum(float x) {
 template <int D>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const Problem p, const BwdArgs a) {
   constexpr int LPR = D / 8;
-  const long long item = ((long long)blockIdx.x * 256 + threadIdx.x) / LPR;  // (b, t, h) flattened
+  const long long item = ((long long)blockIdx.x * 256 + threadIdx.x) / LPR;  // (token row, h) flattened
   const int li = threadIdx.x % LPR;
-  const long long items = (long long)p.B * a.n * p.Hq;
+  const long long tokens = a.cu_seqlens ? a.total : (long long)p.B * a.n;
+  const long long items = tokens * p.Hq;
   float s = 0.f;
   if (item < items) {
     const uint4 g = *(const uint4 *)(a.dout + item * D + li * 8);
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const Problem p, const B
   if (item < items && li == 0) {
     const long long bt = item / p.Hq;
     const int h = (int)(item % p.Hq);
-    const long long b = bt / a.n, t = bt % a.n;
-    a.delta[(b * p.Hq + h) * a.n + t] = s;
+    const SeqSpan sq = seq_span(p, a, seq_of_row(p, a, bt));
+    a.delta[sq.stat0 + h * sq.stat_stride + (bt - sq.row0)] = s;
   }
 }
 
@@ -62,11 +63,13 @@ __global__ __launch_bounds__(256) void bwd_dq_fp32_kernel(const Problem p, const
   constexpr int E = D / 64;
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const long long rows = (long long)p.B * a.n * p.Hq;
+  const long long tokens = a.cu_seqlens ? a.total : (long long)p.B * a.n;
+  const long long rows = tokens * p.Hq;
   if (row >= rows) return;
   const int h = (int)(row % p.Hq);
   const long long bt = row / p.Hq;
-  const long long b = bt / a.n, t = bt % a.n;
+  const SeqSpan sq = seq_span(p, a, seq_of_row(p, a, bt));
+  const long long t = bt - sq.row0;
   const int kv = h / p.g, pol = p.policy[kv];
   const long long s0 = t / p.S * p.S;
   long long lo = s0;
@@ -79,11 +82,11 @@ __global__ __launch_bounds__(256) void bwd_dq_fp32_kernel(const Problem p, const
     gv[e] = bf(a.dout[row * D + lane * E + e]);
     acc[e] = 0.f;
   }
-  const float lse = a.lse[(b * p.Hq + h) * a.n + t];
-  const float delta = a.delta[(b * p.Hq + h) * a.n + t];
+  const float lse = a.lse[sq.stat0 + h * sq.stat_stride + t];
+  const float delta = a.delta[sq.stat0 + h * sq.stat_stride + t];
   for (long long j = lo; j <= t; ++j) {
-    const unsigned short *kr = a.k + ((b * a.n + j) * p.Hkv + kv) * D + lane * E;
-    const unsigned short *vr = a.v + ((b * a.n + j) * p.Hkv + kv) * D + lane * E;
+    const unsigned short *kr = a.k + ((sq.row0 + j) * p.Hkv + kv) * D + lane * E;
+    const unsigned short *vr = a.v + ((sq.row0 + j) * p.Hkv + kv) * D + lane * E;
     float kx[E], sd = 0.f, pd = 0.f;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -113,17 +116,19 @@ __global__ __launch_bounds__(256) void bwd_dkv_fp32_kernel(const Problem p, cons
   constexpr int E = D / 64;
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const long long rows = (long long)p.B * a.n * p.Hkv;
+  const long long tokens = a.cu_seqlens ? a.total : (long long)p.B * a.n;
+  const long long rows = tokens * p.Hkv;
   if (row >= rows) return;
   const int kv = (int)(row % p.Hkv), pol = p.policy[kv];
   const long long bj = row / p.Hkv;
-  const long long b = bj / a.n, j = bj % a.n;
+  const SeqSpan sq = seq_span(p, a, seq_of_row(p, a, bj));
+  const long long j = bj - sq.row0, n_b = sq.n;
   const long long s0 = j / p.S * p.S;
-  const long long seg_end = s0 + p.S < a.n ? s0 + p.S : a.n;
+  const long long seg_end = s0 + p.S < n_b ? s0 + p.S : n_b;
   // queries of the next segment see j through the carried tail
   long long next_end = seg_end;
   if ((pol & SEGATTN_TAIL) && seg_end == s0 + p.S && j >= seg_end - p.T)
-    next_end = seg_end + p.S < a.n ? seg_end + p.S : a.n;
+    next_end = seg_end + p.S < n_b ? seg_end + p.S : n_b;
   float kx[E], vx[E], dk[E], dv[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) {
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_fp32_kernel(const Problem p, cons
   }
   for (int hq = kv * p.g; hq < (kv + 1) * p.g; ++hq) {
     for (long long i = j; i < next_end; ++i) {
-      const long long qrow = ((b * a.n + i) * p.Hq + hq) * D + lane * E;
+      const long long qrow = ((sq.row0 + i) * p.Hq + hq) * D + lane * E;
       float qx[E], gx[E], sd = 0.f, pd = 0.f;
 #pragma unroll
       for (int e = 0; e < E; ++e) {
@@ -144,8 +149,8 @@ __global__ __launch_bounds__(256) void bwd_dkv_fp32_kernel(const Problem p, cons
       }
       sd = wave_sum(sd);
       pd = wave_sum(pd);
-      const float pr = __expf(sd * p.scale - a.lse[(b * p.Hq + hq) * a.n + i]);
-      const float ds = pr * (pd - a.delta[(b * p.Hq + hq) * a.n + i]);
+      const float pr = __expf(sd * p.scale - a.lse[sq.stat0 + hq * sq.stat_stride + i]);
+      const float ds = pr * (pd - a.delta[sq.stat0 + hq * sq.stat_stride + i]);
 #pragma unroll
       for (int e = 0; e < E; ++e) {
         dv[e] = fmaf(pr, gx[e], dv[e]);
@@ -167,7 +172,8 @@ __global__ __launch_bounds__(256) void bwd_dkv_fp32_kernel(const Problem p, cons
 }
 
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st) {
-  const long long threads = (long long)p.B * a.n * p.Hq * (p.D / 8);
+  const long long tokens = a.cu_seqlens ? a.total : (long long)p.B * a.n;
+  const long long threads = tokens * p.Hq * (p.D / 8);
   const dim3 grid((unsigned)((threads + 255) / 256));
   if (p.D == 128) hipLaunchKernelGGL(bwd_delta_kernel<128>, grid, dim3(256), 0, st, p, a);
   else hipLaunchKernelGGL(bwd_delta_kernel<64>, grid, dim3(256), 0, st, p, a);
@@ -175,7 +181,8 @@ hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st) 
 }
 
 hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st) {
-  const long long qrows = (long long)p.B * a.n * p.Hq, krows = (long long)p.B * a.n * p.Hkv;
+  const long long tokens = a.cu_seqlens ? a.total : (long long)p.B * a.n;
+  const long long qrows = tokens * p.Hq, krows = tokens * p.Hkv;
   const dim3 gq((unsigned)((qrows + 3) / 4)), gk((unsigned)((krows + 3) / 4));
   if (p.D == 128) hipLaunchKernelGGL(bwd_dq_fp32_kernel<128>, gq, dim3(256), 0, st, p, a);
   else hipLaunchKernelGGL(bwd_dq_fp32_kernel<64>, gq, dim3(256), 0, st, p, a);

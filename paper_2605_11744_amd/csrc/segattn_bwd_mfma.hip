@@ -55,7 +55,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   const int kv = rest % p.Hkv;
   const int b = rest / p.Hkv;
   const int pol = p.policy[kv];
-  const long long N = a.n;
+  SeqSpan sq = seq_span(p, a, b);  // the same for the whole workgroup: keep it in scalar registers
+  sq.row0 = uniform_i64(sq.row0);
+  sq.n = uniform_i64(sq.n);
+  sq.stat0 = uniform_i64(sq.stat0);
+  sq.stat_stride = uniform_i64(sq.stat_stride);
+  const long long N = sq.n;
   const long long s0 = (long long)seg * p.S;
   const long long seg_end = s0 + p.S < N ? s0 + p.S : N;
   const long long j0 = s0 + (long long)kb * BK;
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   long long jk = jw0 + col;
   const bool key_ok = jk < j_end;
   jk = key_ok ? jk : j_end - 1;
-  const long long koff = ((b * N + jk) * p.Hkv + kv) * D;
+  const long long koff = ((sq.row0 + jk) * p.Hkv + kv) * D;
   // K^T and V^T operands of this lane's key: only ever MFMA operands, so they are parked in
   // accumulation registers and the vector registers stay free for operand prefetch
   bf16x8 Kr[NC], Vr[NC];
@@ -117,8 +122,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   // moves with the cursor plus a 32-bit lane offset fixed for the whole kernel; only the last step
   // of a head can reach past the last query row, and only then are the lane's rows clamped.
   int f_head = 0, f_step = 0;
-  const long long head0_q = ((b * N) * p.Hq + (long long)kv * p.g) * D;   // element offset of (b, row 0, first head)
-  const long long head0_s = ((long long)b * p.Hq + (long long)kv * p.g) * N;
+  const long long head0_q = (sq.row0 * p.Hq + (long long)kv * p.g) * D;   // element offset of (b, row 0, first head)
+  const long long head0_s = sq.stat0 + (long long)kv * p.g * sq.stat_stride;
   const unsigned char *fq0 = (const unsigned char *)(a.q + head0_q + q_begin * q_stride);
   const unsigned char *fg0 = (const unsigned char *)(a.dout + head0_q + q_begin * q_stride);
   const unsigned row_bytes = (unsigned)(q_stride * 2);
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
     if (tid < 2 * kBwdStep) {                                                                         \
       int r_ = r0_ + (tid & 31);                                                                      \
       r_ = r_ < last_rel ? r_ : last_rel;                                                             \
-      ns = f_stat0[(long long)f_head * N + r_];                                                       \
+      ns = f_stat0[(long long)f_head * sq.stat_stride + r_];                                          \
     }                                                                                                 \
     if (!(f_head == p.g - 1 && f_step == steps_per_head - 1)) {                                       \
       f_step += 1;                                                                                    \

@@ -87,8 +87,42 @@ struct BwdArgs {
   const float *lse;                        // [B,Hq,n]
   float *delta;                            // [B,Hq,n] workspace: sum_d dO*O
   void *dq, *dk, *dv;                      // bf16, or fp32 if Problem::out_fp32
-  int n;
+  int n;                                   // rows per sequence (packed batch: of the longest sequence)
+  const int *cu_seqlens;                   // packed ragged batch: device [B+1] row offsets, else nullptr
+  long long total;                         // rows of the packed batch; lse, delta are [Hq,total] then
 };
+
+// Where sequence b of a backward call lives: its first row and length in the token-major tensors,
+// and the index of (head 0, row 0) and the head stride in lse / delta.
+struct SeqSpan {
+  long long row0, n, stat0, stat_stride;
+};
+__device__ inline SeqSpan seq_span(const Problem &p, const BwdArgs &a, int b) {
+  SeqSpan s;
+  if (a.cu_seqlens) {
+    s.row0 = a.cu_seqlens[b];
+    s.n = a.cu_seqlens[b + 1] - s.row0;
+    s.stat0 = s.row0;
+    s.stat_stride = a.total;
+  } else {
+    s.row0 = (long long)b * a.n;
+    s.n = a.n;
+    s.stat0 = (long long)b * p.Hq * a.n;
+    s.stat_stride = a.n;
+  }
+  return s;
+}
+// Sequence of global token row `row` (dense: row / n; packed: binary search in cu_seqlens).
+__device__ inline int seq_of_row(const Problem &p, const BwdArgs &a, long long row) {
+  if (!a.cu_seqlens) return (int)(row / a.n);
+  int lo = 0, hi = p.B - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (a.cu_seqlens[mid] <= row) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
 
 struct SelectArgs {
   const int *idx;        // [B, n_past, R] pool row numbers

@@ -134,6 +134,11 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
 }
 
 __device__ inline int uniform_i32(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ inline long long uniform_i64(long long x) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)x);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)x >> 32));
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
 template <typename T>
 __device__ inline T *uniform_ptr(T *ptr) {
   const unsigned long long u = (unsigned long long)ptr;

@@ -99,3 +99,36 @@ def test_backward_validates_arguments():
     with pytest.raises(sa.SegattnError) as e:
         sa.seg_attn_bwd_seq(cfg, 256, 256, 256, 256, 256, 0, 64, 256, 256, 256, 256, 1 << 20)  # null dout
     assert e.value.status == sa.SEGATTN_EINVAL
+
+
+@pytest.mark.parametrize("fp32_check", [True, False])
+@pytest.mark.parametrize("D,Hq,Hkv,policy", [(128, 8, 2, [1, 3]), (64, 4, 4, [1, 3, 0, 2])])
+def test_packed_ragged_backward_matches_oracle(fp32_check, D, Hq, Hkv, policy):
+    """seg_attn_fwd_varlen then seg_attn_bwd_varlen on sequences of different lengths packed without
+    padding (an empty one, a one-token one, one ending a row past a segment boundary) against the
+    oracle's per-sequence backward."""
+    lens = [300, 1, 0, 257, 128, 77]
+    S, T = 128, 32
+    total = sum(lens)
+    w = W.small("ragged_bwd", index=150, seq_len=total, seg_len=S, tail_len=T, n_q_heads=Hq, n_kv_heads=Hkv,
+                head_dim=D, kv_policy=policy)
+    q, k, v = W.prefill_inputs(w)
+    go = W.grad_inputs(w)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cfg = config_of(w, fp32_check=fp32_check, out_fp32=True, batch=len(lens))
+    qd, kd, vd, gd = dev_bf16(q[0]), dev_bf16(k[0]), dev_bf16(v[0]), dev_bf16(go[0])
+    cud = torch.from_numpy(cu).cuda()
+    out = torch.empty((total, Hq, D), dtype=torch.float32, device="cuda")
+    lse = torch.empty((Hq, total), dtype=torch.float32, device="cuda")
+    dq = torch.full_like(out, float("nan"))
+    dk = torch.full((total, Hkv, D), float("nan"), dtype=torch.float32, device="cuda")
+    dv = torch.full_like(dk, float("nan"))
+    nws = sa.seg_attn_bwd_varlen_workspace_bytes(cfg, total)
+    assert nws >= Hq * total * 4
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    sa.seg_attn_fwd_varlen(cfg, qd, kd, vd, cud, total, max(lens), out, lse, st)
+    sa.seg_attn_bwd_varlen(cfg, qd, kd, vd, out, lse, gd, cud, total, max(lens), dq, dk, dv, ws, nws, st)
+    torch.cuda.synchronize()
+    ref = orc.attend_backward_packed(q[0], k[0], v[0], go[0], cu, seg_len=S, tail_len=T, kv_policy=policy)
+    assert_grad_parity((to_f64(dq), to_f64(dk), to_f64(dv)), ref, fp32_check=fp32_check, what="packed backward")

@@ -60,6 +60,7 @@ MUTANTS = {
     "retrieval_result_unsorted": ("res = np.array(sorted(chosen), dtype=np.int64)", "res = np.array(chosen, dtype=np.int64)"),
     "packed_segment_grid_runs_through_the_pack": ("            o, l = attend(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], **kw)\n            out[lo:hi], lse[:, lo:hi] = o[0], l[0]", "            o, l = attend(q[None, :hi], k[None, :hi], v[None, :hi], **kw)\n            out[lo:hi], lse[:, lo:hi] = o[0, lo:], l[0, :, lo:]"),
     "packed_lse_of_first_head_for_all": ("out[lo:hi], lse[:, lo:hi] = o[0], l[0]", "out[lo:hi], lse[:, lo:hi] = o[0], l[0, :1]"),
+    "packed_backward_runs_through_the_pack": ("            gq, gk, gv = attend_backward(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], dout[None, lo:hi], **kw)\n            dq[lo:hi], dk[lo:hi], dv[lo:hi] = gq[0], gk[0], gv[0]", "            gq, gk, gv = attend_backward(q[None, :hi], k[None, :hi], v[None, :hi], dout[None, :hi], **kw)\n            dq[lo:hi], dk[lo:hi], dv[lo:hi] = gq[0, lo:], gk[0, lo:], gv[0, lo:]"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 

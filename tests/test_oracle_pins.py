@@ -708,3 +708,34 @@ def test_packed_batch_keeps_sequences_apart_and_restarts_the_segment_grid():
             pr = np.exp(sc - sc.max())
             pr /= pr.sum()
             np.testing.assert_allclose(o1[lo + t, h], pr @ v[lo:lo + t + 1, h // 2], rtol=0, atol=1e-12)
+
+
+def test_packed_backward_is_the_gradient_of_the_packed_forward():
+    """attend_backward_packed against central differences of L = sum(attend_packed(...) * dO):
+    the gradient of a packed batch, including that nothing leaks across sequence boundaries
+    (TAIL | SEG policies only: no forward-only rows, so the full gradient is the paper's)."""
+    rng = np.random.default_rng(78)
+    Hq, Hkv, D, S, T = 2, 1, 4, 3, 2
+    kw = dict(seg_len=S, tail_len=T, kv_policy=[1])
+    lens = [5, 0, 2, 7]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    tot = int(cu[-1])
+    q, k, v, g = (rng.standard_normal((tot, h, D)) for h in (Hq, Hkv, Hkv, Hq))
+
+    def loss(q_, k_, v_):
+        o, _ = orc.attend_packed(q_, k_, v_, cu, **kw)
+        return float((o * g).sum())
+
+    dq, dk, dv = orc.attend_backward_packed(q, k, v, g, cu, **kw)
+    eps = 1e-6
+    for name, x, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        for idx in [(0, 0, 1), (4, 0, 3), (5, 0, 0), (6, 0, 2), (7, 0, 1), (13, 0, 0)]:
+            if idx[1] >= x.shape[1]:
+                continue
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps
+            xm[idx] -= eps
+            args_p = {"q": (xp, k, v), "k": (q, xp, v), "v": (q, k, xp)}[name]
+            args_m = {"q": (xm, k, v), "k": (q, xm, v), "v": (q, k, xm)}[name]
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
