@@ -120,8 +120,6 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
   constexpr int NC = D / 16;
   __shared__ float sc[kChunkRows];
   __shared__ __attribute__((aligned(16))) unsigned char stage[4][32 * 2 * D];  // one K tile per wave
-  __shared__ float sm_v[4];
-  __shared__ int sm_i[4];
   const int b = blockIdx.y / p.n_past, np = blockIdx.y % p.n_past;
   const int kv = p.order[np];
   const int *meta = rmeta(a.cache, a.geom, p, b, kv);
@@ -191,30 +189,76 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
     for (int i = 0; i < NL; ++i) cur[i] = nxt[i];
   }
   __syncthreads();
-  // the chunk's best n_anchors rows: every thread owns 16 scores; n_anchors rounds of a
-  // workgroup-wide arg-max, the winner's owner retires it
+  // The chunk's best n_anchors rows, in order.  Every thread owns kChunkRows/256 scores.  Each wave
+  // first finds the best n_anchors of its own quarter (rounds of a wave-wide arg-max by shuffles,
+  // the winner's owner retires it: no workgroup barrier), then the first wave merges the four
+  // sorted lists (lane w < 4 holds the head of list w).
   float mine[kChunkRows / 256];
 #pragma unroll
   for (int e = 0; e < kChunkRows / 256; ++e) mine[e] = sc[tid + 256 * e];
+  __shared__ float wl_v[4][kMaxAnchors];
+  __shared__ int wl_i[4][kMaxAnchors];
   for (int r = 0; r < a.n_anchors; ++r) {
-    float v = -INFINITY;
-    int i = 0x7fffffff;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
 #pragma unroll
     for (int e = 0; e < kChunkRows / 256; ++e)
-      if (better(mine[e], c0 + tid + 256 * e, v, i)) {
-        v = mine[e];
-        i = c0 + tid + 256 * e;
+      if (better(mine[e], c0 + tid + 256 * e, bv, bi)) {
+        bv = mine[e];
+        bi = c0 + tid + 256 * e;
       }
-    block_best(v, i, sm_v, sm_i);
-    if (tid == 0) {
-      cv[r] = v;
-      ci[r] = v == -INFINITY ? 0x7fffffff : i;
+    float v = bv;
+    int i = bi;
+#pragma unroll
+    for (int sh = 32; sh >= 1; sh >>= 1) {
+      const float w = __shfl_xor(v, sh);
+      const int j = __shfl_xor(i, sh);
+      if (better(w, j, v, i)) {
+        v = w;
+        i = j;
+      }
     }
-    const int off = i - c0;
-    if (v != -INFINITY && (off & 255) == tid) {
+    if (lane == 0) {
+      wl_v[wave][r] = v;
+      wl_i[wave][r] = v == -INFINITY ? 0x7fffffff : i;
+    }
+    if (v != -INFINITY && bi == i) {  // this lane owns the winner
+      const int off = i - c0;
 #pragma unroll
       for (int e = 0; e < kChunkRows / 256; ++e)
         if (e == off / 256) mine[e] = -INFINITY;
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {
+    int hp = 0;
+    const bool list = tid < 4 && a.n_anchors > 0;
+    float hv = list ? wl_v[tid][0] : -INFINITY;
+    int hr = list ? wl_i[tid][0] : 0x7fffffff;
+    for (int r = 0; r < a.n_anchors; ++r) {
+      float v = hv;
+      int i = hr;
+#pragma unroll
+      for (int sh = 2; sh >= 1; sh >>= 1) {  // the four heads sit in lanes 0..3
+        const float w = __shfl_xor(v, sh);
+        const int j = __shfl_xor(i, sh);
+        if (better(w, j, v, i)) {
+          v = w;
+          i = j;
+        }
+      }
+      v = __shfl(v, 0);
+      i = __shfl(i, 0);
+      if (tid == 0) {
+        cv[r] = v;
+        ci[r] = v == -INFINITY ? 0x7fffffff : i;
+      }
+      if (list && v != -INFINITY && hr == i) {
+        hp += 1;
+        const bool more = hp < a.n_anchors;
+        hv = more ? wl_v[tid][more ? hp : 0] : -INFINITY;
+        hr = more ? wl_i[tid][more ? hp : 0] : 0x7fffffff;
+      }
     }
   }
 }
@@ -250,41 +294,98 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
       lc_i[c] = a.cand_idx[src];
     }
   __syncthreads();
-  // anchors: n_anchors rounds of arg-max over the candidates (value desc, row asc); a candidate
-  // is retired by remembering the last winner: the order is total, so "strictly after the last
-  // winner" selects the next one without writing anything
-  float last_v = INFINITY;
-  int last_i = -1;
+  // anchors: the n_anchors best candidates (value desc, row asc)
   int n_anch = 0;
-  for (int r = 0; r < a.n_anchors; ++r) {
-    float v = -INFINITY;
-    int i = 0x7fffffff;
-    for (int c = tid; c < n_cand; c += 256) {
-      float w;
-      int j;
-      if (in_lds) {
-        w = lc_v[c];
-        j = lc_i[c];
-      } else {
-        const long long src = base + (long long)(c / a.n_anchors) * kMaxAnchors + c % a.n_anchors;
-        w = a.cand_val[src];
-        j = a.cand_idx[src];
+  constexpr int kHeads = 4;  // chunk lists per lane in the single-wave merge
+  if (in_lds && a.n_chunks <= 64 * kHeads) {
+    // Every chunk's list is already sorted (the score kernel emits its winners in order), so the
+    // global order is a merge of sorted lists: one wave, lane l owns the lists of chunks
+    // l, l+64, ... and keeps their heads in registers; a round takes the best head over the wave
+    // and only the owning lane moves that list on.  No workgroup barrier in the loop.
+    if (tid < 64) {
+      float hv[kHeads];
+      int hr[kHeads], hp[kHeads];
+#pragma unroll
+      for (int k = 0; k < kHeads; ++k) {
+        const int ch = tid + 64 * k;
+        const bool ok = ch < a.n_chunks && a.n_anchors > 0;
+        hp[k] = 0;
+        hv[k] = ok ? lc_v[ch * a.n_anchors] : -INFINITY;
+        hr[k] = ok ? lc_i[ch * a.n_anchors] : 0x7fffffff;
       }
-      if (w == -INFINITY) continue;
-      if (better(w, j, last_v, last_i) || (w == last_v && j == last_i)) continue;  // taken already
-      if (better(w, j, v, i)) {
-        v = w;
-        i = j;
+      for (int r = 0; r < a.n_anchors; ++r) {
+        float bv = hv[0];
+        int bi = hr[0], bk = 0;
+#pragma unroll
+        for (int k = 1; k < kHeads; ++k)
+          if (better(hv[k], hr[k], bv, bi)) {
+            bv = hv[k];
+            bi = hr[k];
+            bk = k;
+          }
+        float v = bv;
+        int i = bi;
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) {
+          const float w = __shfl_xor(v, sh);
+          const int j = __shfl_xor(i, sh);
+          if (better(w, j, v, i)) {
+            v = w;
+            i = j;
+          }
+        }
+        if (v == -INFINITY) break;
+        if (tid == 0) anchors[r] = i;
+        n_anch = r + 1;
+        if (bv == v && bi == i) {  // rows are unique over the chunks: exactly one lane owns the winner
+#pragma unroll
+          for (int k = 0; k < kHeads; ++k)
+            if (k == bk) {
+              hp[k] += 1;
+              const int src = (tid + 64 * k) * a.n_anchors + hp[k];
+              const bool more = hp[k] < a.n_anchors;
+              hv[k] = more ? lc_v[more ? src : 0] : -INFINITY;
+              hr[k] = more ? lc_i[more ? src : 0] : 0x7fffffff;
+            }
+        }
       }
     }
-    block_best(v, i, sm_v, sm_i);
-    if (v == -INFINITY) break;
-    if (tid == 0) anchors[r] = i;
-    last_v = v;
-    last_i = i;
-    n_anch = r + 1;
+  } else {
+    // many chunks: n_anchors rounds of a workgroup-wide arg-max over all candidates; a candidate
+    // is retired by remembering the last winner: the order is total, so "strictly after the last
+    // winner" selects the next one without writing anything
+    float last_v = INFINITY;
+    int last_i = -1;
+    for (int r = 0; r < a.n_anchors; ++r) {
+      float v = -INFINITY;
+      int i = 0x7fffffff;
+      for (int c = tid; c < n_cand; c += 256) {
+        float w;
+        int j;
+        if (in_lds) {
+          w = lc_v[c];
+          j = lc_i[c];
+        } else {
+          const long long src = base + (long long)(c / a.n_anchors) * kMaxAnchors + c % a.n_anchors;
+          w = a.cand_val[src];
+          j = a.cand_idx[src];
+        }
+        if (w == -INFINITY) continue;
+        if (better(w, j, last_v, last_i) || (w == last_v && j == last_i)) continue;  // taken already
+        if (better(w, j, v, i)) {
+          v = w;
+          i = j;
+        }
+      }
+      block_best(v, i, sm_v, sm_i);
+      if (v == -INFINITY) break;
+      if (tid == 0) anchors[r] = i;
+      last_v = v;
+      last_i = i;
+      n_anch = r + 1;
+    }
   }
-  __syncthreads();
+  __syncthreads();  // anchors[] is complete (the first wave uses it below)
   const int visible = pool - lo;
   const int want = a.R < visible ? a.R : visible;
   if (tid < 64) {
