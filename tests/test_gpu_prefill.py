@@ -89,3 +89,38 @@ def test_packed_ragged_batch_matches_per_sequence_oracle(fp32_check, waves):
         if n:
             G.assert_parity(o_gpu[lo:hi], l_gpu[:, lo:hi], o_ref[lo:hi], l_ref[:, lo:hi], fp32_check=fp32_check,
                             what=f"ragged sequence {b} (n={n})")
+
+
+def test_packed_batch_of_one_equals_the_dense_call_and_max_seqlen_only_sizes_the_launch():
+    """A pack that holds a single sequence is the dense problem: same kernel, same order of
+    operations, so the results are bit-identical; max_seqlen only sizes the launch, so a value
+    above the longest sequence (up to the total) changes nothing."""
+    import gpu_util as G
+    w = W.small("one", index=141, seq_len=700, seg_len=256, tail_len=64, n_q_heads=8, n_kv_heads=2, head_dim=128)
+    q, k, v = W.prefill_inputs(w)
+    cfg = G.config_of(w, out_fp32=True, batch=1)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    st = torch.cuda.current_stream().cuda_stream
+    o1 = torch.empty((1, 700, 8, 128), dtype=torch.float32, device="cuda")
+    l1 = torch.empty((1, 8, 700), dtype=torch.float32, device="cuda")
+    G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, 700, o1, l1, st)
+    cu = torch.tensor([0, 700], dtype=torch.int32, device="cuda")
+    o2 = torch.full((700, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    l2 = torch.full((8, 700), float("nan"), dtype=torch.float32, device="cuda")
+    G.sa.seg_attn_fwd_varlen(cfg, qd[0], kd[0], vd[0], cu, 700, 700, o2, l2, st)
+    torch.cuda.synchronize()
+    assert torch.equal(o1[0], o2) and torch.equal(l1[0], l2)
+    # two sequences: the launch sized by the longest (400) or by more than that (700)
+    cfg2 = G.config_of(w, out_fp32=True, batch=2)
+    cu2 = torch.tensor([0, 300, 700], dtype=torch.int32, device="cuda")
+    res = []
+    for max_len in (400, 700):
+        o3 = torch.full((700, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+        l3 = torch.full((8, 700), float("nan"), dtype=torch.float32, device="cuda")
+        G.sa.seg_attn_fwd_varlen(cfg2, qd[0], kd[0], vd[0], cu2, 700, max_len, o3, l3, st)
+        torch.cuda.synchronize()
+        res.append((o3, l3))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    assert bool(torch.isfinite(res[0][0]).all())
+    with pytest.raises(G.sa.SegattnError):
+        G.sa.seg_attn_fwd_varlen(cfg, qd[0], kd[0], vd[0], cu, 700, 701, o2, l2, st)   # max_seqlen > total
