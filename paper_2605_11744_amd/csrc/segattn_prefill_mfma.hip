@@ -23,8 +23,10 @@
 // the common path has no accumulator rescale and exp2 never overflows.
 //
 // K/V rows travel HBM -> LDS with global_load_lds_dwordx4 (no staging registers) into a ring
-// of 5 step slots, three steps ahead of their use; the 16-byte chunks of a row are XOR-
-// swizzled by the loading lanes so that both the row-wise K reads and the transposing V reads
+// of step slots, three or more steps ahead of their use (eight-wave workgroups: 8 slots, the
+// waves meet at a barrier only every other step and fetch two steps there; otherwise 5 slots and
+// a barrier per step); the 16-byte chunks of a row are XOR-swizzled by the loading lanes so that
+// both the row-wise K reads and the transposing V reads
 // are free of bank conflicts.  Steps that need an element mask (the diagonal of the query's
 // own segment, the ragged end of a span) run the same pipelined step with the mask applied to
 // S^T first, and the loader keeps a constant number of loads in flight to the very end (it
@@ -54,11 +56,18 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 #define GLB_AS __attribute__((address_space(1)))
 
 constexpr int kStepKeys = 32;
-#ifndef SEGATTN_PREFILL_SLOTS
-#define SEGATTN_PREFILL_SLOTS 5
+// LDS ring of step slots.  Per-step sync: steps j-1 .. j+3 are resident or in flight (5 slots, one
+// step of loads may still be in flight at a sync).  Pair sync (eight-wave workgroups): the waves
+// meet only at every other step and fetch two steps there; steps j-1 .. j+6 (8 slots, two steps in
+// flight at a sync).
+__host__ __device__ constexpr bool pair_sync(int nw, int qb) {
+#ifdef SEGATTN_PREFILL_STEP_SYNC
+  return false;
+#else
+  return nw == 8 && qb == 1;
 #endif
-constexpr int kSlots = SEGATTN_PREFILL_SLOTS;                 // LDS ring: steps j-1 .. j+kSlots-2 are resident or in flight
-constexpr int kAhead = kSlots - 4;        // whole steps of loads that may still be in flight at a sync
+}
+__host__ __device__ constexpr int ring_slots(int nw, int qb) { return pair_sync(nw, qb) ? 8 : 5; }
 constexpr float kLazyLimit = 256.f;  // a lane's 16-weight row sum above this triggers a rescale
 
 template <int D>
@@ -104,6 +113,9 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   constexpr int NC = D / 16;        // k-chunks of the QK^T product
   constexpr int NB = D / 32;        // 32-row blocks of O^T
   constexpr int LPW = G::kInstr / NW;  // wave-wide 1 KB loads per tensor, step and wave
+  constexpr bool kPair = pair_sync(NW, QB);
+  constexpr int kSlots = ring_slots(NW, QB);
+  constexpr int kAhead = kPair ? 2 : 1;  // whole steps of loads that may still be in flight at a sync
   static_assert(LPW >= 1, "too many waves for this tile");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -219,18 +231,25 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     }
   };
   // s_waitcnt vmcnt: at most kAhead whole steps of this wave's loads stay in flight
-  static_assert(kAhead >= 1 && kAhead * 2 * LPW < 64, "vmcnt is a 6-bit counter");
+  static_assert(kAhead * 2 * LPW < 64, "vmcnt is a 6-bit counter");
 #define SEGATTN_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
-  // Executed once per step j by every wave (in the prologue for j = 0, in the middle of step j
-  // otherwise): the loads of steps <= j+2 have landed for every wave and every wave is done
-  // reading the slot of step j-1, which now receives the loads of step j+kSlots-1.
+  // The sync of step j, executed by every wave in the middle of the step (in the prologue for
+  // j = 0).  Per-step form: the loads of steps <= j+2 have landed for every wave and every wave is
+  // done reading the slot of step j-1, which now receives the loads of step j+4.  Pair form: only
+  // even steps sync; the loads of steps <= j+3 have landed (the odd step that follows needs j+2
+  // and j+3 and meets nobody) and the slots of steps j-2 and j-1 receive steps j+6 and j+7.
+  // The loader is left at the last step fetched; the caller moves it on once more.
   auto sync_step = [&]() __attribute__((always_inline)) {
     SEGATTN_VMCNT(kAhead * 2 * LPW);
     __builtin_amdgcn_s_barrier();
     issue_loads();
+    if constexpr (kPair) {
+      loader_advance();
+      issue_loads();
+    }
   };
 
-  for (int i = 0; i < kSlots - 1; ++i) {
+  for (int i = 0; i < (kPair ? kSlots - 2 : kSlots - 1); ++i) {
     issue_loads();
     loader_advance();
   }
@@ -459,6 +478,16 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
         if (8 * (r >> 2) + (r & 3) >= lim) S[qb][r] = -INFINITY;
     }
   };
+  auto sync_step_hot = [&](auto plain) __attribute__((always_inline)) {
+    SEGATTN_VMCNT(kAhead * 2 * LPW);
+    __builtin_amdgcn_s_barrier();
+    issue_loads();
+    if constexpr (kPair) {
+      if constexpr (decltype(plain)::value) loader_advance_plain();
+      else loader_advance();
+      issue_loads();
+    }
+  };
   // One pipelined step j >= 1.  On entry Kr holds the K operands of step j+1, Sc is S^T of step
   // j and Pp is P of step j-1.  The step forms S^T(j+1) -> Sn, adds PV of step j-1, turns Sc
   // into Pc, runs the step's sync in the middle and leaves the K operands of step j+2 in Kr.
@@ -475,7 +504,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   //   (sync, then the K reads of step j+2, two per slot)
   //   slots .. end            PV(j-1), last 16 keys
   //   odd slots               convert pair i to bf16 and add it to the row sum
-  auto hot_step = [&](auto masked, auto plain, int j, i32x4(&Kr)[NC], float(&Sc)[QB][16], float(&Sn)[QB][16],
+  auto hot_step = [&](auto masked, auto plain, auto syncs, int j, i32x4(&Kr)[NC], float(&Sc)[QB][16], float(&Sn)[QB][16],
                       const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) __attribute__((always_inline)) {
     if constexpr (decltype(masked)::value) mask_step(Sc, j);
     constexpr int NS = QB * NC, NP = QB * NB;  // slots of the S^T product / of half a PV product
@@ -550,7 +579,11 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       // ---- after the S^T slots: V^T has arrived; sync; then the K reads of step j+2, one per slot
       if (slot == NS - 1) {
         v_wait(Vr);
-        sync_step();
+        if constexpr (std::is_same<decltype(syncs), bool>::value) {
+          if (syncs) sync_step_hot(plain);  // decided at run time (uniform): the general step
+        } else if constexpr (decltype(syncs)::value) {
+          sync_step_hot(plain);
+        }
       }
       if (slot >= NS && slot < NS + NC) {
         const int kc = slot - NS;
@@ -576,8 +609,12 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     s_fetch(Sacc, Sn);
     k_wait(Kr);
     settle(Sc, Pc, psum);
-    if constexpr (decltype(plain)::value) loader_advance_plain();
-    else loader_advance();
+    if constexpr (std::is_same<decltype(syncs), bool>::value) {
+      if (syncs) loader_advance();
+    } else if constexpr (decltype(syncs)::value) {
+      if constexpr (decltype(plain)::value) loader_advance_plain();
+      else loader_advance();
+    }
   };
   // =========================== main sequence ===========================
   sync_step();
@@ -615,19 +652,24 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // here and at the top of every iteration below: Sa = S^T(j), Pb = P(j-1), Kr = K operands of j+1
   while (j < n_act) {
     // pairs of steps that need no mask while the loader stays inside plain full steps of its span
-    while (j + 1 < f && ld_js + 2 < ld_full_end) {
-      hot_step(no, yes, j, Kr, Sa, Sb, Pb, Pa);
-      advance();
-      hot_step(no, yes, j + 1, Kr, Sb, Sa, Pa, Pb);
-      advance();
-      j += 2;
+    // (with the pair sync a pair is an odd step, which meets nobody, and the even step after it)
+    if (!kPair || (j & 1)) {
+      while (j + 1 < f && ld_js + 2 < ld_full_end) {
+        if constexpr (kPair) hot_step(no, yes, no, j, Kr, Sa, Sb, Pb, Pa);
+        else hot_step(no, yes, yes, j, Kr, Sa, Sb, Pb, Pa);
+        advance();
+        hot_step(no, yes, yes, j + 1, Kr, Sb, Sa, Pa, Pb);
+        advance();
+        j += 2;
+      }
+      if (j >= n_act) break;
     }
-    if (j >= n_act) break;
     // any other step (the loader is at a span switch, a ragged step or its last step, or the
     // step needs a mask): the masked step with the loader's general advance; a mask that hides
     // nothing is harmless.  Its results move back into (Sa, Pb) so that the roles stay fixed
     // (choosing between the two register sets at run time would put them in memory).
-    hot_step(yes, no, j, Kr, Sa, Sb, Pb, Pa);
+    if constexpr (kPair) hot_step(yes, no, !(j & 1), j, Kr, Sa, Sb, Pb, Pa);
+    else hot_step(yes, no, yes, j, Kr, Sa, Sb, Pb, Pa);
     advance();
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -643,8 +685,10 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // steps that only other waves of the workgroup need (a workgroup with several 32-row blocks per
   // head ends on the diagonal of its last block): keep loading and meeting at the barriers
   for (; j < n; ++j) {
-    sync_step();
-    loader_advance();
+    if (!kPair || !(j & 1)) {
+      sync_step();
+      loader_advance();
+    }
   }
   SEGATTN_VMCNT(0);  // the loader's surplus loads have landed: the ring may be reused
 
@@ -704,7 +748,7 @@ static int heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2
 
 template <int D, int HS, int QB, int NW>
 static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a, long long grid, hipStream_t st) {
-  constexpr int ring = kSlots * StepGeom<D>::kSlotBytes;
+  constexpr int ring = ring_slots(NW, QB) * StepGeom<D>::kSlotBytes;
   constexpr int epilogue = NW * 32 * (D * 4 + 8);  // fp32 output staging, one block per wave
   constexpr int lds = ring > epilogue ? ring : epilogue;
   auto kern = prefill_mfma_kernel<D, HS, QB, NW>;
