@@ -545,6 +545,10 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
           psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][w8]), ones, psum[qb], false);
       }
     };
+    // transposing V^T reads per slot: one more than an even spread needs, so that the last reads
+    // have two product slots to land before the wait in front of the sync (measured: +1.7 %;
+    // denser bursts lose)
+    constexpr int VPS = (4 * NB + NS - 1) / NS + 1;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int slot = 0; slot < NSLOT; ++slot) {
@@ -561,7 +565,6 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       // ---- V^T reads (h2-major), spread over the S^T slots so that the four waves of the
       //      workgroup, which run in lockstep, do not all hit the LDS in one burst
       {
-        constexpr int VPS = (4 * NB + NS - 1) / NS;  // transposing reads per slot
 #pragma unroll
         for (int u = 0; u < VPS; ++u) {
           const int idx = VPS * slot + u;  // 0 .. 4 NB - 1: (h2, nb, half)
@@ -577,7 +580,8 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
         }
       }
       // ---- after the S^T slots: V^T has arrived; sync; then the K reads of step j+2, one per slot
-      if (slot == NS - 1) {
+      constexpr int kSyncSlot = NS - 1;
+      if (slot == kSyncSlot) {
         v_wait(Vr);
         if constexpr (std::is_same<decltype(syncs), bool>::value) {
           if (syncs) sync_step_hot(plain);  // decided at run time (uniform): the general step
@@ -585,8 +589,8 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
           sync_step_hot(plain);
         }
       }
-      if (slot >= NS && slot < NS + NC) {
-        const int kc = slot - NS;
+      if (slot > kSyncSlot && slot - kSyncSlot - 1 < NC) {
+        const int kc = slot - kSyncSlot - 1;
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
       }
       valu_chunk(slot);
@@ -607,6 +611,9 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
         Pc[qb][h2] = __builtin_bit_cast(bf16x8, w4);
       }
     s_fetch(Sacc, Sn);
+    // (All K reads are waited for here, not one by one in front of their products in the next
+    // step: until the wait the compiler believes the registers already hold the data, and any
+    // move it placed in between -- a spill, a copy at the loop edge -- would carry stale values.)
     k_wait(Kr);
     settle(Sc, Pc, psum);
     if constexpr (std::is_same<decltype(syncs), bool>::value) {
