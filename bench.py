@@ -6,8 +6,8 @@ A step is one pass of the whole hot path over one synthetic 128K-token prompt (B
 
   1. seg_attn_fwd_seq   one launch over all 32 segments (range resolution, work ordering, MFMA
                         QK^T / online softmax / PV, epilogue with LSE);
-  2. seg_kv_commit      once per segment: tail hand-off and past-pool append, leaving the cache
-                        exactly as segment-by-segment execution would;
+  2. seg_kv_commit_seq  the whole prompt's tail hand-off and past-pool append in one call, leaving
+                        the cache exactly as segment-by-segment execution would;
   3. seg_kv_past_evict  (bookkeeping only; evicts 0 rows) and
   4. seg_attn_decode    one token on top of the 128K context (split-K + combine).
 
@@ -93,9 +93,6 @@ def main() -> int:
     def dev(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
 
-    def dense(t):  # a row slice of a B=1 tensor is already dense; copy otherwise
-        return t if t.is_contiguous() else t.contiguous()
-
     qb, kb, vb = W.prefill_inputs(w)
     q, k, v = dev(qb), dev(kb), dev(vb)
     out = torch.empty((w.batch, N, Hq, D), dtype=torch.bfloat16, device="cuda")
@@ -111,7 +108,6 @@ def main() -> int:
     v1 = torch.randn((w.batch, Hkv, D), device="cuda").to(torch.bfloat16)
     o1 = torch.empty((w.batch, Hq, D), dtype=torch.bfloat16, device="cuda")
     l1 = torch.empty((w.batch, Hq), dtype=torch.float32, device="cuda")
-    n_seg = (N + S - 1) // S
     ev_k0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     ev_k1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
 
@@ -122,9 +118,7 @@ def main() -> int:
         sa.seg_attn_fwd_seq(cfg, q, k, v, N, out, lse, stream)
         if i is not None:
             ev_k1[i].record()
-        for s in range(n_seg):
-            m = min(S, N - s * S)
-            sa.seg_kv_commit(ctx, dense(k[:, s * S:s * S + m]), dense(v[:, s * S:s * S + m]), m, stream)
+        sa.seg_kv_commit_seq(ctx, k, v, N, stream)
         for h in past_heads[:1]:
             sa.seg_kv_past_evict(ctx, h, 0, stream)
         sa.seg_attn_decode(ctx, q1, k1, v1, o1, l1, stream)
@@ -159,7 +153,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "seq_len": N, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "seg_len": S, "tail_len": T, "kv_policy": list(w.kv_policy),
-                   "step": "fwd_seq + commit x%d + evict + decode x1" % n_seg},
+                   "step": "fwd_seq + commit_seq + evict + decode x1"},
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),

@@ -193,6 +193,15 @@ segattn_status seg_attn_bwd_varlen(const segattn_config *cfg, const void *q, con
 segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int32_t m,
                              void *stream);
 
+/* The same for a whole prompt handed over at once: k,v [B,n,Hkv,D], every sequence's open segment
+ * empty (ESTATE otherwise).  Leaves exactly the state that n/S calls of seg_kv_commit with S rows
+ * and one with the remaining n%S rows would leave (pools of the PAST heads grown by the whole
+ * segments, the tail of the last whole segment, the open rows), in two launches.  It is the
+ * companion of seg_attn_fwd_seq: prefill in one launch, commit in one call, then decode.
+ * ECAPACITY if a pool cannot take n more rows. */
+segattn_status seg_kv_commit_seq(segattn_ctx *ctx, const void *k, const void *v, int64_t n,
+                                 void *stream);
+
 /* Append `rows` explicit rows k,v [B,rows,D] (e.g. rows gathered by a retrieval step,
  * Appendix D "Output") to the past pool of one PAST head, for every sequence.  Only valid
  * between segments (no open segment: ESTATE otherwise); EINVAL if the head is not PAST. */

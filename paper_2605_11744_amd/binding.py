@@ -64,6 +64,7 @@ def lib() -> ctypes.CDLL:
             "seg_attn_bwd_varlen_workspace_bytes": (sz, [cfgp, i64]),
             "seg_attn_bwd_varlen": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]),
             "seg_kv_commit": (ctypes.c_int, [vp, vp, vp, i32, vp]),
+            "seg_kv_commit_seq": (ctypes.c_int, [vp, vp, vp, i64, vp]),
             "seg_kv_past_append": (ctypes.c_int, [vp, i32, vp, vp, i64, vp]),
             "seg_kv_past_select": (ctypes.c_int, [vp, vp, i32, vp]),
             "seg_kv_past_evict": (ctypes.c_int, [vp, i32, i64, vp]),
@@ -87,7 +88,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
+           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -194,6 +195,10 @@ def seg_attn_bwd_varlen(cfg: segattn_config, q, k, v, out, lse, dout, cu_seqlens
 
 def seg_kv_commit(ctx: int, k, v, m: int, stream=None) -> None:
     _check(lib().seg_kv_commit(ctx, _ptr(k), _ptr(v), m, _ptr(stream)), "seg_kv_commit")
+
+
+def seg_kv_commit_seq(ctx: int, k, v, n: int, stream=None) -> None:
+    _check(lib().seg_kv_commit_seq(ctx, _ptr(k), _ptr(v), n, _ptr(stream)), "seg_kv_commit_seq")
 
 
 def seg_kv_past_append(ctx: int, kv_head: int, k, v, rows: int, stream=None) -> None:

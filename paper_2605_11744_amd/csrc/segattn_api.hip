@@ -357,6 +357,38 @@ segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int
   return SEGATTN_OK;
 }
 
+segattn_status seg_kv_commit_seq(segattn_ctx *ctx, const void *k, const void *v, int64_t n, void *stream) {
+  if (!ctx || !k || !v || n < 1 || n >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
+  if (!ctx->ready) return SEGATTN_ESTATE;
+  const Problem &p = ctx->p;
+  for (int b = 0; b < p.B; ++b) {
+    if (ctx->fill[b] != 0) return SEGATTN_ESTATE;
+    for (int h = 0; h < p.Hkv; ++h)
+      if ((p.policy[h] & SEGATTN_PAST) && ctx->pool[(size_t)b * p.Hkv + h] + n > (long long)ctx->g.pool_cap)
+        return SEGATTN_ECAPACITY;
+  }
+  CopyArgs a;
+  memset(&a, 0, sizeof(a));
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.cache = ctx->cache;
+  a.geom = ctx->g;
+  a.m = (int)n;
+  if (launch_cache_commit_seq(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  const long long n_full = n / p.S;
+  for (int b = 0; b < p.B; ++b) {
+    ctx->fill[b] = (int)(n % p.S);
+    if (n_full > 0) {
+      ctx->tail[b] = p.T;
+      ctx->ret[b] = 0;
+      ctx->closed[b] += n_full * p.S;
+      for (int h = 0; h < p.Hkv; ++h)
+        if (p.policy[h] & SEGATTN_PAST) ctx->pool[(size_t)b * p.Hkv + h] += n_full * p.S;
+    }
+  }
+  return SEGATTN_OK;
+}
+
 segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void *k, const void *v,
                                   int64_t rows, void *stream) {
   if (!ctx || !k || !v || rows < 1 || kv_head < 0 || kv_head >= ctx->p.Hkv) return SEGATTN_EINVAL;

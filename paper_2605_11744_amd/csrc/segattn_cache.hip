@@ -127,6 +127,74 @@ __global__ __launch_bounds__(256) void cache_close_kernel(const Problem p, unsig
   }
 }
 
+// Whole prompt at once: rows k,v [B,n,Hkv,D] of a sequence whose open segment is empty -> the state
+// n/S commits of S rows and one of n%S rows would leave.  PAST heads: every row goes to the pool
+// (whole segments, then the open one behind them).  Other heads: the last T rows of the last whole
+// segment become the tail, the n%S open rows follow it.  The open rows are mirrored into the
+// attention view in retrieval mode.  grid = (row chunks, B*Hkv); counters: cache_commit_seq_meta.
+template <int D>
+__global__ __launch_bounds__(256) void cache_commit_seq_kernel(const Problem p, const CopyArgs a) {
+  constexpr int CPR = D / 8;
+  const int b = blockIdx.y / p.Hkv, h = blockIdx.y % p.Hkv;
+  const int *meta = meta_of(a.cache, a.geom, p, b, h);
+  const bool past = p.policy[h] & SEGATTN_PAST;
+  const int n = a.m, n_full = n / p.S, open = n % p.S, closed_rows = n_full * p.S;
+  const int tail_rows = (!past && n_full > 0) ? p.T : 0;
+  // virtual rows of this head: [0, head_rows): PAST: source rows 0..n-1 -> pool + r;
+  // otherwise: tail rows (source closed_rows - T + r -> r), then open rows (source closed_rows + r' -> T + r')
+  const int head_rows = past ? n : tail_rows + open;
+  const int pool = meta[META_POOL];
+  const uint4 *ks = (const uint4 *)(a.k + ((long long)b * n * p.Hkv + h) * D);
+  const uint4 *vs = (const uint4 *)(a.v + ((long long)b * n * p.Hkv + h) * D);
+  uint4 *kd = (uint4 *)(a.cache + k_block_off(p, a.geom, b, h));
+  uint4 *vd = (uint4 *)(a.cache + v_block_off(p, a.geom, b, h));
+  uint4 *km = nullptr, *vm = nullptr;
+  if (uses_view(p, a.geom, h)) {
+    km = (uint4 *)(a.cache + view_k_off(p, a.geom, b, h)) + (long long)a.geom.ret_cap * CPR;
+    vm = (uint4 *)(a.cache + view_v_off(p, a.geom, b, h)) + (long long)a.geom.ret_cap * CPR;
+  }
+  const long long src_stride = (long long)p.Hkv * CPR;
+  const int rows_per_block = 256 / CPR * 8;
+  const int r_begin = blockIdx.x * rows_per_block;
+  const int r_end = min(head_rows, r_begin + rows_per_block);
+  const int c = threadIdx.x % CPR;
+  for (int r = r_begin + threadIdx.x / CPR; r < r_end; r += 256 / CPR) {
+    int src, dst;
+    if (past) {
+      src = r;
+      dst = pool + r;
+    } else if (r < tail_rows) {
+      src = closed_rows - p.T + r;
+      dst = r;
+    } else {
+      src = closed_rows + (r - tail_rows);
+      dst = p.T + (r - tail_rows);
+    }
+    const uint4 kx = ks[(long long)src * src_stride + c];
+    const uint4 vx = vs[(long long)src * src_stride + c];
+    kd[(long long)dst * CPR + c] = kx;
+    vd[(long long)dst * CPR + c] = vx;
+    if (km && src >= closed_rows) {
+      km[(long long)(src - closed_rows) * CPR + c] = kx;
+      vm[(long long)(src - closed_rows) * CPR + c] = vx;
+    }
+  }
+}
+
+__global__ void cache_commit_seq_meta(const Problem p, unsigned char *cache, const CacheGeom g, const int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= p.B * p.Hkv) return;
+  const int b = i / p.Hkv, h = i % p.Hkv;
+  int *meta = meta_of(cache, g, p, b, h);
+  const int n_full = n / p.S;
+  if (n_full > 0) {
+    if (p.policy[h] & SEGATTN_PAST) meta[META_POOL] += n_full * p.S;
+    meta[META_TAIL] = p.T;
+    meta[META_RET] = 0;
+  }
+  meta[META_FILL] = n % p.S;
+}
+
 // One new row k,v [B,Hkv,D] per sequence -> open segment; fill += 1.  One wave per (b,h).
 template <int D>
 __global__ __launch_bounds__(64) void cache_decode_append_kernel(const Problem p, const CopyArgs a) {
@@ -244,6 +312,22 @@ hipError_t launch_cache_append(const Problem &p, const CopyArgs &a, hipStream_t 
   const dim3 grid((a.m + rows_per_block - 1) / rows_per_block, p.B * p.Hkv);
   if (p.D == 128) hipLaunchKernelGGL(cache_append_kernel<128>, grid, dim3(256), 0, st, p, a);
   else hipLaunchKernelGGL(cache_append_kernel<64>, grid, dim3(256), 0, st, p, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_commit_seq(const Problem &p, const CopyArgs &a, hipStream_t st) {
+  const int cpr = p.D / 8, rows_per_block = 256 / cpr * 8;
+  const int n = a.m, open = n % p.S;
+  int max_rows = p.T + open;  // rows written for a non-PAST head
+  if (p.n_past > 0 && n > max_rows) max_rows = n;
+  if (max_rows > 0) {
+    const dim3 grid((unsigned)((max_rows + rows_per_block - 1) / rows_per_block), (unsigned)(p.B * p.Hkv));
+    if (p.D == 128) hipLaunchKernelGGL(cache_commit_seq_kernel<128>, grid, dim3(256), 0, st, p, a);
+    else hipLaunchKernelGGL(cache_commit_seq_kernel<64>, grid, dim3(256), 0, st, p, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(cache_commit_seq_meta, dim3((p.B * p.Hkv + 63) / 64), dim3(64), 0, st, p, a.cache, a.geom, n);
   return hipGetLastError();
 }
 

@@ -211,6 +211,7 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st
 hipError_t launch_decode(const Problem &p, const DecodeArgs &a, int B, hipStream_t st);
 hipError_t launch_cache_reset(const Problem &p, unsigned char *cache, const CacheGeom &g, hipStream_t st);
 hipError_t launch_cache_append(const Problem &p, const CopyArgs &a, hipStream_t st);
+hipError_t launch_cache_commit_seq(const Problem &p, const CopyArgs &a, hipStream_t st);
 hipError_t launch_cache_close(const Problem &p, unsigned char *cache, const CacheGeom &g, int add,
                               hipStream_t st);
 hipError_t launch_cache_decode_append(const Problem &p, const CopyArgs &a, hipStream_t st);

@@ -209,3 +209,69 @@ def test_past_append_explicit_rows_act_as_prefix():
         G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="past_append")
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("n,retrieved", [(300, 0), (256, 0), (50, 0), (641, 0), (300, 48), (384, 48)])
+def test_whole_prompt_commit_leaves_the_state_of_per_segment_commits(n, retrieved):
+    """seg_kv_commit_seq against a chain of seg_kv_commit calls: same counters, and the same decode
+    step and next prefill chunk afterwards (bit for bit: both read the same rows), also on top of
+    an earlier segment and in retrieval mode; and the decode row against the oracle."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    S, T, first = 128, 40, 128
+    policy = [2, 1, 0, 2] if retrieved else [3, 1, 0, 2]
+    w = W.small("bulk", index=260, seq_len=first + n + 25, seg_len=S, tail_len=T, n_q_heads=8, n_kv_heads=4,
+                head_dim=128, kv_policy=policy, batch=2)
+    q, k, v = W.prefill_inputs(w)
+    caches = [G.Cache(w, past_capacity=1024, retrieved_capacity=retrieved) for _ in range(2)]
+    try:
+        outs = []
+        for which, c in enumerate(caches):
+            kd, vd = G.dev_bf16(k), G.dev_bf16(v)
+            sa.seg_kv_commit(c.ctx, kd[:, :first].contiguous(), vd[:, :first].contiguous(), first, c.stream)
+            if which == 0:
+                sa.seg_kv_commit_seq(c.ctx, kd[:, first:first + n].contiguous(), vd[:, first:first + n].contiguous(), n, c.stream)
+            else:
+                pos = first
+                while pos < first + n:
+                    m = min(S - (pos - first) % S, first + n - pos)
+                    sa.seg_kv_commit(c.ctx, kd[:, pos:pos + m].contiguous(), vd[:, pos:pos + m].contiguous(), m, c.stream)
+                    pos += m
+            lengths = sa.seg_kv_lengths(c.ctx, 2, 4)
+            if retrieved and n % S == 0:   # a selection needs a segment boundary; a close drops the last one
+                idx = np.tile(np.arange(retrieved, dtype=np.int32)[None, None], (2, 2, 1)) * 2   # rows 0, 2, 4, ...
+                c.select(idx)
+            p = first + n
+            od, ld = c.decode(q[:, p], k[:, p], v[:, p])
+            oc, lc = c.fwd(q[:, p + 1:p + 25], k[:, p + 1:p + 25], v[:, p + 1:p + 25])
+            outs.append((lengths, od, ld, oc, lc))
+        assert outs[0][0] == outs[1][0]
+        for a, b in zip(outs[0][1:], outs[1][1:]):
+            np.testing.assert_array_equal(a, b)
+        if not retrieved:
+            o_ref, l_ref = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=policy, rows=[first + n])
+            G.assert_parity(outs[0][1], outs[0][2], o_ref[:, 0], l_ref[:, :, 0], fp32_check=False, what="decode after bulk commit")
+            o_ref, l_ref = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=policy, rows=list(range(first + n + 1, first + n + 25)))
+            G.assert_parity(outs[0][3], outs[0][4], o_ref, l_ref, fp32_check=False, what="chunk after bulk commit")
+    finally:
+        for c in caches:
+            c.close()
+
+
+def test_whole_prompt_commit_rejects_an_open_segment_and_an_overfull_pool():
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    w = W.small("bulk_err", index=261, seq_len=400, seg_len=128, tail_len=32, n_q_heads=4, n_kv_heads=2,
+                head_dim=64, kv_policy=[3, 1])
+    _, k, v = W.prefill_inputs(w)
+    c = G.Cache(w, past_capacity=256)
+    try:
+        kd, vd = G.dev_bf16(k), G.dev_bf16(v)
+        with pytest.raises(sa.SegattnError):   # 400 rows do not fit a pool of 256
+            sa.seg_kv_commit_seq(c.ctx, kd, vd, 400, c.stream)
+        sa.seg_kv_commit(c.ctx, kd[:, :10].contiguous(), vd[:, :10].contiguous(), 10, c.stream)
+        with pytest.raises(sa.SegattnError):   # a segment is open
+            sa.seg_kv_commit_seq(c.ctx, kd[:, 10:100].contiguous(), vd[:, 10:100].contiguous(), 90, c.stream)
+        assert sa.seg_kv_lengths(c.ctx, 1, 2) == ([[0, 0]], [0], [10])   # refused calls changed nothing
+    finally:
+        c.close()
