@@ -44,15 +44,15 @@ bool build_problem(const segattn_config *cfg, bool need_cache, Problem &p) {
   for (int h = 0; h < p.Hkv; ++h) {
     if (cfg->kv_policy[h] > 3) return false;
     p.policy[h] = cfg->kv_policy[h];
-    p.past_before[h] = (unsigned short)n_past;
+    p.past_before[h] = n_past;
     if (p.policy[h] & SEGATTN_PAST) ++n_past;
   }
   p.n_past = n_past;
   int o = 0;
   for (int h = 0; h < p.Hkv; ++h)
-    if (p.policy[h] & SEGATTN_PAST) p.order[o++] = (unsigned char)h;
+    if (p.policy[h] & SEGATTN_PAST) p.order[o++] = h;
   for (int h = 0; h < p.Hkv; ++h)
-    if (!(p.policy[h] & SEGATTN_PAST)) p.order[o++] = (unsigned char)h;
+    if (!(p.policy[h] & SEGATTN_PAST)) p.order[o++] = h;
   if (need_cache && n_past > 0) {
     if (cfg->past_capacity < cfg->seg_len || cfg->past_capacity >= (1ll << 31) - 4096) return false;
   }
@@ -70,8 +70,8 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
   g.ret_cap = cfg->retrieved_capacity;
   g.decode_chunk = kDecodeChunk;
   const unsigned long long past_window = g.ret_cap ? (unsigned long long)g.ret_cap + p.S : g.pool_cap;
-  g.ws_splits_past = (int)((past_window + kDecodeChunk - 1) / kDecodeChunk);
-  g.ws_splits_other = (p.T + p.S + kDecodeChunk - 1) / kDecodeChunk;
+  g.ws_splits_past = (int)((past_window + kDecodeChunk - 1) / kDecodeChunk) + 1;
+  g.ws_splits_other = (p.T + p.S + kDecodeChunk - 1) / kDecodeChunk + 1;
   g.rows_per_seq = (unsigned long long)p.n_past * g.pool_cap +
                    (unsigned long long)(p.Hkv - p.n_past) * (unsigned long long)(p.T + p.S);
   g.meta_off = 0;
@@ -80,7 +80,7 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
   const unsigned long long slots = (unsigned long long)p.B * p.g *
                                    ((unsigned long long)p.n_past * g.ws_splits_past +
                                     (unsigned long long)(p.Hkv - p.n_past) * g.ws_splits_other);
-  g.kv_off = align_up(g.ws_off + slots * (2ull + p.D) * 4ull);
+  g.kv_off = align_up(g.ws_off + ws_header_bytes(p) + slots * (unsigned long long)ws_slot_floats(p.D) * 4ull);
   g.view_off = align_up(g.kv_off + (unsigned long long)p.B * g.rows_per_seq * 2ull * p.D * 2ull);
   total = g.view_off;
   if (g.ret_cap)
@@ -620,7 +620,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   if (!ctx || !q || !k_new || !v_new || !out || !lse) return SEGATTN_EINVAL;
   if (!ctx->ready) return SEGATTN_ESTATE;
   const Problem &p = ctx->p;
-  long long max_window = 1, max_window_past = 1;
+  long long total_rows = 0;
   bool any_full = false;
   for (int b = 0; b < p.B; ++b) {
     for (int h = 0; h < p.Hkv; ++h) {
@@ -632,8 +632,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
       } else {
         win = ((p.policy[h] & SEGATTN_TAIL) ? ctx->tail[b] : 0) + ctx->fill[b] + 1;
       }
-      long long &mw = (p.policy[h] & SEGATTN_PAST) ? max_window_past : max_window;
-      if (win > mw) mw = win;
+      total_rows += win;
     }
     any_full |= ctx->fill[b] + 1 == p.S;
   }
@@ -655,8 +654,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   da.lse = lse;
   da.cache = ctx->cache;
   da.geom = ctx->g;
-  da.splits_past = (int)((max_window_past + kDecodeChunk - 1) / kDecodeChunk);
-  da.splits_other = (int)((max_window + kDecodeChunk - 1) / kDecodeChunk);
+  da.total_rows = total_rows;
   if (launch_decode(p, da, p.B, st) != hipSuccess) return SEGATTN_EHIP;
   if (any_full && launch_cache_close(p, ctx->cache, ctx->g, 0, st) != hipSuccess) return SEGATTN_EHIP;
   for (int b = 0; b < p.B; ++b) {

@@ -28,11 +28,21 @@ struct CacheGeom {
   unsigned long long rows_per_seq;     // sum of cap(h) over heads
   unsigned long long pool_cap;         // rows per PAST head
   int ret_cap;                         // rows of retrieved prefix a view can hold; 0: no views
-  int ws_splits_past, ws_splits_other; // split-K slots per query head (PAST / other heads)
+  int ws_splits_past, ws_splits_other; // split-K slots per query head (PAST / other heads): one more
+                                       // than the chunks of the largest window (slices need not
+                                       // start at a window's first row)
   int decode_chunk;                    // keys per split
 };
 
+// One split-K partial of the decode path: D accumulator floats, then the reference maximum and the
+// row sum, padded so that every slot starts on a 128-byte line and is written by one workgroup in
+// whole lines (slots sharing lines, written from different XCDs, cost the split kernel 13 %).
+constexpr int kWsTailFloats = 32;
+__host__ __device__ inline int ws_slot_floats(int D) { return D + kWsTailFloats; }
+
 // Everything a kernel needs to know about the problem; passed by value as kernel argument.
+struct Problem;
+__host__ __device__ inline unsigned long long ws_header_bytes(const Problem &p);
 struct Problem {
   int B, Hq, Hkv, g, D, S, T;
   float scale;          // multiplies q.k
@@ -40,10 +50,18 @@ struct Problem {
   int out_fp32;         // `out` holds fp32 instead of bf16
   int fp32_math;        // validation mode: fp32 FMA kernels
   int n_past;           // number of PAST heads
-  unsigned char policy[kMaxKvHeads];
-  unsigned char order[kMaxKvHeads];     // KV heads, PAST heads first
-  unsigned short past_before[kMaxKvHeads];  // number of PAST heads with a smaller index
+  // Per-head tables as 32-bit words: a kernel indexes them with a workgroup-uniform value, and
+  // only whole words of the argument block can be fetched with scalar loads (bytes would go
+  // through the vector memory path and cost every workgroup a memory round trip each).
+  int policy[kMaxKvHeads];
+  int order[kMaxKvHeads];         // KV heads, PAST heads first
+  int past_before[kMaxKvHeads];   // number of PAST heads with a smaller index
 };
+
+// The decode workspace starts with one int per (sequence, KV head): partials written for its window.
+__host__ __device__ inline unsigned long long ws_header_bytes(const Problem &p) {
+  return ((unsigned long long)p.B * p.Hkv * 4ull + 127ull) / 128ull * 128ull;
+}
 
 // Arguments of the prefill kernels.  SEQ mode (cache == nullptr): q/k/v hold n_rows = N tokens
 // per sequence and every segment is processed in this launch.  CTX mode: q/k/v hold the
@@ -68,8 +86,8 @@ struct DecodeArgs {
   float *lse;
   unsigned char *cache;
   CacheGeom geom;
-  int splits_past;       // chunks of the longest window among PAST heads (>= 1)
-  int splits_other;      // same among the other heads (>= 1)
+  long long total_rows;  // visible rows summed over every (sequence, KV head) window
+  int rows_per_wg;       // rows per workgroup of the split kernel (>= geom.decode_chunk); set by the launcher
 };
 
 struct CopyArgs {

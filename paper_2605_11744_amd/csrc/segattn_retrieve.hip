@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
     for (int i = 0; i < NL; ++i) {
       long long row = (long long)c0 + t0 + RPL * i + lane / CH;
       row = row < last_byte_row ? row : last_byte_row;  // clamp: stays inside the pool
-      dst[i] = *(const u32x4 *)(kb + row * (2 * D) + (lane % CH) * 16);
+      dst[i] = __builtin_nontemporal_load((const u32x4 *)(kb + row * (2 * D) + (lane % CH) * 16));  // read once
     }
   };
   unsigned char *tile = stage[wave];

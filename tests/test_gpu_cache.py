@@ -95,22 +95,18 @@ def test_decode_after_prefill_crosses_segment_boundaries(fp32_check):
         c.close()
 
 
-def test_decode_ragged_batch_from_restored_cache():
-    """Sequences of different lengths: rows are written into the arena through
-    segattn_cache_span, lengths declared with seg_kv_set_lengths, one decode step checked
-    against the decode oracle per sequence."""
+def _decode_from_restored_cache(w, k_done, c_fill, fp32_check=False):
+    """Rows written into the arena through segattn_cache_span, lengths declared with
+    seg_kv_set_lengths, one decode step checked against the decode oracle per sequence."""
     import gpu_util as G
     import paper_2605_11744_amd as sa
-    S, T = 64, 24
-    w = W.Workload("dec_ragged", 220, 3, 0, 16, 4, 128, S, T, (1, 3, 0, 2), decode=True, max_context=64 * 9)
-    k_done = np.array([1, 8, 3])
-    c_fill = np.array([64, 1, 37])
+    S, T, B, Hkv, D = w.seg_len, w.tail_len, w.batch, w.n_kv_heads, w.head_dim
     q, ks, vs, _, _ = W.decode_inputs(w, k_done, c_fill)
-    c = G.Cache(w, past_capacity=64 * 9)
+    c = G.Cache(w, past_capacity=w.max_context, fp32_check=fp32_check)
     try:
-        k_new = np.zeros((3, 4, 128), dtype=np.uint16)
-        v_new = np.zeros((3, 4, 128), dtype=np.uint16)
-        for b in range(3):
+        k_new = np.zeros((B, Hkv, D), dtype=np.uint16)
+        v_new = np.zeros((B, Hkv, D), dtype=np.uint16)
+        for b in range(B):
             for h, pol in enumerate(w.kv_policy):
                 kk, vv = ks[b][h], vs[b][h]            # kept rows, newest (being decoded) last
                 k_new[b, h], v_new[b, h] = kk[-1], vv[-1]
@@ -120,23 +116,43 @@ def test_decode_ragged_batch_from_restored_cache():
                 if n_prev:
                     kd[first:first + n_prev] = G.dev_bf16(kk[:-1])
                     vd[first:first + n_prev] = G.dev_bf16(vv[:-1])
-        sa.seg_kv_set_lengths(c.ctx, list(k_done * S), [T] * 3, list(c_fill - 1), c.stream)
+        sa.seg_kv_set_lengths(c.ctx, [int(x) * S for x in k_done], [T] * B, [int(x) - 1 for x in c_fill], c.stream)
         o, l = c.decode(q, k_new, v_new)
-        for b in range(3):
+        for b in range(B):
             n_b = int(k_done[b]) * S + int(c_fill[b])
-            kf = np.zeros((n_b, 4, 128))
-            vf = np.zeros((n_b, 4, 128))
-            for h in range(4):
+            kf = np.zeros((n_b, Hkv, D))
+            vf = np.zeros((n_b, Hkv, D))
+            for h in range(Hkv):
                 kept = ks[b][h].shape[0]
                 kf[n_b - kept:, h] = orc.widen(ks[b][h])
                 vf[n_b - kept:, h] = orc.widen(vs[b][h])
             o_ref, l_ref = orc.decode_attend(q[b], kf, vf, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
-            G.assert_parity(o[b], l[b], o_ref, l_ref, fp32_check=False, what=f"ragged decode b={b}")
-        # sequence 0 filled its segment with this token: it must have been closed
-        past, tail, fill = sa.seg_kv_lengths(c.ctx, 3, 4)
-        assert fill == [0, 1, 37] and past[0][1] == 128 and past[0][3] == 128
+            G.assert_parity(o[b], l[b], o_ref, l_ref, fp32_check=fp32_check, what=f"{w.name} decode b={b}")
+        return sa.seg_kv_lengths(c.ctx, B, Hkv)
     finally:
         c.close()
+
+
+def test_decode_ragged_batch_from_restored_cache():
+    """Sequences of different lengths, one of them filling its segment with this token."""
+    S, T = 64, 24
+    w = W.Workload("dec_ragged", 220, 3, 0, 16, 4, 128, S, T, (1, 3, 0, 2), decode=True, max_context=64 * 9)
+    past, tail, fill = _decode_from_restored_cache(w, np.array([1, 8, 3]), np.array([64, 1, 37]))
+    # sequence 0 filled its segment with this token: it must have been closed
+    assert fill == [0, 1, 37] and past[0][1] == 128 and past[0][3] == 128
+
+
+@pytest.mark.parametrize("n_q_heads,head_dim,fp32_check", [(16, 128, False), (8, 128, False), (4, 64, False),
+                                                           (32, 64, False), (12, 128, False), (16, 128, True)])
+def test_decode_slices_cut_windows_anywhere(n_q_heads, head_dim, fp32_check):
+    """Windows of 1 to ~2800 rows (about 17K rows in all): the split kernel's equal slices of 512
+    rows begin and end inside windows, cover several short windows at once, and a long window
+    gets partials from several workgroups; every GQA group size (1, 2, 3, 4, 8 heads per KV head:
+    one, two or three passes of the split kernel)."""
+    S, T = 256, 100
+    w = W.Workload("dec_slices", 221, 5, 0, n_q_heads, 4, head_dim, S, T, (1, 3, 0, 2), decode=True,
+                   max_context=S * 12)
+    _decode_from_restored_cache(w, np.array([1, 11, 3, 7, 5]), np.array([256, 1, 37, 200, 129]), fp32_check)
 
 
 def test_evict_hides_oldest_pool_rows():
