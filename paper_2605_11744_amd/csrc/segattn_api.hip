@@ -85,6 +85,22 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
   total = g.view_off;
   if (g.ret_cap)
     total += (unsigned long long)p.B * p.n_past * 2ull * (unsigned long long)(g.ret_cap + p.S) * p.D * 2ull;
+  // Split-prefix workspace of the segment-by-segment prefill: only where one segment's PAST query
+  // blocks (64 rows, up to 4 heads) are at most half as many as the CUs of a 256-CU part -- then
+  // the workspace is at most 256 blocks x 64 rows x 4 heads of fp32 output rows (34 MB).
+  g.part_max = 1;
+  g.part_off = 0;
+  if (p.n_past > 0 && g.ret_cap == 0 && p.D == 128 && !p.fp32_math) {
+    const int hs = (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1;
+    const long long long_wgs = (long long)p.B * p.n_past * (p.g / hs) * ((p.S + (8 / hs) * 32 - 1) / ((8 / hs) * 32));
+    long long parts = 256 / long_wgs;
+    if (parts > 4) parts = 4;
+    if (parts >= 2) {
+      g.part_max = (int)parts;
+      g.part_off = align_up(total);
+      total = g.part_off + part_ws_bytes(p, g.part_max);
+    }
+  }
   return total < (1ull << 46);
 }
 
@@ -179,6 +195,18 @@ segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, cons
   a.geom = ctx->g;
   a.n_rows = m;
   a.n_seg = 1;
+  a.min_past_prefix = 0;
+  if (ctx->g.part_max > 1) {  // fewest prefix rows among the PAST windows: how far their work can be split
+    long long least = -1;
+    for (int b = 0; b < p.B; ++b)
+      for (int h = 0; h < p.Hkv; ++h)
+        if (p.policy[h] & SEGATTN_PAST) {
+          const size_t i = (size_t)b * p.Hkv + h;
+          const long long rows = ctx->pool[i] - ctx->lo[i] + ctx->fill[b];
+          if (least < 0 || rows < least) least = rows;
+        }
+    a.min_past_prefix = least < 0 ? 0 : least;
+  }
   return hip_status(launch_prefill(p, a, (hipStream_t)stream));
 }
 
@@ -441,6 +469,9 @@ namespace {
 constexpr int kRetrieveCand = 32;
 // pool rows per scoring workgroup: small chunks when (sequences x long-range heads) are few
 int retrieve_chunk_rows(const segattn_ctx *ctx) {
+#ifdef SEGATTN_RETRIEVE_CHUNK
+  return SEGATTN_RETRIEVE_CHUNK;
+#endif
   const unsigned long long big = (ctx->g.pool_cap + 4095) / 4096 * ctx->p.B * ctx->p.n_past;
   return big >= 1024 ? 4096 : 1024;
 }

@@ -25,6 +25,8 @@ enum MetaSlot { META_POOL = 0, META_TAIL = 1, META_FILL = 2, META_LO = 3, META_R
 // open segment (which is appended to the pool as well).
 struct CacheGeom {
   unsigned long long meta_off, ws_off, kv_off, view_off;
+  unsigned long long part_off;         // split-prefix workspace of the segment-by-segment prefill (0: none)
+  int part_max;                        // most parts a PAST head's prefix may be cut into (1: never split)
   unsigned long long rows_per_seq;     // sum of cap(h) over heads
   unsigned long long pool_cap;         // rows per PAST head
   int ret_cap;                         // rows of retrieved prefix a view can hold; 0: no views
@@ -78,6 +80,13 @@ struct PrefillArgs {
   int n_seg;             // segments covered by the launch (1 in CTX mode)
   int q_blocks_per_seg;  // ceil(min(S, n_rows) / rows per workgroup); set by the launcher
   int pair_stride;       // spreads the (segment, sequence, head) groups of non-PAST heads over the XCDs (0 = 1)
+  // CTX mode, split prefix: the prefix of every PAST head is cut into `parts` pieces, each handled
+  // by a workgroup of its own (the last one also takes the open segment); the pieces' normalised
+  // fp32 outputs and their LSEs go to the workspace and prefill_part_combine_kernel merges them.
+  int parts;             // 0 or 1: no split
+  long long min_past_prefix;  // host: fewest prefix rows among the PAST windows (sets how far to split)
+  float *part_out;       // [B][parts][n_rows][n_past*g][D]
+  float *part_lse;       // [B][parts][n_past*g][n_rows]
 };
 
 struct DecodeArgs {
@@ -226,6 +235,10 @@ __host__ __device__ inline void window_of(const Problem &p, const CacheGeom &g, 
 
 // ---- launchers (defined in the .hip files) ------------------------------------------------
 hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st);
+// bytes of split-prefix workspace for `parts` pieces (fp32 outputs + LSEs of one segment of every sequence)
+__host__ __device__ inline unsigned long long part_ws_bytes(const Problem &p, int parts) {
+  return (unsigned long long)p.B * parts * p.S * p.n_past * p.g * (unsigned long long)(p.D + 1) * 4ull;
+}
 hipError_t launch_decode(const Problem &p, const DecodeArgs &a, int B, hipStream_t st);
 hipError_t launch_cache_reset(const Problem &p, unsigned char *cache, const CacheGeom &g, hipStream_t st);
 hipError_t launch_cache_append(const Problem &p, const CopyArgs &a, hipStream_t st);

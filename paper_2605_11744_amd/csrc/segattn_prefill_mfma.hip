@@ -129,7 +129,8 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   const int i16 = lane & 15, g16 = (lane >> 4) & 1;
   const int head = w.kv * p.g + w.hsub * HS + (wave % HS);
   const int tw0 = w.t0 + (wave / HS) * RW;  // first query row of this wave
-  const int last_row = w.n1 - 1;
+  const int ohead = w.ohead0 + (wave % HS);  // the same head where this workgroup's output goes
+  const int last_row = w.nq - 1;
   const float c = p.scale_log2e;
 
   // ---- step schedule (workgroup) and this wave's share of it
@@ -705,7 +706,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   // [32 rows][D] staging block (rows padded by 8 bytes against bank conflicts), and the wave
   // reads the block back row-major.
   __syncthreads();  // every wave is past its last read of the K/V ring
-  const bool wide = p.out_fp32 != 0;
+  const bool wide = w.wide;
   const int es = wide ? 4 : 2;                 // bytes per output element
   const int row_bytes = D * es + 8;
   unsigned char *stage = smem + wave * (32 * (D * es + 8));
@@ -716,7 +717,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     const int t = tw0 + 32 * qb + col;
     const float l = half_sum(l_run[qb]);
     const float inv = 1.f / l;
-    if (hi == 0 && t <= last_row) w.lse[(long long)head * w.lse_head_stride + t] = m_ref[qb] * p.scale + __logf(l);
+    if (hi == 0 && t <= last_row) w.lse[(long long)ohead * w.lse_head_stride + t] = m_ref[qb] * p.scale + __logf(l);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -739,11 +740,52 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
       if (tr > last_row) break;
       const unsigned char *src = stage + r * row_bytes + piece * 16;
       const uint2 a0 = *(const uint2 *)src, a1 = *(const uint2 *)(src + 8);
-      unsigned char *gdst = (unsigned char *)w.out + (((long long)tr * p.Hq + head) * D) * es + piece * 16;
+      unsigned char *gdst = (unsigned char *)w.out + (((long long)tr * w.out_heads + ohead) * D) * es + piece * 16;
       *(uint4 *)gdst = uint4{a0.x, a0.y, a1.x, a1.y};
     }
     __syncthreads();
   }
+}
+
+// =============================================================================================
+// split prefix (segment-by-segment prefill): merge the pieces
+// =============================================================================================
+// Every piece of a PAST head's keys left a normalised fp32 output row and its LSE in the
+// workspace; softmax over the union is the LSE-weighted mean of the pieces (the same identity the
+// decode path and a sharded prefix use).  32 lanes per (sequence, row, head), D/32 channels each.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_part_combine_kernel(const Problem p, const PrefillArgs a) {
+  constexpr int CPL = D / 32;  // channels per lane
+  const int ph = p.n_past * p.g;
+  const long long m = a.n_rows;
+  const long long item = (long long)blockIdx.x * 8 + (threadIdx.x >> 5);
+  if (item >= (long long)p.B * m * ph) return;
+  const int lane = threadIdx.x & 31;
+  const int hc = (int)(item % ph);
+  const long long row = (item / ph) % m;
+  const int b = (int)(item / ((long long)ph * m));
+  const int head = p.order[hc / p.g] * p.g + hc % p.g;
+  float mx = -INFINITY;
+  for (int pt = 0; pt < a.parts; ++pt)
+    mx = fmaxf(mx, a.part_lse[(((long long)b * a.parts + pt) * ph + hc) * m + row]);
+  float sum = 0.f, acc[CPL];
+#pragma unroll
+  for (int e = 0; e < CPL; ++e) acc[e] = 0.f;
+  for (int pt = 0; pt < a.parts; ++pt) {
+    const float wgt = __expf(a.part_lse[(((long long)b * a.parts + pt) * ph + hc) * m + row] - mx);
+    const float *src = a.part_out + ((((long long)b * a.parts + pt) * m + row) * ph + hc) * D + lane * CPL;
+    sum += wgt;
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) acc[e] = fmaf(wgt, src[e], acc[e]);
+  }
+  const float inv = 1.f / sum;
+  const long long o = (((long long)b * m + row) * p.Hq + head) * D + lane * CPL;
+#pragma unroll
+  for (int e = 0; e < CPL; ++e) {
+    if (p.out_fp32) ((float *)a.out)[o + e] = acc[e] * inv;
+    else ((__bf16 *)a.out)[o + e] = (__bf16)(acc[e] * inv);
+  }
+  if (lane == 0) a.lse[((long long)b * p.Hq + head) * m + row] = mx + __logf(sum);
 }
 
 // =============================================================================================
@@ -816,31 +858,71 @@ static int waves_d128(const Problem &p, const PrefillArgs &a, int hs) {
   return heads * blocks8 < n_cu ? 4 : 8;
 }
 
+static int device_cus() {
+  static const int n_cu = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    return cus;
+  }();
+  return n_cu;
+}
+
+// Segment-by-segment prefill: pieces to cut every PAST head's prefix into.  One segment has few
+// query blocks, and the ones of the PAST heads carry nearly all the work: with one workgroup per
+// block the launch takes as long as its longest workgroup while most CUs idle.  Cut so that the
+// long workgroups are about as many as the CUs (eight-wave workgroups, one per CU), every piece
+// keeping at least 1024 rows.
+static int prefix_parts(const Problem &p, const PrefillArgs &a, int hs) {
+  if (a.cache == nullptr || a.geom.part_max < 2 || p.n_past == 0 || a.geom.ret_cap > 0 || p.D != 128) return 1;
+  if (getenv("SEGATTN_PREFILL_WAVES")) return 1;  // a forced workgroup shape runs unsplit
+  const int rows8 = (8 / hs) * 32;
+  const long long long_wgs = (long long)p.B * p.n_past * (p.g / hs) * ((a.n_rows + rows8 - 1) / rows8);
+  long long parts = device_cus() / long_wgs;
+  if (parts > a.geom.part_max) parts = a.geom.part_max;
+  if (parts > a.min_past_prefix / 1024) parts = a.min_past_prefix / 1024;
+  return parts < 2 ? 1 : (int)parts;
+}
+
 hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t st) {
   const bool fp32 = p.fp32_math != 0;
   const int hs = fp32 ? 1 : heads_per_wg(p);
-  const int nw = p.D == 128 ? waves_d128(p, a_in, hs) : 4;
-  const int rows = fp32 ? 64 : (p.D == 128 ? (nw / hs) * 32 : (4 / hs) * 64);
   PrefillArgs a = a_in;
+  a.parts = fp32 ? 1 : prefix_parts(p, a, hs);
+  const int nw = p.D == 128 ? (a.parts > 1 ? 8 : waves_d128(p, a_in, hs)) : 4;
+  const int rows = fp32 ? 64 : (p.D == 128 ? (nw / hs) * 32 : (4 / hs) * 64);
   const long long seg_rows = a.n_rows < p.S ? a.n_rows : p.S;
   a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
-  const long long grid = (long long)p.B * p.Hkv * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
+  const long long per_head = (long long)p.B * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
+  const long long grid = per_head * ((long long)p.n_past * a.parts + (p.Hkv - p.n_past));
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   a.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * a.n_seg);
+  if (a.parts > 1) {
+    a.part_out = (float *)(a.cache + a.geom.part_off);
+    a.part_lse = a.part_out + (long long)p.B * a.parts * a.n_rows * p.n_past * p.g * p.D;
+  }
   if (fp32) return launch_prefill_fp32(p, a, grid, st);
+  hipError_t e;
   if (p.D == 128) {
     if (nw == 8) {
-      if (hs == 4) return launch_mfma<128, 4, 1, 8>(p, a, grid, st);
-      if (hs == 2) return launch_mfma<128, 2, 1, 8>(p, a, grid, st);
-      return launch_mfma<128, 1, 1, 8>(p, a, grid, st);
+      if (hs == 4) e = launch_mfma<128, 4, 1, 8>(p, a, grid, st);
+      else if (hs == 2) e = launch_mfma<128, 2, 1, 8>(p, a, grid, st);
+      else e = launch_mfma<128, 1, 1, 8>(p, a, grid, st);
+    } else {
+      if (hs == 4) e = launch_mfma<128, 4, 1, 4>(p, a, grid, st);
+      else if (hs == 2) e = launch_mfma<128, 2, 1, 4>(p, a, grid, st);
+      else e = launch_mfma<128, 1, 1, 4>(p, a, grid, st);
     }
-    if (hs == 4) return launch_mfma<128, 4, 1, 4>(p, a, grid, st);
-    if (hs == 2) return launch_mfma<128, 2, 1, 4>(p, a, grid, st);
-    return launch_mfma<128, 1, 1, 4>(p, a, grid, st);
+  } else {
+    if (hs == 4) e = launch_mfma<64, 4, 2, 4>(p, a, grid, st);
+    else if (hs == 2) e = launch_mfma<64, 2, 2, 4>(p, a, grid, st);
+    else e = launch_mfma<64, 1, 2, 4>(p, a, grid, st);
   }
-  if (hs == 4) return launch_mfma<64, 4, 2, 4>(p, a, grid, st);
-  if (hs == 2) return launch_mfma<64, 2, 2, 4>(p, a, grid, st);
-  return launch_mfma<64, 1, 2, 4>(p, a, grid, st);
+  if (e != hipSuccess || a.parts < 2) return e;
+  const long long items = (long long)p.B * a.n_rows * p.n_past * p.g;
+  hipLaunchKernelGGL(prefill_part_combine_kernel<128>, dim3((unsigned)((items + 7) / 8)), dim3(256), 0, st, p, a);
+  return hipGetLastError();
 }
 
 }  // namespace segattn

@@ -21,6 +21,11 @@ struct WorkItem {
   long long lse_head_stride;                // floats between heads in lse
   int t0;                                   // first in-segment query row of the workgroup
   int kv, hsub, b;
+  // Where the MFMA prefill kernel writes: rows of `out_heads` heads, this workgroup's first head
+  // at `ohead0`, fp32 if `wide`.  Normally the caller's tensor; the workspace for a split prefix.
+  int nq;                                   // query rows of the segment present (n1, except for a prefix piece)
+  int out_heads, ohead0;
+  bool wide;
   bool valid;
 };
 
@@ -33,12 +38,15 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   const int nhs = p.g / heads_per_wg;
   const int nqb = a.q_blocks_per_seg;
   const int n_other = p.Hkv - p.n_past;
-  const long long past_items = (long long)p.B * p.n_past * nhs * a.n_seg * nqb;
-  int seg, qblk, hidx, b, hs;
+  const int parts = (a.cache != nullptr && a.parts > 1) ? a.parts : 1;
+  const long long past_items = (long long)p.B * p.n_past * nhs * a.n_seg * nqb * parts;
+  int seg, qblk, hidx, b, hs, part = 0;
   if (bid < past_items) {
-    const int per = p.B * p.n_past * nhs;
+    const int per = p.B * p.n_past * nhs * parts;
     const int gq = a.n_seg * nqb - 1 - bid / per;
     int rest = bid % per;
+    part = rest % parts;
+    rest /= parts;
     seg = gq / nqb;
     qblk = gq % nqb;
     hs = rest % nhs;
@@ -129,7 +137,34 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     w.lse = a.lse + (long long)b * p.Hq * m;
     w.lse_head_stride = m;
   }
-  w.valid = w.t0 < w.n1;
+  w.nq = w.n1;
+  w.out_heads = p.Hq;
+  w.ohead0 = kv * p.g + hs * heads_per_wg;
+  w.wide = p.out_fp32 != 0;
+  if (parts > 1 && (pol & SEGATTN_PAST)) {
+    // Piece `part` of the prefix.  The last piece also takes the open segment (about n1/2 keys per
+    // query on average), so the others get a little more of the prefix: t rows each, a multiple of
+    // the 32-key step, and the last one the rest (the host only splits prefixes of >= 1024 rows per
+    // piece, so the rest is never empty).
+    const int n0 = w.n0;
+    int t = ((n0 + w.n1 / 2) / parts + 31) & ~31;
+    const int t_max = ((n0 - 32) / (parts - 1)) & ~31;
+    t = t < t_max ? t : t_max;
+    const int start = part * t;
+    w.k0 += (long long)start * p.D;
+    w.v0 += (long long)start * p.D;
+    w.n0 = (part == parts - 1) ? n0 - start : t;
+    if (part != parts - 1) w.n1 = 0;
+    const int ph = p.n_past * p.g;  // heads per workspace row
+    const long long m = a.n_rows;
+    w.out = (unsigned char *)(a.part_out + (((long long)b * parts + part) * m * ph) * p.D);
+    w.lse = a.part_lse + ((long long)b * parts + part) * ph * m;
+    w.lse_head_stride = m;
+    w.out_heads = ph;
+    w.ohead0 = p.past_before[kv] * p.g + hs * heads_per_wg;
+    w.wide = true;
+  }
+  w.valid = w.t0 < w.nq;
   return w;
 }
 
@@ -153,6 +188,7 @@ __device__ inline T *uniform_ptr(T *ptr) {
 __device__ inline void pin_uniform(WorkItem &w) {
   w.n0 = uniform_i32(w.n0);
   w.n1 = uniform_i32(w.n1);
+  w.nq = uniform_i32(w.nq);
   w.t0 = uniform_i32(w.t0);
   w.stride0 = uniform_i32((int)w.stride0);
   w.stride1 = uniform_i32((int)w.stride1);

@@ -20,6 +20,12 @@ STREAM_CASES = [
     (dict(seq_len=300, seg_len=64, tail_len=64, n_q_heads=4, n_kv_heads=4, head_dim=64), [64]),
     (dict(seq_len=520, seg_len=128, tail_len=40, n_q_heads=16, n_kv_heads=4, head_dim=128, batch=2), [50, 78, 128, 1, 127]),
     (dict(seq_len=257, seg_len=256, tail_len=0, n_q_heads=8, n_kv_heads=4, head_dim=64), [200, 56, 1]),
+    # prefixes of thousands of rows: the library cuts a PAST head's prefix into 2 to 4 pieces per
+    # query block (separate workgroups, merged afterwards), also with a partly filled open segment
+    (dict(seq_len=5500, seg_len=1024, tail_len=128, n_q_heads=8, n_kv_heads=2, head_dim=128, kv_policy=[3, 1],
+          batch=2), [1024, 600, 424]),
+    (dict(seq_len=3400, seg_len=512, tail_len=64, n_q_heads=4, n_kv_heads=2, head_dim=128, kv_policy=[2, 1]),
+     [512, 100, 412]),
 ]
 
 
