@@ -95,6 +95,7 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
     const long long long_wgs = (long long)p.B * p.n_past * (p.g / hs) * ((p.S + (8 / hs) * 32 - 1) / ((8 / hs) * 32));
     long long parts = 256 / long_wgs;
     if (parts > 4) parts = 4;
+    if (parts > (long long)(g.pool_cap / 1024)) parts = (long long)(g.pool_cap / 1024);  // >= 1024 rows per piece
     if (parts >= 2) {
       g.part_max = (int)parts;
       g.part_off = align_up(total);

@@ -40,6 +40,13 @@ def test_cache_bytes_accounts_for_rows_counters_and_workspace():
     kv_bytes = kv_rows * 2 * 128 * 2
     assert kv_bytes < total < kv_bytes + 64 * 1024
     assert sa.segattn_cache_bytes(_cfg(batch=3)) > 3 * kv_bytes
+    # a pool that can hold prefixes worth cutting into pieces (>= 1024 rows each) adds the
+    # split-prefix workspace: fp32 output rows + LSEs of one segment per piece, at most 4 pieces
+    big = _cfg(seg_len=512, tail_len=64, past_capacity=8192)
+    kv_big = (8192 + (64 + 512)) * 2 * 128 * 2
+    ws = 4 * 512 * 4 * (128 + 1) * 4               # pieces x S x (1 PAST head x g = 4 heads) x (D + 1) floats
+    assert kv_big + ws < sa.segattn_cache_bytes(big) < kv_big + ws + 256 * 1024
+    assert sa.segattn_cache_bytes(_cfg(seg_len=512, tail_len=64, past_capacity=8192, batch=64)) < 64 * (kv_big + 256 * 1024)
 
 
 @pytest.mark.parametrize("bad", [
