@@ -468,13 +468,24 @@ segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t 
 
 namespace {
 constexpr int kRetrieveCand = 32;
-// pool rows per scoring workgroup: small chunks when (sequences x long-range heads) are few
+// Pool rows per scoring workgroup: 4096, or 1024 where that would leave the chip short of work --
+// fewer chunks with visible rows than four rounds of resident workgroups (3 per CU), where the
+// last, partly filled round costs more than the extra per-chunk selections.  The workspace is
+// sized for the small chunks.
+constexpr int kRetrieveChunkSmall = 1024, kRetrieveChunkBig = 4096;
 int retrieve_chunk_rows(const segattn_ctx *ctx) {
 #ifdef SEGATTN_RETRIEVE_CHUNK
   return SEGATTN_RETRIEVE_CHUNK;
 #endif
-  const unsigned long long big = (ctx->g.pool_cap + 4095) / 4096 * ctx->p.B * ctx->p.n_past;
-  return big >= 1024 ? 4096 : 1024;
+  const Problem &p = ctx->p;
+  long long active = 0;
+  for (int b = 0; b < p.B; ++b)
+    for (int h = 0; h < p.Hkv; ++h) {
+      const size_t i = (size_t)b * p.Hkv + h;
+      if ((p.policy[h] & SEGATTN_PAST) && ctx->pool[i] > ctx->lo[i])
+        active += (ctx->pool[i] - 1) / kRetrieveChunkBig - ctx->lo[i] / kRetrieveChunkBig + 1;
+    }
+  return active >= 4 * 3 * 256 ? kRetrieveChunkBig : kRetrieveChunkSmall;
 }
 bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &nsp, int &n_chunks,
                       unsigned long long &off_val, unsigned long long &off_idx, unsigned long long &total) {
@@ -486,8 +497,7 @@ bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &n
   const long long n_sum = (long long)(r->n_queries + r->pool_window - 1) / r->pool_window + 1;
   if (n_sum * ctx->p.g > 64) return false;
   nsp = (int)((n_sum * ctx->p.g + 31) / 32 * 32);
-  const int chunk = retrieve_chunk_rows(ctx);
-  n_chunks = (int)((ctx->g.pool_cap + chunk - 1) / chunk);
+  n_chunks = (int)((ctx->g.pool_cap + kRetrieveChunkSmall - 1) / kRetrieveChunkSmall);  // the most a call can use
   const unsigned long long heads = (unsigned long long)ctx->p.B * ctx->p.n_past;
   off_val = align_up(heads * nsp * ctx->p.D * 2ull);
   off_idx = align_up(off_val + heads * n_chunks * kRetrieveCand * 4ull);
@@ -529,8 +539,14 @@ segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, con
   a.m = m;
   a.R = R;
   a.nsp = nsp;
-  a.n_chunks = n_chunks;
   a.chunk_rows = retrieve_chunk_rows(ctx);
+  long long longest = 1;  // chunks up to the longest pool only
+  for (int b = 0; b < p.B; ++b)
+    for (int h = 0; h < p.Hkv; ++h)
+      if ((p.policy[h] & SEGATTN_PAST) && ctx->pool[(size_t)b * p.Hkv + h] > longest)
+        longest = ctx->pool[(size_t)b * p.Hkv + h];
+  a.n_chunks = (int)((longest + a.chunk_rows - 1) / a.chunk_rows);
+  if (a.n_chunks > n_chunks) return SEGATTN_EINVAL;
   a.n_queries = r->n_queries;
   a.pool_window = r->pool_window;
   a.tail_avg = r->tail_avg;
