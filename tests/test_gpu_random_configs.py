@@ -72,3 +72,61 @@ def test_random_config_forward_and_backward(c, waves, monkeypatch):
             err = np.abs(g_ - r_)
             G = max(1.0, float(np.abs(r_).max()))
             assert err.max() <= 1e-2 * G and err.mean() <= 1e-3 * G, f"{name}: max {err.max():.3e} mean {err.mean():.3e} G={G:.2f}"
+
+
+def _stateful_configs(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        long_prefix = i % 4 == 3   # every fourth: prefixes of thousands of rows (the library splits them)
+        D = 128 if long_prefix else int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        g = int(rng.choice([1, 2, 3, 4, 8])) if not long_prefix else int(rng.choice([1, 2, 4]))
+        S = int(rng.choice([512, 700, 1024])) if long_prefix else int(rng.choice([7, 32, 33, 64, 95, 128, 200]))
+        T = int(rng.integers(0, min(S, 300) + 1))
+        B = int(rng.integers(1, 4)) if not long_prefix else int(rng.integers(1, 3))
+        n_pre = int(rng.integers(3 * S, 6 * S)) if long_prefix else int(rng.integers(1, 4 * S + 20))
+        n_dec = int(rng.integers(1, 6))
+        policy = [int(rng.integers(0, 4)) for _ in range(Hkv)]
+        if long_prefix and not any(p & 2 for p in policy):
+            policy[0] |= 2
+        chunks = [int(rng.integers(1, S + 1)) for _ in range(5)]
+        out.append(dict(D=D, Hkv=Hkv, g=g, S=S, T=T, B=B, n_pre=n_pre, n_dec=n_dec, policy=policy, chunks=chunks,
+                        idx=500 + i))
+    return out
+
+
+@pytest.mark.parametrize("c", _stateful_configs(16, 20260512),
+                         ids=lambda c: f"D{c['D']}g{c['g']}kv{c['Hkv']}S{c['S']}T{c['T']}B{c['B']}n{c['n_pre']}+{c['n_dec']}")
+def test_random_config_streaming_then_decode(c, monkeypatch):
+    """Segment-by-segment prefill in random chunks (the library's own choice of workgroup shape and
+    of prefix pieces), then a few decode steps: every output row against the oracle's row of the
+    full sequence."""
+    from gpu_util import Cache
+    monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
+    D, Hkv, g, S, T, B = c["D"], c["Hkv"], c["g"], c["S"], c["T"], c["B"]
+    n_pre, n_dec, policy, chunks = c["n_pre"], c["n_dec"], c["policy"], c["chunks"]
+    N = n_pre + n_dec
+    w = W.small("rnd_state", index=c["idx"], seq_len=N, seg_len=S, tail_len=T, n_q_heads=Hkv * g, n_kv_heads=Hkv,
+                head_dim=D, kv_policy=policy, batch=B)
+    q, k, v = W.prefill_inputs(w)
+    o_ref, l_ref = orc.attend(q, k, v, seg_len=S, tail_len=T, kv_policy=policy)
+    cache = Cache(w, past_capacity=((N + S) // S) * S)
+    try:
+        o = np.zeros_like(o_ref)
+        l = np.zeros_like(l_ref)
+        pos, i = 0, 0
+        while pos < n_pre:
+            m = min(chunks[i % len(chunks)], S - pos % S, n_pre - pos)
+            i += 1
+            oc, lc = cache.fwd(q[:, pos:pos + m], k[:, pos:pos + m], v[:, pos:pos + m])
+            o[:, pos:pos + m] = oc
+            l[:, :, pos:pos + m] = lc
+            pos += m
+        for p_ in range(n_pre, N):
+            od, ld = cache.decode(q[:, p_], k[:, p_], v[:, p_])
+            o[:, p_] = od
+            l[:, :, p_] = ld
+        assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="streaming + decode")
+    finally:
+        cache.close()
