@@ -89,7 +89,10 @@ typedef struct {
 /* Bytes of device memory the cache arena needs for this configuration (0 if invalid).
  * Per TAIL/SEG head: (T + S) rows of K and of V; per PAST head: past_capacity rows (in
  * retrieval mode also retrieved_capacity + S rows: retrieved prefix and a copy of the open
- * segment); plus per-(sequence, head) counters and the split-K workspace of the decode path. */
+ * segment); plus per-(sequence, head) counters, the split-K workspace of the decode path and,
+ * where one segment alone cannot fill the chip with the query blocks of its PAST heads (few
+ * sequences, few PAST heads) and the pool can hold 2048 rows or more, at most 34 MB of workspace
+ * in which seg_attn_fwd merges the pieces it cuts such a head's prefix into. */
 size_t segattn_cache_bytes(const segattn_config *cfg);
 
 /* Create a context over a caller-allocated arena (device, >= segattn_cache_bytes(), aligned
