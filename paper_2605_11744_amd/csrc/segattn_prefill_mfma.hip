@@ -2,8 +2,9 @@
 // per-head context of Eq. 13, Appendix C) for gfx950.
 //
 // Workgroup = 8 waves (two per SIMD, 256 registers each) for head_dim 128, 4 waves for head_dim
-// 64.  HS query heads of one GQA group share the staged K/V rows; each wave owns one head and
-// 32 (head_dim 128) or 64 consecutive query rows.  Keys are consumed in steps of 32:
+// 64 (152 registers: three workgroups share a CU).  HS query heads of one GQA group share the
+// staged K/V rows; each wave owns one head and 32 consecutive query rows.  Keys are consumed in
+// steps of 32:
 //
 //   S^T[key][query] = K_step . Q^T      v_mfma_f32_32x32x16_bf16, A = K rows read from LDS
 //   P = exp2(S^T c - m c)               per query, m a running reference maximum
@@ -97,7 +98,9 @@ __device__ inline float half_sum(float x) {
   return __int_as_float(sw[0]) + __int_as_float(sw[1]);
 }
 
-// QB = 32-query blocks per wave, NW = waves per workgroup.  (D, QB, NW) = (128, 1, 8): two
+// QB = 32-query blocks per wave (1 in every instantiation in use; a head_dim-64 form with 2, one
+// wave per SIMD, was 6 to 40 % slower than three 32-row workgroups per CU), NW = waves per
+// workgroup.  (D, QB, NW) = (128, 1, 8): two
 // waves per SIMD share the issue slots -- while one is blocked behind a matrix product or a
 // wait the other issues its softmax -- at the price of reading every K/V operand from LDS for
 // half as many products.  All products are compiler builtins in VGPR form (the file is built
@@ -829,7 +832,7 @@ int prefill_pair_stride(long long groups) {
 }
 
 // Waves per workgroup for head_dim 128 (each wave owns one head x 32 query rows; D = 64 always
-// runs four waves of 64 rows).  Eight waves -- 64 rows per head, one workgroup per CU, two waves
+// runs four waves, whose step of 32 keys is only four 1 KB loads per tensor).  Eight waves -- 64 rows per head, one workgroup per CU, two waves
 // per SIMD -- move half as many K/V bytes per query row and are the choice whenever there is
 // enough work to fill the chip.  Four waves -- 32 rows per head, two workgroups fit a CU -- double
 // the number of workgroups: right when the long (PAST) workgroups of a launch would otherwise
@@ -891,7 +894,7 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t
   PrefillArgs a = a_in;
   a.parts = fp32 ? 1 : prefix_parts(p, a, hs);
   const int nw = p.D == 128 ? (a.parts > 1 ? 8 : waves_d128(p, a_in, hs)) : 4;
-  const int rows = fp32 ? 64 : (p.D == 128 ? (nw / hs) * 32 : (4 / hs) * 64);
+  const int rows = fp32 ? 64 : (p.D == 128 ? (nw / hs) * 32 : (4 / hs) * 32);
   const long long seg_rows = a.n_rows < p.S ? a.n_rows : p.S;
   a.q_blocks_per_seg = (int)((seg_rows + rows - 1) / rows);
   const long long per_head = (long long)p.B * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
@@ -915,9 +918,9 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t
       else e = launch_mfma<128, 1, 1, 4>(p, a, grid, st);
     }
   } else {
-    if (hs == 4) e = launch_mfma<64, 4, 2, 4>(p, a, grid, st);
-    else if (hs == 2) e = launch_mfma<64, 2, 2, 4>(p, a, grid, st);
-    else e = launch_mfma<64, 1, 2, 4>(p, a, grid, st);
+    if (hs == 4) e = launch_mfma<64, 4, 1, 4>(p, a, grid, st);
+    else if (hs == 2) e = launch_mfma<64, 2, 1, 4>(p, a, grid, st);
+    else e = launch_mfma<64, 1, 1, 4>(p, a, grid, st);
   }
   if (e != hipSuccess || a.parts < 2) return e;
   const long long items = (long long)p.B * a.n_rows * p.n_past * p.g;
