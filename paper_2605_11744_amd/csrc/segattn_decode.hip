@@ -84,11 +84,11 @@ __device__ inline float dot2_bf16(unsigned a, unsigned b, float c) {  // a.lo*b.
 // use v_dot2_f32_bf16 on the bf16 pairs as they come from memory, and the weights are rounded to
 // bf16 for the PV product (as in the prefill kernel; the row sums use the same rounded values).
 template <int D, int GH, bool EXACT>
-__global__ __launch_bounds__(256, SEGATTN_DECODE_WAVES) void decode_split_kernel(const Problem p, const DecodeArgs a,
+__global__ __launch_bounds__(256, GH == 8 ? 2 : SEGATTN_DECODE_WAVES) void decode_split_kernel(const Problem p, const DecodeArgs a,
                                                           const int head_pass) {
   constexpr int LPR = D / 8;        // lanes per key row
   constexpr int GPW = 64 / LPR;     // key rows per wave-wide load
-  constexpr int U = SEGATTN_DECODE_U;  // rows in flight per lane group
+  constexpr int U = GH == 8 ? SEGATTN_DECODE_U / 2 : SEGATTN_DECODE_U;  // rows in flight per lane group
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int grp = lane / LPR, li = lane % LPR;
   const float c = p.scale_log2e;
@@ -418,6 +418,7 @@ static hipError_t launch_split_gh(const Problem &p, DecodeArgs a, hipStream_t st
 template <int D, bool EXACT>
 static hipError_t launch_split(const Problem &p, const DecodeArgs &a, hipStream_t st) {
   if (a.total_rows < 1) return hipErrorInvalidValue;
+  if (p.g % 8 == 0) return launch_split_gh<D, 8, EXACT>(p, a, st);  // one pass over K/V for 8 heads
   if (p.g % 4 == 0) return launch_split_gh<D, 4, EXACT>(p, a, st);
   if (p.g % 2 == 0) return launch_split_gh<D, 2, EXACT>(p, a, st);
   return launch_split_gh<D, 1, EXACT>(p, a, st);
