@@ -163,12 +163,15 @@ __global__ __launch_bounds__(256, GH == 8 ? 2 : SEGATTN_DECODE_WAVES) void decod
     if (c1 <= c0) continue;
     remaining -= c1 - c0;
     const int head0 = kv * p.g + head_pass * GH;
+    // heads of the group this pass covers; with a group size that is no multiple of GH the last
+    // pass computes surplus heads on a repeated query row and drops them
+    const int live = min(GH, p.g - head_pass * GH);
 
     uint4 qp[GH];   // this lane's 8 query elements per head, as bf16 pairs
     float qf[EXACT ? GH : 1][8];
 #pragma unroll
     for (int h = 0; h < GH; ++h) {
-      qp[h] = *(const uint4 *)(a.q + ((long long)b * p.Hq + head0 + h) * D + li * 8);
+      qp[h] = *(const uint4 *)(a.q + ((long long)b * p.Hq + head0 + (h < live ? h : live - 1)) * D + li * 8);
       if (EXACT) unpack8(qp[h], qf[h]);
     }
 
@@ -323,6 +326,7 @@ __global__ __launch_bounds__(256, GH == 8 ? 2 : SEGATTN_DECODE_WAVES) void decod
         o.z += x.z * wgt;
         o.w += x.w * wgt;
       }
+      if (h >= live) continue;
       float *slot = slots + (ws_slot_base(p, a.geom, b, head0 + h) + split) * ws_slot_floats(D);
       *(float4 *)(slot + d) = o;
       if (d == 0) *(float2 *)(slot + D) = float2{mx, l};
@@ -406,7 +410,7 @@ static hipError_t launch_split_gh(const Problem &p, DecodeArgs a, hipStream_t st
   if (per > 0x7fffff00LL) return hipErrorInvalidValue;
   a.rows_per_wg = (int)per;
   const long long blocks = (a.total_rows + per - 1) / per;
-  for (int pass = 0; pass < p.g / GH; ++pass) {
+  for (int pass = 0; pass < (p.g + GH - 1) / GH; ++pass) {
     hipLaunchKernelGGL((decode_split_kernel<D, GH, EXACT>), dim3((unsigned)blocks), dim3(256), 0, st, p, a, pass);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -418,9 +422,10 @@ static hipError_t launch_split_gh(const Problem &p, DecodeArgs a, hipStream_t st
 template <int D, bool EXACT>
 static hipError_t launch_split(const Problem &p, const DecodeArgs &a, hipStream_t st) {
   if (a.total_rows < 1) return hipErrorInvalidValue;
-  if (p.g % 8 == 0) return launch_split_gh<D, 8, EXACT>(p, a, st);  // one pass over K/V for 8 heads
-  if (p.g % 4 == 0) return launch_split_gh<D, 4, EXACT>(p, a, st);
-  if (p.g % 2 == 0) return launch_split_gh<D, 2, EXACT>(p, a, st);
+  // heads per pass: the smallest of 1, 2, 4, 8 that covers the group (8 for larger groups)
+  if (p.g > 4) return launch_split_gh<D, 8, EXACT>(p, a, st);
+  if (p.g > 2) return launch_split_gh<D, 4, EXACT>(p, a, st);
+  if (p.g == 2) return launch_split_gh<D, 2, EXACT>(p, a, st);
   return launch_split_gh<D, 1, EXACT>(p, a, st);
 }
 
