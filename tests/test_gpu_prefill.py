@@ -124,3 +124,39 @@ def test_packed_batch_of_one_equals_the_dense_call_and_max_seqlen_only_sizes_the
     assert bool(torch.isfinite(res[0][0]).all())
     with pytest.raises(G.sa.SegattnError):
         G.sa.seg_attn_fwd_varlen(cfg, qd[0], kd[0], vd[0], cu, 700, 701, o2, l2, st)   # max_seqlen > total
+
+
+def test_stateless_forward_replays_from_a_captured_graph():
+    """seg_attn_fwd_seq enqueues kernels only: captured once (after a warm-up call, which sets the
+    kernel's shared-memory attribute), every replay on new inputs must equal the eager result,
+    with eager launches and synchronisations between the replays."""
+    import gpu_util as G
+    w = W.small("graph", index=142, seq_len=900, seg_len=256, tail_len=64, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                kv_policy=[3, 1])
+    cfg = G.config_of(w, out_fp32=True, batch=1)
+    q, k, v = W.prefill_inputs(w)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    out = torch.empty((1, 900, 8, 128), dtype=torch.float32, device="cuda")
+    lse = torch.empty((1, 8, 900), dtype=torch.float32, device="cuda")
+    out_e, lse_e = torch.empty_like(out), torch.empty_like(lse)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, 900, out, lse, side.cuda_stream)   # warm-up outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, 900, out, lse, torch.cuda.current_stream().cuda_stream)
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for _ in range(4):
+        for t in (qd, kd, vd):   # new inputs in the captured buffers
+            t.copy_(torch.randn(t.shape, device="cuda", generator=gen).to(torch.bfloat16))
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, 900, out_e, lse_e, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out_e) and torch.equal(lse, lse_e)
+    bits = [t.view(torch.int16).cpu().numpy().view(np.uint16) for t in (qd, kd, vd)]   # the last inputs
+    o_ref, l_ref = _oracle(w, *bits)
+    G.assert_parity(G.to_f64(out), G.to_f64(lse), o_ref, l_ref, fp32_check=False, what="graph replay")
