@@ -300,3 +300,12 @@ def test_whole_prompt_commit_rejects_an_open_segment_and_an_overfull_pool():
         assert sa.seg_kv_lengths(c.ctx, 1, 2) == ([[0, 0]], [0], [10])   # refused calls changed nothing
     finally:
         c.close()
+
+
+def test_decode_many_short_windows():
+    """600 windows of 1 to 100 rows: every thread of a split workgroup sums a run of several windows
+    to find where its slice starts, and one slice covers dozens of whole windows."""
+    S, T, B = 32, 8, 150
+    w = W.Workload("dec_many", 222, B, 0, 8, 4, 64, S, T, (1, 3, 0, 2), decode=True, max_context=S * 4)
+    rng = np.random.default_rng(222)
+    _decode_from_restored_cache(w, rng.integers(1, 3, size=B), rng.integers(1, S + 1, size=B))
