@@ -900,7 +900,8 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t
   const long long per_head = (long long)p.B * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
   const long long grid = per_head * ((long long)p.n_past * a.parts + (p.Hkv - p.n_past));
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  a.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * a.n_seg);
+  const int n_first = (a.cache != nullptr && a.geom.ret_cap > 0) ? 0 : p.n_past;  // as in resolve()
+  a.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - n_first) * (p.g / hs) * a.n_seg);
   if (a.parts > 1) {
     a.part_out = (float *)(a.cache + a.geom.part_off);
     a.part_lse = a.part_out + (long long)p.B * a.parts * a.n_rows * p.n_past * p.g * p.D;

@@ -37,12 +37,16 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   WorkItem w;
   const int nhs = p.g / heads_per_wg;
   const int nqb = a.q_blocks_per_seg;
-  const int n_other = p.Hkv - p.n_past;
+  // heads listed first, longest work first: the PAST heads -- unless they attend to a retrieved
+  // prefix of bounded size, in which case their key ranges are as short as everybody's and all
+  // heads go into the common list below
+  const int n_first = (a.cache != nullptr && a.geom.ret_cap > 0) ? 0 : p.n_past;
+  const int n_other = p.Hkv - n_first;
   const int parts = (a.cache != nullptr && a.parts > 1) ? a.parts : 1;
-  const long long past_items = (long long)p.B * p.n_past * nhs * a.n_seg * nqb * parts;
+  const long long past_items = (long long)p.B * n_first * nhs * a.n_seg * nqb * parts;
   int seg, qblk, hidx, b, hs, part = 0;
   if (bid < past_items) {
-    const int per = p.B * p.n_past * nhs * parts;
+    const int per = p.B * n_first * nhs * parts;
     const int gq = a.n_seg * nqb - 1 - bid / per;
     int rest = bid % per;
     part = rest % parts;
@@ -51,8 +55,8 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     qblk = gq % nqb;
     hs = rest % nhs;
     rest /= nhs;
-    hidx = rest % p.n_past;
-    b = rest / p.n_past;
+    hidx = rest % n_first;
+    b = rest / n_first;
   } else {
     // Heads without the PAST bit: the query blocks of one (sequence, head, segment) read the same
     // few MB of K/V, so they should run at the same time behind the same L2.  Workgroups go to the
@@ -78,7 +82,7 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     int rest = (int)((L / nqb) * (a.pair_stride > 0 ? a.pair_stride : 1) % groups);
     hs = rest % nhs;
     rest /= nhs;
-    hidx = p.n_past + rest % n_other;
+    hidx = n_first + rest % n_other;
     rest /= n_other;
     b = rest % p.B;
     seg = rest / p.B;
