@@ -3,20 +3,27 @@
 // conditioning on x_<t, C_{i-1}, R_{i-1}).  The work is HBM-bound (every visible K and V row
 // is read once per KV head and serves the g query heads of the group), so it is a split-K
 // reduction over an even partition of the rows:
-//   decode_split_kernel    the windows of all (sequence, KV head) pairs are laid end to end and cut
+//   split kernel           the windows of all (sequence, KV head) pairs are laid end to end and cut
 //                          into one slice of rows_per_wg rows per workgroup, as many workgroups as
-//                          the chip holds at once.  A workgroup streams its slice with 16-byte
-//                          coalesced loads (D/8 lanes per key row), forms the g dot products per
-//                          row with a DPP reduction inside each lane group, keeps an online-softmax
-//                          state per lane group, and at the end of every window it touches merges
-//                          the groups with wave shuffles and the four waves through LDS and writes
-//                          one partial (acc[D], m, l) per query head.
+//                          the chip holds at once; at the end of every window a workgroup touches
+//                          it writes one partial (acc[D], m, l) per query head.
 //   decode_combine_kernel  one workgroup per (b, query head): merges the partials of its window.
 // Equal slices instead of fixed chunks: no empty workgroups, no uneven tail, and few partials --
 // the partials' stores, spread over tens of MB in the middle of the read stream, cost a fixed-chunk
 // version 13 % of its time.
+// Two split kernels.  The bf16 path runs on the matrix cores (segattn_decode_mfma.hip).  The one
+// in this file works on the vector ALUs: a workgroup streams its slice with 16-byte coalesced
+// loads (D/8 lanes per key row), forms the dot products per row with v_dot2 and a DPP reduction
+// inside each lane group, keeps an online-softmax state per lane group and merges the groups with
+// wave shuffles and the four waves through LDS.  It is the fp32 validation form (EXACT: fp32 FMAs,
+// unrounded weights); its bf16 instantiations (SEGATTN_DECODE_MFMA_MIN_G above the group size
+// selects them) reach the same speed for groups of up to four heads and are bound by their ~150
+// instructions per row and lane group beyond that.
 #include "segattn_internal.h"
 
+#ifndef SEGATTN_DECODE_MFMA_MIN_G
+#define SEGATTN_DECODE_MFMA_MIN_G 1
+#endif
 #ifndef SEGATTN_DECODE_WAVES
 #define SEGATTN_DECODE_WAVES 3
 #endif
@@ -25,28 +32,6 @@
 #endif
 
 namespace segattn {
-
-__device__ inline const int *meta_ro(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b,
-                                     int h) {
-  return (const int *)(cache + g.meta_off) + ((long long)b * p.Hkv + h) * kMetaInts;
-}
-
-// The split-K workspace: one int per (b, KV head) window (number of partials written), then the
-// partial slots.
-__device__ inline int *ws_counts(unsigned char *cache, const CacheGeom &g) { return (int *)(cache + g.ws_off); }
-__device__ inline float *ws_slots(unsigned char *cache, const CacheGeom &g, const Problem &p) {
-  return (float *)(cache + g.ws_off + ws_header_bytes(p));
-}
-// split-K slots (ws_slot_floats(D) floats each) before those of (b, query head)
-__device__ inline long long ws_slot_base(const Problem &p, const CacheGeom &g, int b, int head) {
-  const int kv = head / p.g;
-  const long long np = p.past_before[kv];
-  const long long per_seq = (long long)p.g * ((long long)p.n_past * g.ws_splits_past +
-                                              (long long)(p.Hkv - p.n_past) * g.ws_splits_other);
-  const long long before = (long long)p.g * (np * g.ws_splits_past + (kv - np) * g.ws_splits_other);
-  const long long mine = (p.policy[kv] & SEGATTN_PAST) ? g.ws_splits_past : g.ws_splits_other;
-  return (long long)b * per_seq + before + (long long)(head % p.g) * mine;
-}
 
 // sum over the LPR lanes of a lane group (LPR = 8 or 16), result in every lane of the group
 template <int LPR>
@@ -422,6 +407,20 @@ static hipError_t launch_split_gh(const Problem &p, DecodeArgs a, hipStream_t st
 template <int D, bool EXACT>
 static hipError_t launch_split(const Problem &p, const DecodeArgs &a, hipStream_t st) {
   if (a.total_rows < 1) return hipErrorInvalidValue;
+  if (!EXACT && p.g >= SEGATTN_DECODE_MFMA_MIN_G) {  // larger groups: the matrix-core form (segattn_decode_mfma.hip)
+    const int resident = decode_mfma_resident(D);
+    if (resident == 0) return hipErrorUnknown;
+    DecodeArgs a2 = a;
+    long long per = (a.total_rows + resident - 1) / resident;
+    if (per < a.geom.decode_chunk) per = a.geom.decode_chunk;
+    per = (per + 127) / 128 * 128;
+    if (per > 0x7fffff00LL) return hipErrorInvalidValue;
+    a2.rows_per_wg = (int)per;
+    const hipError_t e = launch_decode_split_mfma(p, a2, (a.total_rows + per - 1) / per, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(p.B * p.Hq), dim3(256), 0, st, p, a2);
+    return hipGetLastError();
+  }
   // heads per pass: the smallest of 1, 2, 4, 8 that covers the group (8 for larger groups)
   if (p.g > 4) return launch_split_gh<D, 8, EXACT>(p, a, st);
   if (p.g > 2) return launch_split_gh<D, 4, EXACT>(p, a, st);

@@ -233,6 +233,30 @@ __host__ __device__ inline void window_of(const Problem &p, const CacheGeom &g, 
   }
 }
 
+// ---- decode: counters and split-K workspace (device side) ---------------------------------------
+__device__ inline const int *meta_ro(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b,
+                                     int h) {
+  return (const int *)(cache + g.meta_off) + ((long long)b * p.Hkv + h) * kMetaInts;
+}
+
+// The split-K workspace: one int per (b, KV head) window (number of partials written), then the
+// partial slots.
+__device__ inline int *ws_counts(unsigned char *cache, const CacheGeom &g) { return (int *)(cache + g.ws_off); }
+__device__ inline float *ws_slots(unsigned char *cache, const CacheGeom &g, const Problem &p) {
+  return (float *)(cache + g.ws_off + ws_header_bytes(p));
+}
+// split-K slots (ws_slot_floats(D) floats each) before those of (b, query head)
+__device__ inline long long ws_slot_base(const Problem &p, const CacheGeom &g, int b, int head) {
+  const int kv = head / p.g;
+  const long long np = p.past_before[kv];
+  const long long per_seq = (long long)p.g * ((long long)p.n_past * g.ws_splits_past +
+                                              (long long)(p.Hkv - p.n_past) * g.ws_splits_other);
+  const long long before = (long long)p.g * (np * g.ws_splits_past + (kv - np) * g.ws_splits_other);
+  const long long mine = (p.policy[kv] & SEGATTN_PAST) ? g.ws_splits_past : g.ws_splits_other;
+  return (long long)b * per_seq + before + (long long)(head % p.g) * mine;
+}
+
+
 // ---- launchers (defined in the .hip files) ------------------------------------------------
 hipError_t launch_prefill(const Problem &p, const PrefillArgs &a, hipStream_t st);
 // bytes of split-prefix workspace for `parts` pieces (fp32 outputs + LSEs of one segment of every sequence)
@@ -240,6 +264,8 @@ __host__ __device__ inline unsigned long long part_ws_bytes(const Problem &p, in
   return (unsigned long long)p.B * parts * p.S * p.n_past * p.g * (unsigned long long)(p.D + 1) * 4ull;
 }
 hipError_t launch_decode(const Problem &p, const DecodeArgs &a, int B, hipStream_t st);
+int decode_mfma_resident(int D);  // workgroups of the matrix-core split kernel the chip holds at once (0: error)
+hipError_t launch_decode_split_mfma(const Problem &p, const DecodeArgs &a, long long blocks, hipStream_t st);
 hipError_t launch_cache_reset(const Problem &p, unsigned char *cache, const CacheGeom &g, hipStream_t st);
 hipError_t launch_cache_append(const Problem &p, const CopyArgs &a, hipStream_t st);
 hipError_t launch_cache_commit_seq(const Problem &p, const CopyArgs &a, hipStream_t st);
