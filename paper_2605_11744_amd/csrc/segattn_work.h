@@ -49,6 +49,10 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     const int per = p.B * n_first * nhs * parts;
     const int gq = a.n_seg * nqb - 1 - bid / per;
     int rest = bid % per;
+    // Packed batch of unequal sequences: the workgroups of one query block index are `per` in a
+    // row, and where `per` is a multiple of 8 a given (sequence, head) would meet the same XCD at
+    // every index -- the long sequences' XCDs would work on while the others idle.  Rotate.
+    if (a.cu_seqlens) rest = (rest + bid / per) % per;
     part = rest % parts;
     rest /= parts;
     seg = gq / nqb;
