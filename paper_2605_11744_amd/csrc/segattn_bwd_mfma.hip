@@ -45,11 +45,18 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
   __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][T::kBytes];  // [buffer][Q,dO]
   __shared__ __attribute__((aligned(16))) float stats[2][2][kBwdStep];                                       // [buffer][lse*log2e, delta]
 
-  // blockIdx -> (key block inside its segment, segment, kv head, b); blocks near the start of a
-  // segment have the most queries after them and come first
+  // blockIdx -> (key block, segment, kv head, b), longest work first: the key blocks that reach
+  // into the carried tail come first (they also see the whole next segment), then the others from
+  // the start of the segment on.  The (segment, head, sequence) of a workgroup rotates with the
+  // block index: workgroups go to the XCDs round-robin in index order, and with a fixed assignment
+  // an XCD would see one segment only -- the last segment's blocks have no next segment and are a
+  // third shorter, so half of the XCDs would wait for the other half.
   const int per = n_seg * p.Hkv * p.B;
-  const int kb = blockIdx.x / per;
-  int rest = blockIdx.x % per;
+  const int ord = blockIdx.x / per;
+  const int kb_tail = (int)((p.S - p.T) / BK);  // first key block with keys in the tail
+  const int n_tail = p.T > 0 && kb_tail < blocks_per_seg ? blocks_per_seg - kb_tail : 0;
+  const int kb = ord < n_tail ? kb_tail + ord : ord - n_tail;
+  int rest = (blockIdx.x % per + ord) % per;
   const int seg = rest % n_seg;
   rest /= n_seg;
   const int kv = rest % p.Hkv;
