@@ -19,7 +19,7 @@
 // unrounded weights); its bf16 instantiations (SEGATTN_DECODE_MFMA_MIN_G above the group size
 // selects them) reach the same speed for groups of up to four heads and are bound by their ~150
 // instructions per row and lane group beyond that.
-#include "segattn_internal.h"
+#include "segattn_decode_slices.h"
 
 #ifndef SEGATTN_DECODE_MFMA_MIN_G
 #define SEGATTN_DECODE_MFMA_MIN_G 1
@@ -78,58 +78,14 @@ __global__ __launch_bounds__(256, GH == 8 ? 2 : SEGATTN_DECODE_WAVES) void decod
   const int grp = lane / LPR, li = lane % LPR;
   const float c = p.scale_log2e;
 
-  __shared__ long long sm_run[256];
-  __shared__ int sm_start[2];
   __shared__ float sm_m[4][GH], sm_l[4][GH];
   __shared__ __align__(16) float sm_acc[4][GH][D];
 
-  // rows of window w = (b, kv) in the order b * Hkv + kv
-  auto window = [&](int w, int &lo, int &hi) {
-    const int kv = w % p.Hkv;
-    const int *meta = meta_ro(a.cache, a.geom, p, w / p.Hkv, kv);
-    int seg_row0;
-    window_of(p, a.geom, kv, meta, lo, seg_row0);
-    hi = seg_row0 + meta[META_FILL];
-  };
-
-  // ---- where this workgroup's slice [start, start + rows_per_wg) of the concatenated windows begins:
-  //      every thread adds up a run of windows, thread 0 walks the 256 run sums and then the run
+  // ---- where this workgroup's slice [start, start + rows_per_wg) of the concatenated windows begins
   const int n_win = p.B * p.Hkv;
-  const int run = (n_win + 255) / 256;
   const long long start = (long long)blockIdx.x * a.rows_per_wg;
-  {
-    long long sum = 0;
-    for (int j = 0; j < run; ++j) {
-      const int w = tid * run + j;
-      if (w < n_win) {
-        int lo, hi;
-        window(w, lo, hi);
-        sum += hi - lo;
-      }
-    }
-    sm_run[tid] = sum;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    long long before = 0;
-    int t = 0;
-    while (t < 256 && before + sm_run[t] <= start) before += sm_run[t++];
-    int w = t * run, found = -1;
-    for (int j = 0; t < 256 && j < run && w < n_win; ++j, ++w) {
-      int lo, hi;
-      window(w, lo, hi);
-      if (before + (hi - lo) > start) {
-        found = w;
-        break;
-      }
-      before += hi - lo;
-    }
-    sm_start[0] = found;
-    sm_start[1] = (int)(start - before);
-  }
-  __syncthreads();
-  int w = __builtin_amdgcn_readfirstlane(sm_start[0]);
-  int off = __builtin_amdgcn_readfirstlane(sm_start[1]);  // rows of window w that earlier workgroups take
+  int w, off;
+  decode_slice_start(p, a, start, w, off);
   if (w < 0) return;  // the slices before this one cover every row
   // this workgroup's ordinal among those that touch window w (windows it enters later start in it)
   int split = (int)((long long)blockIdx.x - (start - off) / a.rows_per_wg);
@@ -140,7 +96,7 @@ __global__ __launch_bounds__(256, GH == 8 ? 2 : SEGATTN_DECODE_WAVES) void decod
   for (; remaining > 0 && w < n_win; ++w, off = 0, split = 0) {
     const int b = w / p.Hkv, kv = w % p.Hkv;
     int lo, hi;
-    window(w, lo, hi);
+    decode_window_rows(p, a, w, lo, hi);
     lo = __builtin_amdgcn_readfirstlane(lo);
     hi = __builtin_amdgcn_readfirstlane(hi);
     const int c0 = lo + off;

@@ -13,7 +13,7 @@
 // partials (acc[D], m, l) and the same combine kernel as that form.  A wave owns every fourth tile
 // of the slice; tiles go HBM -> registers (one tile ahead) -> a wave-private LDS tile with the
 // prefill kernel's chunk swizzles -> operands, so the loop needs no barrier.
-#include "segattn_internal.h"
+#include "segattn_decode_slices.h"
 
 namespace segattn {
 
@@ -58,55 +58,13 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma_kernel(const Problem
 
   // [K tile | V tile] per wave; the merge of the four waves at the end of a window reuses it
   __shared__ __attribute__((aligned(1024))) unsigned char tiles[4][2 * kTileBytes];
-  __shared__ long long sm_run[256];
-  __shared__ int sm_start[2];
   static_assert(4 * 2 * kTileBytes >= (int)sizeof(float) * 4 * kDecHeads * (D + 2), "merge area fits the tiles");
 
-  auto window = [&](int w, int &lo, int &hi_) {
-    const int kv = w % p.Hkv;
-    const int *meta = meta_ro(a.cache, a.geom, p, w / p.Hkv, kv);
-    int seg_row0;
-    window_of(p, a.geom, kv, meta, lo, seg_row0);
-    hi_ = seg_row0 + meta[META_FILL];
-  };
-
-  // ---- where this workgroup's slice begins (as in the vector-ALU kernel)
+  // ---- where this workgroup's slice begins
   const int n_win = p.B * p.Hkv;
-  const int run = (n_win + 255) / 256;
   const long long start = (long long)blockIdx.x * a.rows_per_wg;
-  {
-    long long sum = 0;
-    for (int j = 0; j < run; ++j) {
-      const int w = tid * run + j;
-      if (w < n_win) {
-        int lo, hi_;
-        window(w, lo, hi_);
-        sum += hi_ - lo;
-      }
-    }
-    sm_run[tid] = sum;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    long long before = 0;
-    int t = 0;
-    while (t < 256 && before + sm_run[t] <= start) before += sm_run[t++];
-    int w = t * run, found = -1;
-    for (int j = 0; t < 256 && j < run && w < n_win; ++j, ++w) {
-      int lo, hi_;
-      window(w, lo, hi_);
-      if (before + (hi_ - lo) > start) {
-        found = w;
-        break;
-      }
-      before += hi_ - lo;
-    }
-    sm_start[0] = found;
-    sm_start[1] = (int)(start - before);
-  }
-  __syncthreads();
-  int w = __builtin_amdgcn_readfirstlane(sm_start[0]);
-  int off = __builtin_amdgcn_readfirstlane(sm_start[1]);
+  int w, off;
+  decode_slice_start(p, a, start, w, off);
   if (w < 0) return;
   int split = (int)((long long)blockIdx.x - (start - off) / a.rows_per_wg);
   int remaining = a.rows_per_wg;
@@ -139,7 +97,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma_kernel(const Problem
   for (; remaining > 0 && w < n_win; ++w, off = 0, split = 0) {
     const int b = w / p.Hkv, kv = w % p.Hkv;
     int lo, hi_;
-    window(w, lo, hi_);
+    decode_window_rows(p, a, w, lo, hi_);
     lo = __builtin_amdgcn_readfirstlane(lo);
     hi_ = __builtin_amdgcn_readfirstlane(hi_);
     const int c0 = lo + off;
