@@ -36,17 +36,46 @@ __device__ inline const int *rmeta(const unsigned char *cache, const CacheGeom &
 // (value, row) pairs ordered by value descending, then row ascending
 __device__ inline bool better(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
 
-// Workgroup-wide best (value, row); every thread gets the result.  sm: 2 * 4 words of LDS.
-__device__ inline void block_best(float &v, int &i, float *sm_v, int *sm_i) {
-#pragma unroll
-  for (int sh = 32; sh >= 1; sh >>= 1) {
-    const float w = __shfl_xor(v, sh);
-    const int j = __shfl_xor(i, sh);
+// Wave-wide best (value, row); every lane gets the result.  The four exchanges inside a row of 16
+// lanes are DPP moves (a register-to-register step of a few cycles each), the exchange between
+// rows one LDS-crossbar shuffle, the one between half-waves a lane swap: a third of the latency of
+// six crossbar shuffles, and this reduction sits inside loops of n_anchors rounds.
+__device__ inline void wave_best(float &v, int &i) {
+#define SEGATTN_BEST_STEP(CTRL)                                                                         \
+  do {                                                                                                \
+    const float w_ = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true)); \
+    const int j_ = __builtin_amdgcn_mov_dpp(i, CTRL, 0xF, 0xF, true);                                   \
+    if (better(w_, j_, v, i)) {                                                                       \
+      v = w_;                                                                                         \
+      i = j_;                                                                                         \
+    }                                                                                                 \
+  } while (0)
+  SEGATTN_BEST_STEP(0xB1);   // quad_perm [1,0,3,2]
+  SEGATTN_BEST_STEP(0x4E);   // quad_perm [2,3,0,1]
+  SEGATTN_BEST_STEP(0x141);  // row_half_mirror
+  SEGATTN_BEST_STEP(0x140);  // row_mirror: all 16 lanes of a row agree
+#undef SEGATTN_BEST_STEP
+  {
+    const float w = __shfl_xor(v, 16);
+    const int j = __shfl_xor(i, 16);
     if (better(w, j, v, i)) {
       v = w;
       i = j;
     }
   }
+  {  // the two halves: one element of each pair is the lane's own value, the other its partner's
+    const auto sv = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+    const auto si = __builtin_amdgcn_permlane32_swap(i, i, false, false);
+    const float v0 = __int_as_float(sv[0]), v1 = __int_as_float(sv[1]);
+    const bool second = better(v1, si[1], v0, si[0]);
+    v = second ? v1 : v0;
+    i = second ? si[1] : si[0];
+  }
+}
+
+// Workgroup-wide best (value, row); every thread gets the result.  sm: 2 * 4 words of LDS.
+__device__ inline void block_best(float &v, int &i, float *sm_v, int *sm_i) {
+  wave_best(v, i);
   const int wave = threadIdx.x >> 6;
   __syncthreads();
   if ((threadIdx.x & 63) == 0) {
@@ -209,15 +238,7 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
       }
     float v = bv;
     int i = bi;
-#pragma unroll
-    for (int sh = 32; sh >= 1; sh >>= 1) {
-      const float w = __shfl_xor(v, sh);
-      const int j = __shfl_xor(i, sh);
-      if (better(w, j, v, i)) {
-        v = w;
-        i = j;
-      }
-    }
+    wave_best(v, i);
     if (lane == 0) {
       wl_v[wave][r] = v;
       wl_i[wave][r] = v == -INFINITY ? 0x7fffffff : i;
@@ -325,15 +346,7 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
           }
         float v = bv;
         int i = bi;
-#pragma unroll
-        for (int sh = 32; sh >= 1; sh >>= 1) {
-          const float w = __shfl_xor(v, sh);
-          const int j = __shfl_xor(i, sh);
-          if (better(w, j, v, i)) {
-            v = w;
-            i = j;
-          }
-        }
+        wave_best(v, i);
         if (v == -INFINITY) break;
         if (tid == 0) anchors[r] = i;
         n_anch = r + 1;
