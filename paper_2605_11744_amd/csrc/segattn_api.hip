@@ -468,24 +468,31 @@ segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t 
 
 namespace {
 constexpr int kRetrieveCand = 32;
-// Pool rows per scoring workgroup: 4096, or 1024 where that would leave the chip short of work --
-// fewer chunks with visible rows than four rounds of resident workgroups (3 per CU), where the
-// last, partly filled round costs more than the extra per-chunk selections.  The workspace is
-// sized for the small chunks.
-constexpr int kRetrieveChunkSmall = 1024, kRetrieveChunkBig = 4096;
+// Pool rows per scoring workgroup.  4096 where that still fills the chip four times over (3
+// workgroups per CU); else 1024 -- a last, partly filled round of 1 MB workgroups costs more than
+// the extra per-chunk selections; and 512 where even 1024-row chunks are fewer than the CUs (one
+// segment's retrieval on a single sequence: the call is then as long as one workgroup's chain
+// of tiles, and halving the chain halves it) as long as the merge kernel's fast path still holds
+// the lists (256 per head).  The workspace is sized for the smallest chunks.
+constexpr int kRetrieveChunkTiny = 512, kRetrieveChunkSmall = 1024, kRetrieveChunkBig = 4096;
 int retrieve_chunk_rows(const segattn_ctx *ctx) {
 #ifdef SEGATTN_RETRIEVE_CHUNK
   return SEGATTN_RETRIEVE_CHUNK;
 #endif
   const Problem &p = ctx->p;
-  long long active = 0;
+  long long active_big = 0, active_small = 0, longest = 0;
   for (int b = 0; b < p.B; ++b)
     for (int h = 0; h < p.Hkv; ++h) {
       const size_t i = (size_t)b * p.Hkv + h;
-      if ((p.policy[h] & SEGATTN_PAST) && ctx->pool[i] > ctx->lo[i])
-        active += (ctx->pool[i] - 1) / kRetrieveChunkBig - ctx->lo[i] / kRetrieveChunkBig + 1;
+      if ((p.policy[h] & SEGATTN_PAST) && ctx->pool[i] > ctx->lo[i]) {
+        active_big += (ctx->pool[i] - 1) / kRetrieveChunkBig - ctx->lo[i] / kRetrieveChunkBig + 1;
+        active_small += (ctx->pool[i] - 1) / kRetrieveChunkSmall - ctx->lo[i] / kRetrieveChunkSmall + 1;
+        if (ctx->pool[i] > longest) longest = ctx->pool[i];
+      }
     }
-  return active >= 4 * 3 * 256 ? kRetrieveChunkBig : kRetrieveChunkSmall;
+  if (active_big >= 4 * 3 * 256) return kRetrieveChunkBig;
+  if (active_small < 256 && (longest + kRetrieveChunkTiny - 1) / kRetrieveChunkTiny <= 256) return kRetrieveChunkTiny;
+  return kRetrieveChunkSmall;
 }
 bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &nsp, int &n_chunks,
                       unsigned long long &off_val, unsigned long long &off_idx, unsigned long long &total) {
@@ -497,7 +504,7 @@ bool retrieval_layout(const segattn_ctx *ctx, const segattn_retrieval *r, int &n
   const long long n_sum = (long long)(r->n_queries + r->pool_window - 1) / r->pool_window + 1;
   if (n_sum * ctx->p.g > 64) return false;
   nsp = (int)((n_sum * ctx->p.g + 31) / 32 * 32);
-  n_chunks = (int)((ctx->g.pool_cap + kRetrieveChunkSmall - 1) / kRetrieveChunkSmall);  // the most a call can use
+  n_chunks = (int)((ctx->g.pool_cap + kRetrieveChunkTiny - 1) / kRetrieveChunkTiny);  // the most a call can use
   const unsigned long long heads = (unsigned long long)ctx->p.B * ctx->p.n_past;
   off_val = align_up(heads * nsp * ctx->p.D * 2ull);
   off_idx = align_up(off_val + heads * n_chunks * kRetrieveCand * 4ull);

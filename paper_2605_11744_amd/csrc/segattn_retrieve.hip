@@ -497,7 +497,8 @@ hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t 
   const int nt = a.nsp / 32;
 #define SEGATTN_SCORE(DD, NTT)                                                                            \
   do {                                                                                                    \
-    if (a.chunk_rows == 1024) hipLaunchKernelGGL((retrieve_score_kernel<DD, NTT, 1024>), grid, dim3(256), 0, st, p, a); \
+    if (a.chunk_rows == 512) hipLaunchKernelGGL((retrieve_score_kernel<DD, NTT, 512>), grid, dim3(256), 0, st, p, a); \
+    else if (a.chunk_rows == 1024) hipLaunchKernelGGL((retrieve_score_kernel<DD, NTT, 1024>), grid, dim3(256), 0, st, p, a); \
     else hipLaunchKernelGGL((retrieve_score_kernel<DD, NTT, 4096>), grid, dim3(256), 0, st, p, a);         \
   } while (0)
   if (p.D == 128) {
