@@ -80,6 +80,8 @@ struct PrefillArgs {
   int n_seg;             // segments covered by the launch (1 in CTX mode)
   int q_blocks_per_seg;  // ceil(min(S, n_rows) / rows per workgroup); set by the launcher
   int pair_stride;       // spreads the (segment, sequence, head) groups of non-PAST heads over the XCDs (0 = 1)
+  int sub_groups;        // a group's query blocks are dealt into this many interleaved sub-groups (0 = 1) so that
+                         // every XCD's share of the non-PAST list is a whole number of (sub-)groups
   // CTX mode, split prefix: the prefix of every PAST head is cut into `parts` pieces, each handled
   // by a workgroup of its own (the last one also takes the open segment); the pieces' normalised
   // fp32 outputs and their LSEs go to the workspace and prefill_part_combine_kernel merges them.

@@ -77,8 +77,17 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
       if (xx < x) start += cnt;
       if (xx == x) first = past_items + o;
     }
-    const long long L = start + ((bid - first) >> 3);
-    qblk = nqb - 1 - (int)(L % nqb);
+    long long L = start + ((bid - first) >> 3);
+    // Position L of the list -> (group, query block).  The XCDs advance in step (workgroups are
+    // dispatched in index order), so the j-th blocks of all XCDs should be equally long: that holds
+    // if every XCD's range is a whole number of groups.  Where the group count is no multiple of 8
+    // the launcher deals each group's blocks into d interleaved sub-groups (block q belongs to
+    // sub-group (nqb-1-q) % d), each with the group's length profile, and the list runs over those.
+    const int d = a.sub_groups > 1 ? a.sub_groups : 1;
+    const int per_sub = nqb / d;
+    const long long sg = L / per_sub;
+    qblk = nqb - 1 - ((int)(sg % d) + d * (int)(L % per_sub));
+    L = (sg / d) * nqb;  // first position of the group, for the group index below
     // Consecutive groups differ little in length for a dense batch but a lot for a ragged one (a
     // whole range of them can be empty): a multiplicative shuffle of the group index (stride
     // coprime to the group count, about an eighth of it) deals each XCD an even sample.

@@ -156,3 +156,18 @@ def test_ragged_batch_full_size_sampled_rows():
         o_gpu = G.to_f64(out.index_select(0, idx))[None]
         l_gpu = G.to_f64(lse.index_select(1, idx))[None]
         _check_rows(w_b, q[:, lo:lo + n], k[:, lo:lo + n], v[:, lo:lo + n], o_gpu, l_gpu, rows, True)
+
+
+@pytest.mark.parametrize("kv_policy,n_kv", [([0, 1], 2), ([1, 0, 0], 3)])
+def test_one_long_segment_sampled_rows(kv_policy, n_kv):
+    """A single segment of 9216 rows (plain causal attention: S >= N): its K/V exceed one L2, so
+    the library deals each head's query blocks to the XCDs in interleaved sub-groups (four per
+    head with two heads, eight with three).  Every row written and finite, sampled rows against
+    the oracle."""
+    import gpu_util as G
+    w = W.small("one_seg", index=150 + n_kv, seq_len=9216, seg_len=9216, tail_len=0, n_q_heads=2 * n_kv,
+                n_kv_heads=n_kv, head_dim=128, kv_policy=kv_policy)
+    q, k, v, out, lse = _run_full(w, bf16_out=False)
+    rows = _sample_rows(w, 48, seed=151)
+    idx = torch.from_numpy(rows).cuda()
+    _check_rows(w, q, k, v, G.to_f64(out.index_select(1, idx)), G.to_f64(lse.index_select(2, idx)), rows, False)
