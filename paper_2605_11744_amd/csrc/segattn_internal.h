@@ -89,7 +89,12 @@ struct PrefillArgs {
   long long min_past_prefix;  // host: fewest prefix rows among the PAST windows (sets how far to split)
   float *part_out;       // [B][parts][n_rows][n_past*g][D]
   float *part_lse;       // [B][parts][n_past*g][n_rows]
+  // Work items of the launch (0: the grid size) and, where the workgroups take their items from
+  // queues, the counters: next item of XCD y's queue at queue[kQueueStride * y], zero at the start.
+  int grid_items;
+  unsigned *queue;       // device; nullptr: workgroup i runs item i
 };
+constexpr int kQueueStride = 32;  // unsigned words between two queue counters (128 bytes)
 
 struct DecodeArgs {
   const unsigned short *q, *k_new, *v_new;

@@ -38,6 +38,8 @@
 // through the same counter the K/V prefetch uses, and waiting for it drains the prefetch queue.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include <type_traits>
 
 #include "segattn_work.h"
@@ -109,7 +111,8 @@ __device__ inline float half_sum(float x) {
 // then moved O^T at a control-flow merge, the move could read an accumulator whose product
 // was still in the pipeline, and results depended on register allocation.
 template <int D, int HS, int QB, int NW>
-__global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(const Problem p, const PrefillArgs a) {
+__device__ __forceinline__ void prefill_mfma_item(const Problem &p, const PrefillArgs &a, const int bid,
+                                                  unsigned char *const smem) {
   using G = StepGeom<D>;  // NW = waves per workgroup; NW * QB = 4 leaves room for two workgroups per CU
   constexpr int RW = 32 * QB;       // query rows per wave
   constexpr int BQ = (NW / HS) * RW; // query rows per workgroup
@@ -120,9 +123,8 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   constexpr int kSlots = ring_slots(NW, QB);
   constexpr int kAhead = kPair ? 2 : 1;  // whole steps of loads that may still be in flight at a sync
   static_assert(LPW >= 1, "too many waves for this tile");
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-  WorkItem w = resolve(p, a, blockIdx.x, BQ, HS);
+  WorkItem w = resolve(p, a, bid, BQ, HS);
   if (!w.valid) return;
   pin_uniform(w);
 
@@ -750,6 +752,75 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
   }
 }
 
+// Which work item a workgroup runs: its block index (PrefillArgs::queue == nullptr), or the next
+// one of eight queues.
+//
+// The hardware deals the workgroups of a launch to the 8 XCDs by index (XCD = index % 8) and every
+// XCD works through its share at its own pace.  Under this kernel the XCDs of one part differ by
+// 4-8 % in speed (timestamps per workgroup: the same work on each, every CU of an XCD finishing
+// together, the XCDs up to 6 % apart), so with a fixed share each the launch ends with most of
+// the chip waiting for the slowest XCD.  The queued form launches an eighth more workgroups than
+// there are items.  Queue x holds the items x, x+8, ... that XCD x would have been dealt, in the
+// same order, and a workgroup on XCD x takes from queue x first: the L2 locality of the mapping in
+// resolve() is untouched.  Once its own queue is empty a workgroup takes from the queue with the
+// most items left, so a fast XCD spends its spare workgroups on the slowest one's items, and the workgroups
+// left over at the end find every queue empty and leave at once.  Nothing waits for another
+// workgroup.  Each queue's counter has a 128-byte line of its own; a one-wave kernel in front of
+// the launch clears them.
+template <int D, int HS, int QB, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(const Problem p, const PrefillArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int bid = (int)blockIdx.x;
+  if (a.queue != nullptr) {
+    __shared__ int claim;
+    if (threadIdx.x == 0) {
+      auto items_of = [&](int y) { return y < a.grid_items ? (unsigned)(a.grid_items - y + 7) >> 3 : 0u; };
+      const int x = (int)blockIdx.x & 7;
+      int got = -1;
+      const unsigned j0 = atomicAdd(a.queue + kQueueStride * x, 1u);  // the XCD's own queue: one round trip
+      if (j0 < items_of(x)) {
+        got = 8 * (int)j0 + x;
+      } else {
+        // Own queue empty: help the XCD that is furthest behind.  Counters only grow, so a queue
+        // seen empty stays empty; a failed attempt marks its queue empty: at most eight attempts.
+        unsigned left[8];
+#pragma unroll
+        for (int y = 0; y < 8; ++y) {
+          const unsigned at = __hip_atomic_load(a.queue + kQueueStride * y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          left[y] = at < items_of(y) ? items_of(y) - at : 0u;
+        }
+#pragma unroll 1
+        for (int t = 0; t < 8 && got < 0; ++t) {
+          unsigned most = 0;
+          int y = -1;
+#pragma unroll
+          for (int z = 0; z < 8; ++z)
+            if (left[z] > most) {
+              most = left[z];
+              y = z;
+            }
+          if (y < 0) break;
+          const unsigned j = atomicAdd(a.queue + kQueueStride * y, 1u);
+          if (j < items_of(y)) got = 8 * (int)j + y;
+#pragma unroll
+          for (int z = 0; z < 8; ++z)
+            if (z == y) left[z] = 0;
+        }
+      }
+      claim = got;
+    }
+    __syncthreads();
+    bid = __builtin_amdgcn_readfirstlane(claim);
+    if (bid < 0) return;
+  }
+  prefill_mfma_item<D, HS, QB, NW>(p, a, bid, smem);
+}
+
+// Clears a set of queue counters (launched in front of every queued launch, on its stream).
+__global__ void prefill_queue_reset_kernel(unsigned *queue) {
+  if (threadIdx.x < 8) queue[kQueueStride * threadIdx.x] = 0;
+}
+
 // =============================================================================================
 // split prefix (segment-by-segment prefill): merge the pieces
 // =============================================================================================
@@ -798,19 +869,106 @@ hipError_t launch_prefill_fp32(const Problem &p, const PrefillArgs &a, long long
 
 static int heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1; }
 
+// ---- counters of the queued form of the kernel
+// Eight counters per set, each on a 128-byte line of its own.  Launches on one stream run one
+// after the other and share a set; launches on different streams may overlap, so every (device, stream) pair that asks gets a
+// set of its own, for as long as the process lives.  When the sets are used up, and for a stream
+// that is being captured (the graph may later be replayed on any stream, next to anything), the
+// launch falls back to one workgroup per item, which needs no counters.
+static int device_cus();
+
+constexpr int kQueueSets = 64;
+constexpr int kQueueDevices = 16;
+static __device__ unsigned g_queue_sets[kQueueSets][8 * kQueueStride];
+
+static unsigned *queue_for(hipStream_t st) {
+  struct Owner {
+    int dev;
+    hipStream_t st;
+  };
+  static std::mutex mu;
+  static Owner owners[kQueueSets];
+  static int n_owners = 0;
+  static unsigned *base[kQueueDevices] = {};
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  if (cs != hipStreamCaptureStatusNone) return nullptr;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kQueueDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!base[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_queue_sets)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    base[dev] = (unsigned *)ptr;
+  }
+  int set = -1;
+  for (int i = 0; i < n_owners; ++i)
+    if (owners[i].dev == dev && owners[i].st == st) set = i;
+  if (set < 0) {
+    if (n_owners == kQueueSets) return nullptr;
+    owners[n_owners] = Owner{dev, st};
+    set = n_owners++;
+  }
+  return base[dev] + 8 * kQueueStride * set;
+}
+
+// SEGATTN_PREFILL_QUEUE in the environment: 0 = never take items from queues, 1 = always (small
+// test inputs too); unset = for a dense launch with at least 16 times as many items as workgroups
+// fit the chip (taking an item costs a round trip to memory, which a launch of few or short
+// items does not earn back: measured slower below that, and for ragged batches, many of whose
+// items are empty).  Read at every launch.
+static int queue_mode() {
+  if (const char *e = getenv("SEGATTN_PREFILL_QUEUE")) {
+    if (e[0] == '0') return 0;
+    if (e[0] == '1') return 1;
+  }
+  return -1;
+}
+
 template <int D, int HS, int QB, int NW>
-static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a, long long grid, hipStream_t st) {
+static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a_in, long long grid, hipStream_t st) {
   constexpr int ring = ring_slots(NW, QB) * StepGeom<D>::kSlotBytes;
   constexpr int epilogue = NW * 32 * (D * 4 + 8);  // fp32 output staging, one block per wave
   constexpr int lds = ring > epilogue ? ring : epilogue;
   auto kern = prefill_mfma_kernel<D, HS, QB, NW>;
   static bool attr_set = false;
+  static int resident = 0;  // workgroups of this kernel that fit the chip at once (-1: unknown)
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
+    int per_cu = 0;
+    resident = -1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * NW, lds) == hipSuccess && per_cu > 0)
+      resident = per_cu * device_cus();
+    else
+      (void)hipGetLastError();
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), lds, st, p, a);
+  PrefillArgs a = a_in;
+  a.grid_items = (int)grid;
+  a.queue = nullptr;
+  long long launch = grid;
+  const int mode = queue_mode();
+  if (resident > 0 && mode != 0 && (mode == 1 ? grid > 1 : (grid >= 16ll * resident && !a.cu_seqlens))) {
+    a.queue = queue_for(st);
+    if (a.queue) launch = (grid + grid / 8 + 7) / 8 * 8;  // an eighth more, a whole number per XCD
+    if (launch > 0x7fffffffLL) {
+      launch = grid;
+      a.queue = nullptr;
+    }
+    if (a.queue) {
+      hipLaunchKernelGGL(prefill_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)launch), dim3(64 * NW), lds, st, p, a);
   return hipGetLastError();
 }
 

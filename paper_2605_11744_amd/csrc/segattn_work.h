@@ -67,7 +67,7 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     // 8 XCDs (one L2 each) round-robin by index: XCD x = bid % 8 takes the bids x, x+8, ... in
     // order.  Give each XCD a contiguous range of the list ordered by (segment, sequence, head,
     // head sub-group) and, inside one of those, by descending query block.
-    const long long items = (long long)gridDim.x - past_items;
+    const long long items = (long long)(a.grid_items > 0 ? a.grid_items : (int)gridDim.x) - past_items;
     const int x = bid & 7;
     long long start = 0, first = 0;
 #pragma unroll

@@ -29,13 +29,18 @@ STREAM_CASES = [
 ]
 
 
-@pytest.mark.parametrize("waves", ["auto", "4", "8"])
+@pytest.mark.parametrize("waves", ["auto", "4", "8", "queue"])
 @pytest.mark.parametrize("fp32_check", [True, False])
 @pytest.mark.parametrize("case", range(len(STREAM_CASES)))
 def test_streaming_prefill_equals_oracle(case, fp32_check, waves, monkeypatch):
     import gpu_util as G
     kw, chunks = STREAM_CASES[case]
-    if waves != "auto":
+    if waves == "queue":   # the library's own workgroup shape, work items taken from queues
+        if fp32_check:
+            pytest.skip("the item queues only exist in the MFMA kernel")
+        monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+        monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
+    elif waves != "auto":
         if fp32_check or kw["head_dim"] != 128:
             pytest.skip("the wave count only exists in the head_dim-128 MFMA kernel")
         monkeypatch.setenv("SEGATTN_PREFILL_WAVES", waves)

@@ -160,3 +160,76 @@ def test_stateless_forward_replays_from_a_captured_graph():
     bits = [t.view(torch.int16).cpu().numpy().view(np.uint16) for t in (qd, kd, vd)]   # the last inputs
     o_ref, l_ref = _oracle(w, *bits)
     G.assert_parity(G.to_f64(out), G.to_f64(lse), o_ref, l_ref, fp32_check=False, what="graph replay")
+
+
+# ---- work items taken from queues (the form large dense launches use; SEGATTN_PREFILL_QUEUE=1
+# ---- forces it for small inputs, =0 switches it off)
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_fwd_seq_small_with_item_queues(case, monkeypatch):
+    import gpu_util as G
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+    w = W.small(f"small{case}", index=100 + case, **SMALL[case])
+    q, k, v = W.prefill_inputs(w)
+    o_ref, l_ref = _oracle(w, q, k, v)
+    o, l = G.fwd_seq(w, q, k, v, fp32_check=False)
+    G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what=f"small{case}, queued")
+
+
+def _fwd(G, cfg, qd, kd, vd, n, stream=None):
+    out = torch.full((qd.shape[0], n, qd.shape[2], qd.shape[3]), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((qd.shape[0], qd.shape[2], n), float("nan"), dtype=torch.float32, device="cuda")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, n, out, lse, st.cuda_stream)
+    return out, lse
+
+
+def test_item_queues_run_every_item_exactly_once(monkeypatch):
+    """Queued or not, an item is the same arithmetic in the same order: over a few thousand items
+    (more than fit the chip at once, so the order they are taken in varies) the two forms must
+    agree bit for bit, on repeated launches (the counters are cleared in front of each), and a
+    launch that has more workgroups than items must leave nothing unwritten."""
+    import gpu_util as G
+    w = W.small("queued", index=143, seq_len=6000, seg_len=1024, tail_len=256, n_q_heads=16, n_kv_heads=8,
+                head_dim=128, kv_policy=[3, 1, 0, 3, 1, 1, 2, 0], batch=2)
+    cfg = G.config_of(w, out_fp32=True, batch=2)
+    q, k, v = W.prefill_inputs(w)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "0")
+    o0, l0 = _fwd(G, cfg, qd, kd, vd, 6000)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(o0).all())
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+    for _ in range(3):
+        o1, l1 = _fwd(G, cfg, qd, kd, vd, 6000)
+        torch.cuda.synchronize()
+        assert torch.equal(o0, o1) and torch.equal(l0, l1)
+    rows = np.array([0, 1023, 1024, 3071, 5999])
+    o_ref, l_ref = _oracle(w, q, k, v, rows=rows)
+    G.assert_parity(G.to_f64(o1)[:, rows], G.to_f64(l1)[:, :, rows], o_ref, l_ref, fp32_check=False, what="queued")
+
+
+def test_item_queues_on_two_streams_do_not_share_counters(monkeypatch):
+    """Launches on different streams may overlap: each stream has queue counters of its own, so
+    two different problems in flight at once both come out as they do alone."""
+    import gpu_util as G
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+    probs = []
+    for i, n in enumerate((5000, 3333)):
+        w = W.small(f"two{i}", index=144 + i, seq_len=n, seg_len=512, tail_len=128, n_q_heads=16, n_kv_heads=4,
+                    head_dim=128, kv_policy=[3, 1, 1, 2])
+        q, k, v = W.prefill_inputs(w)
+        qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+        cfg = G.config_of(w, out_fp32=True, batch=1)
+        alone = _fwd(G, cfg, qd, kd, vd, n)
+        probs.append((cfg, qd, kd, vd, n, alone))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for _ in range(3):
+        got = []
+        for _rep in range(4):   # several launches per stream, interleaved on the host
+            for (cfg, qd, kd, vd, n, _), s in zip(probs, streams):
+                got.append(_fwd(G, cfg, qd, kd, vd, n, stream=s))
+        torch.cuda.synchronize()
+        for j, (o, l) in enumerate(got):
+            o_a, l_a = probs[j % 2][5]
+            assert torch.equal(o, o_a) and torch.equal(l, l_a)
