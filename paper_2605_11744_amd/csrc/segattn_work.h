@@ -78,8 +78,9 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
       if (xx == x) first = past_items + o;
     }
     long long L = start + ((bid - first) >> 3);
-    // Position L of the list -> (group, query block).  The XCDs advance in step (workgroups are
-    // dispatched in index order), so the j-th blocks of all XCDs should be equally long: that holds
+    // Position L of the list -> (group, query block).  Every XCD takes its workgroups in index
+    // order, so at equal speed the XCDs advance in step and the j-th blocks of all XCDs should
+    // be equally long: that holds
     // if every XCD's range is a whole number of groups.  Where the group count is no multiple of 8
     // the launcher deals each group's blocks into d interleaved sub-groups (block q belongs to
     // sub-group (nqb-1-q) % d), each with the group's length profile, and the list runs over those.
