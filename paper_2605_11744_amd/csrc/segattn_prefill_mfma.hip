@@ -111,8 +111,11 @@ __device__ inline float half_sum(float x) {
 // then moved O^T at a control-flow merge, the move could read an accumulator whose product
 // was still in the pipeline, and results depended on register allocation.
 template <int D, int HS, int QB, int NW>
-__device__ __forceinline__ void prefill_mfma_item(const Problem &p, const PrefillArgs &a, const int bid,
-                                                  unsigned char *const smem) {
+__device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const PrefillArgs &a, const int bid,
+                                                      unsigned char *const smem, unsigned *const next_from) {
+  // next_from: nullptr, or the queue counter this workgroup takes its next item from.  Thread 0
+  // draws the ticket while the output is still being written and hands it back (other threads: 0),
+  // so the round trip is over by the time the next round starts.
   using G = StepGeom<D>;  // NW = waves per workgroup; NW * QB = 4 leaves room for two workgroups per CU
   constexpr int RW = 32 * QB;       // query rows per wave
   constexpr int BQ = (NW / HS) * RW; // query rows per workgroup
@@ -125,10 +128,11 @@ __device__ __forceinline__ void prefill_mfma_item(const Problem &p, const Prefil
   static_assert(LPW >= 1, "too many waves for this tile");
 
   WorkItem w = resolve(p, a, bid, BQ, HS);
-  if (!w.valid) return;
+  if (!w.valid) return (next_from && threadIdx.x == 0) ? atomicAdd(next_from, 1u) : 0u;
   pin_uniform(w);
 
-  const int tid = threadIdx.x;
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // not a loop invariant of the caller's loop (see prefill_mfma_kernel)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int hi = lane >> 5, col = lane & 31;
   const int i16 = lane & 15, g16 = (lane >> 4) & 1;
@@ -704,6 +708,8 @@ __device__ __forceinline__ void prefill_mfma_item(const Problem &p, const Prefil
     }
   }
   SEGATTN_VMCNT(0);  // the loader's surplus loads have landed: the ring may be reused
+  unsigned ticket = 0;
+  if (next_from && tid == 0) ticket = atomicAdd(next_from, 1u);
 
   // ---- epilogue: normalise, write LSE, and write O through LDS so that every store
   // instruction covers whole 16-byte pieces of contiguous output rows.  A lane holds four
@@ -750,70 +756,91 @@ __device__ __forceinline__ void prefill_mfma_item(const Problem &p, const Prefil
     }
     __syncthreads();
   }
+  return ticket;
 }
 
-// Which work item a workgroup runs: its block index (PrefillArgs::queue == nullptr), or the next
-// one of eight queues.
+// One work item per workgroup, the block index (PrefillArgs::queue == nullptr), or a resident
+// grid -- as many workgroups as fit the chip -- that takes item after item from eight queues.
 //
 // The hardware deals the workgroups of a launch to the 8 XCDs by index (XCD = index % 8) and every
 // XCD works through its share at its own pace.  Under this kernel the XCDs of one part differ by
 // 4-8 % in speed (timestamps per workgroup: the same work on each, every CU of an XCD finishing
 // together, the XCDs up to 6 % apart), so with a fixed share each the launch ends with most of
-// the chip waiting for the slowest XCD.  The queued form launches an eighth more workgroups than
-// there are items.  Queue x holds the items x, x+8, ... that XCD x would have been dealt, in the
-// same order, and a workgroup on XCD x takes from queue x first: the L2 locality of the mapping in
+// the chip waiting for the slowest XCD; and between two workgroups a CU idles 4-6 us.  In the
+// queued form queue x holds the items x, x+8, ... that XCD x would have been dealt, in the same
+// order, and a workgroup on XCD x takes from queue x first: the L2 locality of the mapping in
 // resolve() is untouched.  Once its own queue is empty a workgroup takes from the queue with the
-// most items left, so a fast XCD spends its spare workgroups on the slowest one's items, and the workgroups
-// left over at the end find every queue empty and leave at once.  Nothing waits for another
-// workgroup.  Each queue's counter has a 128-byte line of its own; a one-wave kernel in front of
+// most items left, so a fast XCD goes on with the slowest one's items; when all eight are empty
+// it leaves.  Nothing waits for another workgroup.  The ticket for the next round is drawn while
+// the output of this one is being written (prefill_mfma_item), so the round trip to the counter
+// is hidden.  Each queue's counter has a 128-byte line of its own; a one-wave kernel in front of
 // the launch clears them.
 template <int D, int HS, int QB, int NW>
-__global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(const Problem p, const PrefillArgs a) {
+__global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(const Problem p_arg, const PrefillArgs a_arg) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  int bid = (int)blockIdx.x;
-  if (a.queue != nullptr) {
-    __shared__ int claim;
-    if (threadIdx.x == 0) {
-      auto items_of = [&](int y) { return y < a.grid_items ? (unsigned)(a.grid_items - y + 7) >> 3 : 0u; };
-      const int x = (int)blockIdx.x & 7;
-      int got = -1;
-      const unsigned j0 = atomicAdd(a.queue + kQueueStride * x, 1u);  // the XCD's own queue: one round trip
-      if (j0 < items_of(x)) {
-        got = 8 * (int)j0 + x;
-      } else {
-        // Own queue empty: help the XCD that is furthest behind.  Counters only grow, so a queue
-        // seen empty stays empty; a failed attempt marks its queue empty: at most eight attempts.
-        unsigned left[8];
+  __shared__ int claim;
+  constexpr unsigned kArgsAt = (sizeof(Problem) + alignof(PrefillArgs) - 1) / alignof(PrefillArgs) * alignof(PrefillArgs);
+  unsigned ticket = 0;  // thread 0: position drawn from the own queue for this round
+  bool drawn = false;   // ... by the previous round already
+  for (;;) {
+    // The arguments are read through a pointer the compiler cannot see through, once per round
+    // (and the item reads its thread index the same way): read as plain kernel arguments and
+    // built-ins they are loop invariants, everything derived from them is hoisted out of the
+    // loop and stays in registers for all of it, and this kernel has none to spare.
+    const __attribute__((address_space(4))) unsigned char *ka =
+        (const __attribute__((address_space(4))) unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka));
+    const Problem &p = *(const Problem *)ka;
+    const PrefillArgs &a = *(const PrefillArgs *)(ka + kArgsAt);
+    int bid = (int)blockIdx.x;
+    const bool queued = a.queue != nullptr;
+    unsigned *const own = queued ? a.queue + kQueueStride * ((int)blockIdx.x & 7) : nullptr;
+    if (queued) {
+      if (threadIdx.x == 0) {
+        auto items_of = [&](int y) { return y < a.grid_items ? (unsigned)(a.grid_items - y + 7) >> 3 : 0u; };
+        const int x = (int)blockIdx.x & 7;
+        int got = -1;
+        const unsigned j0 = drawn ? ticket : atomicAdd(own, 1u);  // the XCD's own queue
+        if (j0 < items_of(x)) {
+          got = 8 * (int)j0 + x;
+        } else {
+          // Own queue empty: help the XCD that is furthest behind.  Counters only grow, so a queue
+          // seen empty stays empty; a failed attempt marks its queue empty: at most eight attempts.
+          unsigned left[8];
 #pragma unroll
-        for (int y = 0; y < 8; ++y) {
-          const unsigned at = __hip_atomic_load(a.queue + kQueueStride * y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          left[y] = at < items_of(y) ? items_of(y) - at : 0u;
-        }
+          for (int y = 0; y < 8; ++y) {
+            const unsigned at = __hip_atomic_load(a.queue + kQueueStride * y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            left[y] = at < items_of(y) ? items_of(y) - at : 0u;
+          }
 #pragma unroll 1
-        for (int t = 0; t < 8 && got < 0; ++t) {
-          unsigned most = 0;
-          int y = -1;
+          for (int t = 0; t < 8 && got < 0; ++t) {
+            unsigned most = 0;
+            int y = -1;
 #pragma unroll
-          for (int z = 0; z < 8; ++z)
-            if (left[z] > most) {
-              most = left[z];
-              y = z;
-            }
-          if (y < 0) break;
-          const unsigned j = atomicAdd(a.queue + kQueueStride * y, 1u);
-          if (j < items_of(y)) got = 8 * (int)j + y;
+            for (int z = 0; z < 8; ++z)
+              if (left[z] > most) {
+                most = left[z];
+                y = z;
+              }
+            if (y < 0) break;
+            const unsigned j = atomicAdd(a.queue + kQueueStride * y, 1u);
+            if (j < items_of(y)) got = 8 * (int)j + y;
 #pragma unroll
-          for (int z = 0; z < 8; ++z)
-            if (z == y) left[z] = 0;
+            for (int z = 0; z < 8; ++z)
+              if (z == y) left[z] = 0;
+          }
         }
+        claim = got;
       }
-      claim = got;
+      __syncthreads();
+      bid = __builtin_amdgcn_readfirstlane(claim);
+      __syncthreads();  // everyone has read it before thread 0 writes the next one
+      if (bid < 0) return;
     }
-    __syncthreads();
-    bid = __builtin_amdgcn_readfirstlane(claim);
-    if (bid < 0) return;
+    ticket = prefill_mfma_item<D, HS, QB, NW>(p, a, bid, smem, own);
+    drawn = true;
+    if (!queued) return;
   }
-  prefill_mfma_item<D, HS, QB, NW>(p, a, bid, smem);
 }
 
 // Clears a set of queue counters (launched in front of every queued launch, on its stream).
@@ -918,15 +945,15 @@ static unsigned *queue_for(hipStream_t st) {
   return base[dev] + 8 * kQueueStride * set;
 }
 
-// SEGATTN_PREFILL_QUEUE in the environment: 0 = never take items from queues, 1 = always (small
-// test inputs too); unset = for a dense launch with at least 16 times as many items as workgroups
-// fit the chip (taking an item costs a round trip to memory, which a launch of few or short
-// items does not earn back: measured slower below that, and for ragged batches, many of whose
-// items are empty).  Read at every launch.
+// SEGATTN_PREFILL_QUEUE in the environment: 0 = never take items from queues; 1 = whenever there
+// is more than one item; 2 = the same with a grid of a third of the items (small test inputs then
+// loop and steal too); unset = when there are more items than workgroups fit the chip at once
+// (with fewer, every workgroup has one item and nothing to balance).  Read at every launch.
 static int queue_mode() {
   if (const char *e = getenv("SEGATTN_PREFILL_QUEUE")) {
     if (e[0] == '0') return 0;
     if (e[0] == '1') return 1;
+    if (e[0] == '2') return 2;
   }
   return -1;
 }
@@ -955,12 +982,11 @@ static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a_in, long lo
   a.queue = nullptr;
   long long launch = grid;
   const int mode = queue_mode();
-  if (resident > 0 && mode != 0 && (mode == 1 ? grid > 1 : (grid >= 16ll * resident && !a.cu_seqlens))) {
+  if (resident > 0 && mode != 0 && (mode > 0 ? grid > 1 : grid > resident)) {
     a.queue = queue_for(st);
-    if (a.queue) launch = (grid + grid / 8 + 7) / 8 * 8;  // an eighth more, a whole number per XCD
-    if (launch > 0x7fffffffLL) {
-      launch = grid;
-      a.queue = nullptr;
+    if (a.queue) {
+      launch = resident < grid ? resident : grid;
+      if (mode == 2 && grid / 3 < launch) launch = grid / 3 > 0 ? grid / 3 : 1;  // small inputs loop too
     }
     if (a.queue) {
       hipLaunchKernelGGL(prefill_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);

@@ -38,7 +38,7 @@ def test_streaming_prefill_equals_oracle(case, fp32_check, waves, monkeypatch):
     if waves == "queue":   # the library's own workgroup shape, work items taken from queues
         if fp32_check:
             pytest.skip("the item queues only exist in the MFMA kernel")
-        monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+        monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
         monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
     elif waves != "auto":
         if fp32_check or kw["head_dim"] != 128:

@@ -162,12 +162,12 @@ def test_stateless_forward_replays_from_a_captured_graph():
     G.assert_parity(G.to_f64(out), G.to_f64(lse), o_ref, l_ref, fp32_check=False, what="graph replay")
 
 
-# ---- work items taken from queues (the form large dense launches use; SEGATTN_PREFILL_QUEUE=1
+# ---- work items taken from queues (the form a launch with more items than fit the chip uses; SEGATTN_PREFILL_QUEUE=2
 # ---- forces it for small inputs, =0 switches it off)
 @pytest.mark.parametrize("case", range(len(SMALL)))
 def test_fwd_seq_small_with_item_queues(case, monkeypatch):
     import gpu_util as G
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
     w = W.small(f"small{case}", index=100 + case, **SMALL[case])
     q, k, v = W.prefill_inputs(w)
     o_ref, l_ref = _oracle(w, q, k, v)
@@ -198,7 +198,7 @@ def test_item_queues_run_every_item_exactly_once(monkeypatch):
     o0, l0 = _fwd(G, cfg, qd, kd, vd, 6000)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(o0).all())
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
     for _ in range(3):
         o1, l1 = _fwd(G, cfg, qd, kd, vd, 6000)
         torch.cuda.synchronize()
@@ -212,7 +212,7 @@ def test_item_queues_on_two_streams_do_not_share_counters(monkeypatch):
     """Launches on different streams may overlap: each stream has queue counters of its own, so
     two different problems in flight at once both come out as they do alone."""
     import gpu_util as G
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "1")
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
     probs = []
     for i, n in enumerate((5000, 3333)):
         w = W.small(f"two{i}", index=144 + i, seq_len=n, seg_len=512, tail_len=128, n_q_heads=16, n_kv_heads=4,
