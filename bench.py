@@ -35,7 +35,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM-side bytes of one prefill_mfma_kernel launch on the 128K workload, from the FETCH_SIZE and
 # WRITE_SIZE counter runs summarised in profiles/prefill_mfma_c4_128k_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": 6.87e9 + 1.09e9}
+MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": 8.73e9 + 1.09e9}
 
 
 def visible_pairs(w) -> int:
