@@ -947,8 +947,10 @@ static unsigned *queue_for(hipStream_t st) {
 
 // SEGATTN_PREFILL_QUEUE in the environment: 0 = never take items from queues; 1 = whenever there
 // is more than one item; 2 = the same with a grid of a third of the items (small test inputs then
-// loop and steal too); unset = when there are more items than workgroups fit the chip at once
-// (with fewer, every workgroup has one item and nothing to balance).  Read at every launch.
+// loop and steal too); unset = when there are more than twice as many items as workgroups fit the
+// chip at once (with two items or fewer per workgroup there is little to balance, and the
+// counters' reset kernel and first round trip are not earned back: measured equal or slightly
+// slower there).  Read at every launch.
 static int queue_mode() {
   if (const char *e = getenv("SEGATTN_PREFILL_QUEUE")) {
     if (e[0] == '0') return 0;
@@ -982,7 +984,7 @@ static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a_in, long lo
   a.queue = nullptr;
   long long launch = grid;
   const int mode = queue_mode();
-  if (resident > 0 && mode != 0 && (mode > 0 ? grid > 1 : grid > resident)) {
+  if (resident > 0 && mode != 0 && (mode > 0 ? grid > 1 : grid > 2ll * resident)) {
     a.queue = queue_for(st);
     if (a.queue) {
       launch = resident < grid ? resident : grid;
