@@ -17,18 +17,24 @@ namespace segattn {
 // ---------------------------------------------------------------------------------------------
 // dQ
 // ---------------------------------------------------------------------------------------------
+// One work item (query block x head sub-group): see bwd_dq_kernel for how items reach workgroups.
+// next_from: nullptr, or the queue counter the workgroup takes its next item from; thread 0 draws
+// the ticket after the last K/V step and hands it back (other threads: 0).
 template <int D, int HS>
-__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p, const PrefillArgs pa, const BwdArgs a) {
+__device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillArgs &pa, const BwdArgs &a,
+                                                const int bid, unsigned char (&smem)[2][2][BwdTile<D>::kBytes],
+                                                unsigned *const next_from) {
   using T = BwdTile<D>;
   constexpr int NC = D / 16, NB = D / 32;
   constexpr int RW = 32;             // query rows per wave
   constexpr int BQ = (4 / HS) * RW;  // query rows per workgroup
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][T::kBytes];  // [buffer][K,V]
 
-  WorkItem w = resolve(p, pa, blockIdx.x, BQ, HS);
-  if (!w.valid) return;
+  WorkItem w = resolve(p, pa, bid, BQ, HS);
+  if (!w.valid) return (next_from && threadIdx.x == 0) ? atomicAdd(next_from, 1u) : 0u;
   pin_uniform(w);
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // not a loop invariant of the caller's loop (see prefill_mfma_kernel)
+  const int wave = tid >> 6, lane = tid & 63;
   const int hi = lane >> 5, col = lane & 31;
   const int head = w.kv * p.g + w.hsub * HS + (wave % HS);
   const int tw0 = w.t0 + (wave / HS) * RW;
@@ -167,18 +173,54 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p, const P
   }
 #undef SEGATTN_BWD_FETCH_KV
 #undef SEGATTN_BWD_STORE_KV
-  if (!row_ok) return;
-  // dQ^T[d][q]: this lane holds, for its query row, d = 32 nb + 8 rg + 4 hi .. +3
+  unsigned ticket = 0;
+  if (next_from && tid == 0) ticket = atomicAdd(next_from, 1u);
+  if (row_ok) {
+    // dQ^T[d][q]: this lane holds, for its query row, d = 32 nb + 8 rg + 4 hi .. +3
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int rg = 0; rg < 4; ++rg) {
-      const int d = 32 * nb + 8 * rg + 4 * hi;
-      const f32x4 o = {acc[nb][4 * rg + 0] * p.scale, acc[nb][4 * rg + 1] * p.scale,
-                       acc[nb][4 * rg + 2] * p.scale, acc[nb][4 * rg + 3] * p.scale};
-      if (p.out_fp32) *(f32x4 *)((float *)a.dq + qoff + d) = o;
-      else *(uint2 *)((unsigned short *)a.dq + qoff + d) = __builtin_bit_cast(uint2, __builtin_convertvector(o, bf16x4));
+      for (int rg = 0; rg < 4; ++rg) {
+        const int d = 32 * nb + 8 * rg + 4 * hi;
+        const f32x4 o = {acc[nb][4 * rg + 0] * p.scale, acc[nb][4 * rg + 1] * p.scale,
+                         acc[nb][4 * rg + 2] * p.scale, acc[nb][4 * rg + 3] * p.scale};
+        if (p.out_fp32) *(f32x4 *)((float *)a.dq + qoff + d) = o;
+        else *(uint2 *)((unsigned short *)a.dq + qoff + d) = __builtin_bit_cast(uint2, __builtin_convertvector(o, bf16x4));
+      }
+  }
+  return ticket;
+}
+
+// One item per workgroup (pa.queue == nullptr), or a resident grid that takes item after item from
+// the per-XCD queues, as the forward kernel does and for the same reasons (prefill_mfma_kernel).
+template <int D, int HS>
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p_arg, const PrefillArgs pa_arg, const BwdArgs a_arg) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][BwdTile<D>::kBytes];  // [buffer][K,V]
+  __shared__ int claim;
+  constexpr unsigned kPaAt = (sizeof(Problem) + alignof(PrefillArgs) - 1) / alignof(PrefillArgs) * alignof(PrefillArgs);
+  constexpr unsigned kAAt = (kPaAt + sizeof(PrefillArgs) + alignof(BwdArgs) - 1) / alignof(BwdArgs) * alignof(BwdArgs);
+  unsigned ticket = 0;
+  bool drawn = false;
+  for (;;) {
+    // arguments through an opaque pointer, once per round: see prefill_mfma_kernel
+    const __attribute__((address_space(4))) unsigned char *ka =
+        (const __attribute__((address_space(4))) unsigned char *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka));
+    const Problem &p = *(const Problem *)ka;
+    const PrefillArgs &pa = *(const PrefillArgs *)(ka + kPaAt);
+    const BwdArgs &a = *(const BwdArgs *)(ka + kAAt);
+    int bid = (int)blockIdx.x;
+    const bool queued = pa.queue != nullptr;
+    unsigned *const own = queued ? pa.queue + kQueueStride * ((int)blockIdx.x & 7) : nullptr;
+    if (queued) {
+      bid = take_item(pa.queue, pa.grid_items, drawn, ticket, &claim);
+      if (bid < 0) return;
     }
+    ticket = bwd_dq_item<D, HS>(p, pa, a, bid, smem, own);
+    drawn = true;
+    if (!queued) return;
+    __syncthreads();  // the item's last reads of the tiles come before the next item's first stores
+  }
 }
 
 static int bwd_heads_per_wg(const Problem &p) { return (p.g % 4 == 0) ? 4 : (p.g % 2 == 0) ? 2 : 1; }
@@ -204,9 +246,33 @@ static hipError_t launch_dq(const Problem &p, const BwdArgs &a, hipStream_t st) 
   pa.pair_stride = prefill_pair_stride((long long)p.B * (p.Hkv - p.n_past) * (p.g / hs) * pa.n_seg);
   const long long grid_q = (long long)p.B * p.Hkv * (p.g / hs) * pa.n_seg * pa.q_blocks_per_seg;
   if (grid_q <= 0 || grid_q > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (hs == 4) hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
-  else if (hs == 2) hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
-  else hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)grid_q), dim3(256), 0, st, p, pa, a);
+  pa.grid_items = (int)grid_q;
+  // resident grid + item queues where every resident workgroup would get more than two items
+  const void *kern = hs == 4 ? (const void *)bwd_dq_kernel<D, 4> : hs == 2 ? (const void *)bwd_dq_kernel<D, 2>
+                                                                            : (const void *)bwd_dq_kernel<D, 1>;
+  long long launch = grid_q;
+  const int mode = item_queue_mode();
+  if (mode != 0) {
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, 0) != hipSuccess || hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+      (void)hipGetLastError();
+      per_cu = 0;
+    }
+    const long long resident = (long long)per_cu * cus;
+    if (resident > 0 && (mode > 0 ? grid_q > 1 : grid_q > 2 * resident)) {
+      pa.queue = item_queue_for(st);
+      if (pa.queue) {
+        launch = resident < grid_q ? resident : grid_q;
+        if (mode == 2 && grid_q / 3 < launch) launch = grid_q / 3 > 0 ? grid_q / 3 : 1;
+        hipError_t e = item_queue_reset(pa.queue, st);
+        if (e != hipSuccess) return e;
+      }
+    }
+  }
+  if (hs == 4) hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3((unsigned)launch), dim3(256), 0, st, p, pa, a);
+  else if (hs == 2) hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3((unsigned)launch), dim3(256), 0, st, p, pa, a);
+  else hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3((unsigned)launch), dim3(256), 0, st, p, pa, a);
   return hipGetLastError();
 }
 

@@ -95,6 +95,13 @@ struct PrefillArgs {
   unsigned *queue;       // device; nullptr: workgroup i runs item i
 };
 constexpr int kQueueStride = 32;  // unsigned words between two queue counters (128 bytes)
+// Host side of the item queues (segattn_prefill_mfma.hip): the counters of this (device, stream),
+// or nullptr where the launch has to run one workgroup per item (stream under capture, no set
+// left); the kernel that clears them, to be launched in front of every queued launch; and the
+// SEGATTN_PREFILL_QUEUE setting (-1 unset, 0 off, 1 on, 2 on with a grid a third of the items).
+unsigned *item_queue_for(hipStream_t st);
+hipError_t item_queue_reset(unsigned *queue, hipStream_t st);
+int item_queue_mode();
 
 struct DecodeArgs {
   const unsigned short *q, *k_new, *v_new;

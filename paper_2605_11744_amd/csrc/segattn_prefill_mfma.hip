@@ -796,45 +796,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     const bool queued = a.queue != nullptr;
     unsigned *const own = queued ? a.queue + kQueueStride * ((int)blockIdx.x & 7) : nullptr;
     if (queued) {
-      if (threadIdx.x == 0) {
-        auto items_of = [&](int y) { return y < a.grid_items ? (unsigned)(a.grid_items - y + 7) >> 3 : 0u; };
-        const int x = (int)blockIdx.x & 7;
-        int got = -1;
-        const unsigned j0 = drawn ? ticket : atomicAdd(own, 1u);  // the XCD's own queue
-        if (j0 < items_of(x)) {
-          got = 8 * (int)j0 + x;
-        } else {
-          // Own queue empty: help the XCD that is furthest behind.  Counters only grow, so a queue
-          // seen empty stays empty; a failed attempt marks its queue empty: at most eight attempts.
-          unsigned left[8];
-#pragma unroll
-          for (int y = 0; y < 8; ++y) {
-            const unsigned at = __hip_atomic_load(a.queue + kQueueStride * y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            left[y] = at < items_of(y) ? items_of(y) - at : 0u;
-          }
-#pragma unroll 1
-          for (int t = 0; t < 8 && got < 0; ++t) {
-            unsigned most = 0;
-            int y = -1;
-#pragma unroll
-            for (int z = 0; z < 8; ++z)
-              if (left[z] > most) {
-                most = left[z];
-                y = z;
-              }
-            if (y < 0) break;
-            const unsigned j = atomicAdd(a.queue + kQueueStride * y, 1u);
-            if (j < items_of(y)) got = 8 * (int)j + y;
-#pragma unroll
-            for (int z = 0; z < 8; ++z)
-              if (z == y) left[z] = 0;
-          }
-        }
-        claim = got;
-      }
-      __syncthreads();
-      bid = __builtin_amdgcn_readfirstlane(claim);
-      __syncthreads();  // everyone has read it before thread 0 writes the next one
+      bid = take_item(a.queue, a.grid_items, drawn, ticket, &claim);
       if (bid < 0) return;
     }
     ticket = prefill_mfma_item<D, HS, QB, NW>(p, a, bid, smem, own);
@@ -844,8 +806,13 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
 }
 
 // Clears a set of queue counters (launched in front of every queued launch, on its stream).
-__global__ void prefill_queue_reset_kernel(unsigned *queue) {
+__global__ void item_queue_reset_kernel(unsigned *queue) {
   if (threadIdx.x < 8) queue[kQueueStride * threadIdx.x] = 0;
+}
+
+hipError_t item_queue_reset(unsigned *queue, hipStream_t st) {
+  hipLaunchKernelGGL(item_queue_reset_kernel, dim3(1), dim3(64), 0, st, queue);
+  return hipGetLastError();
 }
 
 // =============================================================================================
@@ -908,7 +875,7 @@ constexpr int kQueueSets = 64;
 constexpr int kQueueDevices = 16;
 static __device__ unsigned g_queue_sets[kQueueSets][8 * kQueueStride];
 
-static unsigned *queue_for(hipStream_t st) {
+unsigned *item_queue_for(hipStream_t st) {
   struct Owner {
     int dev;
     hipStream_t st;
@@ -951,7 +918,7 @@ static unsigned *queue_for(hipStream_t st) {
 // chip at once (with two items or fewer per workgroup there is little to balance, and the
 // counters' reset kernel and first round trip are not earned back: measured equal or slightly
 // slower there).  Read at every launch.
-static int queue_mode() {
+int item_queue_mode() {
   if (const char *e = getenv("SEGATTN_PREFILL_QUEUE")) {
     if (e[0] == '0') return 0;
     if (e[0] == '1') return 1;
@@ -983,16 +950,15 @@ static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a_in, long lo
   a.grid_items = (int)grid;
   a.queue = nullptr;
   long long launch = grid;
-  const int mode = queue_mode();
+  const int mode = item_queue_mode();
   if (resident > 0 && mode != 0 && (mode > 0 ? grid > 1 : grid > 2ll * resident)) {
-    a.queue = queue_for(st);
+    a.queue = item_queue_for(st);
     if (a.queue) {
       launch = resident < grid ? resident : grid;
       if (mode == 2 && grid / 3 < launch) launch = grid / 3 > 0 ? grid / 3 : 1;  // small inputs loop too
     }
     if (a.queue) {
-      hipLaunchKernelGGL(prefill_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);
-      hipError_t e = hipGetLastError();
+      hipError_t e = item_queue_reset(a.queue, st);
       if (e != hipSuccess) return e;
     }
   }

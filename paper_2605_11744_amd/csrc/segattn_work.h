@@ -29,6 +29,57 @@ struct WorkItem {
   bool valid;
 };
 
+// ---- work items from queues (kernels that run as a resident grid)
+// Queue y (counter at queue[kQueueStride * y]) holds the items y, y+8, ... of a launch of
+// `n_items`, in order: what XCD y would be dealt if every item were a workgroup of its own.  A
+// workgroup (on XCD blockIdx.x % 8) takes from its XCD's queue first; once that is empty, from the
+// queue with the most items left (the XCD furthest behind); -1 when all are empty.  Thread 0 does
+// the work, `slot` (shared memory) carries the answer to the others; two workgroup barriers.
+// drawn / ticket: thread 0 may already hold a position drawn from the own queue (by atomicAdd,
+// while the previous item was finishing), so that the round trip is over by now.
+__device__ __forceinline__ int take_item(unsigned *queue, int n_items, bool drawn, unsigned ticket, int *slot) {
+  if (threadIdx.x == 0) {
+    auto items_of = [&](int y) { return y < n_items ? (unsigned)(n_items - y + 7) >> 3 : 0u; };
+    const int x = (int)blockIdx.x & 7;
+    int got = -1;
+    const unsigned j0 = drawn ? ticket : atomicAdd(queue + kQueueStride * x, 1u);
+    if (j0 < items_of(x)) {
+      got = 8 * (int)j0 + x;
+    } else {
+      // Counters only grow, so a queue seen empty stays empty; a failed attempt marks its queue
+      // empty: at most eight attempts.
+      unsigned left[8];
+#pragma unroll
+      for (int y = 0; y < 8; ++y) {
+        const unsigned at = __hip_atomic_load(queue + kQueueStride * y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        left[y] = at < items_of(y) ? items_of(y) - at : 0u;
+      }
+#pragma unroll 1
+      for (int t = 0; t < 8 && got < 0; ++t) {
+        unsigned most = 0;
+        int y = -1;
+#pragma unroll
+        for (int z = 0; z < 8; ++z)
+          if (left[z] > most) {
+            most = left[z];
+            y = z;
+          }
+        if (y < 0) break;
+        const unsigned j = atomicAdd(queue + kQueueStride * y, 1u);
+        if (j < items_of(y)) got = 8 * (int)j + y;
+#pragma unroll
+        for (int z = 0; z < 8; ++z)
+          if (z == y) left[z] = 0;
+      }
+    }
+    *slot = got;
+  }
+  __syncthreads();
+  const int bid = __builtin_amdgcn_readfirstlane(*slot);
+  __syncthreads();  // everyone has read it before thread 0 writes the next one
+  return bid;
+}
+
 // blockIdx -> (sequence, KV head, head sub-group, segment, query block): all PAST workgroups by
 // descending absolute query block (longest work first), then the others grouped so that the
 // query blocks sharing K/V rows run together on one XCD.
