@@ -265,10 +265,14 @@ static hipError_t launch_dq(const Problem &p, const BwdArgs &a, hipStream_t st) 
       if (pa.queue) {
         launch = resident < grid_q ? resident : grid_q;
         if (mode == 2 && grid_q / 3 < launch) launch = grid_q / 3 > 0 ? grid_q / 3 : 1;
-        hipError_t e = item_queue_reset(pa.queue, st);
-        if (e != hipSuccess) return e;
       }
     }
+  }
+  std::unique_lock<std::mutex> pair;  // reset and launch enter the stream back to back
+  if (pa.queue) {
+    pair = std::unique_lock<std::mutex>(item_queue_launch_mutex());
+    hipError_t e = item_queue_reset(pa.queue, st);
+    if (e != hipSuccess) return e;
   }
   if (hs == 4) hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3((unsigned)launch), dim3(256), 0, st, p, pa, a);
   else if (hs == 2) hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3((unsigned)launch), dim3(256), 0, st, p, pa, a);

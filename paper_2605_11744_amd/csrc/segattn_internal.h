@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "segattn.h"
 
 namespace segattn {
@@ -99,8 +101,11 @@ constexpr int kQueueStride = 32;  // unsigned words between two queue counters (
 // or nullptr where the launch has to run one workgroup per item (stream under capture, no set
 // left); the kernel that clears them, to be launched in front of every queued launch; and the
 // SEGATTN_PREFILL_QUEUE setting (-1 unset, 0 off, 1 on, 2 on with a grid a third of the items).
+// The reset and the launch that uses the counters must enter the stream back to back: hold
+// item_queue_launch_mutex() around the pair (two host threads may launch into one stream).
 unsigned *item_queue_for(hipStream_t st);
 hipError_t item_queue_reset(unsigned *queue, hipStream_t st);
+std::mutex &item_queue_launch_mutex();
 int item_queue_mode();
 
 struct DecodeArgs {

@@ -810,6 +810,11 @@ __global__ void item_queue_reset_kernel(unsigned *queue) {
   if (threadIdx.x < 8) queue[kQueueStride * threadIdx.x] = 0;
 }
 
+std::mutex &item_queue_launch_mutex() {
+  static std::mutex mu;
+  return mu;
+}
+
 hipError_t item_queue_reset(unsigned *queue, hipStream_t st) {
   hipLaunchKernelGGL(item_queue_reset_kernel, dim3(1), dim3(64), 0, st, queue);
   return hipGetLastError();
@@ -957,11 +962,15 @@ static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a_in, long lo
       launch = resident < grid ? resident : grid;
       if (mode == 2 && grid / 3 < launch) launch = grid / 3 > 0 ? grid / 3 : 1;  // small inputs loop too
     }
-    if (a.queue) {
-      hipError_t e = item_queue_reset(a.queue, st);
-      if (e != hipSuccess) return e;
-    }
   }
+  if (!a.queue) {
+    hipLaunchKernelGGL(kern, dim3((unsigned)launch), dim3(64 * NW), lds, st, p, a);
+    return hipGetLastError();
+  }
+  // reset and launch go into the stream back to back, also when several host threads use it
+  std::lock_guard<std::mutex> pair(item_queue_launch_mutex());
+  hipError_t e = item_queue_reset(a.queue, st);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)launch), dim3(64 * NW), lds, st, p, a);
   return hipGetLastError();
 }

@@ -233,3 +233,43 @@ def test_item_queues_on_two_streams_do_not_share_counters(monkeypatch):
         for j, (o, l) in enumerate(got):
             o_a, l_a = probs[j % 2][5]
             assert torch.equal(o, o_a) and torch.equal(l, l_a)
+
+
+def test_item_queues_with_two_host_threads_on_one_stream(monkeypatch):
+    """Two host threads that launch into the same stream: every launch's counter reset and the
+    launch itself must enter the stream as a pair, whatever the threads' timing."""
+    import threading
+    import gpu_util as G
+    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
+    stream = torch.cuda.Stream()
+    probs = []
+    for i, n in enumerate((2100, 1500)):
+        w = W.small(f"thr{i}", index=146 + i, seq_len=n, seg_len=512, tail_len=128, n_q_heads=8, n_kv_heads=2,
+                    head_dim=128, kv_policy=[3, 1])
+        q, k, v = W.prefill_inputs(w)
+        qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+        cfg = G.config_of(w, out_fp32=True, batch=1)
+        alone = _fwd(G, cfg, qd, kd, vd, n)
+        outs = [(torch.empty_like(alone[0]), torch.empty_like(alone[1])) for _ in range(12)]
+        probs.append((cfg, qd, kd, vd, n, alone, outs))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(prob):
+        cfg, qd, kd, vd, n, _, outs = prob
+        try:
+            for o, l in outs:
+                G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, n, o, l, stream.cuda_stream)
+        except Exception as e:   # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(pr,)) for pr in probs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    stream.synchronize()
+    assert not errors
+    for _, _, _, _, _, alone, outs in probs:
+        for o, l in outs:
+            assert torch.equal(o, alone[0]) and torch.equal(l, alone[1])
