@@ -331,13 +331,18 @@ def attend_reindexed(q, k, v, *, seg_len: int, tail_len: int, kv_policy: Sequenc
 
 
 def round_bf16(x: np.ndarray) -> np.ndarray:
-    """Nearest bfloat16 (ties to even) of float64 values, returned as float64."""
-    u = np.asarray(x, dtype=np.float64).astype(np.float32).view(np.uint32)
-    # the float32 step can only matter on an exact bf16 tie of the float64 value; inputs here are
-    # means of a few bf16 numbers, which float32 holds exactly
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    r = ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)) << np.uint32(16)
-    return r.astype(np.uint32).view(np.float32).astype(np.float64)
+    """Nearest bfloat16 of float64 values, ties to the even significand, returned as float64.
+
+    bfloat16 keeps 8 significant bits (1 sign, 8 exponent, 7 stored fraction bits; the binary32
+    exponent range): a value of magnitude in [2^e, 2^(e+1)) lies on a grid of spacing 2^(e-7),
+    never finer than the subnormal spacing 2^-133, and what rounds to 2^128 or beyond is
+    infinite.  Rounded straight from the float64 value (one rounding, not two)."""
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)                                # |x| in [2^(e-1), 2^e)
+    quantum = np.ldexp(1.0, np.maximum(e - 8, -133))  # spacing of the bf16 grid at x
+    r = np.rint(x / quantum) * quantum                # rint rounds halves to the even integer
+    r = np.where(np.abs(r) >= 2.0 ** 128, np.copysign(np.inf, x), r)
+    return np.where(np.isfinite(x), r, x)
 
 
 def retrieval_summaries(q_prev, *, n_queries: int, pool_window: int, tail_avg: int) -> np.ndarray:
@@ -358,13 +363,16 @@ def retrieval_summaries(q_prev, *, n_queries: int, pool_window: int, tail_avg: i
 
 def retrieve_indices(q_prev, k_pool, *, R: int, n_queries: int, pool_window: int, tail_avg: int,
                      n_anchors: int, win_before: int, win_after: int, evicted: int = 0,
-                     return_scores: bool = False):
+                     return_scores: bool = False, summaries_bf16: bool = True):
     """Top-k retrieval operator of Appendix D for one sequence and one KV head, as read here.
 
     q_prev [m, g, D]: previous-segment queries of the g query heads of the group; k_pool [n, D]:
-    the head's pool.  Scoring: dot products between every summary (rounded to bf16, the form in
-    which the kernel's matrix cores take them) and every pool key; a row's score is its best
-    over the summaries.  Anchors: the n_anchors rows with the highest scores (ties: lower row
+    the head's pool.  Scoring: dot products between every summary and every pool key; a row's
+    score is its best over the summaries.  Appendix D fixes no precision for the summaries; by
+    default they are rounded to bf16 like every query and key of the bf16 backbones the paper
+    runs (Sec. 4), and summaries_bf16=False keeps the float64 means instead.  The two readings
+    can only pick different anchors where scores lie within the rounding of each other (each
+    score moves by at most 2^-8 sum_d |s_d k_d|); test_oracle_pins checks exactly that.  Anchors: the n_anchors rows with the highest scores (ties: lower row
     first) -- the same rows as "per-summary top-k, de-duplicate, keep the highest-scoring
     anchors" for any k >= n_anchors.  Window expansion: anchors in descending score order each
     add rows a-win_before .. a+win_after (clipped to the pool, ascending, skipping rows already
@@ -372,8 +380,9 @@ def retrieve_indices(q_prev, k_pool, *, R: int, n_queries: int, pool_window: int
     Result: the min(R, n - evicted) rows, sorted ascending."""
     q_prev, k_pool = widen(q_prev), widen(k_pool)
     n = k_pool.shape[0]
-    summ = round_bf16(retrieval_summaries(q_prev, n_queries=n_queries, pool_window=pool_window,
-                                          tail_avg=tail_avg))
+    summ = retrieval_summaries(q_prev, n_queries=n_queries, pool_window=pool_window, tail_avg=tail_avg)
+    if summaries_bf16:
+        summ = round_bf16(summ)
     sig = summ.reshape(-1, summ.shape[-1])                  # all summaries of all heads of the group
     scores = (sig @ k_pool.T).max(axis=0)                   # [n]
     scores[:evicted] = -np.inf

@@ -61,6 +61,12 @@ MUTANTS = {
     "packed_segment_grid_runs_through_the_pack": ("            o, l = attend(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], **kw)\n            out[lo:hi], lse[:, lo:hi] = o[0], l[0]", "            o, l = attend(q[None, :hi], k[None, :hi], v[None, :hi], **kw)\n            out[lo:hi], lse[:, lo:hi] = o[0, lo:], l[0, :, lo:]"),
     "packed_lse_of_first_head_for_all": ("out[lo:hi], lse[:, lo:hi] = o[0], l[0]", "out[lo:hi], lse[:, lo:hi] = o[0], l[0, :1]"),
     "packed_backward_runs_through_the_pack": ("            gq, gk, gv = attend_backward(q[None, lo:hi], k[None, lo:hi], v[None, lo:hi], dout[None, lo:hi], **kw)\n            dq[lo:hi], dk[lo:hi], dv[lo:hi] = gq[0], gk[0], gv[0]", "            gq, gk, gv = attend_backward(q[None, :hi], k[None, :hi], v[None, :hi], dout[None, :hi], **kw)\n            dq[lo:hi], dk[lo:hi], dv[lo:hi] = gq[0, lo:], gk[0, lo:], gv[0, lo:]"),
+    "bf16_rounding_truncates": ("np.rint(x / quantum)", "np.trunc(x / quantum)"),
+    "bf16_rounding_ties_away_from_zero": ("np.rint(x / quantum)", "(np.sign(x) * np.floor(np.abs(x / quantum) + 0.5))"),
+    "bf16_rounding_through_binary32": ("    x = np.asarray(x, dtype=np.float64)\n    _, e = np.frexp(x)", "    x = np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)\n    _, e = np.frexp(x)"),
+    "bf16_grid_without_subnormal_floor": ("np.maximum(e - 8, -133)", "(e - 8)"),
+    "bf16_grid_one_bit_too_fine": ("np.maximum(e - 8, -133)", "np.maximum(e - 9, -133)"),
+    "bf16_overflow_saturates": ("np.copysign(np.inf, x), r)", "np.copysign(2.0 ** 127 * (2 - 2.0 ** -7), x), r)"),
     "tail_of_takes_head": ("return k_seg[m - t:], v_seg[m - t:]", "return k_seg[:t], v_seg[:t]"),
 }
 

@@ -303,6 +303,42 @@ def test_bf16_widening_is_exact():
     np.testing.assert_array_equal(orc.widen(bits), np.array(exp))
 
 
+def _bf16_bits(x):
+    """Bit patterns of float64 values that already are bfloat16 numbers (exact in binary32)."""
+    return (np.asarray(x, dtype=np.float64).astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def test_round_bf16_matches_hand_worked_table():
+    """Listed binary64 values against their hand-worked bfloat16 patterns: exact ties both ways,
+    values a hair off a tie (which a detour over binary32 would misplace), both zeros,
+    subnormals, the overflow threshold."""
+    rows = _read("bf16_rounding_table.txt")
+    assert len(rows) >= 25
+    x = np.array([float.fromhex(r[0]) for r in rows])
+    want = np.array([int(r[1], 16) for r in rows], dtype=np.uint16)
+    got = orc.round_bf16(x)
+    np.testing.assert_array_equal(_bf16_bits(got), want)
+    np.testing.assert_array_equal(np.signbit(got), np.signbit(x))
+
+
+def test_round_bf16_is_the_nearest_grid_point_and_idempotent():
+    """Properties of round-to-nearest on any input: the result is a bfloat16 number (widening its
+    own pattern gives it back), no other bfloat16 number is nearer (checked against the two
+    neighbouring patterns), and rounding twice changes nothing."""
+    rng = np.random.default_rng(17)
+    x = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-30, 30, 4000),
+                        rng.standard_normal(500) * 2.0 ** -130])
+    r = orc.round_bf16(x)
+    bits = _bf16_bits(r)
+    np.testing.assert_array_equal(orc.widen(bits), r)
+    np.testing.assert_array_equal(orc.round_bf16(r), r)
+    mag = bits & np.uint16(0x7FFF)
+    up = orc.widen(((mag + 1) | (bits & np.uint16(0x8000))).astype(np.uint16))          # next larger magnitude
+    dn = orc.widen(((np.maximum(mag, 1) - 1) | (bits & np.uint16(0x8000))).astype(np.uint16))
+    err = np.abs(r - x)
+    assert np.all(err <= np.abs(up - x)) and np.all(err <= np.abs(dn - x))
+
+
 def test_tail_of_is_last_rows():
     k = np.arange(10.0).reshape(5, 2)
     kt, vt = orc.tail_of(k, -k, 3)
@@ -650,6 +686,34 @@ def test_retrieve_indices_equals_literal_steps(seed, n, R, k_top):
     got = orc.retrieve_indices(q_prev, k_pool, R=R, **RET)
     assert list(got) == literal_appendix_d(q_prev, k_pool, R, k_top, RET)
     assert len(got) == min(R, n) and len(set(got)) == len(got) and list(got) == sorted(got)
+
+
+def test_bf16_summaries_change_the_result_only_in_near_ties():
+    """The summaries' precision is a reading (Appendix D states none).  Rounding a summary to bf16
+    moves each of its components by at most 2^-8 relative (half a spacing of 2^-7), hence a row's score by at most
+    eps_r = 2^-8 max_summary sum_d |s_d k_rd|.  Whenever the n_anchors + 1 best float64 scores are
+    further apart than twice the largest eps, both readings must pick the same anchors in the same
+    order and so return the same list; only closer calls may differ."""
+    separated = differing = 0
+    for seed in range(60):
+        rng = np.random.default_rng(7000 + seed)
+        n = int(rng.integers(12, 80))
+        q_prev = orc.round_bf16(rng.standard_normal((9, 2, 8)))
+        k_pool = orc.round_bf16(rng.standard_normal((n, 8)))
+        R = int(rng.integers(2, 10))
+        a, sa_ = orc.retrieve_indices(q_prev, k_pool, R=R, return_scores=True, **RET)
+        b, sb = orc.retrieve_indices(q_prev, k_pool, R=R, return_scores=True, summaries_bf16=False, **RET)
+        summ = orc.retrieval_summaries(q_prev, n_queries=RET["n_queries"], pool_window=RET["pool_window"],
+                                       tail_avg=RET["tail_avg"]).reshape(-1, 8)
+        eps = 2.0 ** -8 * (np.abs(summ) @ np.abs(k_pool).T).max(axis=0)
+        assert np.all(np.abs(sa_ - sb) <= eps + 1e-15)
+        top = np.sort(sb)[::-1][:RET["n_anchors"] + 1]
+        if np.all(top[:-1] - top[1:] > 2 * eps.max()):
+            separated += 1
+            assert list(a) == list(b), seed
+        elif list(a) != list(b):
+            differing += 1
+    assert separated >= 30          # the claim is not vacuous on this data
 
 
 def test_retrieve_indices_planted_rows_and_fallback():
