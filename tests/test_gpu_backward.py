@@ -93,6 +93,37 @@ def test_backward_two_segment_window_in_bf16_outputs():
         assert err.max() <= 2e-2 * G and err.mean() <= 2e-3 * G, f"{name}: {err.max():.3e} {err.mean():.3e} G={G:.2f}"
 
 
+_WINDOW_REF = {}
+
+
+@pytest.mark.parametrize("out_fp32", [False, True])
+def test_backward_training_window_at_benchmark_shape(out_fp32):
+    """The 8K training window of truncation depth 1 at the shape the benchmark times (two segments
+    of 4096, tail 1024, 32 query / 8 KV heads of width 128, two PAST groups), one sequence, launched
+    as the library chooses (dQ as a resident grid on the item queues, dK/dV longest blocks first
+    with the rotating assignment): every element of dQ, dK, dV against the oracle.  With bf16
+    results (the benchmark's configuration) the forward output that feeds delta and the three
+    gradients are stored in bf16, which adds half a bf16 spacing (2^-8 relative) per element."""
+    S, T, n = 4096, 1024, 8192
+    w = W.small("tbptt1_window", index=160, seq_len=n, seg_len=S, tail_len=T, n_q_heads=32, n_kv_heads=8,
+                head_dim=128, kv_policy=list(W.C4.kv_policy))
+    q, k, v = W.prefill_inputs(w)
+    go = W.grad_inputs(w)
+    got = run_backward(w, q, k, v, go, fp32_check=False, out_fp32=out_fp32)
+    if "ref" not in _WINDOW_REF:   # about a minute of fp64 on the host cores: once for both result types
+        _WINDOW_REF["ref"] = orc.attend_backward(q, k, v, go, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
+    ref = _WINDOW_REF["ref"]
+    for name, g_, r_ in zip(("dQ", "dK", "dV"), got, ref):
+        assert np.isfinite(g_).all(), f"{name} not finite"
+        err = np.abs(g_ - r_)
+        G = max(1.0, float(np.abs(r_).max()))
+        print(f"backward 2x4096 ({'fp32' if out_fp32 else 'bf16'} results) {name}: max-abs {err.max():.3e} "
+              f"mean-abs {err.mean():.3e}, max |gradient| {G:.2f}")
+        slack = 0.0 if out_fp32 else np.abs(r_) * 2.0 ** -8
+        assert np.all(err <= 1e-2 * G + slack), f"{name}: max-abs {err.max():.3e} (G={G:.2f})"
+        assert err.mean() <= 1e-3 * G, f"{name}: mean-abs {err.mean():.3e} (G={G:.2f})"
+
+
 def test_backward_validates_arguments():
     w = W.small(seq_len=64, seg_len=32, tail_len=8, n_q_heads=2, n_kv_heads=2, head_dim=64, kv_policy=[1, 1])
     cfg = config_of(w)

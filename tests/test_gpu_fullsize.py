@@ -69,6 +69,35 @@ def test_prefill_full_size_sampled_rows(name, n_random, bf16_out):
     _check_rows(w, q, k, v, o_gpu, l_gpu, rows, bf16_out)
 
 
+@pytest.mark.parametrize("name,n_random", [
+    ("c2_16k_gqa_outliers", 200), ("c3_32k_llama3_8b_layer", 80), ("c4_128k_prefill", 40),
+])
+def test_prefill_full_size_fp32_check_mode(name, n_random):
+    """Validation mode (fp32 FMA kernels, fp32 output) at the real shapes: one seg_attn_fwd_seq
+    launch over the whole workload, sampled rows -- the fixed boundary rows plus seeded random
+    ones, every head -- against the oracle at max-abs 1e-4 on O and on LSE.  C2 carries the x8
+    outlier key channels, C4 rows that sum 131072 weights in fp32."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    w = W.WORKLOADS[name]
+    q, k, v = W.prefill_inputs(w)
+    cfg = G.config_of(w, fp32_check=True)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    out = torch.full((w.batch, w.seq_len, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((w.batch, w.n_q_heads, w.seq_len), float("nan"), dtype=torch.float32, device="cuda")
+    sa.seg_attn_fwd_seq(cfg, qd, kd, vd, w.seq_len, out, lse, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    rows = _sample_rows(w, n_random, w.seed + 3)
+    idx = torch.from_numpy(rows).cuda()
+    o_gpu, l_gpu = G.to_f64(out.index_select(1, idx)), G.to_f64(lse.index_select(2, idx))
+    o_ref, l_ref = orc.attend(q, k, v, seg_len=w.seg_len, tail_len=w.tail_len, kv_policy=w.kv_policy, rows=rows)
+    eo, el = np.abs(o_gpu - o_ref), np.abs(l_gpu - l_ref)
+    print(f"fp32 check mode {name}: {rows.size} rows x {w.n_q_heads} heads: |dO| max {eo.max():.3e} mean {eo.mean():.3e}, "
+          f"|dLSE| max {el.max():.3e}")
+    assert eo.max() <= G.FP32_MAX_ABS and el.max() <= G.FP32_MAX_ABS
+
+
 def test_prefill_interleaved_policy_full_size():
     """Same FLOPs, different load balance: PAST heads spread over the KV heads (Table 11 contrasts
     contiguous and interleaved head groupings)."""
@@ -81,15 +110,17 @@ def test_prefill_interleaved_policy_full_size():
     _check_rows(w, q, k, v, G.to_f64(out.index_select(1, idx)), G.to_f64(lse.index_select(2, idx)), rows, True)
 
 
-def test_decode_c5_full_batch():
+@pytest.mark.parametrize("fp32_check", [False, True])
+def test_decode_c5_full_batch(fp32_check):
     """The B=64 decode workload exactly as the benchmark runs it (bf16 output), every output
-    checked: cache rows written through segattn_cache_span, lengths declared, one step."""
+    checked: cache rows written through segattn_cache_span, lengths declared, one step.  Also in
+    validation mode (fp32 split-K kernels and fp32 output, windows of up to 64K rows) at 1e-4."""
     import gpu_util as G
     import paper_2605_11744_amd as sa
     w = W.C5
     S, T, D, Hkv = w.seg_len, w.tail_len, w.head_dim, w.n_kv_heads
     q, ks, vs, k_done, c_fill = W.decode_inputs(w)
-    c = G.Cache(w, past_capacity=w.max_context, out_fp32=False)
+    c = G.Cache(w, past_capacity=w.max_context, out_fp32=False, fp32_check=fp32_check)
     try:
         k_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
         v_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
@@ -105,7 +136,7 @@ def test_decode_c5_full_batch():
                     vd[first:first + n_prev] = G.dev_bf16(vv[:-1])
         sa.seg_kv_set_lengths(c.ctx, [int(x) * S for x in k_done], [T] * w.batch, [int(x) - 1 for x in c_fill], c.stream)
         o, l = c.decode(q, k_new, v_new)
-        worst = 0.0
+        worst = worst_l = 0.0
         for b in range(w.batch):
             n_b = int(k_done[b]) * S + int(c_fill[b])
             kf = np.zeros((n_b, Hkv, D))
@@ -116,10 +147,14 @@ def test_decode_c5_full_batch():
                 vf[n_b - kept:, h] = orc.widen(vs[b][h])
             o_ref, l_ref = orc.decode_attend(q[b], kf, vf, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
             eo, el = np.abs(o[b] - o_ref), np.abs(l[b] - l_ref)
-            assert np.all(eo <= 1e-2 + np.abs(o_ref) * 2.0 ** -8) and eo.mean() <= 1e-3, (b, eo.max(), eo.mean())
-            assert el.max() <= 1e-2 and el.mean() <= 1e-3, (b, el.max())
+            if fp32_check:
+                assert eo.max() <= G.FP32_MAX_ABS and el.max() <= G.FP32_MAX_ABS, (b, eo.max(), el.max())
+            else:
+                assert np.all(eo <= 1e-2 + np.abs(o_ref) * 2.0 ** -8) and eo.mean() <= 1e-3, (b, eo.max(), eo.mean())
+                assert el.max() <= 1e-2 and el.mean() <= 1e-3, (b, el.max())
             worst = max(worst, eo.max())
-        print(f"decode C5: worst |dO| = {worst:.3e}")
+            worst_l = max(worst_l, el.max())
+        print(f"decode C5 ({'fp32 check mode' if fp32_check else 'bf16'}): worst |dO| = {worst:.3e}, worst |dLSE| = {worst_l:.3e}")
     finally:
         c.close()
 
