@@ -453,10 +453,13 @@ def decode_leg(sa, W):
     lse = torch.empty((B, Hq), dtype=torch.float32, device="cuda")
     closed = [int(x) * S for x in k_done]
     fill0 = [int(c) - 1 for c in c_fill]
+    # algorithmic bytes: every K and V row the step's queries may attend to, once per KV head
+    # (Eq. 13: own open segment; plus the carried tail for TAIL; plus the whole pool for PAST)
     rows = 0
     for b in range(B):
         for pol in w.kv_policy:
-            rows += W.decode_rows_kept(pol, int(k_done[b]), int(c_fill[b]), S, T)
+            closed_b = int(k_done[b]) * S
+            rows += int(c_fill[b]) + (closed_b if pol & 2 else min(T, closed_b) if pol & 1 else 0)
     kv_bytes = rows * D * 2 * 2
     times = []
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -29,8 +29,12 @@
  *              sum_j exp(scale * q.k_j) over the visible keys.  Query head h reads KV head
  *              h / (Hq / Hkv).
  *   Errors     Every call validates its arguments and the context state before it enqueues
- *              anything and returns a segattn_status; nothing aborts or throws.  After an
- *              error the context is unchanged.
+ *              anything and returns a segattn_status; nothing aborts or throws.  After EINVAL,
+ *              ECAPACITY or ESTATE nothing was enqueued and the context is unchanged.  EHIP means
+ *              the HIP runtime refused a launch or a copy, possibly after earlier kernels of the
+ *              same call had entered the stream: the device counters of the cache may then be
+ *              ahead of the context's bookkeeping, so the context is marked not ready and every
+ *              stateful call returns ESTATE until segattn_reset() or seg_kv_set_lengths().
  *   Threads    A context is not thread-safe; distinct contexts are independent.
  */
 #ifndef SEGATTN_H
@@ -82,6 +86,14 @@ typedef struct {
                               rotary embedding (Appendix E): seg_rope_apply() rotates by it, and
                               in retrieval mode the gathered K rows are re-rotated (see
                               seg_kv_past_select)                                              */
+  /* Launch-shape overrides for tests and A/B timing; 0 everywhere = the library chooses.  Results
+   * do not depend on them beyond rounding order. */
+  int32_t prefill_waves;   /* 4 or 8: waves per workgroup of the head_dim-128 bf16 forward kernel
+                              (a forced shape also keeps seg_attn_fwd from cutting prefixes)     */
+  int32_t item_queues;     /* forward and dQ kernels as a resident grid that takes its work items
+                              from per-XCD queues: 1 never, 2 whenever a launch has more than one
+                              item, 3 the same with a grid a third of the items (so that small
+                              inputs loop and take over items of other queues too)               */
 } segattn_config;
 
 /* ---- context --------------------------------------------------------------------------- */
@@ -114,8 +126,7 @@ segattn_status segattn_reset(segattn_ctx *ctx, void *stream);
  * Requires 1 <= m and fill + m <= S for every sequence (ESTATE otherwise).  Reads the cache,
  * does not change it: follow with seg_kv_commit() on the same stream.
  * (All prefill entry points, head_dim 128: the library runs workgroups of eight or of four waves
- * depending on how much work the launch has; the environment variable SEGATTN_PREFILL_WAVES=4|8,
- * read at every launch, forces one of them.  Results do not depend on it beyond rounding.) */
+ * depending on how much work the launch has; segattn_config.prefill_waves forces one of them.) */
 segattn_status seg_attn_fwd(segattn_ctx *ctx, const void *q, const void *k, const void *v,
                             int32_t m, void *out, float *lse, void *stream);
 

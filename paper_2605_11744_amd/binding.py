@@ -27,6 +27,7 @@ class segattn_config(ctypes.Structure):
         ("past_capacity", ctypes.c_int64), ("kv_policy", ctypes.POINTER(ctypes.c_uint8)),
         ("scale", ctypes.c_float), ("fp32_check", ctypes.c_int32), ("out_fp32", ctypes.c_int32),
         ("retrieved_capacity", ctypes.c_int32), ("rope_theta", ctypes.c_float),
+        ("prefill_waves", ctypes.c_int32), ("item_queues", ctypes.c_int32),
     ]
 
 
@@ -109,11 +110,13 @@ def _check(st: int, where: str) -> None:
 def make_config(*, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seg_len: int,
                 tail_len: int, kv_policy: Sequence[int], past_capacity: int = 0, scale: float = 0.0,
                 fp32_check: bool = False, out_fp32: bool = False,
-                retrieved_capacity: int = 0, rope_theta: float = 0.0) -> segattn_config:
+                retrieved_capacity: int = 0, rope_theta: float = 0.0, prefill_waves: int = 0,
+                item_queues: int = 0) -> segattn_config:
     pol = (ctypes.c_uint8 * len(kv_policy))(*[int(p) for p in kv_policy])
     cfg = segattn_config(batch, n_q_heads, n_kv_heads, head_dim, seg_len, tail_len, past_capacity,
                          ctypes.cast(pol, ctypes.POINTER(ctypes.c_uint8)), scale,
-                         int(fp32_check), int(out_fp32), int(retrieved_capacity), float(rope_theta))
+                         int(fp32_check), int(out_fp32), int(retrieved_capacity), float(rope_theta),
+                         int(prefill_waves), int(item_queues))
     cfg._policy_keepalive = pol
     return cfg
 

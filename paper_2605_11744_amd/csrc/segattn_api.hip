@@ -28,7 +28,11 @@ bool build_problem(const segattn_config *cfg, bool need_cache, Problem &p) {
   if ((long long)cfg->seg_len + cfg->tail_len >= (1ll << 30)) return false;
   if (!(cfg->scale >= 0.f) || isinf(cfg->scale)) return false;
   if (!(cfg->rope_theta >= 0.f) || isinf(cfg->rope_theta)) return false;
+  if (cfg->prefill_waves != 0 && cfg->prefill_waves != 4 && cfg->prefill_waves != 8) return false;
+  if (cfg->item_queues < 0 || cfg->item_queues > 3) return false;
   memset(&p, 0, sizeof(p));
+  p.tune_waves = cfg->prefill_waves;
+  p.tune_queue = cfg->item_queues;
   p.B = cfg->batch;
   p.Hq = cfg->n_q_heads;
   p.Hkv = cfg->n_kv_heads;
@@ -107,6 +111,15 @@ bool build_geom(const segattn_config *cfg, const Problem &p, CacheGeom &g, unsig
 
 segattn_status hip_status(hipError_t e) { return e == hipSuccess ? SEGATTN_OK : SEGATTN_EHIP; }
 
+// After the runtime has refused a launch or a copy in the middle of a stateful call, earlier
+// kernels of that call may already be in the stream, so the device counters can be ahead of the
+// host mirror.  The context stops accepting stateful calls until reset / set_lengths.
+template <typename Ctx>
+segattn_status hip_failed(Ctx *ctx) {
+  ctx->ready = false;
+  return SEGATTN_EHIP;
+}
+
 void fill_inv_freq(double (&t)[64], int D, float theta) {
   for (int i = 0; i < 64; ++i) t[i] = i < D / 2 ? pow((double)theta, -2.0 * i / D) : 0.0;
 }
@@ -123,7 +136,6 @@ struct segattn_ctx {
   std::vector<int> tail, fill;      // [B]
   std::vector<long long> pool, lo;  // [B*Hkv] (PAST heads)
   std::vector<int> ret;             // [B] rows of the retrieved prefix (retrieval mode)
-  std::vector<int> staging;         // host image of the device counters for set_lengths
 };
 
 extern "C" {
@@ -167,7 +179,7 @@ void segattn_destroy(segattn_ctx *ctx) { delete ctx; }
 segattn_status segattn_reset(segattn_ctx *ctx, void *stream) {
   if (!ctx) return SEGATTN_EINVAL;
   hipError_t e = launch_cache_reset(ctx->p, ctx->cache, ctx->g, (hipStream_t)stream);
-  if (e != hipSuccess) return SEGATTN_EHIP;
+  if (e != hipSuccess) return hip_failed(ctx);
   std::fill(ctx->closed.begin(), ctx->closed.end(), 0);
   std::fill(ctx->tail.begin(), ctx->tail.end(), 0);
   std::fill(ctx->fill.begin(), ctx->fill.end(), 0);
@@ -370,7 +382,7 @@ segattn_status seg_kv_commit(segattn_ctx *ctx, const void *k, const void *v, int
   a.m = m;
   hipError_t e = launch_cache_append(p, a, (hipStream_t)stream);
   if (e == hipSuccess) e = launch_cache_close(p, ctx->cache, ctx->g, m, (hipStream_t)stream);
-  if (e != hipSuccess) return SEGATTN_EHIP;
+  if (e != hipSuccess) return hip_failed(ctx);
   (void)any_full;
   for (int b = 0; b < p.B; ++b) {
     ctx->fill[b] += m;
@@ -403,7 +415,7 @@ segattn_status seg_kv_commit_seq(segattn_ctx *ctx, const void *k, const void *v,
   a.cache = ctx->cache;
   a.geom = ctx->g;
   a.m = (int)n;
-  if (launch_cache_commit_seq(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  if (launch_cache_commit_seq(p, a, (hipStream_t)stream) != hipSuccess) return hip_failed(ctx);
   const long long n_full = n / p.S;
   for (int b = 0; b < p.B; ++b) {
     ctx->fill[b] = (int)(n % p.S);
@@ -436,7 +448,7 @@ segattn_status seg_kv_past_append(segattn_ctx *ctx, int32_t kv_head, const void 
   a.geom = ctx->g;
   a.m = (int)rows;
   a.kv_head = kv_head;
-  if (launch_cache_past_append(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  if (launch_cache_past_append(p, a, (hipStream_t)stream) != hipSuccess) return hip_failed(ctx);
   for (int b = 0; b < p.B; ++b) ctx->pool[(size_t)b * p.Hkv + kv_head] += rows;
   return SEGATTN_OK;
 }
@@ -461,7 +473,7 @@ segattn_status seg_kv_past_select(segattn_ctx *ctx, const int32_t *idx, int32_t 
   a.R = R;
   a.rope = ctx->rope_theta > 0.f;
   if (a.rope) fill_inv_freq(a.inv_freq, p.D, ctx->rope_theta);
-  if (launch_cache_select(p, a, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  if (launch_cache_select(p, a, (hipStream_t)stream) != hipSuccess) return hip_failed(ctx);
   for (int b = 0; b < p.B; ++b) ctx->ret[b] = R;
   return SEGATTN_OK;
 }
@@ -571,16 +583,16 @@ static segattn_status evict_rows(segattn_ctx *ctx, int32_t kv_head, int64_t n_ol
   if (!(p.policy[kv_head] & SEGATTN_PAST)) return SEGATTN_EINVAL;
   if (!ctx->ready) return SEGATTN_ESTATE;
   if (launch_cache_evict(p, ctx->cache, ctx->g, kv_head, n_oldest, keep, (hipStream_t)stream) != hipSuccess)
-    return SEGATTN_EHIP;
+    return hip_failed(ctx);
   for (int b = 0; b < p.B; ++b) {
     const size_t i = (size_t)b * p.Hkv + kv_head;
     long long limit = ctx->pool[i];
     long long n = n_oldest;
     if (keep >= 0) n = limit - ctx->lo[i] > keep ? limit - ctx->lo[i] - keep : 0;
     if (p.policy[kv_head] & SEGATTN_TAIL) limit -= ctx->tail[b];
-    long long lo_new = ctx->lo[i] + n < limit ? ctx->lo[i] + n : limit;
-    if (lo_new < ctx->lo[i]) lo_new = ctx->lo[i];
-    ctx->lo[i] = lo_new;
+    // at most the rows still visible below the limit (n may be anything up to INT64_MAX)
+    const long long room = limit > ctx->lo[i] ? limit - ctx->lo[i] : 0;
+    ctx->lo[i] += n < room ? n : room;
   }
   return SEGATTN_OK;
 }
@@ -621,18 +633,20 @@ segattn_status seg_kv_set_lengths(segattn_ctx *ctx, const int64_t *closed_rows, 
     if (tail[b] < 0 || tail[b] > p.T || tail[b] > closed_rows[b]) return SEGATTN_EINVAL;
     if (p.n_past && closed_rows[b] + seg_fill[b] > (long long)ctx->g.pool_cap) return SEGATTN_ECAPACITY;
   }
-  ctx->staging.assign((size_t)p.B * p.Hkv * kMetaInts, 0);
-  for (int b = 0; b < p.B; ++b)
-    for (int h = 0; h < p.Hkv; ++h) {
-      int *m = &ctx->staging[((size_t)b * p.Hkv + h) * kMetaInts];
-      m[META_POOL] = (p.policy[h] & SEGATTN_PAST) ? (int)closed_rows[b] : 0;
-      m[META_TAIL] = tail[b];
-      m[META_FILL] = seg_fill[b];
-      m[META_LO] = 0;
+  // The counters are written by a kernel that takes the lengths by value (a chunk of sequences
+  // per launch): nothing the stream still has to read lives in host memory after the call.
+  for (int b0 = 0; b0 < p.B; b0 += kLengthsChunk) {
+    LengthsArgs la;
+    memset(&la, 0, sizeof(la));
+    la.b0 = b0;
+    la.count = p.B - b0 < kLengthsChunk ? p.B - b0 : kLengthsChunk;
+    for (int i = 0; i < la.count; ++i) {
+      la.closed[i] = (int)closed_rows[b0 + i];
+      la.tail[i] = tail[b0 + i];
+      la.fill[i] = seg_fill[b0 + i];
     }
-  if (hipMemcpyAsync(ctx->cache + ctx->g.meta_off, ctx->staging.data(), ctx->staging.size() * sizeof(int),
-                     hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
-    return SEGATTN_EHIP;
+    if (launch_cache_set_lengths(p, ctx->cache, ctx->g, la, (hipStream_t)stream) != hipSuccess) return hip_failed(ctx);
+  }
   for (int b = 0; b < p.B; ++b) {
     ctx->closed[b] = closed_rows[b];
     ctx->tail[b] = tail[b];
@@ -699,7 +713,7 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   ca.cache = ctx->cache;
   ca.geom = ctx->g;
   ca.m = 1;
-  if (launch_cache_decode_append(p, ca, st) != hipSuccess) return SEGATTN_EHIP;
+  if (launch_cache_decode_append(p, ca, st) != hipSuccess) return hip_failed(ctx);
   DecodeArgs da;
   memset(&da, 0, sizeof(da));
   da.q = (const unsigned short *)q;
@@ -710,8 +724,8 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   da.cache = ctx->cache;
   da.geom = ctx->g;
   da.total_rows = total_rows;
-  if (launch_decode(p, da, p.B, st) != hipSuccess) return SEGATTN_EHIP;
-  if (any_full && launch_cache_close(p, ctx->cache, ctx->g, 0, st) != hipSuccess) return SEGATTN_EHIP;
+  if (launch_decode(p, da, p.B, st) != hipSuccess) return hip_failed(ctx);
+  if (any_full && launch_cache_close(p, ctx->cache, ctx->g, 0, st) != hipSuccess) return hip_failed(ctx);
   for (int b = 0; b < p.B; ++b) {
     ctx->fill[b] += 1;
     if (ctx->fill[b] == p.S) {

@@ -250,23 +250,12 @@ static hipError_t launch_dq(const Problem &p, const BwdArgs &a, hipStream_t st) 
   // resident grid + item queues where every resident workgroup would get more than two items
   const void *kern = hs == 4 ? (const void *)bwd_dq_kernel<D, 4> : hs == 2 ? (const void *)bwd_dq_kernel<D, 2>
                                                                             : (const void *)bwd_dq_kernel<D, 1>;
-  long long launch = grid_q;
-  const int mode = item_queue_mode();
-  if (mode != 0) {
-    int per_cu = 0, dev = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, 0) != hipSuccess || hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
-      (void)hipGetLastError();
-      per_cu = 0;
-    }
-    const long long resident = (long long)per_cu * cus;
-    if (resident > 0 && (mode > 0 ? grid_q > 1 : grid_q > 2 * resident)) {
-      pa.queue = item_queue_for(st);
-      if (pa.queue) {
-        launch = resident < grid_q ? resident : grid_q;
-        if (mode == 2 && grid_q / 3 < launch) launch = grid_q / 3 > 0 ? grid_q / 3 : 1;
-      }
-    }
+  static ResidentCount resident_count[3];  // per heads-per-workgroup instantiation, asked once
+  const int resident = p.tune_queue == 1 ? 0 : resident_count[hs == 4 ? 2 : hs == 2 ? 1 : 0].get(kern, 256, 0);
+  long long launch = item_queue_grid(p, grid_q, resident);
+  if (launch != grid_q || (p.tune_queue >= 2 && grid_q > 1 && resident > 0)) {
+    pa.queue = item_queue_for(st);
+    if (!pa.queue) launch = grid_q;
   }
   std::unique_lock<std::mutex> pair;  // reset and launch enter the stream back to back
   if (pa.queue) {

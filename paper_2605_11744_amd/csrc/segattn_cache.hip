@@ -256,9 +256,25 @@ __global__ void cache_evict_kernel(const Problem p, unsigned char *cache, const 
   long long limit = meta[META_POOL];
   if (keep >= 0) n = limit - lo > keep ? limit - lo - keep : 0;
   if (p.policy[h] & SEGATTN_TAIL) limit -= meta[META_TAIL];
-  long long lo_new = lo + n < limit ? lo + n : limit;
-  if (lo_new < lo) lo_new = lo;
-  meta[META_LO] = (int)lo_new;
+  // at most the rows still visible below the limit (n may be anything up to INT64_MAX)
+  const long long room = limit > lo ? limit - lo : 0;
+  meta[META_LO] = (int)(lo + (n < room ? n : room));
+}
+
+// Counters of a chunk of sequences as the caller declares them (seg_kv_set_lengths): pool rows
+// of a PAST head = the rows in closed segments, nothing evicted, no retrieved prefix.
+__global__ void cache_set_lengths_kernel(const Problem p, unsigned char *cache, const CacheGeom g,
+                                         const LengthsArgs a) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.count * p.Hkv) return;
+  const int s = i / p.Hkv, h = i % p.Hkv;
+  int *meta = meta_of(cache, g, p, a.b0 + s, h);
+  meta[META_POOL] = (p.policy[h] & SEGATTN_PAST) ? a.closed[s] : 0;
+  meta[META_TAIL] = a.tail[s];
+  meta[META_FILL] = a.fill[s];
+  meta[META_LO] = 0;
+  meta[META_RET] = 0;
+  meta[5] = meta[6] = meta[7] = 0;
 }
 
 // Retrieved prefix of every PAST head (Appendix D "Output"): pool rows idx[b][past head][0..R)
@@ -368,6 +384,13 @@ hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_
   const dim3 grid(chunks, p.B * p.n_past);
   if (p.D == 128) hipLaunchKernelGGL(cache_select_kernel<128>, grid, dim3(256), 0, st, p, a);
   else hipLaunchKernelGGL(cache_select_kernel<64>, grid, dim3(256), 0, st, p, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_set_lengths(const Problem &p, unsigned char *cache, const CacheGeom &g, const LengthsArgs &a,
+                                    hipStream_t st) {
+  const int n = a.count * p.Hkv;
+  hipLaunchKernelGGL(cache_set_lengths_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, cache, g, a);
   return hipGetLastError();
 }
 

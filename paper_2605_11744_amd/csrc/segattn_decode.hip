@@ -327,17 +327,8 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const Problem p, co
 // Workgroups of the split kernel the chip holds at once (per instantiation, asked once).
 template <int D, int GH, bool EXACT>
 static int resident_workgroups() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_kernel<D, GH, EXACT>, 256, 0) != hipSuccess ||
-        cus < 1 || per_cu < 1)
-      return 0;
-    n = cus * per_cu;
-  }
-  return n;
+  static ResidentCount count;
+  return count.get((const void *)decode_split_kernel<D, GH, EXACT>, 256, 0);
 }
 
 template <int D, int GH, bool EXACT>

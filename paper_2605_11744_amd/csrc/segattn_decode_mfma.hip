@@ -248,19 +248,9 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma_kernel(const Problem
 }
 
 int decode_mfma_resident(int D) {
-  static int n[2] = {0, 0};
-  int &r = n[D == 128];
-  if (r == 0) {
-    int dev = 0, cus = 0, per_cu = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e == hipSuccess)
-      e = D == 128 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<128>, 256, 0)
-                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_split_mfma_kernel<64>, 256, 0);
-    if (e != hipSuccess || cus < 1 || per_cu < 1) return 0;
-    r = cus * per_cu;
-  }
-  return r;
+  static ResidentCount count[2];
+  return D == 128 ? count[1].get((const void *)decode_split_mfma_kernel<128>, 256, 0)
+                  : count[0].get((const void *)decode_split_mfma_kernel<64>, 256, 0);
 }
 
 hipError_t launch_decode_split_mfma(const Problem &p, const DecodeArgs &a, long long blocks, hipStream_t st) {

@@ -4,6 +4,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "segattn.h"
@@ -54,6 +55,8 @@ struct Problem {
   int out_fp32;         // `out` holds fp32 instead of bf16
   int fp32_math;        // validation mode: fp32 FMA kernels
   int n_past;           // number of PAST heads
+  int tune_waves;       // host only: 0, or the forced waves per workgroup of the D = 128 forward kernel (4 / 8)
+  int tune_queue;       // host only: item queues -- 0 the library chooses, 1 never, 2 always, 3 always, small grid
   // Per-head tables as 32-bit words: a kernel indexes them with a workgroup-uniform value, and
   // only whole words of the argument block can be fetched with scalar loads (bytes would go
   // through the vector memory path and cost every workgroup a memory round trip each).
@@ -99,14 +102,49 @@ struct PrefillArgs {
 constexpr int kQueueStride = 32;  // unsigned words between two queue counters (128 bytes)
 // Host side of the item queues (segattn_prefill_mfma.hip): the counters of this (device, stream),
 // or nullptr where the launch has to run one workgroup per item (stream under capture, no set
-// left); the kernel that clears them, to be launched in front of every queued launch; and the
-// SEGATTN_PREFILL_QUEUE setting (-1 unset, 0 off, 1 on, 2 on with a grid a third of the items).
+// left); and the kernel that clears them, to be launched in front of every queued launch.
 // The reset and the launch that uses the counters must enter the stream back to back: hold
 // item_queue_launch_mutex() around the pair (two host threads may launch into one stream).
 unsigned *item_queue_for(hipStream_t st);
 hipError_t item_queue_reset(unsigned *queue, hipStream_t st);
 std::mutex &item_queue_launch_mutex();
-int item_queue_mode();
+// Grid of a launch of `items` work items whose kernel fits `resident` workgroups on the chip at
+// once, under Problem::tune_queue: `items` (one workgroup per item, no queues), or fewer
+// workgroups that take their items from the queues.  The library's own choice is the resident
+// grid whenever a workgroup would get more than two items (with fewer there is little to balance
+// and the counters' reset kernel and first round trip are not earned back).
+inline long long item_queue_grid(const Problem &p, long long items, long long resident) {
+  if (resident <= 0 || p.tune_queue == 1) return items;
+  if (p.tune_queue >= 2 ? items <= 1 : items <= 2 * resident) return items;
+  long long launch = resident < items ? resident : items;
+  if (p.tune_queue == 3 && items / 3 < launch) launch = items / 3 > 0 ? items / 3 : 1;
+  return launch;
+}
+
+// Workgroups of one kernel that the device holds at once: asked from the runtime by the first
+// launch and kept.  Safe from any number of host threads: racing first calls ask the same
+// question and store the same answer.  0: the query failed (asked again by the next launch).
+class ResidentCount {
+ public:
+  int get(const void *kernel, int threads, size_t dynamic_lds) {
+    int v = n_.load(std::memory_order_acquire);
+    if (v > 0) return v;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dynamic_lds) != hipSuccess ||
+        cus < 1 || per_cu < 1) {
+      (void)hipGetLastError();
+      return 0;
+    }
+    v = cus * per_cu;
+    n_.store(v, std::memory_order_release);
+    return v;
+  }
+
+ private:
+  std::atomic<int> n_{0};
+};
 
 struct DecodeArgs {
   const unsigned short *q, *k_new, *v_new;
@@ -169,6 +207,13 @@ __device__ inline int seq_of_row(const Problem &p, const BwdArgs &a, long long r
   }
   return lo;
 }
+
+// seg_kv_set_lengths: the declared lengths of a chunk of sequences, by value.
+constexpr int kLengthsChunk = 128;
+struct LengthsArgs {
+  int b0, count;                       // sequences b0 .. b0 + count - 1
+  int closed[kLengthsChunk], tail[kLengthsChunk], fill[kLengthsChunk];
+};
 
 struct SelectArgs {
   const int *idx;        // [B, n_past, R] pool row numbers
@@ -295,6 +340,8 @@ hipError_t launch_cache_past_append(const Problem &p, const CopyArgs &a, hipStre
 hipError_t launch_cache_evict(const Problem &p, unsigned char *cache, const CacheGeom &g, int kv_head,
                               long long n_oldest, long long keep, hipStream_t st);
 hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_t st);
+hipError_t launch_cache_set_lengths(const Problem &p, unsigned char *cache, const CacheGeom &g, const LengthsArgs &a,
+                                    hipStream_t st);
 hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t st);
 hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st);
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);

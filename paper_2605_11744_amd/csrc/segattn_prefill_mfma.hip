@@ -36,8 +36,7 @@
 // the barriers until the other waves of the workgroup are done.  Paths outside that step matter
 // more than their share of the arithmetic suggests: a register spilled there is reloaded
 // through the same counter the K/V prefetch uses, and waiting for it drains the prefetch queue.
-#include <stdlib.h>
-
+#include <atomic>
 #include <mutex>
 
 #include <type_traits>
@@ -917,51 +916,30 @@ unsigned *item_queue_for(hipStream_t st) {
   return base[dev] + 8 * kQueueStride * set;
 }
 
-// SEGATTN_PREFILL_QUEUE in the environment: 0 = never take items from queues; 1 = whenever there
-// is more than one item; 2 = the same with a grid of a third of the items (small test inputs then
-// loop and steal too); unset = when there are more than twice as many items as workgroups fit the
-// chip at once (with two items or fewer per workgroup there is little to balance, and the
-// counters' reset kernel and first round trip are not earned back: measured equal or slightly
-// slower there).  Read at every launch.
-int item_queue_mode() {
-  if (const char *e = getenv("SEGATTN_PREFILL_QUEUE")) {
-    if (e[0] == '0') return 0;
-    if (e[0] == '1') return 1;
-    if (e[0] == '2') return 2;
-  }
-  return -1;
-}
-
 template <int D, int HS, int QB, int NW>
 static hipError_t launch_mfma(const Problem &p, const PrefillArgs &a_in, long long grid, hipStream_t st) {
   constexpr int ring = ring_slots(NW, QB) * StepGeom<D>::kSlotBytes;
   constexpr int epilogue = NW * 32 * (D * 4 + 8);  // fp32 output staging, one block per wave
   constexpr int lds = ring > epilogue ? ring : epilogue;
   auto kern = prefill_mfma_kernel<D, HS, QB, NW>;
-  static bool attr_set = false;
-  static int resident = 0;  // workgroups of this kernel that fit the chip at once (-1: unknown)
-  if (!attr_set) {
+  // First launch of this instantiation: allow the kernel its LDS, ask how many workgroups the chip
+  // holds.  Both steps give the same result whoever does them, so host threads racing through
+  // their first call simply do them twice; `ready` is set only after the attribute is in place.
+  static std::atomic<bool> ready{false};
+  static ResidentCount resident_count;
+  if (!ready.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    int per_cu = 0;
-    resident = -1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * NW, lds) == hipSuccess && per_cu > 0)
-      resident = per_cu * device_cus();
-    else
-      (void)hipGetLastError();
-    attr_set = true;
+    ready.store(true, std::memory_order_release);
   }
+  const int resident = resident_count.get((const void *)kern, 64 * NW, lds);  // 0: unknown, no queues
   PrefillArgs a = a_in;
   a.grid_items = (int)grid;
   a.queue = nullptr;
-  long long launch = grid;
-  const int mode = item_queue_mode();
-  if (resident > 0 && mode != 0 && (mode > 0 ? grid > 1 : grid > 2ll * resident)) {
+  long long launch = item_queue_grid(p, grid, resident);
+  if (launch != grid || (p.tune_queue >= 2 && grid > 1 && resident > 0)) {
     a.queue = item_queue_for(st);
-    if (a.queue) {
-      launch = resident < grid ? resident : grid;
-      if (mode == 2 && grid / 3 < launch) launch = grid / 3 > 0 ? grid / 3 : 1;  // small inputs loop too
-    }
+    if (!a.queue) launch = grid;
   }
   if (!a.queue) {
     hipLaunchKernelGGL(kern, dim3((unsigned)launch), dim3(64 * NW), lds, st, p, a);
@@ -999,20 +977,10 @@ int prefill_pair_stride(long long groups) {
 // the number of workgroups: right when the long (PAST) workgroups of a launch would otherwise
 // leave CUs idle, which is the case for a segment-by-segment prefill (one segment has 64-row
 // blocks for only half of the CUs, and they carry nearly all of the work).
-// SEGATTN_PREFILL_WAVES=4|8 in the environment overrides the choice (used by the tests to run
-// both variants on small inputs).
+// segattn_config.prefill_waves overrides the choice (the tests run both shapes on small inputs).
 static int waves_d128(const Problem &p, const PrefillArgs &a, int hs) {
-  if (const char *e = getenv("SEGATTN_PREFILL_WAVES")) {  // read at every launch: tests switch it
-    const int v = atoi(e);
-    if (v == 4 || v == 8) return v;
-  }
-  static const int n_cu = [] {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    return cus;
-  }();
+  if (p.tune_waves == 4 || p.tune_waves == 8) return p.tune_waves;
+  const int n_cu = device_cus();
   const long long seg_rows = a.n_rows < p.S ? a.n_rows : p.S;
   const int rows8 = (8 / hs) * 32;
   const long long blocks8 = (long long)a.n_seg * ((seg_rows + rows8 - 1) / rows8);
@@ -1040,7 +1008,7 @@ static int device_cus() {
 // keeping at least 1024 rows.
 static int prefix_parts(const Problem &p, const PrefillArgs &a, int hs) {
   if (a.cache == nullptr || a.geom.part_max < 2 || p.n_past == 0 || a.geom.ret_cap > 0 || p.D != 128) return 1;
-  if (getenv("SEGATTN_PREFILL_WAVES")) return 1;  // a forced workgroup shape runs unsplit
+  if (p.tune_waves != 0) return 1;  // a forced workgroup shape runs unsplit
   const int rows8 = (8 / hs) * 32;
   const long long long_wgs = (long long)p.B * p.n_past * (p.g / hs) * ((a.n_rows + rows8 - 1) / rows8);
   long long parts = device_cus() / long_wgs;

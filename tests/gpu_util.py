@@ -9,6 +9,12 @@ import paper_2605_11744_amd as sa
 BF16_MAX_ABS, BF16_MEAN_ABS, FP32_MAX_ABS = 1e-2, 1e-3, 1e-4
 
 
+# Launch-shape overrides every configuration built by config_of() carries (segattn_config.
+# prefill_waves / item_queues); tests switch them with monkeypatch.setitem.
+TUNING = {"prefill_waves": 0, "item_queues": 0}
+QUEUES_OFF, QUEUES_ON, QUEUES_ON_SMALL_GRID = 1, 2, 3
+
+
 def dev_bf16(bits: np.ndarray) -> torch.Tensor:
     t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
     return t.cuda().view(torch.bfloat16)
@@ -24,7 +30,7 @@ def config_of(w, *, fp32_check=False, out_fp32=False, past_capacity=0, batch=Non
                           n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, seg_len=w.seg_len,
                           tail_len=w.tail_len, kv_policy=w.kv_policy, past_capacity=past_capacity,
                           scale=scale, fp32_check=fp32_check, out_fp32=out_fp32,
-                          retrieved_capacity=retrieved_capacity)
+                          retrieved_capacity=retrieved_capacity, **TUNING)
 
 
 def fwd_seq(w, q_bits, k_bits, v_bits, *, fp32_check=False, out_fp32=True, scale=0.0):
@@ -52,6 +58,52 @@ def assert_parity(o_gpu, l_gpu, o_ref, l_ref, *, fp32_check, what=""):
         assert eo.mean() <= BF16_MEAN_ABS, f"{what}: O mean-abs {eo.mean():.3e}"
         assert el.mean() <= BF16_MEAN_ABS, f"{what}: LSE mean-abs {el.mean():.3e}"
     return eo.max(), eo.mean(), el.max(), el.mean()
+
+
+def cache_rows_held(w, k_done, c_fill):
+    """[B][Hkv]: how many trailing rows of a sequence's history the cache arena has room for when
+    the token at in-segment offset c_fill - 1 is being decoded, by the layout segattn_cache_span
+    documents: a PAST head's block holds every position; any other head's block holds T tail slots
+    and the open segment."""
+    return [[int(k_done[b]) * w.seg_len + int(c_fill[b]) if pol & 2
+             else min(w.tail_len, int(k_done[b]) * w.seg_len) + int(c_fill[b])
+             for pol in w.kv_policy] for b in range(w.batch)]
+
+
+def fill_cache_for_decode(c, w, ks, vs, k_done, c_fill):
+    """Write the rows before the token being decoded into the arena of Cache `c` through
+    segattn_cache_span's layout (PAST head: row = position; other heads: tail in rows [T - tail, T),
+    open segment from row T) and declare the lengths.  ks[b][h], vs[b][h] hold trailing rows of the
+    history (at least as many as cache_rows_held), newest last.  Returns (k_new, v_new) [B,Hkv,D]."""
+    S, T, D, Hkv = w.seg_len, w.tail_len, w.head_dim, w.n_kv_heads
+    k_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
+    v_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
+    held = cache_rows_held(w, k_done, c_fill)
+    for b in range(w.batch):
+        for h, pol in enumerate(w.kv_policy):
+            kk, vv = ks[b][h][-held[b][h]:], vs[b][h][-held[b][h]:]
+            k_new[b, h], v_new[b, h] = kk[-1], vv[-1]
+            kd, vd = c.rows_view(b, h)
+            n_prev = kk.shape[0] - 1
+            first = 0 if pol & 2 else T - min(T, int(k_done[b]) * S)
+            if n_prev:
+                kd[first:first + n_prev] = dev_bf16(kk[:-1])
+                vd[first:first + n_prev] = dev_bf16(vv[:-1])
+    sa.seg_kv_set_lengths(c.ctx, [int(x) * S for x in k_done], [min(T, int(x) * S) for x in k_done],
+                          [int(x) - 1 for x in c_fill], c.stream)
+    return k_new, v_new
+
+
+def full_history(ks_b, vs_b, n_b, Hkv, D):
+    """[n_b, Hkv, D] float64 K and V of one sequence for the oracle: rows that were not drawn
+    (older than a head's trailing rows) are zero."""
+    from oracle import segattn_oracle as orc
+    kf, vf = np.zeros((n_b, Hkv, D)), np.zeros((n_b, Hkv, D))
+    for h in range(Hkv):
+        kept = ks_b[h].shape[0]
+        kf[n_b - kept:, h] = orc.widen(ks_b[h])
+        vf[n_b - kept:, h] = orc.widen(vs_b[h])
+    return kf, vf
 
 
 class Cache:

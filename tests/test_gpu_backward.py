@@ -66,7 +66,8 @@ CASES = [
 def test_backward_matches_oracle(fp32_check, D, Hq, Hkv, S, T, n, policy, batch, monkeypatch):
     if fp32_check == "queued":   # the MFMA kernels, dQ (and the forward) as a resident grid that takes
         fp32_check = False       # its work items from queues (what large launches do by themselves)
-        monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
+        import gpu_util
+        monkeypatch.setitem(gpu_util.TUNING, "item_queues", gpu_util.QUEUES_ON_SMALL_GRID)
     w = W.small(seq_len=n, seg_len=S, tail_len=T, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D,
                 kv_policy=policy, batch=batch)
     q, k, v = W.prefill_inputs(w)

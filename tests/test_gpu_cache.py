@@ -38,14 +38,11 @@ def test_streaming_prefill_equals_oracle(case, fp32_check, waves, monkeypatch):
     if waves == "queue":   # the library's own workgroup shape, work items taken from queues
         if fp32_check:
             pytest.skip("the item queues only exist in the MFMA kernel")
-        monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
-        monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
+        monkeypatch.setitem(G.TUNING, "item_queues", G.QUEUES_ON_SMALL_GRID)
     elif waves != "auto":
         if fp32_check or kw["head_dim"] != 128:
             pytest.skip("the wave count only exists in the head_dim-128 MFMA kernel")
-        monkeypatch.setenv("SEGATTN_PREFILL_WAVES", waves)
-    else:
-        monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
+        monkeypatch.setitem(G.TUNING, "prefill_waves", int(waves))
     w = W.small(f"stream{case}", index=200 + case, **kw)
     q, k, v = W.prefill_inputs(w)
     o_ref, l_ref = _oracle(w, q, k, v)
@@ -112,31 +109,14 @@ def _decode_from_restored_cache(w, k_done, c_fill, fp32_check=False):
     import gpu_util as G
     import paper_2605_11744_amd as sa
     S, T, B, Hkv, D = w.seg_len, w.tail_len, w.batch, w.n_kv_heads, w.head_dim
-    q, ks, vs, _, _ = W.decode_inputs(w, k_done, c_fill)
+    q, ks, vs, _, _ = W.decode_inputs(w, k_done, c_fill)      # whole histories: the oracle sees every row
     c = G.Cache(w, past_capacity=w.max_context, fp32_check=fp32_check)
     try:
-        k_new = np.zeros((B, Hkv, D), dtype=np.uint16)
-        v_new = np.zeros((B, Hkv, D), dtype=np.uint16)
-        for b in range(B):
-            for h, pol in enumerate(w.kv_policy):
-                kk, vv = ks[b][h], vs[b][h]            # kept rows, newest (being decoded) last
-                k_new[b, h], v_new[b, h] = kk[-1], vv[-1]
-                kd, vd = c.rows_view(b, h)
-                n_prev = kk.shape[0] - 1
-                first = 0 if pol & 2 else (T - min(T, int(k_done[b]) * S) if pol & 1 else T)
-                if n_prev:
-                    kd[first:first + n_prev] = G.dev_bf16(kk[:-1])
-                    vd[first:first + n_prev] = G.dev_bf16(vv[:-1])
-        sa.seg_kv_set_lengths(c.ctx, [int(x) * S for x in k_done], [T] * B, [int(x) - 1 for x in c_fill], c.stream)
+        k_new, v_new = G.fill_cache_for_decode(c, w, ks, vs, k_done, c_fill)
         o, l = c.decode(q, k_new, v_new)
         for b in range(B):
             n_b = int(k_done[b]) * S + int(c_fill[b])
-            kf = np.zeros((n_b, Hkv, D))
-            vf = np.zeros((n_b, Hkv, D))
-            for h in range(Hkv):
-                kept = ks[b][h].shape[0]
-                kf[n_b - kept:, h] = orc.widen(ks[b][h])
-                vf[n_b - kept:, h] = orc.widen(vs[b][h])
+            kf, vf = G.full_history(ks[b], vs[b], n_b, Hkv, D)
             o_ref, l_ref = orc.decode_attend(q[b], kf, vf, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
             G.assert_parity(o[b], l[b], o_ref, l_ref, fp32_check=fp32_check, what=f"{w.name} decode b={b}")
         return sa.seg_kv_lengths(c.ctx, B, Hkv)
@@ -187,6 +167,32 @@ def test_evict_hides_oldest_pool_rows():
         G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="evict")
         past, _, _ = sa.seg_kv_lengths(c.ctx, 1, 2)
         assert past[0] == [256 - 176, 256 - 50]      # the last fwd committed a fourth segment
+    finally:
+        c.close()
+
+
+def test_evicting_more_rows_than_any_count_hides_the_whole_pool():
+    """n_oldest up to INT64_MAX after an earlier eviction (the first visible row is no longer 0, so
+    first + n must not wrap): everything goes, except the tail window of a TAIL|PAST head; device
+    counters and the host's bookkeeping agree (the next segment matches the oracle)."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    w = W.small("evict_all", index=231, seq_len=256, seg_len=64, tail_len=16, n_q_heads=4, n_kv_heads=2,
+                head_dim=64, kv_policy=[3, 2])
+    q, k, v = W.prefill_inputs(w)
+    c = G.Cache(w, past_capacity=256)
+    try:
+        for s in range(0, 192, 64):
+            c.fwd(q[:, s:s + 64], k[:, s:s + 64], v[:, s:s + 64])
+        sa.seg_kv_past_evict(c.ctx, 0, 7, c.stream)
+        sa.seg_kv_past_evict(c.ctx, 1, 9, c.stream)
+        for h in (0, 1):
+            sa.seg_kv_past_evict(c.ctx, h, 2 ** 63 - 1, c.stream)
+        past, _, _ = sa.seg_kv_lengths(c.ctx, 1, 2)
+        assert past[0] == [16, 0]
+        o, l = c.fwd(q[:, 192:], k[:, 192:], v[:, 192:])
+        o_ref, l_ref = _oracle(w, q, k, v, rows=np.arange(192, 256), evicted=[192, 192])
+        G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="evict everything")
     finally:
         c.close()
 

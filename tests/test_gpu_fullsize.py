@@ -119,32 +119,18 @@ def test_decode_c5_full_batch(fp32_check):
     import paper_2605_11744_amd as sa
     w = W.C5
     S, T, D, Hkv = w.seg_len, w.tail_len, w.head_dim, w.n_kv_heads
-    q, ks, vs, k_done, c_fill = W.decode_inputs(w)
+    k_done, c_fill = W.decode_lengths(w)
+    # only the rows the arena has room for are drawn (3 GB instead of 9 GB); the oracle gets zeros
+    # for the rest, so a row wrongly visible or wrongly dropped on either side shows up
+    q, ks, vs, _, _ = W.decode_inputs(w, k_done, c_fill, trailing_rows=G.cache_rows_held(w, k_done, c_fill))
     c = G.Cache(w, past_capacity=w.max_context, out_fp32=False, fp32_check=fp32_check)
     try:
-        k_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
-        v_new = np.zeros((w.batch, Hkv, D), dtype=np.uint16)
-        for b in range(w.batch):
-            for h, pol in enumerate(w.kv_policy):
-                kk, vv = ks[b][h], vs[b][h]
-                k_new[b, h], v_new[b, h] = kk[-1], vv[-1]
-                kd, vd = c.rows_view(b, h)
-                n_prev = kk.shape[0] - 1
-                first = 0 if pol & 2 else (T - min(T, int(k_done[b]) * S) if pol & 1 else T)
-                if n_prev:
-                    kd[first:first + n_prev] = G.dev_bf16(kk[:-1])
-                    vd[first:first + n_prev] = G.dev_bf16(vv[:-1])
-        sa.seg_kv_set_lengths(c.ctx, [int(x) * S for x in k_done], [T] * w.batch, [int(x) - 1 for x in c_fill], c.stream)
+        k_new, v_new = G.fill_cache_for_decode(c, w, ks, vs, k_done, c_fill)
         o, l = c.decode(q, k_new, v_new)
         worst = worst_l = 0.0
         for b in range(w.batch):
             n_b = int(k_done[b]) * S + int(c_fill[b])
-            kf = np.zeros((n_b, Hkv, D))
-            vf = np.zeros((n_b, Hkv, D))
-            for h in range(Hkv):
-                kept = ks[b][h].shape[0]
-                kf[n_b - kept:, h] = orc.widen(ks[b][h])
-                vf[n_b - kept:, h] = orc.widen(vs[b][h])
+            kf, vf = G.full_history(ks[b], vs[b], n_b, Hkv, D)
             o_ref, l_ref = orc.decode_attend(q[b], kf, vf, seg_len=S, tail_len=T, kv_policy=w.kv_policy)
             eo, el = np.abs(o[b] - o_ref), np.abs(l[b] - l_ref)
             if fp32_check:

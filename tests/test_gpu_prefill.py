@@ -31,10 +31,8 @@ SMALL = [
 @pytest.fixture(params=["auto", "4", "8"])
 def waves(request, monkeypatch):
     """Workgroup shape of the head_dim-128 MFMA kernel: the library's own choice, or forced."""
-    if request.param == "auto":
-        monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
-    else:
-        monkeypatch.setenv("SEGATTN_PREFILL_WAVES", request.param)
+    import gpu_util as G
+    monkeypatch.setitem(G.TUNING, "prefill_waves", 0 if request.param == "auto" else int(request.param))
     return request.param
 
 
@@ -162,12 +160,12 @@ def test_stateless_forward_replays_from_a_captured_graph():
     G.assert_parity(G.to_f64(out), G.to_f64(lse), o_ref, l_ref, fp32_check=False, what="graph replay")
 
 
-# ---- work items taken from queues (the form a launch with more items than fit the chip uses; SEGATTN_PREFILL_QUEUE=2
-# ---- forces it for small inputs, =0 switches it off)
+# ---- work items taken from queues (the form a launch with more items than fit the chip uses;
+# ---- segattn_config.item_queues = 3 forces it for small inputs, = 1 switches it off)
 @pytest.mark.parametrize("case", range(len(SMALL)))
 def test_fwd_seq_small_with_item_queues(case, monkeypatch):
     import gpu_util as G
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
+    monkeypatch.setitem(G.TUNING, "item_queues", G.QUEUES_ON_SMALL_GRID)
     w = W.small(f"small{case}", index=100 + case, **SMALL[case])
     q, k, v = W.prefill_inputs(w)
     o_ref, l_ref = _oracle(w, q, k, v)
@@ -191,14 +189,15 @@ def test_item_queues_run_every_item_exactly_once(monkeypatch):
     import gpu_util as G
     w = W.small("queued", index=143, seq_len=6000, seg_len=1024, tail_len=256, n_q_heads=16, n_kv_heads=8,
                 head_dim=128, kv_policy=[3, 1, 0, 3, 1, 1, 2, 0], batch=2)
-    cfg = G.config_of(w, out_fp32=True, batch=2)
     q, k, v = W.prefill_inputs(w)
     qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "0")
+    monkeypatch.setitem(G.TUNING, "item_queues", G.QUEUES_OFF)
+    cfg = G.config_of(w, out_fp32=True, batch=2)
     o0, l0 = _fwd(G, cfg, qd, kd, vd, 6000)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(o0).all())
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
+    monkeypatch.setitem(G.TUNING, "item_queues", G.QUEUES_ON_SMALL_GRID)
+    cfg = G.config_of(w, out_fp32=True, batch=2)
     for _ in range(3):
         o1, l1 = _fwd(G, cfg, qd, kd, vd, 6000)
         torch.cuda.synchronize()
@@ -212,7 +211,7 @@ def test_item_queues_on_two_streams_do_not_share_counters(monkeypatch):
     """Launches on different streams may overlap: each stream has queue counters of its own, so
     two different problems in flight at once both come out as they do alone."""
     import gpu_util as G
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
+    monkeypatch.setitem(G.TUNING, "item_queues", G.QUEUES_ON_SMALL_GRID)
     probs = []
     for i, n in enumerate((5000, 3333)):
         w = W.small(f"two{i}", index=144 + i, seq_len=n, seg_len=512, tail_len=128, n_q_heads=16, n_kv_heads=4,
@@ -240,7 +239,7 @@ def test_item_queues_with_two_host_threads_on_one_stream(monkeypatch):
     launch itself must enter the stream as a pair, whatever the threads' timing."""
     import threading
     import gpu_util as G
-    monkeypatch.setenv("SEGATTN_PREFILL_QUEUE", "2")
+    monkeypatch.setitem(G.TUNING, "item_queues", G.QUEUES_ON_SMALL_GRID)
     stream = torch.cuda.Stream()
     probs = []
     for i, n in enumerate((2100, 1500)):
@@ -273,3 +272,57 @@ def test_item_queues_with_two_host_threads_on_one_stream(monkeypatch):
     for _, _, _, _, _, alone, outs in probs:
         for o, l in outs:
             assert torch.equal(o, alone[0]) and torch.equal(l, alone[1])
+
+
+_FIRST_CALLS_SCRIPT = r"""
+import sys, threading
+import numpy as np, torch
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + "/tests")
+import workloads as W, gpu_util as G
+G.TUNING["item_queues"] = G.QUEUES_ON_SMALL_GRID
+torch.zeros(1, device="cuda")                       # the runtime is up; the library has launched nothing yet
+probs = []
+for i, n in enumerate((2300, 1700)):
+    w = W.small(f"first{i}", index=170 + i, seq_len=n, seg_len=512, tail_len=128, n_q_heads=8, n_kv_heads=2,
+                head_dim=128, kv_policy=[3, 1])
+    q, k, v = W.prefill_inputs(w)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    cfg = G.config_of(w, out_fp32=True, batch=1)
+    outs = [(torch.full((1, n, 8, 128), float("nan"), device="cuda"), torch.full((1, 8, n), float("nan"), device="cuda"))
+            for _ in range(6)]
+    probs.append((cfg, qd, kd, vd, n, outs, torch.cuda.Stream()))
+torch.cuda.synchronize()
+gate, errors = threading.Barrier(2), []
+def work(pr):
+    cfg, qd, kd, vd, n, outs, st = pr
+    try:
+        gate.wait()                                 # both threads make their first library call together
+        for o, l in outs:
+            G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, n, o, l, st.cuda_stream)
+    except Exception as e:
+        errors.append(repr(e))
+ts = [threading.Thread(target=work, args=(pr,)) for pr in probs]
+[t.start() for t in ts]; [t.join() for t in ts]
+torch.cuda.synchronize()
+assert not errors, errors
+for cfg, qd, kd, vd, n, outs, st in probs:          # afterwards, one thread: the reference
+    o_ref, l_ref = torch.empty_like(outs[0][0]), torch.empty_like(outs[0][1])
+    G.sa.seg_attn_fwd_seq(cfg, qd, kd, vd, n, o_ref, l_ref, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(o_ref).all())
+    for o, l in outs:
+        assert torch.equal(o, o_ref) and torch.equal(l, l_ref)
+print("first calls ok")
+"""
+
+
+def test_first_library_calls_from_two_host_threads():
+    """A fresh process whose very first launches come from two host threads at once (same kernel
+    instantiation, item queues on, a stream each): the one-time set-up of a kernel -- its LDS
+    allowance, the resident-workgroup count, the queue counters' address -- must be safe to race
+    through, and every launch must come out as it does later from one thread."""
+    import subprocess
+    import sys
+    from conftest import ROOT
+    res = subprocess.run([sys.executable, "-c", _FIRST_CALLS_SCRIPT, ROOT], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and "first calls ok" in res.stdout, res.stdout[-2000:] + res.stderr[-2000:]

@@ -38,7 +38,8 @@ CONFIGS = _configs(28, 20260511)
 def test_random_config_forward_and_backward(c, waves, monkeypatch):
     if c["D"] != 128 and waves == "4":
         pytest.skip("the wave count only exists in the head_dim-128 MFMA kernel")
-    monkeypatch.setenv("SEGATTN_PREFILL_WAVES", waves)
+    import gpu_util
+    monkeypatch.setitem(gpu_util.TUNING, "prefill_waves", int(waves))
     D, Hkv, g, S, T, lens, policy = c["D"], c["Hkv"], c["g"], c["S"], c["T"], c["lens"], c["policy"]
     Hq = Hkv * g
     total = sum(lens)
@@ -103,7 +104,6 @@ def test_random_config_streaming_then_decode(c, monkeypatch):
     of prefix pieces), then a few decode steps: every output row against the oracle's row of the
     full sequence."""
     from gpu_util import Cache
-    monkeypatch.delenv("SEGATTN_PREFILL_WAVES", raising=False)
     D, Hkv, g, S, T, B = c["D"], c["Hkv"], c["g"], c["S"], c["T"], c["B"]
     n_pre, n_dec, policy, chunks = c["n_pre"], c["n_dec"], c["policy"], c["chunks"]
     N = n_pre + n_dec

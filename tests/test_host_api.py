@@ -53,6 +53,7 @@ def test_cache_bytes_accounts_for_rows_counters_and_workspace():
     dict(head_dim=96), dict(n_q_heads=7), dict(tail_len=65), dict(seg_len=0), dict(batch=0),
     dict(kv_policy=[1, 4]), dict(past_capacity=32), dict(tail_len=-1), dict(scale=-1.0),
     dict(n_kv_heads=0, n_q_heads=0, kv_policy=[]), dict(rope_theta=-1.0),
+    dict(prefill_waves=2), dict(prefill_waves=-8), dict(item_queues=4), dict(item_queues=-1),
 ])
 def test_invalid_configurations_are_rejected(bad):
     cfg = _cfg(**bad)

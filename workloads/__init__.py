@@ -176,34 +176,25 @@ def decode_lengths(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
     return k_done, c_fill
 
 
-def decode_rows_kept(policy: int, k_done: int, c_fill: int, seg_len: int, tail_len: int) -> int:
-    """How many trailing rows of a sequence's history a KV head with this policy still
-    holds when the token at in-segment offset c_fill-1 is decoded: everything for a PAST
-    head, the carried tail plus the partial segment for a TAIL head, the partial segment
-    alone otherwise."""
-    if policy & POLICY_PAST:
-        return k_done * seg_len + c_fill
-    if policy & POLICY_TAIL:
-        return min(tail_len, k_done * seg_len) + c_fill
-    return c_fill
-
-
 def decode_inputs(w: Workload, k_done: Optional[np.ndarray] = None,
-                  c_fill: Optional[np.ndarray] = None):
-    """Decode workload: q [B,Hq,D] bf16 bits for the token being decoded and, per
-    sequence b and KV head h, the K and V rows [kept, D] that head still holds
-    (the trailing `decode_rows_kept` rows of the context of n_b = k_b*S + c_b tokens;
-    the last row belongs to the token being decoded).  Rows a head has dropped are never
-    drawn, which keeps the 64-sequence workload at ~3 GB instead of ~9 GB."""
+                  c_fill: Optional[np.ndarray] = None, trailing_rows=None):
+    """Decode workload: q [B,Hq,D] bf16 bits for the token being decoded and, per sequence b
+    and KV head h, K and V rows [rows, D] of that head's history of n_b = k_b*S + c_b tokens,
+    the last row belonging to the token being decoded.  By default the whole history is drawn.
+    trailing_rows [B][Hkv], if given, asks for only that many trailing rows of each history:
+    input-size bookkeeping for callers whose cache cannot hold (and whose reference zero-fills)
+    the older rows of some heads -- the 64-sequence workload is ~3 GB that way instead of ~9 GB.
+    Which rows a head may attend to is not decided here."""
     if k_done is None or c_fill is None:
         k_done, c_fill = decode_lengths(w)
     q = normal_bf16(w.seed, _TENSOR_Q, w.batch, 1, w.n_q_heads, w.head_dim)[:, 0]
     jobs = []
     for b in range(w.batch):
-        for h, pol in enumerate(w.kv_policy):
-            kept = decode_rows_kept(pol, int(k_done[b]), int(c_fill[b]), w.seg_len, w.tail_len)
-            jobs.append((w.seed + 1000 * (b + 1), _TENSOR_K, h, kept, w.head_dim))
-            jobs.append((w.seed + 1000 * (b + 1), _TENSOR_V, h, kept, w.head_dim))
+        n_b = int(k_done[b]) * w.seg_len + int(c_fill[b])
+        for h in range(w.n_kv_heads):
+            rows = n_b if trailing_rows is None else min(n_b, int(trailing_rows[b][h]))
+            jobs.append((w.seed + 1000 * (b + 1), _TENSOR_K, h, rows, w.head_dim))
+            jobs.append((w.seed + 1000 * (b + 1), _TENSOR_V, h, rows, w.head_dim))
     with ThreadPoolExecutor(_n_threads()) as ex:
         res = list(ex.map(lambda a: _head_rows(*a), jobs))
     n_kv = w.n_kv_heads
