@@ -54,7 +54,8 @@ typedef enum {
   SEGATTN_EINVAL = 1,    /* bad argument or unsupported configuration               */
   SEGATTN_ECAPACITY = 2, /* a PAST head would hold more than past_capacity rows      */
   SEGATTN_ESTATE = 3,    /* call not valid in the current cache state                */
-  SEGATTN_EHIP = 4       /* the HIP runtime reported an error on launch / copy       */
+  SEGATTN_EHIP = 4,      /* the HIP runtime reported an error on launch / copy       */
+  SEGATTN_ESCRATCH = 5   /* the problem does not fit the library's built-in scratch   */
 } segattn_status;
 
 /* Per-KV-head access policy (Eq. 13), a bit mask.  SEG: own segment only (a long-range head
@@ -185,6 +186,23 @@ segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const 
                                 const void *v, const void *out, const float *lse,
                                 const void *dout, int64_t n, void *dq, void *dk, void *dv,
                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* seg_attn_bwd_seq for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
+ * Same arguments without the workspace, same kernels, same results bit for bit; the [B,Hq,n] fp32
+ * row statistic that the backward kernels hand to each other lives in an array inside the
+ * library's device image instead (SEGATTN_BWD_STATIC_SCRATCH_BYTES per GPU, held from the moment
+ * the library is loaded until the process ends).  The call allocates and frees nothing.
+ * SEGATTN_ESCRATCH, before anything is enqueued, if B * Hq * n * 4 bytes exceed the array (4 MiB:
+ * e.g. four 8192-token training windows of 32 query heads).  All calls on one GPU share that
+ * GPU's array: calls whose kernels may overlap (different streams, several host threads) race on
+ * it and must be ordered by the caller; the array keeps the last call's contents and nothing in
+ * it needs clearing, since every call overwrites what it reads. */
+#define SEGATTN_BWD_STATIC_SCRATCH_BYTES (4u << 20)
+segattn_status seg_attn_bwd_seq_static(const segattn_config *cfg, const void *q, const void *k,
+                                       const void *v, const void *out, const float *lse,
+                                       const void *dout, int64_t n, void *dq, void *dk, void *dv,
+                                       void *stream);
 
 /* The same backward pass for a packed ragged batch (layout and cu_seqlens as for
  * seg_attn_fwd_varlen: q, out, dout, dq [total,Hq,D]; k, v, dk, dv [total,Hkv,D]; lse [Hq,total]);

@@ -10,7 +10,8 @@ from typing import Optional, Sequence
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
 
-SEGATTN_OK, SEGATTN_EINVAL, SEGATTN_ECAPACITY, SEGATTN_ESTATE, SEGATTN_EHIP = range(5)
+SEGATTN_OK, SEGATTN_EINVAL, SEGATTN_ECAPACITY, SEGATTN_ESTATE, SEGATTN_EHIP, SEGATTN_ESCRATCH = range(6)
+SEGATTN_BWD_STATIC_SCRATCH_BYTES = 4 << 20
 SEGATTN_SEG, SEGATTN_TAIL, SEGATTN_PAST = 0, 1, 2
 
 
@@ -62,6 +63,7 @@ def lib() -> ctypes.CDLL:
             "seg_rope_apply": (ctypes.c_int, [cfgp, vp, vp, i64, vp, vp]),
             "seg_attn_bwd_workspace_bytes": (sz, [cfgp, i64]),
             "seg_attn_bwd_seq": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]),
+            "seg_attn_bwd_seq_static": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]),
             "seg_attn_bwd_varlen_workspace_bytes": (sz, [cfgp, i64]),
             "seg_attn_bwd_varlen": (ctypes.c_int, [cfgp, vp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]),
             "seg_kv_commit": (ctypes.c_int, [vp, vp, vp, i32, vp]),
@@ -89,7 +91,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
+           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_seq_static", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -183,6 +185,12 @@ def seg_attn_bwd_seq(cfg: segattn_config, q, k, v, out, lse, dout, n: int, dq, d
     _check(lib().seg_attn_bwd_seq(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), n,
                                   _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), workspace_bytes, _ptr(stream)),
            "seg_attn_bwd_seq")
+
+
+def seg_attn_bwd_seq_static(cfg: segattn_config, q, k, v, out, lse, dout, n: int, dq, dk, dv, stream=None) -> None:
+    _check(lib().seg_attn_bwd_seq_static(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+                                         _ptr(dout), n, _ptr(dq), _ptr(dk), _ptr(dv), _ptr(stream)),
+           "seg_attn_bwd_seq_static")
 
 
 def seg_attn_bwd_varlen_workspace_bytes(cfg: segattn_config, total: int) -> int:

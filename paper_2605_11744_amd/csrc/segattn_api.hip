@@ -2,6 +2,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -296,6 +297,29 @@ size_t seg_attn_bwd_workspace_bytes(const segattn_config *cfg, int64_t n) {
   return (size_t)align_up((unsigned long long)p.B * p.Hq * (unsigned long long)n * 4ull);
 }
 
+// Common part of the two whole-sequence backward entry points: `delta` is the [B,Hq,n] fp32 row
+// statistic the kernels keep between them, wherever the caller of this function found room for it.
+static segattn_status bwd_seq_launch(const Problem &p, const void *q, const void *k, const void *v, const void *out,
+                                     const float *lse, const void *dout, int64_t n, void *dq, void *dk, void *dv,
+                                     float *delta, void *stream) {
+  BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.dout = (const unsigned short *)dout;
+  a.out = out;
+  a.lse = lse;
+  a.delta = delta;
+  a.dq = dq;
+  a.dk = dk;
+  a.dv = dv;
+  a.n = (int)n;
+  const hipStream_t st = (hipStream_t)stream;
+  if (launch_bwd_delta(p, a, st) != hipSuccess) return SEGATTN_EHIP;
+  return hip_status(p.fp32_math ? launch_bwd_fp32(p, a, st) : launch_bwd_mfma(p, a, st));
+}
+
 segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const void *k, const void *v,
                                 const void *out, const float *lse, const void *dout, int64_t n, void *dq,
                                 void *dk, void *dv, void *workspace, size_t workspace_bytes, void *stream) {
@@ -305,22 +329,58 @@ segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const 
   if (n < 1 || n >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
   if (workspace_bytes < seg_attn_bwd_workspace_bytes(cfg, n) || ((uintptr_t)workspace % kAlign))
     return SEGATTN_EINVAL;
-  BwdArgs a;
-  memset(&a, 0, sizeof(a));
-  a.q = (const unsigned short *)q;
-  a.k = (const unsigned short *)k;
-  a.v = (const unsigned short *)v;
-  a.dout = (const unsigned short *)dout;
-  a.out = out;
-  a.lse = lse;
-  a.delta = (float *)workspace;
-  a.dq = dq;
-  a.dk = dk;
-  a.dv = dv;
-  a.n = (int)n;
-  const hipStream_t st = (hipStream_t)stream;
-  if (launch_bwd_delta(p, a, st) != hipSuccess) return SEGATTN_EHIP;
-  return hip_status(p.fp32_math ? launch_bwd_fp32(p, a, st) : launch_bwd_mfma(p, a, st));
+  return bwd_seq_launch(p, q, k, v, out, lse, dout, n, dq, dk, dv, (float *)workspace, stream);
+}
+
+// ---- the same backward pass for callers that cannot allocate ------------------------------------
+// The row statistic lives in an array that is part of the library's device image: one copy per
+// GPU, at an address of its own, present from the moment the image is loaded until the process
+// ends.  In host code the array's name is only a handle for the runtime; the address kernels and
+// copies can use is asked from the runtime once per device (with that device current) and kept.
+namespace {
+static __device__ __align__(256) unsigned char scratch[SEGATTN_BWD_STATIC_SCRATCH_BYTES];
+constexpr int kScratchDevices = 64;
+
+float *static_scratch(hipError_t &err) {
+  static std::mutex mu;
+  static void *addr[kScratchDevices] = {};
+  int dev = -1;
+  err = hipGetDevice(&dev);
+  if (err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kScratchDevices) {
+    err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void *ptr = nullptr;
+    err = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (err == hipSuccess && !ptr) err = hipErrorInvalidSymbol;
+    if (err != hipSuccess) return nullptr;
+    addr[dev] = ptr;
+  }
+  return (float *)addr[dev];
+}
+}  // namespace
+
+segattn_status seg_attn_bwd_seq_static(const segattn_config *cfg, const void *q, const void *k, const void *v,
+                                       const void *out, const float *lse, const void *dout, int64_t n, void *dq,
+                                       void *dk, void *dv, void *stream) {
+  Problem p;
+  if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return SEGATTN_EINVAL;
+  if (n < 1 || n >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
+  // B * Hq * n floats must fit the array (checked before anything touches the device)
+  if ((unsigned long long)p.B * p.Hq * (unsigned long long)n * 4ull > (unsigned long long)SEGATTN_BWD_STATIC_SCRATCH_BYTES)
+    return SEGATTN_ESCRATCH;
+  hipError_t err = hipSuccess;
+  float *delta = static_scratch(err);
+  if (!delta) {
+    (void)hipGetLastError();
+    return SEGATTN_EHIP;
+  }
+  // nothing in the array has to start at zero: the first kernel overwrites all B * Hq * n entries
+  return bwd_seq_launch(p, q, k, v, out, lse, dout, n, dq, dk, dv, delta, stream);
 }
 
 size_t seg_attn_bwd_varlen_workspace_bytes(const segattn_config *cfg, int64_t total) {
@@ -747,6 +807,7 @@ const char *segattn_strerror(segattn_status st) {
     case SEGATTN_ECAPACITY: return "past pool capacity exceeded";
     case SEGATTN_ESTATE: return "call not valid in the current cache state";
     case SEGATTN_EHIP: return "HIP runtime error";
+    case SEGATTN_ESCRATCH: return "problem too large for the library's built-in scratch buffer";
   }
   return "unknown status";
 }
