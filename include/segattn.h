@@ -189,16 +189,16 @@ segattn_status seg_attn_bwd_seq(const segattn_config *cfg, const void *q, const 
 
 /* seg_attn_bwd_seq for callers that cannot allocate device memory or pass a workspace: code
  * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
- * Same arguments without the workspace, same kernels, same results bit for bit; the [B,Hq,n] fp32
- * row statistic that the backward kernels hand to each other lives in an array inside the
+ * Same arguments without the workspace, same kernels, same results bit for bit; the two [B,Hq,n]
+ * fp32 row statistics that the backward kernels hand to each other live in an array inside the
  * library's device image instead (SEGATTN_BWD_STATIC_SCRATCH_BYTES per GPU, held from the moment
  * the library is loaded until the process ends).  The call allocates and frees nothing.
- * SEGATTN_ESCRATCH, before anything is enqueued, if B * Hq * n * 4 bytes exceed the array (4 MiB:
- * e.g. four 8192-token training windows of 32 query heads).  All calls on one GPU share that
+ * SEGATTN_ESCRATCH, before anything is enqueued, if the two statistics -- 2 * B * Hq * n * 4
+ * bytes -- exceed the array (8 MiB: e.g. four 8192-token training windows of 32 query heads).  All calls on one GPU share that
  * GPU's array: calls whose kernels may overlap (different streams, several host threads) race on
  * it and must be ordered by the caller; the array keeps the last call's contents and nothing in
  * it needs clearing, since every call overwrites what it reads. */
-#define SEGATTN_BWD_STATIC_SCRATCH_BYTES (4u << 20)
+#define SEGATTN_BWD_STATIC_SCRATCH_BYTES (8u << 20)
 segattn_status seg_attn_bwd_seq_static(const segattn_config *cfg, const void *q, const void *k,
                                        const void *v, const void *out, const float *lse,
                                        const void *dout, int64_t n, void *dq, void *dk, void *dv,

@@ -11,7 +11,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
 
 SEGATTN_OK, SEGATTN_EINVAL, SEGATTN_ECAPACITY, SEGATTN_ESTATE, SEGATTN_EHIP, SEGATTN_ESCRATCH = range(6)
-SEGATTN_BWD_STATIC_SCRATCH_BYTES = 4 << 20
+SEGATTN_BWD_STATIC_SCRATCH_BYTES = 8 << 20
 SEGATTN_SEG, SEGATTN_TAIL, SEGATTN_PAST = 0, 1, 2
 
 

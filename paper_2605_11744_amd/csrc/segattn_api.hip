@@ -291,17 +291,24 @@ segattn_status seg_rope_apply(const segattn_config *cfg, void *q, void *k, int64
   return hip_status(launch_rope_apply(p, a, (hipStream_t)stream));
 }
 
+// One row statistic of the backward pass (a float per query head and token row), 256-byte aligned;
+// the workspace holds two: delta and -LSE/scale.
+static unsigned long long bwd_stat_bytes(const Problem &p, unsigned long long token_rows) {
+  return align_up((unsigned long long)p.Hq * token_rows * 4ull);
+}
+
 size_t seg_attn_bwd_workspace_bytes(const segattn_config *cfg, int64_t n) {
   Problem p;
   if (!build_problem(cfg, false, p) || n < 1 || n >= (1ll << 31) - 4096) return 0;
-  return (size_t)align_up((unsigned long long)p.B * p.Hq * (unsigned long long)n * 4ull);
+  return (size_t)(2ull * bwd_stat_bytes(p, (unsigned long long)p.B * (unsigned long long)n));
 }
 
-// Common part of the two whole-sequence backward entry points: `delta` is the [B,Hq,n] fp32 row
-// statistic the kernels keep between them, wherever the caller of this function found room for it.
+// Common part of the two whole-sequence backward entry points: `stats` holds the two [B,Hq,n] fp32
+// row statistics the kernels keep between them (delta, then -LSE/scale), wherever the caller of
+// this function found room for them.
 static segattn_status bwd_seq_launch(const Problem &p, const void *q, const void *k, const void *v, const void *out,
                                      const float *lse, const void *dout, int64_t n, void *dq, void *dk, void *dv,
-                                     float *delta, void *stream) {
+                                     float *stats, void *stream) {
   BwdArgs a;
   memset(&a, 0, sizeof(a));
   a.q = (const unsigned short *)q;
@@ -310,7 +317,8 @@ static segattn_status bwd_seq_launch(const Problem &p, const void *q, const void
   a.dout = (const unsigned short *)dout;
   a.out = out;
   a.lse = lse;
-  a.delta = delta;
+  a.delta = stats;
+  a.nls = stats + bwd_stat_bytes(p, (unsigned long long)p.B * (unsigned long long)n) / 4;
   a.dq = dq;
   a.dk = dk;
   a.dv = dv;
@@ -370,23 +378,23 @@ segattn_status seg_attn_bwd_seq_static(const segattn_config *cfg, const void *q,
   if (!build_problem(cfg, false, p)) return SEGATTN_EINVAL;
   if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return SEGATTN_EINVAL;
   if (n < 1 || n >= (1ll << 31) - 4096) return SEGATTN_EINVAL;
-  // B * Hq * n floats must fit the array (checked before anything touches the device)
-  if ((unsigned long long)p.B * p.Hq * (unsigned long long)n * 4ull > (unsigned long long)SEGATTN_BWD_STATIC_SCRATCH_BYTES)
+  // two statistics of B * Hq * n floats must fit the array (checked before anything touches the device)
+  if (2ull * bwd_stat_bytes(p, (unsigned long long)p.B * (unsigned long long)n) > (unsigned long long)SEGATTN_BWD_STATIC_SCRATCH_BYTES)
     return SEGATTN_ESCRATCH;
   hipError_t err = hipSuccess;
-  float *delta = static_scratch(err);
-  if (!delta) {
+  float *stats = static_scratch(err);
+  if (!stats) {
     (void)hipGetLastError();
     return SEGATTN_EHIP;
   }
-  // nothing in the array has to start at zero: the first kernel overwrites all B * Hq * n entries
-  return bwd_seq_launch(p, q, k, v, out, lse, dout, n, dq, dk, dv, delta, stream);
+  // nothing in the array has to start at zero: the first kernel overwrites every entry that is read
+  return bwd_seq_launch(p, q, k, v, out, lse, dout, n, dq, dk, dv, stats, stream);
 }
 
 size_t seg_attn_bwd_varlen_workspace_bytes(const segattn_config *cfg, int64_t total) {
   Problem p;
   if (!build_problem(cfg, false, p) || total < 1 || total >= (1ll << 31) - 4096) return 0;
-  return (size_t)align_up((unsigned long long)p.Hq * (unsigned long long)total * 4ull);
+  return (size_t)(2ull * bwd_stat_bytes(p, (unsigned long long)total));
 }
 
 segattn_status seg_attn_bwd_varlen(const segattn_config *cfg, const void *q, const void *k, const void *v,
@@ -409,6 +417,7 @@ segattn_status seg_attn_bwd_varlen(const segattn_config *cfg, const void *q, con
   a.out = out;
   a.lse = lse;
   a.delta = (float *)workspace;
+  a.nls = a.delta + bwd_stat_bytes(p, (unsigned long long)total) / 4;
   a.dq = dq;
   a.dk = dk;
   a.dv = dv;

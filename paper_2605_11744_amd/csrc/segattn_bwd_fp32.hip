@@ -21,7 +21,9 @@ __device__ inline float wave_sum(float x) {
   return x;
 }
 
-// delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d].  D/8 lanes per (row, head), 8 elements each.
+// delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d], and next to it nls = -lse / scale (the dK/dV
+// kernel streams both per step as the starting values of its dP and score accumulators).  D/8 lanes
+// per (row, head), 8 elements each.
 template <int D>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const Problem p, const BwdArgs a) {
   constexpr int LPR = D / 8;
@@ -53,7 +55,9 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const Problem p, const B
     const long long bt = item / p.Hq;
     const int h = (int)(item % p.Hq);
     const SeqSpan sq = seq_span(p, a, seq_of_row(p, a, bt));
-    a.delta[sq.stat0 + h * sq.stat_stride + (bt - sq.row0)] = s;
+    const long long at = sq.stat0 + h * sq.stat_stride + (bt - sq.row0);
+    a.delta[at] = s;
+    a.nls[at] = -a.lse[at] / p.scale;
   }
 }
 

@@ -170,6 +170,8 @@ struct BwdArgs {
   const void *out;                         // forward output: bf16, or fp32 if Problem::out_fp32
   const float *lse;                        // [B,Hq,n]
   float *delta;                            // [B,Hq,n] workspace: sum_d dO*O
+  float *nls;                              // [B,Hq,n] workspace: -lse / scale (the dK/dV kernel starts its score
+                                           // accumulators there: exp2((q.k - lse/scale) scale log2 e) is the weight)
   void *dq, *dk, *dv;                      // bf16, or fp32 if Problem::out_fp32
   int n;                                   // rows per sequence (packed batch: of the longest sequence)
   const int *cu_seqlens;                   // packed ragged batch: device [B+1] row offsets, else nullptr

@@ -70,7 +70,7 @@ def test_static_scratch_backward_rejects_what_does_not_fit():
     w = W.small("noalloc_c", index=182, seq_len=64, seg_len=32, tail_len=8, n_q_heads=32, n_kv_heads=8, head_dim=128,
                 kv_policy=[1] * 8, batch=4)
     cfg = G.config_of(w)
-    n_fit = sa.SEGATTN_BWD_STATIC_SCRATCH_BYTES // (4 * 32 * 4)            # 8192 rows: exactly the array
+    n_fit = sa.SEGATTN_BWD_STATIC_SCRATCH_BYTES // (2 * 4 * 32 * 4)        # 8192 rows: exactly the array
     for n, status in ((n_fit + 1, sa.SEGATTN_ESCRATCH), (1 << 22, sa.SEGATTN_ESCRATCH), (0, sa.SEGATTN_EINVAL)):
         with pytest.raises(sa.SegattnError) as e:                           # refused before any pointer is used
             sa.seg_attn_bwd_seq_static(cfg, 256, 256, 256, 256, 256, 256, n, 256, 256, 256)
