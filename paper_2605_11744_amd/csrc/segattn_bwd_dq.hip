@@ -4,7 +4,8 @@
 //   S^T  = K . Q^T          P^T = exp2(S^T c - LSE)
 //   dP^T = V . dO^T         dS^T = P^T (dP^T - delta)
 //   dQ^T += K^T . dS^T      (every visible key contributes, past rows too)
-// Built with the compiler's VGPR form of the matrix products (-amdgpu-mfma-vgpr-form): the whole
+// K/V tiles travel HBM -> LDS by DMA into a ring of three step buffers, two steps ahead of their
+// use; one barrier per step.  Built with the compiler's VGPR form of the matrix products (-amdgpu-mfma-vgpr-form): the whole
 // state of a wave -- Q^T and dO^T operands, the dQ^T accumulators, the score tiles -- fits 256
 // vector registers, so two workgroups share a CU and one fills the other's stalls (each step is
 // a chain products -> exponentials -> products with a barrier at its end).
@@ -20,22 +21,36 @@ namespace segattn {
 // One work item (query block x head sub-group): see bwd_dq_kernel for how items reach workgroups.
 // next_from: nullptr, or the queue counter the workgroup takes its next item from; thread 0 draws
 // the ticket after the last K/V step and hands it back (other threads: 0).
+// LDS of the dQ kernel: a ring of three step buffers, [K tile][V tile] each.
+template <int D>
+struct DqGeom {
+  static constexpr int kTile = BwdTile<D>::kBytes;
+  static constexpr int kBuf = 2 * kTile;
+  static constexpr int kBufs = 3;
+  static constexpr int kBytes = kBufs * kBuf;
+};
+
 template <int D, int HS>
 __device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillArgs &pa, const BwdArgs &a,
-                                                const int bid, unsigned char (&smem)[2][2][BwdTile<D>::kBytes],
-                                                unsigned *const next_from) {
+                                                const int bid, unsigned char *const smem, unsigned *const next_from) {
   using T = BwdTile<D>;
+  using G = DqGeom<D>;
   constexpr int NC = D / 16, NB = D / 32;
   constexpr int RW = 32;             // query rows per wave
   constexpr int BQ = (4 / HS) * RW;  // query rows per workgroup
+  constexpr int kTile = G::kTile, kBuf = G::kBuf, NBUF = G::kBufs;
+  constexpr int LPW = T::kChunks / 8;     // wave-wide 1 KB loads per tensor, step and wave
+  constexpr int kLoadsPerStep = 2 * LPW;  // per wave: K, V
+  static_assert((NBUF - 1) * kBuf + kTile + 16 * T::kRowBytes < 65536, "LDS offsets must fit the 16-bit immediate");
 
   WorkItem w = resolve(p, pa, bid, BQ, HS);
   if (!w.valid) return (next_from && threadIdx.x == 0) ? atomicAdd(next_from, 1u) : 0u;
   pin_uniform(w);
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));  // not a loop invariant of the caller's loop (see prefill_mfma_kernel)
-  const int wave = tid >> 6, lane = tid & 63;
-  const int hi = lane >> 5, col = lane & 31;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hi = lane >> 5, col = lane & 31, i16 = lane & 15, g16 = (lane >> 4) & 1;
   const int head = w.kv * p.g + w.hsub * HS + (wave % HS);
   const int tw0 = w.t0 + (wave / HS) * RW;
   const int last_row = w.n1 - 1;
@@ -46,7 +61,7 @@ __device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillA
   const bool row_ok = t <= last_row;
   t = row_ok ? t : last_row;
   const long long qoff = ((seg_row + t) * p.Hq + head) * D;
-  const long long stat = (w.lse - a.lse) + (long long)head * w.lse_head_stride + t;  // index into lse / delta
+  const long long stat = (w.lse - a.lse) + (long long)head * w.lse_head_stride + t;  // index into the row statistics
   const float lse2 = a.lse[stat] * kLog2e, delta = a.delta[stat];
 
   bf16x8 Qr[NC], Gr[NC];  // Q^T and dO^T operands: row `col`, elements 16 kc + 8 hi .. +7
@@ -65,114 +80,196 @@ __device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillA
   const int nst0 = (w.n0 + kBwdStep - 1) / kBwdStep;
   const int nst1 = (n1_needed + kBwdStep - 1) / kBwdStep;
   const int nsteps = nst0 + nst1;
-  const int my_last = tw0 + RW - 1;  // keys of the own segment beyond this row are invisible to the wave
 
-  // Tiles of step j (clamped to the last step, whose re-fetch is not used): global -> registers.
-  // A scalar base per step plus a 32-bit lane offset fixed for the kernel (both spans have the
-  // same row stride here: the backward pass reads K/V by absolute position); only the last step
-  // of a span can reach past its end, and only then are the lane's rows clamped.
+  // ---- HBM -> LDS by DMA (global_load_lds): load i of a wave covers bytes [(wave LPW + i) 1024,
+  // +1024) of a tile, i.e. row (wave LPW + i) rows-per-KB + lane / chunks, chunk slot lane % chunks,
+  // which receives the global chunk slot ^ swz(row): the tile's swizzle applied on the global side
+  // (the LDS side of such a load is linear in the lane).  Both spans have the same row stride here
+  // (the backward pass reads K/V by absolute position).  The fetch cursor walks the steps in
+  // order and stays on the last one (fetched again, never read), so every wait is one constant.
   const unsigned row_bytes = (unsigned)(w.stride1 * 2);
-  int f_row[T::kLoads];
-  unsigned f_col2[T::kLoads], f_off[T::kLoads];
+  constexpr int kRowsPerKB = 1024 / T::kRowBytes;
+  int f_row[LPW];
+  unsigned f_chunk[LPW], f_off[LPW];
 #pragma unroll
-  for (int i = 0; i < T::kLoads; ++i) {
-    f_row[i] = (tid + 256 * i) / T::kChunks;
-    f_col2[i] = (unsigned)((tid + 256 * i) % T::kChunks) * 16;
-    f_off[i] = (unsigned)f_row[i] * row_bytes + f_col2[i];
+  for (int i = 0; i < LPW; ++i) {
+    f_row[i] = (wave * LPW + i) * kRowsPerKB + lane / T::kChunks;
+    f_chunk[i] = (unsigned)(((lane % T::kChunks) ^ T::swz(f_row[i])) << 4);
+    f_off[i] = (unsigned)f_row[i] * row_bytes + f_chunk[i];
   }
-  u32x4 kr[T::kLoads], vr[T::kLoads];
-#define SEGATTN_BWD_FETCH_KV(jj)                                                                      \
-  do {                                                                                                \
-    int j_ = (jj);                                                                                    \
-    j_ = j_ < nsteps ? j_ : nsteps - 1;                                                               \
-    const bool s1_ = j_ >= nst0;                                                                      \
-    const int jl_ = s1_ ? j_ - nst0 : j_;                                                             \
-    const int left_ = (s1_ ? w.n1 : w.n0) - jl_ * kBwdStep;                                           \
-    const unsigned long long so_ = (unsigned long long)jl_ * kBwdStep * row_bytes;                    \
-    const GLB_AS unsigned char *kb_ = (const GLB_AS unsigned char *)(s1_ ? w.k1 : w.k0) + so_;        \
-    const GLB_AS unsigned char *vb_ = (const GLB_AS unsigned char *)(s1_ ? w.v1 : w.v0) + so_;        \
-    if (left_ >= kBwdStep) {                                                                          \
-      _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                      \
-        kr[i_] = *(const GLB_AS u32x4 *)(kb_ + f_off[i_]);                                            \
-        vr[i_] = *(const GLB_AS u32x4 *)(vb_ + f_off[i_]);                                            \
-      }                                                                                               \
-    } else {                                                                                          \
-      _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                      \
-        const int r_ = f_row[i_] < left_ ? f_row[i_] : left_ - 1;                                     \
-        const unsigned o_ = (unsigned)r_ * row_bytes + f_col2[i_];                                    \
-        kr[i_] = *(const GLB_AS u32x4 *)(kb_ + o_);                                                   \
-        vr[i_] = *(const GLB_AS u32x4 *)(vb_ + o_);                                                   \
-      }                                                                                               \
-    }                                                                                                 \
-  } while (0)
-#define SEGATTN_BWD_STORE_KV(buf)                                                                     \
-  do {                                                                                                \
-    _Pragma("unroll") for (int i_ = 0; i_ < T::kLoads; ++i_) {                                        \
-      const int off_ = T::at(f_row[i_], (int)(f_col2[i_] / 16));                                      \
-      *(u32x4 *)(smem[buf][0] + off_) = kr[i_];                                                       \
-      *(u32x4 *)(smem[buf][1] + off_) = vr[i_];                                                       \
-    }                                                                                                 \
-  } while (0)
-  SEGATTN_BWD_FETCH_KV(0);
-  SEGATTN_BWD_STORE_KV(0);
-  __syncthreads();
-  (void)my_last;
-  for (int j = 0; j < nsteps; ++j) {
-    const int cur = j & 1;
-    SEGATTN_BWD_FETCH_KV(j + 1);
-    const bool own = j >= nst0;
-    const int k0 = (own ? j - nst0 : j) * kBwdStep;           // first key of the step inside its span
-    const int span_len = own ? w.n1 : w.n0;
-    {
-      const unsigned char *kt = smem[cur][0], *vt = smem[cur][1];
-      f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 dP = S;
+  LDS_AS unsigned char *const lds = (LDS_AS unsigned char *)smem;
+  const unsigned lds_base = (unsigned)(size_t)lds;
+  int f_j = 0, f_left = nst0 > 0 ? w.n0 : w.n1;  // step to fetch next, rows its span has from its first row on
+  const unsigned char *f_k = (const unsigned char *)(nst0 > 0 ? w.k0 : w.k1);
+  const unsigned char *f_v = (const unsigned char *)(nst0 > 0 ? w.v0 : w.v1);
+  auto fetch_next = [&](int buf) __attribute__((always_inline)) {
+    LDS_AS unsigned char *dst = lds + buf * kBuf + wave * (LPW * 1024);
+    if (f_left >= kBwdStep) {
 #pragma unroll
-      for (int kc = 0; kc < NC; ++kc) {
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(kt, lane, kc), Qr[kc], S, 0, 0, 0);
-        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_row<D>(vt, lane, kc), Gr[kc], dP, 0, 0, 0);
+      for (int i = 0; i < LPW; ++i) {
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(f_k + f_off[i]), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(f_v + f_off[i]), (LDS_AS void *)(dst + kTile + i * 1024), 16, 0, 0);
       }
-      bf16x8 dS[2];
-      // a step whose 32 keys are visible to all 32 queries of the wave needs no masks: keys of the
-      // prefix span short of its ragged end, keys of the own segment up to the wave's first row
-      const bool all_visible = own ? (k0 + kBwdStep - 1 <= tw0 && tw0 + RW - 1 <= last_row) : (k0 + kBwdStep <= span_len);
-      if (all_visible) {
+    } else {  // the last step of a span can reach past its end: clamp the lane's rows
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          f32x8 e;
-#pragma unroll
-          for (int x = 0; x < 8; ++x) {
-            const int r = 8 * h2 + x;
-            e[x] = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2)) * (dP[r] - delta);
-          }
-          dS[h2] = __builtin_convertvector(e, bf16x8);
-        }
-      } else {
-        const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1;  // last visible key of the span
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          f32x8 e;
-#pragma unroll
-          for (int x = 0; x < 8; ++x) {
-            const int r = 8 * h2 + x;
-            const int key = k0 + 8 * (r / 4) + 4 * hi + r % 4;
-            // a masked pair gets exponent -inf: its weight is exactly 0, without a branch
-            const float pr = __builtin_amdgcn_exp2f(key <= kmax ? fmaf(S[r], c, -lse2) : -INFINITY);
-            e[x] = pr * (dP[r] - delta);
-          }
-          dS[h2] = __builtin_convertvector(e, bf16x8);
-        }
+      for (int i = 0; i < LPW; ++i) {
+        const int r = f_row[i] < f_left ? f_row[i] : f_left - 1;
+        const unsigned o = (unsigned)r * row_bytes + f_chunk[i];
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(f_k + o), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const GLB_AS void *)(f_v + o), (LDS_AS void *)(dst + kTile + i * 1024), 16, 0, 0);
       }
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) mma_acc(acc[nb], read_transposed<D>(kt, lane, nb, h2), dS[h2]);
     }
-    SEGATTN_BWD_STORE_KV(cur ^ 1);
-    __syncthreads();
+    if (f_j + 1 < nsteps) {
+      f_j += 1;
+      if (f_j == nst0) {  // on to the own segment
+        f_k = (const unsigned char *)w.k1;
+        f_v = (const unsigned char *)w.v1;
+        f_left = w.n1;
+      } else {
+        f_k += (size_t)kBwdStep * row_bytes;
+        f_v += (size_t)kBwdStep * row_bytes;
+        f_left -= kBwdStep;
+      }
+    }
+  };
+#define SEGATTN_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
+
+  // ---- per-lane LDS read addresses inside a step buffer (buffer and tensor are immediates)
+  unsigned ro[NC];  // row operands: tile row `col`, logical chunk 2 kc + hi
+#pragma unroll
+  for (int kc = 0; kc < NC; ++kc) ro[kc] = lds_base + (unsigned)T::at(col, 2 * kc + hi);
+  unsigned tro[NB][2];  // transposed operands (see read_transposed); rows 16 apart share the swizzle: h2 is an immediate
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      tro[nb][u] = lds_base + (unsigned)(T::at(4 * hi + (i16 >> 2) + 8 * u, 4 * nb + 2 * g16 + ((i16 & 3) >> 1)) + 8 * (i16 & 1));
+  static_assert(T::swz(0) == T::swz(16) && T::swz(5) == T::swz(21) && T::swz(15) == T::swz(31), "h2 as an immediate");
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+  // One step on the tile in buffer B (LDS reads are inline asm with explicit waits: the compiler
+  // would make every LDS read wait for all outstanding DMA):
+  //   request the tile two steps on (its buffer was last read before the previous barrier)
+  //   S^T = K Q^T, dP^T = V dO^T (row operands from LDS, in two halves), with the transposed K
+  //   operands read behind the second half's products
+  //   dS^T = exp2(S^T c - LSE) (dP^T - delta) (keys the queries may not see get score -inf first), bf16
+  //   dQ^T += K^T dS^T
+  //   the next step's tile has landed (this wave's part); barrier: everyone's, and nobody reads
+  //   this step's tile any more
+#define SEGATTN_DQ_STEP(B)                                                                                       \
+  do {                                                                                                           \
+    constexpr int BO = (B) * kBuf, BF = ((B) + NBUF - 1) % NBUF;                                                 \
+    const bool own = j >= nst0;                                                                                  \
+    const int k0 = (own ? j - nst0 : j) * kBwdStep; /* first key of the step inside its span */                  \
+    const int span_len = own ? w.n1 : w.n0;                                                                      \
+    /* a step whose 32 keys are visible to all 32 queries of the wave needs no masks: keys of the prefix         \
+       span short of its ragged end, keys of the own segment up to the wave's first row */                       \
+    const bool all_visible = own ? (k0 + kBwdStep - 1 <= tw0 && tw0 + RW - 1 <= last_row) : (k0 + kBwdStep <= span_len); \
+    fetch_next(BF);                                                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
+    /* row operands in two halves (registers: the second half takes the place of the first as its products     \
+       are issued); the transposed K operands are read behind the second half's products */                      \
+    i32x4 ka[NC], va[NC];                                                                                        \
+    s16x4 kt[2][NB][2];                                                                                          \
+    _Pragma("unroll") for (int kc = 0; kc < NC / 2; ++kc) {                                                      \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ka[kc]) : "v"(ro[kc]), "n"(BO));                       \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(va[kc]) : "v"(ro[kc]), "n"(BO + kTile));               \
+    }                                                                                                            \
+    SEGATTN_DQ_ROWS_WAIT(0);                                                                                     \
+    f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};                 \
+    f32x16 dP = S;                                                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
+    _Pragma("unroll") for (int kc = 0; kc < NC / 2; ++kc) {                                                      \
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kc]), Qr[kc], S, 0, 0, 0);       \
+      dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[kc]), Gr[kc], dP, 0, 0, 0);     \
+      __builtin_amdgcn_sched_barrier(0);                                                                         \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ka[kc + NC / 2]) : "v"(ro[kc + NC / 2]), "n"(BO));     \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(va[kc + NC / 2]) : "v"(ro[kc + NC / 2]), "n"(BO + kTile)); \
+      __builtin_amdgcn_sched_barrier(0);                                                                         \
+    }                                                                                                            \
+    SEGATTN_DQ_ROWS_WAIT(NC / 2);                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
+    _Pragma("unroll") for (int kc = NC / 2; kc < NC; ++kc) {                                                     \
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kc]), Qr[kc], S, 0, 0, 0);       \
+      dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[kc]), Gr[kc], dP, 0, 0, 0);     \
+      __builtin_amdgcn_sched_barrier(0);                                                                         \
+      { /* 4 NB transposed reads over NC / 2 product pairs */                                                    \
+        constexpr int per = 4 * NB / (NC / 2);                                                                   \
+        _Pragma("unroll") for (int e = 0; e < per; ++e) {                                                        \
+          const int idx = (kc - NC / 2) * per + e, h2 = idx / (2 * NB), nb = (idx / 2) % NB, u = idx % 2;        \
+          if (h2 == 0)                                                                                           \
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(kt[0][nb][u]) : "v"(tro[nb][u]), "n"(BO));  \
+          else                                                                                                   \
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(kt[1][nb][u]) : "v"(tro[nb][u]), "n"(BO + 16 * T::kRowBytes)); \
+        }                                                                                                        \
+      }                                                                                                          \
+      __builtin_amdgcn_sched_barrier(0);                                                                         \
+    }                                                                                                            \
+    if (!all_visible) {                                                                                          \
+      const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1; /* last visible key of the span */ \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                             \
+        S[r] = (k0 + 8 * (r / 4) + 4 * hi + r % 4 <= kmax) ? S[r] : -INFINITY; /* weight exactly 0 */            \
+    }                                                                                                            \
+    bf16x8 dS[2];                                                                                                \
+    _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2) {                                                           \
+      f32x8 e;                                                                                                   \
+      _Pragma("unroll") for (int x = 0; x < 8; ++x)                                                              \
+        e[x] = __builtin_amdgcn_exp2f(fmaf(S[8 * h2 + x], c, -lse2)) * (dP[8 * h2 + x] - delta);                 \
+      dS[h2] = __builtin_convertvector(e, bf16x8);                                                               \
+    }                                                                                                            \
+    SEGATTN_DQ_TR_WAIT();                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
+    _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2)                                                             \
+      _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                                          \
+        mma_acc(acc[nb], __builtin_bit_cast(bf16x8, __builtin_shufflevector(kt[h2][nb][0], kt[h2][nb][1], 0, 1, 2, 3, 4, 5, 6, 7)), dS[h2]); \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
+    SEGATTN_VMCNT(kLoadsPerStep);                                                                                \
+    __builtin_amdgcn_s_barrier();                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
+  } while (0)
+#define SEGATTN_DQ_ROWS_WAIT(F) /* the NC / 2 row operand pairs from index F on have arrived */                \
+  do {                                                                                                           \
+    if constexpr (NC == 8) {                                                                                     \
+      asm volatile("s_waitcnt lgkmcnt(0)"                                                                        \
+                   : "+v"(ka[(F)]), "+v"(ka[(F) + 1]), "+v"(ka[(F) + 2]), "+v"(ka[(F) + 3]), "+v"(va[(F)]),       \
+                     "+v"(va[(F) + 1]), "+v"(va[(F) + 2]), "+v"(va[(F) + 3]));                                   \
+    } else {                                                                                                     \
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ka[(F)]), "+v"(ka[(F) + 1]), "+v"(va[(F)]), "+v"(va[(F) + 1])); \
+    }                                                                                                            \
+  } while (0)
+#define SEGATTN_DQ_TR_WAIT()                                                                                     \
+  do {                                                                                                           \
+    if constexpr (NB == 4) {                                                                                     \
+      asm volatile("s_waitcnt lgkmcnt(0)"                                                                        \
+                   : "+v"(kt[0][0][0]), "+v"(kt[0][0][1]), "+v"(kt[0][1][0]), "+v"(kt[0][1][1]), "+v"(kt[0][2][0]),  \
+                     "+v"(kt[0][2][1]), "+v"(kt[0][3][0]), "+v"(kt[0][3][1]), "+v"(kt[1][0][0]), "+v"(kt[1][0][1]),  \
+                     "+v"(kt[1][1][0]), "+v"(kt[1][1][1]), "+v"(kt[1][2][0]), "+v"(kt[1][2][1]), "+v"(kt[1][3][0]),  \
+                     "+v"(kt[1][3][1]));                                                                         \
+    } else {                                                                                                     \
+      asm volatile("s_waitcnt lgkmcnt(0)"                                                                        \
+                   : "+v"(kt[0][0][0]), "+v"(kt[0][0][1]), "+v"(kt[0][1][0]), "+v"(kt[0][1][1]), "+v"(kt[1][0][0]),  \
+                     "+v"(kt[1][0][1]), "+v"(kt[1][1][0]), "+v"(kt[1][1][1]));                                   \
+    }                                                                                                            \
+  } while (0)
+
+  // Prologue: tiles of steps 0 and 1 on their way, tile 0 landed for everyone.
+  fetch_next(0);
+  fetch_next(1);
+  SEGATTN_VMCNT(kLoadsPerStep);
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0;;) {
+    SEGATTN_DQ_STEP(0);
+    if (++j == nsteps) break;
+    SEGATTN_DQ_STEP(1);
+    if (++j == nsteps) break;
+    SEGATTN_DQ_STEP(2);
+    if (++j == nsteps) break;
   }
-#undef SEGATTN_BWD_FETCH_KV
-#undef SEGATTN_BWD_STORE_KV
+  SEGATTN_VMCNT(0);  // the surplus fetches have landed: the ring may be reused by the next item
+#undef SEGATTN_DQ_STEP
+#undef SEGATTN_DQ_ROWS_WAIT
+#undef SEGATTN_DQ_TR_WAIT
+#undef SEGATTN_VMCNT
   unsigned ticket = 0;
   if (next_from && tid == 0) ticket = atomicAdd(next_from, 1u);
   if (row_ok) {
@@ -195,7 +292,7 @@ __device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillA
 // the per-XCD queues, as the forward kernel does and for the same reasons (prefill_mfma_kernel).
 template <int D, int HS>
 __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const Problem p_arg, const PrefillArgs pa_arg, const BwdArgs a_arg) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][BwdTile<D>::kBytes];  // [buffer][K,V]
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[DqGeom<D>::kBytes];  // ring of [K tile][V tile]
   __shared__ int claim;
   constexpr unsigned kPaAt = (sizeof(Problem) + alignof(PrefillArgs) - 1) / alignof(PrefillArgs) * alignof(PrefillArgs);
   constexpr unsigned kAAt = (kPaAt + sizeof(PrefillArgs) + alignof(BwdArgs) - 1) / alignof(BwdArgs) * alignof(BwdArgs);
