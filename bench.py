@@ -60,7 +60,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c4_128k_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode and streaming legs")
-    ap.add_argument("--only", choices=("backward", "decode", "retrieve"),
+    ap.add_argument("--only", choices=("backward", "decode", "retrieve", "retrieval_seq"),
                     help="profiling aid: run just this leg (none of them needs the 128K inputs) and print it alone")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
@@ -83,8 +83,15 @@ def main() -> int:
     torch.cuda.set_device(0)
     w = W.WORKLOADS[args.workload]
     if args.only:
+        def retrieval_seq_only():   # random bf16 rows of the workload's shape, drawn on the GPU (timing only)
+            g = torch.Generator(device="cuda").manual_seed(w.seed)
+            mk = lambda h: torch.randn((w.batch, w.seq_len, h, w.head_dim), device="cuda", generator=g).to(torch.bfloat16)
+            q_, k_, v_ = mk(w.n_q_heads), mk(w.n_kv_heads), mk(w.n_kv_heads)
+            o_ = torch.empty_like(q_)
+            return {"main": retrieval_seq_leg(sa, W, w, q_, k_, v_, o_),
+                    "paper_point": retrieval_seq_leg(sa, W, w, q_, k_, v_, o_, tail=512, long_groups=4)}
         leg = {"backward": lambda: backward_leg(sa, W, w), "decode": lambda: decode_leg(sa, W),
-               "retrieve": lambda: retrieve_leg(sa, W)}[args.only]
+               "retrieve": lambda: retrieve_leg(sa, W), "retrieval_seq": retrieval_seq_only}[args.only]
         print(json.dumps({args.only: leg()}))
         return 0
     N, Hq, Hkv, D, S, T = w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seg_len, w.tail_len
@@ -169,6 +176,8 @@ def main() -> int:
     if not args.no_extras:
         result["streaming"] = streaming_leg(sa, W, w, q, k, v, out, lse, flops)
         result["retrieval"] = retrieval_leg(sa, W, w, q, k, v, out)
+        result["retrieval_seq"] = retrieval_seq_leg(sa, W, w, q, k, v, out)
+        result["retrieval_seq_paper_point"] = retrieval_seq_leg(sa, W, w, q, k, v, out, tail=512, long_groups=4)
         result["ragged"] = ragged_leg(sa, W, w, q, k, v, out)
         result["rope"] = rope_leg(sa, W, w, q, k)
         del q, k, v, out, lse
@@ -275,6 +284,64 @@ def retrieval_leg(sa, W, w, q, k, v, out, R=512):
            "resident_kv_bytes": sa.segattn_resident_bytes(ctx), "arena_bytes": nbytes}
     sa.segattn_destroy(ctx)
     return res
+
+
+def retrieval_seq_leg(sa, W, w, q, k, v, out, R=512, tail=None, long_groups=None):
+    """Retrieval mode for the whole 128K prompt without the per-segment host chain: one
+    seg_kv_retrieve_seq (every segment's summaries scored against its pool, anchors, windows) and one
+    seg_attn_fwd_seq_retrieved (gather of all retrieved prefixes, one attention launch).  Default:
+    the main workload's tail and long-range groups; tail=512, long_groups=4 is the paper's operating
+    point (Appendix F: M = 512, R = 512, half of the heads long-range).  Open sizes as in
+    retrieval_leg."""
+    import torch
+    N, S = w.seq_len, w.seg_len
+    T = w.tail_len if tail is None else tail
+    n_long = sum(1 for p in w.kv_policy if p & 2) if long_groups is None else long_groups
+    policy = [2] * n_long + [1] * (w.n_kv_heads - n_long)
+    cfg = sa.make_config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                         seg_len=S, tail_len=T, kv_policy=policy)
+    n_seg = (N + S - 1) // S
+    rp = sa.make_retrieval(n_queries=32, pool_window=8, tail_avg=4, n_anchors=16, win_before=8, win_after=23)
+    nws = sa.seg_kv_retrieve_seq_workspace_bytes(cfg, rp, N)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    nws2 = sa.seg_attn_fwd_seq_retrieved_workspace_bytes(cfg, N, R)
+    ws2 = torch.empty(nws2, dtype=torch.uint8, device="cuda")
+    idx = torch.empty((w.batch, n_seg, n_long, R), dtype=torch.int32, device="cuda")
+    lse = torch.empty((w.batch, w.n_q_heads, N), dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    gq = w.n_q_heads // w.n_kv_heads
+    pairs = 0
+    for s in range(0, N, S):
+        m = min(S, N - s)
+        for p in policy:
+            prefix = min(R, s) if (p & 2) else (min(T, s) if (p & 1) else 0)
+            pairs += gq * (m * (m + 1) // 2 + m * prefix)
+    flops = 4 * w.head_dim * pairs * w.batch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def run(timed=False):
+        if timed:
+            ev[0].record()
+        sa.seg_kv_retrieve_seq(cfg, rp, q, k, N, R, idx, ws, nws, st)
+        if timed:
+            ev[1].record()
+        sa.seg_attn_fwd_seq_retrieved(cfg, q, k, v, N, idx, R, ws2, nws2, out, lse, st)
+        if timed:
+            ev[2].record()
+
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    reps, t_ret, t_att = 5, 0.0, 0.0
+    for _ in range(reps):
+        run(True)
+        torch.cuda.synchronize()
+        t_ret += ev[0].elapsed_time(ev[1]) / reps
+        t_att += ev[1].elapsed_time(ev[2]) / reps
+    ms = t_ret + t_att
+    return {"R": R, "tail_len": T, "kv_policy": policy, "ms": round(ms, 3), "ms_retrieve": round(t_ret, 3),
+            "ms_gather_and_attention": round(t_att, 3), "useful_flops": flops,
+            "tflops_useful": round(flops / ms / 1e9, 2), "frac_of_bf16_mfma_peak": round(flops / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
 
 
 def ragged_leg(sa, W, w, q, k, v, out):

@@ -290,6 +290,39 @@ segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, con
                                int32_t m, int32_t R, int32_t *idx_out, void *workspace,
                                size_t workspace_bytes, void *stream);
 
+/* ---- retrieval mode for a whole prompt, stateless ------------------------------------------------
+ * During prefill every segment's queries and every earlier key are present at once, so the
+ * per-segment chain retrieve -> select -> attend -> commit (the calls above; they remain the form
+ * for decoding) collapses into two calls with no context and no cache:
+ *
+ * seg_kv_retrieve_seq: the top-k retrieval operator (Appendix D, same reading and sizes as
+ * seg_kv_retrieve) for every segment i >= 1 of q [B,n,Hq,D], k [B,n,Hkv,D] at once: the queries
+ * are the last L_q rows of segment i-1, the pool of a PAST head is its keys [0, i S).  idx_out:
+ * device int32 [B, n_seg, n_past, R], n_seg = ceil(n / S), PAST heads in ascending KV-head order;
+ * the lists of segment 0 (no history) are not meaningful.  Requires 1 <= R <= S, at least one PAST
+ * head and none with TAIL as well (Eq. 13), n <= 2^20; workspace: device, 256-byte aligned,
+ * >= seg_kv_retrieve_seq_workspace_bytes() (0 if the sizes are invalid).
+ *
+ * seg_attn_fwd_seq_retrieved: seg_attn_fwd_seq in which a PAST head attends to [the R rows idx
+ * names for its segment ; own segment] (Eq. 13, second case) instead of its whole history; the
+ * first segment has no prefix.  idx as above (from seg_kv_retrieve_seq or the caller's own):
+ * positions before the segment's start, distinct; an out-of-range entry is clamped into the
+ * history, never read out of bounds.  The rows are first gathered into the workspace (device,
+ * 256-byte aligned, >= seg_attn_fwd_seq_retrieved_workspace_bytes(): 2 R D bf16 per (sequence,
+ * segment, PAST head)), with cfg->rope_theta > 0 re-rotated from their absolute positions to the
+ * R positions just before the segment as seg_kv_past_select does; then one attention launch. */
+size_t seg_kv_retrieve_seq_workspace_bytes(const segattn_config *cfg, const segattn_retrieval *r,
+                                           int64_t n);
+segattn_status seg_kv_retrieve_seq(const segattn_config *cfg, const segattn_retrieval *r,
+                                   const void *q, const void *k, int64_t n, int32_t R,
+                                   int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+size_t seg_attn_fwd_seq_retrieved_workspace_bytes(const segattn_config *cfg, int64_t n, int32_t R);
+segattn_status seg_attn_fwd_seq_retrieved(const segattn_config *cfg, const void *q, const void *k,
+                                          const void *v, int64_t n, const int32_t *idx, int32_t R,
+                                          void *workspace, size_t workspace_bytes, void *out,
+                                          float *lse, void *stream);
+
 /* Hide the n_oldest oldest rows of one PAST head's pool from now on (all sequences).  Pure
  * bookkeeping: nothing is copied and the rows' storage is not reused.  If the head also has
  * the TAIL bit, rows inside the current tail window stay visible.  Evicting more rows than

@@ -74,6 +74,10 @@ def lib() -> ctypes.CDLL:
             "seg_kv_past_keep_recent": (ctypes.c_int, [vp, i32, i64, vp]),
             "seg_kv_retrieve_workspace_bytes": (sz, [vp, ctypes.POINTER(segattn_retrieval)]),
             "seg_kv_retrieve": (ctypes.c_int, [vp, ctypes.POINTER(segattn_retrieval), vp, i32, i32, vp, vp, sz, vp]),
+            "seg_kv_retrieve_seq_workspace_bytes": (sz, [cfgp, ctypes.POINTER(segattn_retrieval), i64]),
+            "seg_kv_retrieve_seq": (ctypes.c_int, [cfgp, ctypes.POINTER(segattn_retrieval), vp, vp, i64, i32, vp, vp, sz, vp]),
+            "seg_attn_fwd_seq_retrieved_workspace_bytes": (sz, [cfgp, i64, i32]),
+            "seg_attn_fwd_seq_retrieved": (ctypes.c_int, [cfgp, vp, vp, vp, i64, vp, i32, vp, sz, vp, vp, vp]),
             "seg_kv_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]),
             "seg_kv_set_lengths": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), vp]),
             "segattn_cache_span": (ctypes.c_int, [vp, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(i64)]),
@@ -91,7 +95,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
-           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_seq_static", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_past_evict", "seg_kv_past_keep_recent",
+           "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_seq_static", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_retrieve_seq_workspace_bytes", "seg_kv_retrieve_seq", "seg_attn_fwd_seq_retrieved_workspace_bytes", "seg_attn_fwd_seq_retrieved", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
            "seg_attn_decode", "segattn_strerror", "segattn_version")
 
@@ -233,6 +237,27 @@ def seg_kv_retrieve(ctx: int, r: segattn_retrieval, q_prev, m: int, R: int, idx_
                     workspace_bytes: int, stream=None) -> None:
     _check(lib().seg_kv_retrieve(ctx, ctypes.byref(r), _ptr(q_prev), m, R, _ptr(idx_out), _ptr(workspace),
                                  workspace_bytes, _ptr(stream)), "seg_kv_retrieve")
+
+
+def seg_kv_retrieve_seq_workspace_bytes(cfg: segattn_config, r: segattn_retrieval, n: int) -> int:
+    return int(lib().seg_kv_retrieve_seq_workspace_bytes(ctypes.byref(cfg), ctypes.byref(r), n))
+
+
+def seg_kv_retrieve_seq(cfg: segattn_config, r: segattn_retrieval, q, k, n: int, R: int, idx_out, workspace,
+                        workspace_bytes: int, stream=None) -> None:
+    _check(lib().seg_kv_retrieve_seq(ctypes.byref(cfg), ctypes.byref(r), _ptr(q), _ptr(k), n, R, _ptr(idx_out),
+                                     _ptr(workspace), workspace_bytes, _ptr(stream)), "seg_kv_retrieve_seq")
+
+
+def seg_attn_fwd_seq_retrieved_workspace_bytes(cfg: segattn_config, n: int, R: int) -> int:
+    return int(lib().seg_attn_fwd_seq_retrieved_workspace_bytes(ctypes.byref(cfg), n, R))
+
+
+def seg_attn_fwd_seq_retrieved(cfg: segattn_config, q, k, v, n: int, idx, R: int, workspace, workspace_bytes: int,
+                               out, lse, stream=None) -> None:
+    _check(lib().seg_attn_fwd_seq_retrieved(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(v), n, _ptr(idx), R,
+                                            _ptr(workspace), workspace_bytes, _ptr(out), _ptr(lse), _ptr(stream)),
+           "seg_attn_fwd_seq_retrieved")
 
 
 def seg_kv_past_evict(ctx: int, kv_head: int, n_oldest: int, stream=None) -> None:

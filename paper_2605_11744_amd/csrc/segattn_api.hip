@@ -644,6 +644,128 @@ segattn_status seg_kv_retrieve(segattn_ctx *ctx, const segattn_retrieval *r, con
   return hip_status(launch_retrieve(p, a, (hipStream_t)stream));
 }
 
+// ---- stateless retrieval mode: the whole prompt at once ---------------------------------------
+namespace {
+// Problem of a stateless retrieval-mode call: at least one PAST head, none with TAIL as well
+// (Eq. 13 gives a long-range head its retrieved prefix and no tail), 1 <= R <= S so that every
+// segment after the first has R pool rows to choose from.
+bool build_retrieval_problem(const segattn_config *cfg, int64_t n, int32_t R, Problem &p, int &n_seg) {
+  if (!build_problem(cfg, false, p)) return false;
+  if (n < 1 || n >= (1ll << 31) - 4096 || R < 1 || R > p.S || p.n_past == 0) return false;
+  for (int h = 0; h < p.Hkv; ++h)
+    if (p.policy[h] == (SEGATTN_TAIL | SEGATTN_PAST)) return false;
+  n_seg = (int)((n + p.S - 1) / p.S);
+  return true;
+}
+constexpr int kRetrieveSeqChunk = 1024;  // pool rows per scoring workgroup of the whole-prompt form
+bool retrieval_seq_layout(const Problem &p, const segattn_retrieval *r, int64_t n, int n_seg, int &nsp, int &n_chunks,
+                          unsigned long long &off_val, unsigned long long &off_idx, unsigned long long &total) {
+  if (!r || r->n_queries < 1 || r->pool_window < 1 || r->tail_avg < 1 || r->n_anchors < 1 || r->n_anchors > kRetrieveCand)
+    return false;
+  if (r->win_before < 0 || r->win_after < 0 || r->win_before > (1 << 20) || r->win_after > (1 << 20)) return false;
+  if (n > (1ll << 20)) return false;
+  const long long n_sum = (long long)(r->n_queries + r->pool_window - 1) / r->pool_window + 1;
+  if (n_sum * p.g > 64) return false;
+  nsp = (int)((n_sum * p.g + 31) / 32 * 32);
+  const long long longest = (long long)(n_seg - 1) * p.S;  // pool of the last segment
+  n_chunks = (int)((longest + kRetrieveSeqChunk - 1) / kRetrieveSeqChunk);
+  if (n_chunks < 1) n_chunks = 1;
+  const unsigned long long heads = (unsigned long long)p.B * n_seg * p.n_past;
+  off_val = align_up(heads * nsp * p.D * 2ull);
+  off_idx = align_up(off_val + heads * n_chunks * kRetrieveCand * 4ull);
+  total = align_up(off_idx + heads * n_chunks * kRetrieveCand * 4ull);
+  return true;
+}
+}  // namespace
+
+size_t seg_kv_retrieve_seq_workspace_bytes(const segattn_config *cfg, const segattn_retrieval *r, int64_t n) {
+  Problem p;
+  int n_seg, nsp, n_chunks;
+  unsigned long long a, b, total;
+  if (!build_retrieval_problem(cfg, n, 1, p, n_seg) || !retrieval_seq_layout(p, r, n, n_seg, nsp, n_chunks, a, b, total))
+    return 0;
+  return (size_t)total;
+}
+
+segattn_status seg_kv_retrieve_seq(const segattn_config *cfg, const segattn_retrieval *r, const void *q, const void *k,
+                                   int64_t n, int32_t R, int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+  Problem p;
+  int n_seg, nsp, n_chunks;
+  unsigned long long off_val, off_idx, total;
+  if (!build_retrieval_problem(cfg, n, R, p, n_seg) ||
+      !retrieval_seq_layout(p, r, n, n_seg, nsp, n_chunks, off_val, off_idx, total))
+    return SEGATTN_EINVAL;
+  if (!q || !k || !idx_out || !workspace || workspace_bytes < total || ((uintptr_t)workspace % kAlign)) return SEGATTN_EINVAL;
+  RetrieveArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q_prev = (const unsigned short *)q;
+  a.k_seq = (const unsigned short *)k;
+  a.n_rows = (int)n;
+  a.n_seg = n_seg;
+  a.summaries = (unsigned short *)workspace;
+  a.cand_val = (float *)((unsigned char *)workspace + off_val);
+  a.cand_idx = (int *)((unsigned char *)workspace + off_idx);
+  a.idx_out = idx_out;
+  a.m = p.S;
+  a.R = R;
+  a.nsp = nsp;
+  a.chunk_rows = kRetrieveSeqChunk;
+  a.n_chunks = n_chunks;
+  a.n_queries = r->n_queries;
+  a.pool_window = r->pool_window;
+  a.tail_avg = r->tail_avg;
+  a.n_anchors = r->n_anchors;
+  a.win_before = r->win_before;
+  a.win_after = r->win_after;
+  return hip_status(launch_retrieve(p, a, (hipStream_t)stream));
+}
+
+size_t seg_attn_fwd_seq_retrieved_workspace_bytes(const segattn_config *cfg, int64_t n, int32_t R) {
+  Problem p;
+  int n_seg;
+  if (!build_retrieval_problem(cfg, n, R, p, n_seg)) return 0;
+  return (size_t)(2ull * align_up((unsigned long long)p.B * n_seg * p.n_past * (unsigned long long)R * p.D * 2ull));
+}
+
+segattn_status seg_attn_fwd_seq_retrieved(const segattn_config *cfg, const void *q, const void *k, const void *v,
+                                          int64_t n, const int32_t *idx, int32_t R, void *workspace,
+                                          size_t workspace_bytes, void *out, float *lse, void *stream) {
+  Problem p;
+  int n_seg;
+  if (!build_retrieval_problem(cfg, n, R, p, n_seg)) return SEGATTN_EINVAL;
+  if (!q || !k || !v || !idx || !out || !lse || !workspace || ((uintptr_t)workspace % kAlign)) return SEGATTN_EINVAL;
+  if (workspace_bytes < seg_attn_fwd_seq_retrieved_workspace_bytes(cfg, n, R)) return SEGATTN_EINVAL;
+  const unsigned long long half = align_up((unsigned long long)p.B * n_seg * p.n_past * (unsigned long long)R * p.D * 2ull);
+  GatherSeqArgs g;
+  memset(&g, 0, sizeof(g));
+  g.k = (const unsigned short *)k;
+  g.v = (const unsigned short *)v;
+  g.idx = idx;
+  g.ret_k = (unsigned short *)workspace;
+  g.ret_v = (unsigned short *)((unsigned char *)workspace + half);
+  g.n = (int)n;
+  g.n_seg = n_seg;
+  g.R = R;
+  g.rope = cfg->rope_theta > 0.f;
+  if (g.rope) fill_inv_freq(g.inv_freq, p.D, cfg->rope_theta);
+  if (launch_gather_seq(p, g, (hipStream_t)stream) != hipSuccess) return SEGATTN_EHIP;
+  PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = (const unsigned short *)q;
+  a.k = (const unsigned short *)k;
+  a.v = (const unsigned short *)v;
+  a.out = out;
+  a.lse = lse;
+  a.cache = nullptr;
+  a.n_rows = (int)n;
+  a.n_seg = n_seg;
+  a.ret_k = g.ret_k;
+  a.ret_v = g.ret_v;
+  a.ret_R = R;
+  return hip_status(launch_prefill(p, a, (hipStream_t)stream));
+}
+
 // n_oldest >= 0 with keep < 0: hide that many more rows; keep >= 0: hide what exceeds `keep`
 // visible rows.  The host mirror follows the device counters.
 static segattn_status evict_rows(segattn_ctx *ctx, int32_t kv_head, int64_t n_oldest, int64_t keep, void *stream) {

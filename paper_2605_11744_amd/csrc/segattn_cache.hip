@@ -315,7 +315,55 @@ __global__ __launch_bounds__(256) void cache_select_kernel(const Problem p, cons
   if (blockIdx.x == 0 && threadIdx.x == 0) meta[META_RET] = pool > 0 ? a.R : 0;
 }
 
+// Retrieved prefixes of a whole prompt (stateless retrieval mode; Appendix D "Output"): rows
+// idx[b][segment][PAST head][0..R) of the token-major k / v -> R dense rows per (b, segment, head),
+// in list order.  An index is clamped into the segment's history [0, segment start), so a bad list
+// cannot read outside the prompt.  With RoPE the pool rows carry their absolute positions and list
+// entry r moves to position s - R + r, s the segment start (Appendix E up to a common shift).
+// grid = (row chunks, B * n_seg * n_past).
+template <int D>
+__global__ __launch_bounds__(256) void gather_seq_kernel(const Problem p, const GatherSeqArgs a) {
+  constexpr int CPR = D / 8;
+  const int np = blockIdx.y % p.n_past;
+  const int seg = (blockIdx.y / p.n_past) % a.n_seg;
+  const int b = blockIdx.y / (p.n_past * a.n_seg);
+  if (seg == 0) return;  // no history: no prefix
+  const int h = p.order[np];
+  const int pool = seg * p.S;
+  const long long slot = ((long long)b * a.n_seg + seg) * p.n_past + np;
+  const int *idx = a.idx + slot * a.R;
+  const long long kv_stride = (long long)p.Hkv * CPR;  // uint4 per token row
+  const uint4 *ks = (const uint4 *)a.k + ((long long)b * a.n * p.Hkv + h) * CPR;
+  const uint4 *vs = (const uint4 *)a.v + ((long long)b * a.n * p.Hkv + h) * CPR;
+  uint4 *kd = (uint4 *)a.ret_k + slot * a.R * CPR;
+  uint4 *vd = (uint4 *)a.ret_v + slot * a.R * CPR;
+  const int c = threadIdx.x % CPR;
+  for (int r = blockIdx.x * (256 / CPR) + threadIdx.x / CPR; r < a.R; r += gridDim.x * (256 / CPR)) {
+    int j = idx[r];
+    j = j < 0 ? 0 : (j >= pool ? pool - 1 : j);
+    vd[(long long)r * CPR + c] = vs[(long long)j * kv_stride + c];
+    if (!a.rope) {
+      kd[(long long)r * CPR + c] = ks[(long long)j * kv_stride + c];
+    } else if (c < CPR / 2) {
+      uint4 lo = ks[(long long)j * kv_stride + c], hi = ks[(long long)j * kv_stride + c + CPR / 2];
+      rerotate8(lo, hi, (double)(pool - a.R + r - j), a.inv_freq, 8 * c);
+      kd[(long long)r * CPR + c] = lo;
+      kd[(long long)r * CPR + c + CPR / 2] = hi;
+    }
+  }
+}
+
 // ---- launchers ----------------------------------------------------------------------------
+hipError_t launch_gather_seq(const Problem &p, const GatherSeqArgs &a, hipStream_t st) {
+  const int rows_per_block = 256 / (p.D / 8);
+  int chunks = (a.R + rows_per_block - 1) / rows_per_block;
+  if (chunks < 1) chunks = 1;
+  const dim3 grid(chunks, p.B * a.n_seg * p.n_past);
+  if (p.D == 128) hipLaunchKernelGGL(gather_seq_kernel<128>, grid, dim3(256), 0, st, p, a);
+  else hipLaunchKernelGGL(gather_seq_kernel<64>, grid, dim3(256), 0, st, p, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_cache_reset(const Problem &p, unsigned char *cache, const CacheGeom &g, hipStream_t st) {
   const int n = p.B * p.Hkv * kMetaInts;
   hipLaunchKernelGGL(cache_reset_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, cache, g);

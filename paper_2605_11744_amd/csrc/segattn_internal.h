@@ -98,6 +98,11 @@ struct PrefillArgs {
   // queues, the counters: next item of XCD y's queue at queue[kQueueStride * y], zero at the start.
   int grid_items;
   unsigned *queue;       // device; nullptr: workgroup i runs item i
+  // SEQ mode, retrieved prefixes (stateless retrieval mode): a PAST head attends to [R gathered rows ;
+  // own segment]; the rows of (b, segment, PAST head) are R dense rows of D at
+  // ret_k / ret_v + (((b * n_seg + segment) * n_past + past index) * R) * D.  nullptr: whole history.
+  const unsigned short *ret_k, *ret_v;
+  int ret_R;
 };
 constexpr int kQueueStride = 32;  // unsigned words between two queue counters (128 bytes)
 // Host side of the item queues (segattn_prefill_mfma.hip): the counters of this (device, stream),
@@ -217,6 +222,17 @@ struct LengthsArgs {
   int closed[kLengthsChunk], tail[kLengthsChunk], fill[kLengthsChunk];
 };
 
+// Gather of the retrieved prefixes of a whole prompt (stateless retrieval mode): for every
+// (b, segment >= 1, PAST head) the R rows idx names, from the token-major k / v into dense rows.
+struct GatherSeqArgs {
+  const unsigned short *k, *v;   // [B, n, Hkv, D]
+  const int *idx;                // [B, n_seg, n_past, R] positions (< segment start)
+  unsigned short *ret_k, *ret_v; // [B, n_seg, n_past, R, D]
+  int n, n_seg, R;
+  int rope;                      // re-rotate the gathered K rows to the positions just before their segment
+  double inv_freq[64];
+};
+
 struct SelectArgs {
   const int *idx;        // [B, n_past, R] pool row numbers
   unsigned char *cache;
@@ -237,6 +253,12 @@ struct RetrieveArgs {
   int *idx_out;                  // [B, n_past, R]
   int m, R, nsp, n_chunks, chunk_rows;
   int n_queries, pool_window, tail_avg, n_anchors, win_before, win_after;
+  // Whole-prompt form (k_seq != nullptr; cache unused): the "sequences" the kernels see are the
+  // pairs (b, segment i), B * n_seg of them; the pool of (b, i) is rows [0, i S) of k_seq
+  // [B, n_rows, Hkv, D] and its query rows are those of segment i - 1 in q_prev [B, n_rows, Hq, D]
+  // (m = S).  Segment 0 has an empty pool and gets an unused list.
+  const unsigned short *k_seq;
+  int n_rows, n_seg;
 };
 
 struct RopeArgs {
@@ -299,6 +321,33 @@ __host__ __device__ inline void window_of(const Problem &p, const CacheGeom &g, 
   }
 }
 
+// The pool of PAST head kv of "sequence" vb as the retrieval kernels see it.
+struct PoolView {
+  const unsigned char *k;   // first K row
+  long long row_bytes;      // bytes between consecutive rows
+  int pool, lo;             // rows held; first visible row
+  const unsigned short *q;  // the m previous-segment query rows [m, Hq, D] the summaries are made of
+};
+__device__ inline PoolView pool_view(const Problem &p, const RetrieveArgs &a, int vb, int kv) {
+  PoolView v;
+  if (a.k_seq) {
+    const int b = vb / a.n_seg, i = vb % a.n_seg;
+    v.k = (const unsigned char *)(a.k_seq + ((long long)b * a.n_rows * p.Hkv + kv) * p.D);
+    v.row_bytes = (long long)p.Hkv * p.D * 2;
+    v.pool = i * p.S;
+    v.lo = 0;
+    v.q = a.q_prev + ((long long)b * a.n_rows + (long long)(i > 0 ? i - 1 : 0) * p.S) * p.Hq * p.D;
+  } else {
+    const int *meta = (const int *)(a.cache + a.geom.meta_off) + ((long long)vb * p.Hkv + kv) * kMetaInts;
+    v.k = a.cache + k_block_off(p, a.geom, vb, kv);
+    v.row_bytes = 2 * p.D;
+    v.pool = meta[META_POOL];
+    v.lo = meta[META_LO];
+    v.q = a.q_prev + (long long)vb * a.m * p.Hq * p.D;
+  }
+  return v;
+}
+
 // ---- decode: counters and split-K workspace (device side) ---------------------------------------
 __device__ inline const int *meta_ro(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b,
                                      int h) {
@@ -345,6 +394,7 @@ hipError_t launch_cache_select(const Problem &p, const SelectArgs &a, hipStream_
 hipError_t launch_cache_set_lengths(const Problem &p, unsigned char *cache, const CacheGeom &g, const LengthsArgs &a,
                                     hipStream_t st);
 hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t st);
+hipError_t launch_gather_seq(const Problem &p, const GatherSeqArgs &a, hipStream_t st);
 hipError_t launch_rope_apply(const Problem &p, const RopeArgs &a, hipStream_t st);
 hipError_t launch_bwd_delta(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);

@@ -985,7 +985,7 @@ static int waves_d128(const Problem &p, const PrefillArgs &a, int hs) {
   const int rows8 = (8 / hs) * 32;
   const long long blocks8 = (long long)a.n_seg * ((seg_rows + rows8 - 1) / rows8);
   // PAST heads carry the long key ranges unless they attend to a retrieved prefix of bounded size
-  const bool long_past = p.n_past > 0 && !(a.cache != nullptr && a.geom.ret_cap > 0);
+  const bool long_past = p.n_past > 0 && !(a.cache != nullptr && a.geom.ret_cap > 0) && a.ret_k == nullptr;
   const long long heads = (long long)p.B * (long_past ? p.n_past : p.Hkv) * (p.g / hs);
   return heads * blocks8 < n_cu ? 4 : 8;
 }
@@ -1029,7 +1029,7 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t
   const long long per_head = (long long)p.B * (p.g / hs) * a.n_seg * a.q_blocks_per_seg;
   const long long grid = per_head * ((long long)p.n_past * a.parts + (p.Hkv - p.n_past));
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  const int n_first = (a.cache != nullptr && a.geom.ret_cap > 0) ? 0 : p.n_past;  // as in resolve()
+  const int n_first = ((a.cache != nullptr && a.geom.ret_cap > 0) || a.ret_k != nullptr) ? 0 : p.n_past;  // as in resolve()
   const long long groups = (long long)p.B * (p.Hkv - n_first) * (p.g / hs) * a.n_seg;
   a.pair_stride = prefill_pair_stride(groups);
   // Interleaved sub-groups per group so that the XCDs' ranges are whole (sub-)groups: see resolve().

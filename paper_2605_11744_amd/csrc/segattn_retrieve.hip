@@ -29,10 +29,6 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxAnchors = 32;
 
-__device__ inline const int *rmeta(const unsigned char *cache, const CacheGeom &g, const Problem &p, int b, int h) {
-  return (const int *)(cache + g.meta_off) + ((long long)b * p.Hkv + h) * kMetaInts;
-}
-
 // (value, row) pairs ordered by value descending, then row ascending
 __device__ inline bool better(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
 
@@ -98,8 +94,9 @@ __device__ inline void block_best(float &v, int &i, float *sm_v, int *sm_i) {
 template <int D>
 __global__ __launch_bounds__(256) void retrieve_summaries_kernel(const Problem p, const RetrieveArgs a) {
   constexpr int CH = D / 8;  // a thread forms 8 channels of one summary
-  const int b = blockIdx.x / p.n_past, np = blockIdx.x % p.n_past;
+  const int b = blockIdx.x / p.n_past, np = blockIdx.x % p.n_past;  // b: sequence, or (sequence, segment)
   const int kv = p.order[np];
+  const PoolView pv = pool_view(p, a, b, kv);
   const int L = a.n_queries < a.m ? a.n_queries : a.m;
   const int n_win = (L + a.pool_window - 1) / a.pool_window;
   const int n_sum = n_win + 1;
@@ -117,7 +114,7 @@ __global__ __launch_bounds__(256) void retrieve_summaries_kernel(const Problem p
       r1 = L;
     }
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const unsigned short *src = a.q_prev + (((long long)b * a.m + (a.m - L)) * p.Hq + hq) * D + 8 * c;
+    const unsigned short *src = pv.q + ((long long)(a.m - L) * p.Hq + hq) * D + 8 * c;
     const long long stride = (long long)p.Hq * D;
 #pragma unroll 4
     for (int r = r0; r < r1; ++r) {
@@ -151,8 +148,8 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
   __shared__ __attribute__((aligned(16))) unsigned char stage[4][32 * 2 * D];  // one K tile per wave
   const int b = blockIdx.y / p.n_past, np = blockIdx.y % p.n_past;
   const int kv = p.order[np];
-  const int *meta = rmeta(a.cache, a.geom, p, b, kv);
-  const int pool = meta[META_POOL], lo = meta[META_LO];
+  const PoolView pv = pool_view(p, a, b, kv);
+  const int pool = pv.pool, lo = pv.lo;
   const int c0 = blockIdx.x * kChunkRows;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, hi = lane >> 5, col = lane & 31;
   float *cv = a.cand_val + (((long long)b * p.n_past + np) * a.n_chunks + blockIdx.x) * kMaxAnchors;
@@ -170,14 +167,15 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
   for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int kc = 0; kc < NC; ++kc) A[t][kc] = *(const bf16x8 *)(sg + (long long)(32 * t + col) * D + 16 * kc + 8 * hi);
-  // K rows travel HBM -> registers with fully coalesced 1 KB wave loads (32 rows of a tile are
-  // contiguous in the pool), are dropped into a wave-private LDS tile with the 16-byte chunks of
+  // K rows travel HBM -> registers with coalesced wave loads (a pool in the cache arena is
+  // contiguous: 1 KB per load; rows of a token-major prompt are 2 D contiguous bytes each), are dropped into a wave-private LDS tile with the 16-byte chunks of
   // a row XOR-swizzled by the row, and come back in operand layout (lane = row).  The loads of
   // the next tile are in flight while the current one is scored.
   constexpr int RPL = 1024 / (2 * D);        // rows per 1 KB load
   constexpr int NL = 32 / RPL;               // loads per tile
   constexpr int CH = D / 8;                  // 16-byte chunks per row
-  const unsigned char *kb = a.cache + k_block_off(p, a.geom, b, kv);
+  const unsigned char *kb = pv.k;
+  const long long row_bytes = pv.row_bytes;
   auto swz = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
   const long long last_byte_row = (long long)(pool - 1);
   u32x4 cur[NL], nxt[NL];
@@ -186,7 +184,7 @@ __global__ __launch_bounds__(256) void retrieve_score_kernel(const Problem p, co
     for (int i = 0; i < NL; ++i) {
       long long row = (long long)c0 + t0 + RPL * i + lane / CH;
       row = row < last_byte_row ? row : last_byte_row;  // clamp: stays inside the pool
-      dst[i] = __builtin_nontemporal_load((const u32x4 *)(kb + row * (2 * D) + (lane % CH) * 16));  // read once
+      dst[i] = __builtin_nontemporal_load((const u32x4 *)(kb + row * row_bytes + (lane % CH) * 16));  // read once
     }
   };
   unsigned char *tile = stage[wave];
@@ -301,8 +299,8 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
   __shared__ int n_pieces;
   const int b = blockIdx.x / p.n_past, np = blockIdx.x % p.n_past;
   const int kv = p.order[np];
-  const int *meta = rmeta(a.cache, a.geom, p, b, kv);
-  const int pool = meta[META_POOL], lo = meta[META_LO];
+  const PoolView pv = pool_view(p, a, b, kv);
+  const int pool = pv.pool, lo = pv.lo;
   const int tid = threadIdx.x;
   const long long base = ((long long)b * p.n_past + np) * a.n_chunks * kMaxAnchors;
   // live candidates: n_anchors per chunk
@@ -488,12 +486,13 @@ __global__ __launch_bounds__(256) void retrieve_select_kernel(const Problem p, c
 }
 
 hipError_t launch_retrieve(const Problem &p, const RetrieveArgs &a, hipStream_t st) {
-  const dim3 heads(p.B * p.n_past);
+  const int seqs = a.k_seq ? p.B * a.n_seg : p.B;  // whole-prompt form: one "sequence" per (b, segment)
+  const dim3 heads(seqs * p.n_past);
   if (p.D == 128) hipLaunchKernelGGL(retrieve_summaries_kernel<128>, heads, dim3(256), 0, st, p, a);
   else hipLaunchKernelGGL(retrieve_summaries_kernel<64>, heads, dim3(256), 0, st, p, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const dim3 grid(a.n_chunks, p.B * p.n_past);
+  const dim3 grid(a.n_chunks, seqs * p.n_past);
   const int nt = a.nsp / 32;
 #define SEGATTN_SCORE(DD, NTT)                                                                            \
   do {                                                                                                    \

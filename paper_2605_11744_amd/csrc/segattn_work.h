@@ -91,7 +91,7 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   // heads listed first, longest work first: the PAST heads -- unless they attend to a retrieved
   // prefix of bounded size, in which case their key ranges are as short as everybody's and all
   // heads go into the common list below
-  const int n_first = (a.cache != nullptr && a.geom.ret_cap > 0) ? 0 : p.n_past;
+  const int n_first = ((a.cache != nullptr && a.geom.ret_cap > 0) || a.ret_k != nullptr) ? 0 : p.n_past;
   const int n_other = p.Hkv - n_first;
   const int parts = (a.cache != nullptr && a.parts > 1) ? a.parts : 1;
   const long long past_items = (long long)p.B * n_first * nhs * a.n_seg * nqb * parts;
@@ -181,6 +181,14 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     w.k1 = a.k + (base + s) * kv_stride + (long long)kv * p.D;
     w.v1 = a.v + (base + s) * kv_stride + (long long)kv * p.D;
     w.stride0 = w.stride1 = kv_stride;
+    if (a.ret_k != nullptr && (pol & SEGATTN_PAST)) {
+      // retrieved prefix of (b, segment, head): R dense gathered rows (none for the first segment)
+      const long long slot = ((long long)b * a.n_seg + seg) * p.n_past + p.past_before[kv];
+      w.n0 = seg > 0 ? a.ret_R : 0;
+      w.k0 = a.ret_k + slot * a.ret_R * p.D;
+      w.v0 = a.ret_v + slot * a.ret_R * p.D;
+      w.stride0 = p.D;
+    }
     w.q = a.q + (base + s) * p.Hq * p.D;
     const long long osz = p.out_fp32 ? 4 : 2;
     w.out = (unsigned char *)a.out + (base + s) * p.Hq * p.D * osz;

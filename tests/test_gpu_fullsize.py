@@ -145,6 +145,68 @@ def test_decode_c5_full_batch(fp32_check):
         c.close()
 
 
+@pytest.mark.parametrize("tail,long_groups", [(1024, 2), (512, 4)])
+def test_whole_prompt_retrieval_mode_full_size_sampled_rows(tail, long_groups):
+    """Retrieval mode on the 128K prompt as the benchmark runs it (bf16 output; R = 512, L_q = 32,
+    16 anchors with 32-row windows): seg_kv_retrieve_seq chooses every segment's rows in one call,
+    seg_attn_fwd_seq_retrieved attends in one launch.  With the main workload's two long-range
+    groups and tail, and at the paper's operating point (Appendix F: tail 512, R = 512, half of the
+    heads long-range).  Lists: sorted, distinct, inside the segment's history, and they contain the
+    windows of the rows whose oracle score clearly wins; attention: sampled rows against the
+    oracle with the same lists."""
+    import gpu_util as G
+    import paper_2605_11744_amd as sa
+    w0 = W.C4
+    R = 512
+    policy = [2] * long_groups + [1] * (w0.n_kv_heads - long_groups)
+    w = W.small("c4_retrieval", index=w0.index, seq_len=w0.seq_len, seg_len=w0.seg_len, tail_len=tail,
+                n_q_heads=w0.n_q_heads, n_kv_heads=w0.n_kv_heads, head_dim=w0.head_dim, kv_policy=policy)
+    params = dict(n_queries=32, pool_window=8, tail_avg=4, n_anchors=16, win_before=8, win_after=23)
+    q, k, v = W.prefill_inputs(w)
+    N, S, g = w.seq_len, w.seg_len, w.group
+    n_seg = N // S
+    cfg = G.config_of(w, out_fp32=False)
+    qd, kd, vd = G.dev_bf16(q), G.dev_bf16(k), G.dev_bf16(v)
+    st = torch.cuda.current_stream().cuda_stream
+    r = sa.make_retrieval(**params)
+    nws = sa.seg_kv_retrieve_seq_workspace_bytes(cfg, r, N)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    idx = torch.full((1, n_seg, long_groups, R), -1, dtype=torch.int32, device="cuda")
+    sa.seg_kv_retrieve_seq(cfg, r, qd, kd, N, R, idx, ws, nws, st)
+    nws2 = sa.seg_attn_fwd_seq_retrieved_workspace_bytes(cfg, N, R)
+    ws2 = torch.empty(nws2, dtype=torch.uint8, device="cuda")
+    out = torch.full((1, N, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((1, w.n_q_heads, N), float("nan"), dtype=torch.float32, device="cuda")
+    sa.seg_attn_fwd_seq_retrieved(cfg, qd, kd, vd, N, idx, R, ws2, nws2, out, lse, st)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    idx_h = idx.cpu().numpy()
+    retrieved = {}
+    for i in range(1, n_seg):
+        for j in range(long_groups):
+            lst = idx_h[0, i, j]
+            assert (np.diff(lst) > 0).all() and lst[0] >= 0 and lst[-1] < i * S, (i, j)
+            retrieved[(0, j, i)] = lst
+    # lists of a few segments against the oracle's scores: every clearly winning row's window is in
+    span = params["win_before"] + params["win_after"] + 1
+    assert params["n_anchors"] * span <= R
+    for i in (1, n_seg // 2, n_seg - 1):
+        for j in range(long_groups):
+            _, sc = orc.retrieve_indices(q[0, (i - 1) * S:i * S, j * g:(j + 1) * g], k[0, :i * S, j], R=R,
+                                         return_scores=True, **params)
+            nth = np.sort(sc)[-params["n_anchors"]]
+            got = set(idx_h[0, i, j].tolist())
+            for a_ in np.nonzero(sc > nth + 0.5)[0]:
+                assert set(range(max(0, a_ - params["win_before"]), min(i * S, a_ + params["win_after"] + 1))) <= got
+    rows = _sample_rows(w, 40, w.seed + 11)
+    sel = torch.from_numpy(rows).cuda()
+    o_ref, l_ref = orc.attend(q, k, v, seg_len=S, tail_len=tail, kv_policy=policy, rows=rows, retrieved=retrieved)
+    o_gpu, l_gpu = G.to_f64(out.index_select(1, sel)), G.to_f64(lse.index_select(2, sel))
+    eo, el = np.abs(o_gpu - o_ref), np.abs(l_gpu - l_ref)
+    assert np.all(eo <= 1e-2 + np.abs(o_ref) * 2.0 ** -8) and eo.mean() <= 1e-3, (eo.max(), eo.mean())
+    assert el.max() <= 1e-2 and el.mean() <= 1e-3, el.max()
+
+
 def test_ragged_batch_full_size_sampled_rows():
     """The packed batch bench.py times (the 128K tokens of the main workload cut into 12 sequences of
     720 .. 32768 tokens, one seg_attn_fwd_varlen launch, bf16 output): rows at the start and end of
