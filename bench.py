@@ -33,9 +33,51 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
-# HBM-side bytes of one prefill_mfma_kernel launch on the 128K workload, from the FETCH_SIZE and
-# WRITE_SIZE counter runs summarised in profiles/prefill_mfma_c4_128k_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": 8.73e9 + 1.09e9}
+# HBM-side bytes of one prefill_mfma_kernel launch on the 128K workload: FETCH_SIZE + WRITE_SIZE of
+# the counter runs summarised in profiles/prefill_mfma_c4_128k_hbm_traffic.txt (reads vary from run
+# to run with what the long key streams find in the last-level cache): median, and (min, max)
+MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": (8.73e9 + 1.09e9, (6.9e9 + 1.09e9, 8.73e9 + 1.09e9))}
+NOMINAL_GFX_MHZ = 2400.0       # the clock the published peaks are quoted at
+
+
+class ClockSampler:
+    """Samples the shader clock of the eight XCDs (amdsmi) from a host thread while a timed region
+    runs, so that a roofline fraction can also be stated against the clock the part actually held."""
+
+    def __init__(self, period_s=0.004):
+        self.period, self.samples, self._stop, self._thread, self._h = period_s, [], False, None, None
+        try:
+            import amdsmi
+            amdsmi.amdsmi_init()
+            self._smi, self._h = amdsmi, amdsmi.amdsmi_get_processor_handles()[0]
+        except Exception:
+            self._h = None
+
+    def _run(self):
+        while not self._stop:
+            try:
+                m = self._smi.amdsmi_get_gpu_metrics_info(self._h)
+                clks = [c for c in m.get("current_gfxclks", []) if isinstance(c, (int, float)) and 0 < c < 10000]
+                if clks:
+                    self.samples.append(sum(clks) / len(clks))
+            except Exception:
+                pass
+            time.sleep(self.period)
+
+    def __enter__(self):
+        if self._h is not None:
+            import threading
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread is not None:
+            self._thread.join()
+
+    def mean_mhz(self):
+        return sum(self.samples) / len(self.samples) if self.samples else None
 
 
 def visible_pairs(w) -> int:
@@ -52,6 +94,14 @@ def visible_pairs(w) -> int:
     return total * w.batch
 
 
+def calibration_copy(torch):
+    """Known traffic for the HBM byte counters: 1 GiB read + 1 GiB written by one copy kernel."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,7 +110,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c4_128k_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode and streaming legs")
-    ap.add_argument("--only", choices=("backward", "decode", "retrieve", "retrieval_seq"),
+    ap.add_argument("--only", choices=("backward", "decode", "retrieve", "retrieval_seq", "rope", "ceiling", "other_configs"),
                     help="profiling aid: run just this leg (none of them needs the 128K inputs) and print it alone")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
@@ -83,6 +133,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     w = W.WORKLOADS[args.workload]
     if args.only:
+        if args.calibration_copy:
+            calibration_copy(torch)
         def retrieval_seq_only():   # random bf16 rows of the workload's shape, drawn on the GPU (timing only)
             g = torch.Generator(device="cuda").manual_seed(w.seed)
             mk = lambda h: torch.randn((w.batch, w.seq_len, h, w.head_dim), device="cuda", generator=g).to(torch.bfloat16)
@@ -90,8 +142,14 @@ def main() -> int:
             o_ = torch.empty_like(q_)
             return {"main": retrieval_seq_leg(sa, W, w, q_, k_, v_, o_),
                     "paper_point": retrieval_seq_leg(sa, W, w, q_, k_, v_, o_, tail=512, long_groups=4)}
+        def rope_only():
+            g = torch.Generator(device="cuda").manual_seed(w.seed)
+            mk = lambda h: torch.randn((w.batch, w.seq_len, h, w.head_dim), device="cuda", generator=g).to(torch.bfloat16)
+            return rope_leg(sa, W, w, mk(w.n_q_heads), mk(w.n_kv_heads))
         leg = {"backward": lambda: backward_leg(sa, W, w), "decode": lambda: decode_leg(sa, W),
-               "retrieve": lambda: retrieve_leg(sa, W), "retrieval_seq": retrieval_seq_only}[args.only]
+               "retrieve": lambda: retrieve_leg(sa, W), "retrieval_seq": retrieval_seq_only, "rope": rope_only,
+               "ceiling": lambda: ceiling_leg(sa, torch.zeros(1 << 28, dtype=torch.float32, device="cuda")),
+               "other_configs": lambda: other_configs_leg(sa, W)}[args.only]
         print(json.dumps({args.only: leg()}))
         return 0
     N, Hq, Hkv, D, S, T = w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim, w.seg_len, w.tail_len
@@ -130,21 +188,19 @@ def main() -> int:
             sa.seg_kv_past_evict(ctx, h, 0, stream)
         sa.seg_attn_decode(ctx, q1, k1, v1, o1, l1, stream)
 
-    if args.calibration_copy:  # known traffic: 1 GiB read + 1 GiB written by one elementwise kernel
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    if args.calibration_copy:
+        calibration_copy(torch)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     torch.cuda.reset_peak_memory_stats()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    with ClockSampler() as clock:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    gfx_mhz = clock.mean_mhz()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kern_ms = sum(a.elapsed_time(b) for a, b in zip(ev_k0, ev_k1)) / args.steps
     flops = 4 * D * visible_pairs(w)
@@ -164,8 +220,15 @@ def main() -> int:
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "kernel_ms": round(kern_ms, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "algorithmic_bytes": w.batch * (2 * N * Hq * D * 2 + 2 * N * Hkv * D * 2 + N * Hq * 4)},
+                     "kernel_ms": round(kern_ms, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, (None, None))[0],
+                     "traffic_range": MEASURED_TRAFFIC_BYTES.get(w.name, (None, None))[1],
+                     "algorithmic_bytes": w.batch * (2 * N * Hq * D * 2 + 2 * N * Hkv * D * 2 + N * Hq * 4),
+                     # the same fraction against the peak scaled to the shader clock the part held during
+                     # the timed steps (mean over the XCDs, sampled every few ms); None without amdsmi
+                     "sustained_gfx_mhz": None if gfx_mhz is None else round(gfx_mhz, 1),
+                     "frac_at_sustained_clock": None if gfx_mhz is None else
+                     round(achieved / (PEAK_BF16_TFLOPS * gfx_mhz / NOMINAL_GFX_MHZ), 4)},
         "memory": {"resident_kv_bytes_after_step": resident, "dense_causal_kv_bytes": dense_kv,
                    "ratio": round(dense_kv / resident, 3),
                    "torch_peak_allocated_bytes": int(torch.cuda.max_memory_allocated())},
@@ -180,8 +243,10 @@ def main() -> int:
         result["retrieval_seq_paper_point"] = retrieval_seq_leg(sa, W, w, q, k, v, out, tail=512, long_groups=4)
         result["ragged"] = ragged_leg(sa, W, w, q, k, v, out)
         result["rope"] = rope_leg(sa, W, w, q, k)
+        result["hbm_ceilings"] = ceiling_leg(sa, q)
         del q, k, v, out, lse
         torch.cuda.empty_cache()
+        result["other_configs"] = other_configs_leg(sa, W)
         result["backward"] = backward_leg(sa, W, w)
         result["decode"] = decode_leg(sa, W)
         result["retrieve"] = retrieve_leg(sa, W)
@@ -402,6 +467,63 @@ def rope_leg(sa, W, w, q, k):
     nbytes = 2 * (q.numel() + k.numel()) * 2
     return {"ms": round(ms, 4), "bytes": nbytes, "achieved_GBps": round(nbytes / ms / 1e6, 1),
             "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
+
+
+def ceiling_leg(sa, buf):
+    """What the part sustains for the access patterns of the HBM-bound kernels, with nothing else in
+    the kernel (segattn_bandwidth_probe on 1 GiB): a non-temporal read of every 16-byte piece (the
+    decode and retrieval scans) and an in-place read + write of every piece (seg_rope_apply).  An even
+    number of read-modify-write passes leaves the buffer as it was."""
+    import torch
+    nbytes = min(buf.numel() * buf.element_size(), 1 << 30)
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    res = {"bytes": nbytes}
+    for mode, name, factor in ((0, "read_GBps", 1), (1, "read_modify_write_GBps", 2)):
+        for _ in range(2):
+            sa.segattn_bandwidth_probe(buf, nbytes, mode, sink, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            sa.segattn_bandwidth_probe(buf, nbytes, mode, sink, st)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(factor * nbytes / (e0.elapsed_time(e1) / reps) / 1e6, 1)
+    return res
+
+
+def other_configs_leg(sa, W):
+    """The other prefill configurations, one seg_attn_fwd_seq launch each on their seeded inputs
+    (bf16 output), after enough launches that the clocks have come up (a 0.8 ms launch on an idle
+    part runs a fifth slower)."""
+    import numpy as np
+    import torch
+    out = {}
+    for name in ("c1_2k_mha", "c2_16k_gqa_outliers", "c3_32k_llama3_8b_layer"):
+        w = W.WORKLOADS[name]
+        q, k, v = [torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16) for x in W.prefill_inputs(w)]
+        o = torch.empty_like(q)
+        lse = torch.empty((w.batch, w.n_q_heads, w.seq_len), dtype=torch.float32, device="cuda")
+        cfg = sa.make_config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                             seg_len=w.seg_len, tail_len=w.tail_len, kv_policy=w.kv_policy)
+        st = torch.cuda.current_stream().cuda_stream
+        for _ in range(20):
+            sa.seg_attn_fwd_seq(cfg, q, k, v, w.seq_len, o, lse, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record()
+        for _ in range(reps):
+            sa.seg_attn_fwd_seq(cfg, q, k, v, w.seq_len, o, lse, st)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        flops = 4 * w.head_dim * visible_pairs(w)
+        out[name] = {"ms": round(ms, 4), "useful_flops": flops, "tflops_useful": round(flops / ms / 1e9, 1),
+                     "frac_of_bf16_mfma_peak": round(flops / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    return out
 
 
 def backward_leg(sa, W, w, batch=4):

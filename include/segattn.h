@@ -375,6 +375,14 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
                                const void *v_new, void *out, float *lse, void *stream);
 
 /* ---- misc ------------------------------------------------------------------------------- */
+/* Diagnostic for benchmarks: stream `bytes` of device memory at buf (16-byte aligned) with one of
+ * the two access patterns of the library's HBM-bound kernels and nothing else.  mode 0: every
+ * 16-byte piece read once, non-temporal (the decode and retrieval scans); sink: device, >= 4
+ * bytes, practically never written.  mode 1: every piece read and written back in place with two
+ * sign bits flipped (the in-place rotation of seg_rope_apply); two calls restore the buffer.
+ * Timing it gives the rate the part sustains for the pattern. */
+segattn_status segattn_bandwidth_probe(void *buf, size_t bytes, int32_t mode, void *sink, void *stream);
+
 const char *segattn_strerror(segattn_status st);
 /* Name and average device time bookkeeping are not kept by the library; the version string
  * names the kernels' target ISA, e.g. "segattn 0.1 gfx950". */

@@ -83,6 +83,7 @@ def lib() -> ctypes.CDLL:
             "segattn_cache_span": (ctypes.c_int, [vp, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(i64)]),
             "segattn_resident_bytes": (sz, [vp]),
             "seg_attn_decode": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
+            "segattn_bandwidth_probe": (ctypes.c_int, [vp, sz, i32, vp, vp]),
             "segattn_strerror": (ctypes.c_char_p, [ctypes.c_int]),
             "segattn_version": (ctypes.c_char_p, []),
         }
@@ -97,7 +98,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
            "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_seq_static", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_retrieve_seq_workspace_bytes", "seg_kv_retrieve_seq", "seg_attn_fwd_seq_retrieved_workspace_bytes", "seg_attn_fwd_seq_retrieved", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
-           "seg_attn_decode", "segattn_strerror", "segattn_version")
+           "seg_attn_decode", "segattn_bandwidth_probe", "segattn_strerror", "segattn_version")
 
 
 def _ptr(x) -> Optional[int]:
@@ -294,6 +295,10 @@ def segattn_cache_span(ctx: int, b: int, kv_head: int):
 
 def segattn_resident_bytes(ctx: int) -> int:
     return int(lib().segattn_resident_bytes(ctx))
+
+
+def segattn_bandwidth_probe(buf, nbytes: int, mode: int, sink, stream=None) -> None:
+    _check(lib().segattn_bandwidth_probe(_ptr(buf), nbytes, mode, _ptr(sink), _ptr(stream)), "segattn_bandwidth_probe")
 
 
 def seg_attn_decode(ctx: int, q, k_new, v_new, out, lse, stream=None) -> None:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsegattn.so")
 SOURCES = ("segattn_api.hip", "segattn_prefill_mfma.hip", "segattn_prefill_fp32.hip", "segattn_decode.hip", "segattn_decode_mfma.hip",
-           "segattn_cache.hip", "segattn_bwd_fp32.hip", "segattn_bwd_dq.hip", "segattn_bwd_mfma.hip", "segattn_rope.hip", "segattn_retrieve.hip")
+           "segattn_cache.hip", "segattn_bwd_fp32.hip", "segattn_bwd_dq.hip", "segattn_bwd_mfma.hip", "segattn_rope.hip", "segattn_retrieve.hip", "segattn_probe.hip")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept out of the generated code on purpose

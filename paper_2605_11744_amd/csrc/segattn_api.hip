@@ -931,6 +931,11 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
   return SEGATTN_OK;
 }
 
+segattn_status segattn_bandwidth_probe(void *buf, size_t bytes, int32_t mode, void *sink, void *stream) {
+  if (!buf || !sink || bytes < 16 || ((uintptr_t)buf % 16) || (mode != 0 && mode != 1)) return SEGATTN_EINVAL;
+  return hip_status(launch_probe(buf, (long long)bytes, mode, sink, (hipStream_t)stream));
+}
+
 const char *segattn_strerror(segattn_status st) {
   switch (st) {
     case SEGATTN_OK: return "ok";

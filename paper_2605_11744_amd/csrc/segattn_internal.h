@@ -401,5 +401,6 @@ hipError_t launch_bwd_fp32(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_dq(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st);
 int prefill_pair_stride(long long groups);
+hipError_t launch_probe(void *buf, long long bytes, int mode, void *sink, hipStream_t st);
 
 }  // namespace segattn

@@ -61,6 +61,7 @@ __global__ __launch_bounds__(256) void rope_apply_kernel(const Problem p, const 
 #pragma unroll
   for (int e = 0; e < 8; ++e) rope_sincos(pos, a.inv_freq[8 * li + e], sn[e], cs[e]);
   unsigned short *qrow = a.q + br * p.Hq * D + 8 * li;
+#pragma unroll 4
   for (int h = 0; h < p.Hq; ++h, qrow += D) {
     uint4 lo = *(const uint4 *)qrow, hi = *(const uint4 *)(qrow + D / 2);
     rope_rotate8(lo, hi, sn, cs);
@@ -68,6 +69,7 @@ __global__ __launch_bounds__(256) void rope_apply_kernel(const Problem p, const 
     *(uint4 *)(qrow + D / 2) = hi;
   }
   unsigned short *krow = a.k + br * p.Hkv * D + 8 * li;
+#pragma unroll 4
   for (int h = 0; h < p.Hkv; ++h, krow += D) {
     uint4 lo = *(const uint4 *)krow, hi = *(const uint4 *)(krow + D / 2);
     rope_rotate8(lo, hi, sn, cs);
