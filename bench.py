@@ -35,49 +35,40 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM-side bytes of one prefill_mfma_kernel launch on the 128K workload: FETCH_SIZE + WRITE_SIZE of
 # the counter runs summarised in profiles/prefill_mfma_c4_128k_hbm_traffic.txt (reads vary from run
-# to run with what the long key streams find in the last-level cache): median, and (min, max)
-MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": (8.73e9 + 1.09e9, (6.9e9 + 1.09e9, 8.73e9 + 1.09e9))}
+# to run with what the long key streams find in the last-level cache): median of the three FETCH_SIZE
+# runs, and (min, max) over their nine dispatches; earlier builds on other boxes measured 7.99e9 and 9.82e9
+MEASURED_TRAFFIC_BYTES = {"c4_128k_prefill": (9.20e9 + 1.09e9, (8.90e9 + 1.09e9, 9.50e9 + 1.09e9))}
 NOMINAL_GFX_MHZ = 2400.0       # the clock the published peaks are quoted at
 
 
-class ClockSampler:
-    """Samples the shader clock of the eight XCDs (amdsmi) from a host thread while a timed region
-    runs, so that a roofline fraction can also be stated against the clock the part actually held."""
+class ClockProbe:
+    """Shader clock held during a timed region, from the library's clock probe: one sleeping wave per
+    XCD, launched on a stream of its own just before the region, counts shader clocks against the
+    device's constant-rate wall clock for `seconds` (chosen a little shorter than the region)."""
 
-    def __init__(self, period_s=0.004):
-        self.period, self.samples, self._stop, self._thread, self._h = period_s, [], False, None, None
-        try:
-            import amdsmi
-            amdsmi.amdsmi_init()
-            self._smi, self._h = amdsmi, amdsmi.amdsmi_get_processor_handles()[0]
-        except Exception:
-            self._h = None
+    def __init__(self, sa, torch):
+        self.sa, self.started = sa, False
+        self.counts = torch.zeros(2 * sa.SEGATTN_CLOCK_PROBE_WAVES, dtype=torch.int64, device="cuda")
+        self.side = torch.cuda.Stream()
 
-    def _run(self):
-        while not self._stop:
-            try:
-                m = self._smi.amdsmi_get_gpu_metrics_info(self._h)
-                clks = [c for c in m.get("current_gfxclks", []) if isinstance(c, (int, float)) and 0 < c < 10000]
-                if clks:
-                    self.samples.append(sum(clks) / len(clks))
-            except Exception:
-                pass
-            time.sleep(self.period)
-
-    def __enter__(self):
-        if self._h is not None:
-            import threading
-            self._thread = threading.Thread(target=self._run, daemon=True)
-            self._thread.start()
-        return self
-
-    def __exit__(self, *exc):
-        self._stop = True
-        if self._thread is not None:
-            self._thread.join()
+    def start(self, seconds):
+        """Call with the device idle (the counts buffer is then cleared); returns at once."""
+        us = int(seconds * 1e6)
+        if 1000 <= us <= 10_000_000:
+            self.khz = self.sa.segattn_clock_probe(us, self.counts, self.side.cuda_stream)
+            self.started = True
 
     def mean_mhz(self):
-        return sum(self.samples) / len(self.samples) if self.samples else None
+        """Call after the device has been synchronized.  None if the probe did not run or its two
+        counters tick at the same rate (no separate shader-clock counter)."""
+        if not self.started:
+            return None
+        c = self.counts.cpu().numpy().reshape(-1, 2).astype(float)
+        mhz = [clk / tck * self.khz / 1e3 for clk, tck in c if tck > 0 and clk > 0]
+        if not mhz:
+            return None
+        m = sum(mhz) / len(mhz)
+        return m if 300.0 < m < 3000.0 and abs(m - self.khz / 1e3) > 1.0 else None
 
 
 def visible_pairs(w) -> int:
@@ -190,16 +181,21 @@ def main() -> int:
 
     if args.calibration_copy:
         calibration_copy(torch)
+    clock = ClockProbe(sa, torch)
+    tw = time.perf_counter()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    warm_s = (time.perf_counter() - tw) / max(args.warmup, 1)
     torch.cuda.reset_peak_memory_stats()
-    with ClockSampler() as clock:
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            step(i)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+    # the probe watches the first 70 % of the time the warm-up predicts for the timed steps, so it has
+    # ended before they have; without warm-up steps there is no prediction and no probe
+    clock.start(0.7 * warm_s * args.steps if args.warmup > 0 else 0.0)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
     gfx_mhz = clock.mean_mhz()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kern_ms = sum(a.elapsed_time(b) for a, b in zip(ev_k0, ev_k1)) / args.steps
@@ -225,7 +221,7 @@ def main() -> int:
                      "traffic_range": MEASURED_TRAFFIC_BYTES.get(w.name, (None, None))[1],
                      "algorithmic_bytes": w.batch * (2 * N * Hq * D * 2 + 2 * N * Hkv * D * 2 + N * Hq * 4),
                      # the same fraction against the peak scaled to the shader clock the part held during
-                     # the timed steps (mean over the XCDs, sampled every few ms); None without amdsmi
+                     # the timed steps (the library's clock probe, mean over the XCDs); None if the probe did not run
                      "sustained_gfx_mhz": None if gfx_mhz is None else round(gfx_mhz, 1),
                      "frac_at_sustained_clock": None if gfx_mhz is None else
                      round(achieved / (PEAK_BF16_TFLOPS * gfx_mhz / NOMINAL_GFX_MHZ), 4)},

@@ -383,6 +383,17 @@ segattn_status seg_attn_decode(segattn_ctx *ctx, const void *q, const void *k_ne
  * Timing it gives the rate the part sustains for the pattern. */
 segattn_status segattn_bandwidth_probe(void *buf, size_t bytes, int32_t mode, void *sink, void *stream);
 
+/* Diagnostic for benchmarks: the shader clock the part holds while other work runs.  Launches
+ * SEGATTN_CLOCK_PROBE_WAVES single-wave workgroups (one per XCD) on `stream`; each sleeps until
+ * `microseconds` (1 .. 10,000,000, else EINVAL) of the device's constant-rate wall clock have
+ * passed, then stores two uint64 into counts (device, 2 x SEGATTN_CLOCK_PROBE_WAVES uint64,
+ * 8-byte aligned): the shader clocks and the wall-clock ticks it saw.  *wall_clock_khz (host,
+ * required) receives the wall clock's rate: clock [MHz] = clocks / ticks * wall_clock_khz / 1000.
+ * Launch it on a stream of its own just before the work to be observed; it occupies one wave
+ * slot with a handful of registers on eight compute units and ends by itself. */
+#define SEGATTN_CLOCK_PROBE_WAVES 8
+segattn_status segattn_clock_probe(uint32_t microseconds, uint64_t *counts, int32_t *wall_clock_khz, void *stream);
+
 const char *segattn_strerror(segattn_status st);
 /* Name and average device time bookkeeping are not kept by the library; the version string
  * names the kernels' target ISA, e.g. "segattn 0.1 gfx950". */

@@ -84,6 +84,7 @@ def lib() -> ctypes.CDLL:
             "segattn_resident_bytes": (sz, [vp]),
             "seg_attn_decode": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
             "segattn_bandwidth_probe": (ctypes.c_int, [vp, sz, i32, vp, vp]),
+            "segattn_clock_probe": (ctypes.c_int, [ctypes.c_uint32, vp, ctypes.POINTER(i32), vp]),
             "segattn_strerror": (ctypes.c_char_p, [ctypes.c_int]),
             "segattn_version": (ctypes.c_char_p, []),
         }
@@ -98,7 +99,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
            "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_seq_static", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_retrieve_seq_workspace_bytes", "seg_kv_retrieve_seq", "seg_attn_fwd_seq_retrieved_workspace_bytes", "seg_attn_fwd_seq_retrieved", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
-           "seg_attn_decode", "segattn_bandwidth_probe", "segattn_strerror", "segattn_version")
+           "seg_attn_decode", "segattn_bandwidth_probe", "segattn_clock_probe", "segattn_strerror", "segattn_version")
 
 
 def _ptr(x) -> Optional[int]:
@@ -299,6 +300,16 @@ def segattn_resident_bytes(ctx: int) -> int:
 
 def segattn_bandwidth_probe(buf, nbytes: int, mode: int, sink, stream=None) -> None:
     _check(lib().segattn_bandwidth_probe(_ptr(buf), nbytes, mode, _ptr(sink), _ptr(stream)), "segattn_bandwidth_probe")
+
+
+SEGATTN_CLOCK_PROBE_WAVES = 8
+
+
+def segattn_clock_probe(microseconds: int, counts, stream=None) -> int:
+    """Launches the clock probe; returns the wall clock's rate in kHz.  counts: device, 16 uint64."""
+    khz = ctypes.c_int32(0)
+    _check(lib().segattn_clock_probe(microseconds, _ptr(counts), ctypes.byref(khz), _ptr(stream)), "segattn_clock_probe")
+    return int(khz.value)
 
 
 def seg_attn_decode(ctx: int, q, k_new, v_new, out, lse, stream=None) -> None:

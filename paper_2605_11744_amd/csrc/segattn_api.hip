@@ -936,6 +936,19 @@ segattn_status segattn_bandwidth_probe(void *buf, size_t bytes, int32_t mode, vo
   return hip_status(launch_probe(buf, (long long)bytes, mode, sink, (hipStream_t)stream));
 }
 
+segattn_status segattn_clock_probe(uint32_t microseconds, uint64_t *counts, int32_t *wall_clock_khz, void *stream) {
+  static_assert(SEGATTN_CLOCK_PROBE_WAVES == kClockProbeWaves, "header and kernel disagree");
+  if (!counts || ((uintptr_t)counts % 8) || !wall_clock_khz || microseconds == 0 || microseconds > 10000000u)
+    return SEGATTN_EINVAL;
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess ||
+      khz <= 0)
+    return SEGATTN_EHIP;
+  *wall_clock_khz = khz;
+  const unsigned long long ticks = (unsigned long long)microseconds * (unsigned long long)khz / 1000ull;
+  return hip_status(launch_clock_probe(ticks > 0 ? ticks : 1, (unsigned long long *)counts, (hipStream_t)stream));
+}
+
 const char *segattn_strerror(segattn_status st) {
   switch (st) {
     case SEGATTN_OK: return "ok";

@@ -402,5 +402,7 @@ hipError_t launch_bwd_dq(const Problem &p, const BwdArgs &a, hipStream_t st);
 hipError_t launch_bwd_mfma(const Problem &p, const BwdArgs &a, hipStream_t st);
 int prefill_pair_stride(long long groups);
 hipError_t launch_probe(void *buf, long long bytes, int mode, void *sink, hipStream_t st);
+constexpr int kClockProbeWaves = 8;  // one per XCD
+hipError_t launch_clock_probe(unsigned long long ticks, unsigned long long *out, hipStream_t st);
 
 }  // namespace segattn

@@ -4,6 +4,8 @@
 //   mode 0  read every 16-byte piece once (non-temporal, as the decode and retrieval scans read
 //           their K/V rows); a checksum per workgroup keeps the loads alive
 //   mode 1  read every 16-byte piece and write it back in place (as the in-place rotation does)
+// and a clock probe: one sleeping wave per XCD that counts shader clocks against the constant-rate
+// wall clock while other kernels run, which gives the clock the part holds under their load.
 #include "segattn_internal.h"
 
 namespace segattn {
@@ -44,6 +46,29 @@ __global__ __launch_bounds__(256) void probe_rmw_kernel(u32x4 *buf, long long pi
       buf[at] = x[i];
     }
   }
+}
+
+// One wave per workgroup, eight workgroups (the dispatcher deals them to the eight XCDs in turn).
+// Each sleeps until `ticks` of the wall clock have passed, a bound every wave reaches, and then
+// stores the shader clocks and wall ticks it saw.
+__global__ __launch_bounds__(64) void clock_probe_kernel(unsigned long long ticks, unsigned long long *out) {
+  const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+  const unsigned long long c0 = __builtin_readcyclecounter();
+  unsigned long long t;
+  do {
+    __builtin_amdgcn_s_sleep(127);
+    t = __builtin_amdgcn_s_memrealtime();
+  } while (t - t0 < ticks);
+  const unsigned long long c1 = __builtin_readcyclecounter();
+  if (threadIdx.x == 0) {
+    out[2 * blockIdx.x] = c1 - c0;
+    out[2 * blockIdx.x + 1] = t - t0;
+  }
+}
+
+hipError_t launch_clock_probe(unsigned long long ticks, unsigned long long *out, hipStream_t st) {
+  hipLaunchKernelGGL(clock_probe_kernel, dim3(kClockProbeWaves), dim3(64), 0, st, ticks, out);
+  return hipGetLastError();
 }
 
 hipError_t launch_probe(void *buf, long long bytes, int mode, void *sink, hipStream_t st) {

@@ -144,6 +144,19 @@ def test_fwd_seq_validates_before_launching():
     assert sa.strerror(sa.SEGATTN_ECAPACITY).startswith("past pool")
 
 
+def test_probes_validate_before_touching_a_device():
+    with pytest.raises(sa.SegattnError) as e:
+        sa.segattn_bandwidth_probe(4096, 1 << 20, 2, 4096)          # no such mode
+    assert e.value.status == sa.SEGATTN_EINVAL
+    with pytest.raises(sa.SegattnError) as e:
+        sa.segattn_bandwidth_probe(4096 + 8, 1 << 20, 0, 4096)      # misaligned
+    assert e.value.status == sa.SEGATTN_EINVAL
+    for us, counts in ((0, 4096), (10_000_001, 4096), (1000, 0), (1000, 4096 + 4)):
+        with pytest.raises(sa.SegattnError) as e:
+            sa.segattn_clock_probe(us, counts)
+        assert e.value.status == sa.SEGATTN_EINVAL
+
+
 def test_layer_policy_follows_the_head_and_layer_sets():
     """Sec. 3.4: local heads carry the tail in every layer; long-range heads read the past in the
     layers of L_long and only their own segment elsewhere."""
