@@ -344,6 +344,7 @@ static hipError_t launch_dq(const Problem &p, const BwdArgs &a, hipStream_t st) 
   const long long grid_q = (long long)p.B * p.Hkv * (p.g / hs) * pa.n_seg * pa.q_blocks_per_seg;
   if (grid_q <= 0 || grid_q > 0x7fffffffLL) return hipErrorInvalidValue;
   pa.grid_items = (int)grid_q;
+  prepare_resolve_divs(p, pa, hs, grid_q);
   // resident grid + item queues where every resident workgroup would get more than two items
   const void *kern = hs == 4 ? (const void *)bwd_dq_kernel<D, 4> : hs == 2 ? (const void *)bwd_dq_kernel<D, 2>
                                                                             : (const void *)bwd_dq_kernel<D, 1>;

@@ -73,6 +73,36 @@ __host__ __device__ inline unsigned long long ws_header_bytes(const Problem &p) 
 // Arguments of the prefill kernels.  SEQ mode (cache == nullptr): q/k/v hold n_rows = N tokens
 // per sequence and every segment is processed in this launch.  CTX mode: q/k/v hold the
 // n_rows = m new rows of the open segment and the prefix comes from the cache arena.
+// n / d for 0 <= n < 2^31 and a divisor d >= 1 that is fixed for a launch: the host prepares
+// mul = ceil(2^shift / d) with shift = 31 + ceil(log2 d); then floor(n * mul / 2^shift) is exact
+// (n * (mul * d - 2^shift) < 2^31 * 2^ceil(log2 d) = 2^shift) and mul fits 32 bits.  A scalar
+// multiply-high and a shift in place of the instruction sequence of an integer division.
+struct FastDiv {
+  unsigned mul, shift, d;
+};
+inline FastDiv fast_div_by(long long d) {
+  FastDiv f{0u, 0u, 0u};
+  if (d < 1 || d >= (1ll << 31)) return f;  // d == 0 marks an unusable entry
+  unsigned s = 0;
+  while ((1ull << s) < (unsigned long long)d) ++s;
+  const unsigned shift = 31 + s;
+  const unsigned long long mul = ((1ull << shift) + (unsigned long long)d - 1) / (unsigned long long)d;
+  f.mul = (unsigned)mul;
+  f.shift = shift;
+  f.d = (unsigned)d;
+  return f;
+}
+__host__ __device__ inline int fast_div(int n, const FastDiv &f) {
+  return (int)(((unsigned long long)(unsigned)n * f.mul) >> f.shift);
+}
+__host__ __device__ inline int fast_mod(int n, const FastDiv &f) { return n - fast_div(n, f) * (int)f.d; }
+// The divisors of resolve() (segattn_work.h), prepared by the launcher; `ok` == 0: resolve()
+// divides as written.
+struct ResolveDivs {
+  int ok;
+  FastDiv per, parts, nqb, nhs, n_first, n_other, batch, per_sub, sub, groups;
+};
+
 struct PrefillArgs {
   const unsigned short *q, *k, *v;
   void *out;
@@ -103,7 +133,40 @@ struct PrefillArgs {
   // ret_k / ret_v + (((b * n_seg + segment) * n_past + past index) * R) * D.  nullptr: whole history.
   const unsigned short *ret_k, *ret_v;
   int ret_R;
+  ResolveDivs dv;
 };
+// Fills a.dv for a launch whose fields resolve() reads are final (q_blocks_per_seg, n_seg, parts,
+// sub_groups, pair_stride, grid_items); heads_per_wg as passed to resolve().
+inline void prepare_resolve_divs(const Problem &p, PrefillArgs &a, int heads_per_wg, long long grid) {
+  ResolveDivs &dv = a.dv;
+  dv.ok = 0;
+  const int nhs = p.g / heads_per_wg;
+  const int nqb = a.q_blocks_per_seg;
+  const int n_first = ((a.cache != nullptr && a.geom.ret_cap > 0) || a.ret_k != nullptr) ? 0 : p.n_past;
+  const int n_other = p.Hkv - n_first;
+  const int parts = (a.cache != nullptr && a.parts > 1) ? a.parts : 1;
+  const long long past_items = (long long)p.B * n_first * nhs * a.n_seg * nqb * parts;
+  const long long items = grid - past_items;
+  const int d = a.sub_groups > 1 ? a.sub_groups : 1;
+  if (nqb < 1 || nhs < 1 || grid >= (1ll << 31) || nqb % d != 0) return;
+  const long long groups = items / nqb;
+  const long long stride = a.pair_stride > 0 ? a.pair_stride : 1;
+  if (groups > 0 && (groups - 1) * stride >= (1ll << 31)) return;  // the shuffled group index must fit
+  dv.per = fast_div_by((long long)p.B * (n_first > 0 ? n_first : 1) * nhs * parts);
+  dv.parts = fast_div_by(parts);
+  dv.nqb = fast_div_by(nqb);
+  dv.nhs = fast_div_by(nhs);
+  dv.n_first = fast_div_by(n_first > 0 ? n_first : 1);
+  dv.n_other = fast_div_by(n_other > 0 ? n_other : 1);
+  dv.batch = fast_div_by(p.B);
+  dv.per_sub = fast_div_by(nqb / d);
+  dv.sub = fast_div_by(d);
+  dv.groups = fast_div_by(groups > 0 ? groups : 1);
+  const FastDiv *all[] = {&dv.per, &dv.parts, &dv.nqb, &dv.nhs, &dv.n_first, &dv.n_other, &dv.batch, &dv.per_sub, &dv.sub, &dv.groups};
+  for (const FastDiv *f : all)
+    if (f->d == 0) return;
+  dv.ok = 1;
+}
 constexpr int kQueueStride = 32;  // unsigned words between two queue counters (128 bytes)
 // Host side of the item queues (segattn_prefill_mfma.hip): the counters of this (device, stream),
 // or nullptr where the launch has to run one workgroup per item (stream under capture, no set

@@ -777,7 +777,10 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
 template <int D, int HS, int QB, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(const Problem p_arg, const PrefillArgs a_arg) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  __shared__ int claim;
+  // take_item's hand-over word lives at the start of the ring, which is idle between two items (a
+  // static variable of its own would be the four bytes by which two four-wave workgroups, 80 KB of
+  // ring each, no longer fit the 160 KB of a CU)
+  int *const claim = (int *)smem;
   constexpr unsigned kArgsAt = (sizeof(Problem) + alignof(PrefillArgs) - 1) / alignof(PrefillArgs) * alignof(PrefillArgs);
   unsigned ticket = 0;  // thread 0: position drawn from the own queue for this round
   bool drawn = false;   // ... by the previous round already
@@ -795,7 +798,7 @@ __global__ __launch_bounds__(64 * NW, 8 / (NW * QB)) void prefill_mfma_kernel(co
     const bool queued = a.queue != nullptr;
     unsigned *const own = queued ? a.queue + kQueueStride * ((int)blockIdx.x & 7) : nullptr;
     if (queued) {
-      bid = take_item(a.queue, a.grid_items, drawn, ticket, &claim);
+      bid = take_item(a.queue, a.grid_items, drawn, ticket, claim);
       if (bid < 0) return;
     }
     ticket = prefill_mfma_item<D, HS, QB, NW>(p, a, bid, smem, own);
@@ -1051,6 +1054,7 @@ hipError_t launch_prefill(const Problem &p, const PrefillArgs &a_in, hipStream_t
     a.part_out = (float *)(a.cache + a.geom.part_off);
     a.part_lse = a.part_out + (long long)p.B * a.parts * a.n_rows * p.n_past * p.g * p.D;
   }
+  prepare_resolve_divs(p, a, hs, grid);
   if (fp32) return launch_prefill_fp32(p, a, grid, st);
   hipError_t e;
   if (p.D == 128) {

@@ -96,7 +96,50 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
   const int parts = (a.cache != nullptr && a.parts > 1) ? a.parts : 1;
   const long long past_items = (long long)p.B * n_first * nhs * a.n_seg * nqb * parts;
   int seg, qblk, hidx, b, hs, part = 0;
-  if (bid < past_items) {
+  if (a.dv.ok) {
+    // the same arithmetic as the branches below with the launch's divisors prepared by the host
+    // (every quantity is below 2^31 then): a few scalar multiplies instead of a dozen divisions
+    const ResolveDivs &dv = a.dv;
+    if (bid < past_items) {
+      const int row = fast_div(bid, dv.per);
+      const int gq = a.n_seg * nqb - 1 - row;
+      int rest = bid - row * (int)dv.per.d;
+      if (a.cu_seqlens) rest = fast_mod(rest + row, dv.per);
+      part = fast_mod(rest, dv.parts);
+      rest = fast_div(rest, dv.parts);
+      seg = fast_div(gq, dv.nqb);
+      qblk = gq - seg * nqb;
+      hs = fast_mod(rest, dv.nhs);
+      rest = fast_div(rest, dv.nhs);
+      b = fast_div(rest, dv.n_first);
+      hidx = rest - b * (int)dv.n_first.d;
+    } else {
+      const int pi = (int)past_items;
+      const int items = (a.grid_items > 0 ? a.grid_items : (int)gridDim.x) - pi;
+      const int x = bid & 7;
+      int start = 0, first = 0;
+#pragma unroll
+      for (int xx = 0; xx < 8; ++xx) {
+        const int o = (xx - pi) & 7;
+        const int cnt = o < items ? (items - o + 7) >> 3 : 0;
+        if (xx < x) start += cnt;
+        if (xx == x) first = pi + o;
+      }
+      const int L = start + ((bid - first) >> 3);
+      const int d = (int)dv.sub.d;
+      const int sg = fast_div(L, dv.per_sub);
+      const int grp = fast_div(sg, dv.sub);
+      qblk = nqb - 1 - ((sg - grp * d) + d * (L - sg * (int)dv.per_sub.d));
+      const long long shuffled = (long long)grp * (a.pair_stride > 0 ? a.pair_stride : 1);  // < 2^31 (host check)
+      int rest = fast_mod((int)shuffled, dv.groups);
+      hs = fast_mod(rest, dv.nhs);
+      rest = fast_div(rest, dv.nhs);
+      const int r2 = fast_div(rest, dv.n_other);
+      hidx = n_first + (rest - r2 * (int)dv.n_other.d);
+      seg = fast_div(r2, dv.batch);
+      b = r2 - seg * (int)dv.batch.d;
+    }
+  } else if (bid < past_items) {
     const int per = p.B * n_first * nhs * parts;
     const int gq = a.n_seg * nqb - 1 - bid / per;
     int rest = bid % per;
