@@ -1,6 +1,7 @@
 // Decode split kernel on the matrix cores (the bf16 path of seg_attn_decode).
 //
-// The g query heads of a GQA group are the columns of one 32-column operand (8 per pass): per tile
+// The g query heads of a GQA group are the columns of one 32-column operand (16 per pass: what the
+// merge area inside the tiles holds; a group of up to 16 heads streams its K/V rows once): per tile
 // of 32 key rows a wave forms
 //   S^T[key][head] = K_tile . Q^T       v_mfma_f32_32x32x16_bf16, A = K rows, B = Q^T (registers)
 //   P = exp2(S^T c - m c)               online softmax per head (lane = head)
@@ -27,7 +28,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
 
 constexpr int kDecTile = 32;   // key rows per tile
-constexpr int kDecHeads = 8;   // query heads per pass (columns in use of the 32-column operand)
+constexpr int kDecHeads = 16;  // query heads per pass (columns in use of the 32-column operand)
 
 __device__ inline float dec_half_max(float x) {  // max over lanes l and l^32
   const int xi = __float_as_int(x);
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma_kernel(const Problem
     // ---- this window's partial: the four waves meet in LDS (over the tiles: everyone is done)
     __syncthreads();
     float *mg = (float *)&tiles[0][0];  // [wave][head][D + 2]: acc, then m, l
-    if (col < kDecHeads) {
+    if (col < live) {
       float *dst = mg + ((long long)wave * kDecHeads + col) * (D + 2);
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
@@ -222,9 +223,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma_kernel(const Problem
       }
     }
     __syncthreads();
-    for (int idx = tid; idx < kDecHeads * D / 4; idx += 256) {
+    for (int idx = tid; idx < live * (D / 4); idx += 256) {
       const int h = idx / (D / 4), d = (idx % (D / 4)) * 4;
-      if (h >= live) continue;
       float mx = -INFINITY;
 #pragma unroll
       for (int wv = 0; wv < 4; ++wv) mx = fmaxf(mx, mg[((long long)wv * kDecHeads + h) * (D + 2) + D]);

@@ -136,13 +136,14 @@ def test_decode_ragged_batch_from_restored_cache():
 @pytest.mark.parametrize("n_q_heads,head_dim,fp32_check", [(16, 128, False), (8, 128, False), (4, 64, False),
                                                            (32, 64, False), (32, 128, False), (12, 128, False),
                                                            (16, 128, True), (32, 128, True), (20, 128, False),
-                                                           (28, 64, False), (48, 128, False), (28, 128, True)])
+                                                           (28, 64, False), (48, 128, False), (28, 128, True),
+                                                           (64, 128, False), (64, 64, False), (96, 128, False)])
 def test_decode_slices_cut_windows_anywhere(n_q_heads, head_dim, fp32_check):
     """Windows of 1 to ~2800 rows (about 17K rows in all): the split kernel's equal slices of 512
     rows begin and end inside windows, cover several short windows at once, and a long window
-    gets partials from several workgroups; GQA group sizes 1, 2, 3, 4, 5, 7, 8 and 12 (the split
-    kernel takes 1, 2, 4 or 8 heads per pass; a group that does not fill its last pass computes
-    surplus heads and drops them)."""
+    gets partials from several workgroups; GQA group sizes 1, 2, 3, 4, 5, 7, 8, 12, 16 and 24 (the
+    matrix-core split kernel takes up to 16 heads per pass, the fp32 one 1, 2, 4 or 8; a group that
+    does not fill its last pass computes surplus heads and drops them)."""
     S, T = 256, 100
     w = W.Workload("dec_slices", 221, 5, 0, n_q_heads, 4, head_dim, S, T, (1, 3, 0, 2), decode=True,
                    max_context=S * 12)
