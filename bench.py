@@ -102,8 +102,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode and streaming legs")
     ap.add_argument("--no-clock-probe", action="store_true",
-                    help="do not run the clock probe beside the timed steps (counter collection runs one kernel "
-                         "at a time: the probe would then sleep alone and the steps would wait for it)")
+                    help="run neither the clock probe beside the timed steps nor the matrix-pipe probe after them "
+                         "(counter collection runs one kernel at a time: the clock probe would sleep alone and "
+                         "the steps would wait for it)")
     ap.add_argument("--only", choices=("backward", "decode", "retrieve", "retrieval_seq", "rope", "ceiling", "other_configs"),
                     help="profiling aid: run just this leg (none of them needs the 128K inputs) and print it alone")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -208,6 +209,8 @@ def main() -> int:
     achieved = flops / (kern_ms * 1e-3) / 1e12
     resident = sa.segattn_resident_bytes(ctx)
     dense_kv = w.batch * Hkv * (N + 1) * D * 2 * 2
+    # what the matrix pipes alone reach on this part with random operands (it is power-limited)
+    pipes = None if args.no_clock_probe else mfma_probe(sa, torch, 0)
 
     result = {
         "metric": "segmented-attn prefill TFLOP/s (useful FLOPs) + % bf16 MFMA peak at 128K",
@@ -228,7 +231,11 @@ def main() -> int:
                      # the timed steps (the library's clock probe, mean over the XCDs); None if the probe did not run
                      "sustained_gfx_mhz": None if gfx_mhz is None else round(gfx_mhz, 1),
                      "frac_at_sustained_clock": None if gfx_mhz is None else
-                     round(achieved / (PEAK_BF16_TFLOPS * gfx_mhz / NOMINAL_GFX_MHZ), 4)},
+                     round(achieved / (PEAK_BF16_TFLOPS * gfx_mhz / NOMINAL_GFX_MHZ), 4),
+                     # the matrix pipes alone, random operands, registers only: rate, clock, and this
+                     # kernel as a fraction of that rate
+                     "mfma_probe": pipes,
+                     "frac_of_mfma_probe": None if pipes is None else round(achieved / pipes["tflops"], 4)},
         "memory": {"resident_kv_bytes_after_step": resident, "dense_causal_kv_bytes": dense_kv,
                    "ratio": round(dense_kv / resident, 3),
                    "torch_peak_allocated_bytes": int(torch.cuda.max_memory_allocated())},
@@ -470,8 +477,8 @@ def rope_leg(sa, W, w, q, k):
 
 
 def ceiling_leg(sa, buf):
-    """What the part sustains for the access patterns of the HBM-bound kernels, with nothing else in
-    the kernel (segattn_bandwidth_probe on 1 GiB): a non-temporal read of every 16-byte piece (the
+    """What the part sustains with nothing else in the kernel.  For the access patterns of the HBM-bound
+    kernels (segattn_bandwidth_probe on 1 GiB): a non-temporal read of every 16-byte piece (the
     decode and retrieval scans) and an in-place read + write of every piece (seg_rope_apply).  An even
     number of read-modify-write passes leaves the buffer as it was."""
     import torch
@@ -491,7 +498,41 @@ def ceiling_leg(sa, buf):
         e1.record()
         torch.cuda.synchronize()
         res[name] = round(factor * nbytes / (e0.elapsed_time(e1) / reps) / 1e6, 1)
+    res["mfma_random_operands"] = mfma_probe(sa, torch, 0)
+    res["mfma_constant_operands"] = mfma_probe(sa, torch, 1)
     return res
+
+
+def mfma_probe(sa, torch, operands):
+    """The matrix pipes with nothing else busy (segattn_mfma_probe: eight independent chains of 32x32x16
+    bf16 products per wave, registers only), launches about as long as the 128K prefill, with the clock
+    probe beside them: the dense rate and the clock the part holds for it.  operands 0: random values
+    (the switching activity of real data), 1: one constant (the part then draws less power and holds a
+    higher clock: the published peak is a figure of the second kind)."""
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    iters = 120_000
+    flops = sa.segattn_mfma_probe(iters, sink, st, operands)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    sa.segattn_mfma_probe(iters, sink, st, operands)
+    e1.record()
+    torch.cuda.synchronize()
+    one_ms = e0.elapsed_time(e1)
+    clock = ClockProbe(sa, torch)
+    torch.cuda.synchronize()
+    reps = 3
+    clock.start(0.7 * reps * one_ms * 1e-3)
+    e0.record()
+    for _ in range(reps):
+        sa.segattn_mfma_probe(iters, sink, st, operands)
+    e1.record()
+    torch.cuda.synchronize()
+    tflops = flops / (e0.elapsed_time(e1) / reps * 1e-3) / 1e12
+    mhz = clock.mean_mhz()
+    return {"tflops": round(tflops, 1), "ms_per_launch": round(e0.elapsed_time(e1) / reps, 3),
+            "gfx_mhz": None if mhz is None else round(mhz, 1), "frac_of_published_peak": round(tflops / PEAK_BF16_TFLOPS, 4)}
 
 
 def other_configs_leg(sa, W):

@@ -394,6 +394,17 @@ segattn_status segattn_bandwidth_probe(void *buf, size_t bytes, int32_t mode, vo
 #define SEGATTN_CLOCK_PROBE_WAVES 8
 segattn_status segattn_clock_probe(uint32_t microseconds, uint64_t *counts, int32_t *wall_clock_khz, void *stream);
 
+/* Diagnostic for benchmarks: the dense bf16 rate of the matrix pipes with nothing else busy.
+ * Launches two 256-thread workgroups per compute unit on `stream`; every wave runs `iterations`
+ * (1 .. 10,000,000, else EINVAL) rounds of eight independent 32x32x16 bf16 products from
+ * registers, no memory access in the loop.  operands = 0: pseudo-random values in [-1, 1), a
+ * different one in every lane and register (the switching activity of real data); 1: one constant
+ * everywhere (almost no switching: the part draws less power and holds a higher clock).  *flops
+ * (host, required) receives the floating-point operations of the launch; sink: device, >= 4
+ * bytes, practically never written.  Timing the launch gives the rate; with segattn_clock_probe
+ * beside it, the clock the part holds for it. */
+segattn_status segattn_mfma_probe(int32_t iterations, int32_t operands, void *sink, int64_t *flops, void *stream);
+
 const char *segattn_strerror(segattn_status st);
 /* Name and average device time bookkeeping are not kept by the library; the version string
  * names the kernels' target ISA, e.g. "segattn 0.1 gfx950". */

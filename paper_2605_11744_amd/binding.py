@@ -85,6 +85,7 @@ def lib() -> ctypes.CDLL:
             "seg_attn_decode": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp]),
             "segattn_bandwidth_probe": (ctypes.c_int, [vp, sz, i32, vp, vp]),
             "segattn_clock_probe": (ctypes.c_int, [ctypes.c_uint32, vp, ctypes.POINTER(i32), vp]),
+            "segattn_mfma_probe": (ctypes.c_int, [i32, i32, vp, ctypes.POINTER(i64), vp]),
             "segattn_strerror": (ctypes.c_char_p, [ctypes.c_int]),
             "segattn_version": (ctypes.c_char_p, []),
         }
@@ -99,7 +100,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("segattn_cache_bytes", "segattn_create", "segattn_destroy", "segattn_reset", "seg_attn_fwd",
            "seg_attn_fwd_seq", "seg_attn_fwd_varlen", "segattn_layer_policy", "seg_rope_apply", "seg_attn_bwd_workspace_bytes", "seg_attn_bwd_seq", "seg_attn_bwd_seq_static", "seg_attn_bwd_varlen_workspace_bytes", "seg_attn_bwd_varlen", "seg_kv_commit", "seg_kv_commit_seq", "seg_kv_past_append", "seg_kv_past_select", "seg_kv_retrieve_workspace_bytes", "seg_kv_retrieve", "seg_kv_retrieve_seq_workspace_bytes", "seg_kv_retrieve_seq", "seg_attn_fwd_seq_retrieved_workspace_bytes", "seg_attn_fwd_seq_retrieved", "seg_kv_past_evict", "seg_kv_past_keep_recent",
            "seg_kv_lengths", "seg_kv_set_lengths", "segattn_cache_span", "segattn_resident_bytes",
-           "seg_attn_decode", "segattn_bandwidth_probe", "segattn_clock_probe", "segattn_strerror", "segattn_version")
+           "seg_attn_decode", "segattn_bandwidth_probe", "segattn_clock_probe", "segattn_mfma_probe", "segattn_strerror", "segattn_version")
 
 
 def _ptr(x) -> Optional[int]:
@@ -310,6 +311,15 @@ def segattn_clock_probe(microseconds: int, counts, stream=None) -> int:
     khz = ctypes.c_int32(0)
     _check(lib().segattn_clock_probe(microseconds, _ptr(counts), ctypes.byref(khz), _ptr(stream)), "segattn_clock_probe")
     return int(khz.value)
+
+
+def segattn_mfma_probe(iterations: int, sink, stream=None, operands: int = 0) -> int:
+    """Launches the matrix-pipe probe (operands 0: random values, 1: one constant); returns the
+    floating-point operations of the launch."""
+    flops = ctypes.c_int64(0)
+    _check(lib().segattn_mfma_probe(iterations, operands, _ptr(sink), ctypes.byref(flops), _ptr(stream)),
+           "segattn_mfma_probe")
+    return int(flops.value)
 
 
 def seg_attn_decode(ctx: int, q, k_new, v_new, out, lse, stream=None) -> None:

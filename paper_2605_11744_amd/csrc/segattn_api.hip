@@ -949,6 +949,18 @@ segattn_status segattn_clock_probe(uint32_t microseconds, uint64_t *counts, int3
   return hip_status(launch_clock_probe(ticks > 0 ? ticks : 1, (unsigned long long *)counts, (hipStream_t)stream));
 }
 
+segattn_status segattn_mfma_probe(int32_t iterations, int32_t operands, void *sink, int64_t *flops, void *stream) {
+  if (!sink || ((uintptr_t)sink % 4) || !flops || iterations < 1 || iterations > 10000000 || (operands != 0 && operands != 1))
+    return SEGATTN_EINVAL;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return SEGATTN_EHIP;
+  const int workgroups = 2 * cus;
+  *flops = (int64_t)workgroups * 4 * (int64_t)iterations * kMfmaProbeFlopsPerWaveIter;
+  return hip_status(launch_mfma_probe(iterations, operands, workgroups, (float *)sink, (hipStream_t)stream));
+}
+
 const char *segattn_strerror(segattn_status st) {
   switch (st) {
     case SEGATTN_OK: return "ok";

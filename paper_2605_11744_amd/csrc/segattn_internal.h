@@ -467,5 +467,7 @@ int prefill_pair_stride(long long groups);
 hipError_t launch_probe(void *buf, long long bytes, int mode, void *sink, hipStream_t st);
 constexpr int kClockProbeWaves = 8;  // one per XCD
 hipError_t launch_clock_probe(unsigned long long ticks, unsigned long long *out, hipStream_t st);
+constexpr int kMfmaProbeFlopsPerWaveIter = 8 * 2 * 32 * 32 * 16;  // eight 32x32x16 products
+hipError_t launch_mfma_probe(int iters, int quiet, int workgroups, float *sink, hipStream_t st);
 
 }  // namespace segattn

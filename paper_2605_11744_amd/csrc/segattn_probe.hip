@@ -71,6 +71,60 @@ hipError_t launch_clock_probe(unsigned long long ticks, unsigned long long *out,
   return hipGetLastError();
 }
 
+// Matrix-pipe ceiling: every wave runs eight independent accumulation chains of
+// v_mfma_f32_32x32x16_bf16 from registers and touches no memory in the loop, so the launch shows
+// the dense bf16 rate the part reaches (and, with the clock probe beside it, the clock it holds)
+// when nothing but the matrix pipes is busy.  The part is power-limited: with random operands it
+// holds a much lower clock than with constant ones.
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kMfmaProbeChains = 8;
+// distinct (A, B) operand pairs the chains rotate through: with one pair every product repeats, with
+// eight the operand fetch, not the pipe, sets the pace (85 % even with constant operands); four keep
+// the pipes 99 % busy
+constexpr int kMfmaProbeOperandSets = 4;
+template <int SETS>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int quiet, unsigned seed, float *sink) {
+  // operands: pseudo-random bf16 in [-1, 1), different for every lane, register and chain; with
+  // `quiet` every operand element is the same constant instead (such products switch almost no
+  // wires, draw far less power and run at a higher clock than products of real data)
+  unsigned h = seed ^ (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
+  auto next = [&]() {
+    h = h * 1664525u + 1013904223u;
+    return quiet ? (__bf16)0.00390625f : (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f);
+  };
+  probe_bf16x8 a[SETS], b[SETS];
+#pragma unroll
+  for (int c = 0; c < SETS; ++c)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[c][i] = next();
+      b[c][i] = next();
+    }
+  probe_f32x16 acc[kMfmaProbeChains];
+#pragma unroll
+  for (int c = 0; c < kMfmaProbeChains; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < kMfmaProbeChains; ++c)
+      acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c % SETS], b[c % SETS], acc[c], 0, 0, 0);
+  }
+  float total = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMfmaProbeChains; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) total += acc[c][r];
+  if (total == -1.2345678e30f) sink[0] = total;  // practically never: keeps the chains alive, no store traffic
+}
+
+hipError_t launch_mfma_probe(int iters, int quiet, int workgroups, float *sink, hipStream_t st) {
+  hipLaunchKernelGGL(probe_mfma_kernel<kMfmaProbeOperandSets>, dim3((unsigned)workgroups), dim3(256), 0, st, iters, quiet,
+                     0x9e3779b9u, sink);
+  return hipGetLastError();
+}
+
 hipError_t launch_probe(void *buf, long long bytes, int mode, void *sink, hipStream_t st) {
   const long long pieces = bytes / 16;
   const long long blocks = (pieces + 256 * kProbePieces - 1) / (256 * kProbePieces);

@@ -46,3 +46,21 @@ def test_clock_probe_ends_by_itself_and_reports_a_plausible_clock():
         with pytest.raises(sa.SegattnError) as e:
             sa.segattn_clock_probe(bad, counts)
         assert e.value.status == sa.SEGATTN_EINVAL
+
+
+def test_mfma_probe_runs_and_reports_its_work():
+    import torch
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    flops = sa.segattn_mfma_probe(1000, sink)
+    torch.cuda.synchronize()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flops == 2 * cus * 4 * 1000 * 8 * 2 * 32 * 32 * 16
+    assert sa.segattn_mfma_probe(500, sink, operands=1) == flops // 2
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0                                 # the sink is never written
+    with pytest.raises(sa.SegattnError):
+        sa.segattn_mfma_probe(500, sink, operands=2)
+    for bad in (0, 10_000_001):
+        with pytest.raises(sa.SegattnError) as e:
+            sa.segattn_mfma_probe(bad, sink)
+        assert e.value.status == sa.SEGATTN_EINVAL

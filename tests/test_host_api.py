@@ -151,6 +151,10 @@ def test_probes_validate_before_touching_a_device():
     with pytest.raises(sa.SegattnError) as e:
         sa.segattn_bandwidth_probe(4096 + 8, 1 << 20, 0, 4096)      # misaligned
     assert e.value.status == sa.SEGATTN_EINVAL
+    for iters, sink in ((0, 4096), (10_000_001, 4096), (1000, 0), (1000, 4096 + 2)):
+        with pytest.raises(sa.SegattnError) as e:
+            sa.segattn_mfma_probe(iters, sink)
+        assert e.value.status == sa.SEGATTN_EINVAL
     for us, counts in ((0, 4096), (10_000_001, 4096), (1000, 0), (1000, 4096 + 4)):
         with pytest.raises(sa.SegattnError) as e:
             sa.segattn_clock_probe(us, counts)
