@@ -205,6 +205,10 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
     LDS_AS unsigned char *dst = lds + ld_slot + wave * (LPW * 1024);
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
+      // (the lane offsets pass through an empty asm so that their widening to 64 bits happens here,
+      // next to the addition: the load then takes a scalar base plus a 32-bit lane offset, and no
+      // vector instruction is spent on its address)
+      asm volatile("" : "+v"(off_k[i]), "+v"(off_v[i]));
       __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_kp + off_k[i]), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((const GLB_AS void *)(ld_vp + off_v[i]),
                                        (LDS_AS void *)(dst + G::kTensorBytes + i * 1024), 16, 0, 0);
@@ -294,6 +298,20 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
     }
   }
 
+  // Eight-slot ring: LDS addresses of the operand reads for the ring's two halves.  A step whose
+  // ring position is known at compile time (the unrolled blocks of eight steps below) reads its
+  // operands at one of these plus an immediate offset and spends no instruction on addresses.
+  constexpr bool kStaticRing = kPair && kSlots == 8 && 4 * G::kSlotBytes <= 65536;
+  constexpr int kHalves = kStaticRing ? 2 : 1;
+  unsigned kbase[kHalves][NKA], vbase[kHalves][NB];
+#pragma unroll
+  for (int hf = 0; hf < kHalves; ++hf) {
+#pragma unroll
+    for (int i = 0; i < NKA; ++i) kbase[hf][i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + hf * 4 * G::kSlotBytes);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) vbase[hf][nb] = (unsigned)(size_t)lds + (unsigned)(voff[nb] + hf * 4 * G::kSlotBytes);
+  }
+
   f32x16 O[QB][NB];
   float m_ref[QB], mc_ref[QB], l_run[QB];  // mc_ref = m_ref * c
 #pragma unroll
@@ -313,7 +331,7 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
   auto k_load = [&](int so, i32x4(&Kr)[NC]) __attribute__((always_inline)) {
     unsigned ka[NKA];
 #pragma unroll
-    for (int i = 0; i < NKA; ++i) ka[i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + so);
+    for (int i = 0; i < NKA; ++i) ka[i] = kbase[0][i] + (unsigned)so;
 #pragma unroll
     for (int kc = 0; kc < NC; ++kc)
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
@@ -333,7 +351,7 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
   auto v_load = [&](int so, s16x4(&Vr)[2][NB][2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const unsigned va = (unsigned)(size_t)lds + (unsigned)(voff[nb] + so);
+      const unsigned va = vbase[0][nb] + (unsigned)so;
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(Vr[h2][nb][0]) : "v"(va), "n"(16 * h2 * G::kRowBytes));
@@ -513,9 +531,16 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
   //   (sync, then the K reads of step j+2, two per slot)
   //   slots .. end            PV(j-1), last 16 keys
   //   odd slots               convert pair i to bf16 and add it to the row sum
-  auto hot_step = [&](auto masked, auto plain, auto syncs, int j, i32x4(&Kr)[NC], float(&Sc)[QB][16], float(&Sn)[QB][16],
-                      const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) __attribute__((always_inline)) {
+  // ring_pos: -1, or (as a compile-time tag) the ring slot of step j-1, from which the slots of the
+  // step's operand reads follow: V^T of step j-1 there, K of step j+2 three slots on.
+  auto hot_step = [&](auto masked, auto plain, auto syncs, auto ring_pos, int j, i32x4(&Kr)[NC], float(&Sc)[QB][16],
+                      float(&Sn)[QB][16], const bf16x8(&Pp)[QB][2], bf16x8(&Pc)[QB][2]) __attribute__((always_inline)) {
     if constexpr (decltype(masked)::value) mask_step(Sc, j);
+    constexpr int RP = decltype(ring_pos)::value;
+    constexpr bool kFixed = RP >= 0;
+    constexpr int vslot = kFixed ? RP : 0, kslot = kFixed ? (RP + 3) % 8 : 0;
+    constexpr int vimm = (vslot % 4) * G::kSlotBytes, kimm = (kslot % 4) * G::kSlotBytes;
+    static_assert(!kFixed || kStaticRing, "fixed ring positions need the eight-slot ring");
     constexpr int NS = QB * NC, NP = QB * NB;  // slots of the S^T product / of half a PV product
     constexpr int NSLOT = NS + 2 * NP;
     constexpr int NE = 16 * QB;                // softmax elements per lane and step
@@ -530,9 +555,11 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
     float ev[NE];   // exp2 results on their way to the bf16 pairs (a few live at a time)
     unsigned va[NB], ka[NKA];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) va[nb] = (unsigned)(size_t)lds + (unsigned)(voff[nb] + so_m1);
+    for (int nb = 0; nb < NB; ++nb)
+      va[nb] = kFixed ? vbase[kFixed ? vslot / 4 : 0][nb] : vbase[0][nb] + (unsigned)so_m1;
 #pragma unroll
-    for (int i = 0; i < NKA; ++i) ka[i] = (unsigned)(size_t)lds + (unsigned)(koff[i] + so_p2);
+    for (int i = 0; i < NKA; ++i)
+      ka[i] = kFixed ? kbase[kFixed ? kslot / 4 : 0][i] : kbase[0][i] + (unsigned)so_p2;
     // vector-ALU work of one slot: exp2 of EPS elements, and half of the conversion / row-sum
     // work of an earlier pair, so that every slot carries the same four issue slots
     auto valu_chunk = [&](int slot) __attribute__((always_inline)) {
@@ -550,8 +577,14 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
           const f32x2 ee = {ev[2 * i], ev[2 * i + 1]};
           Pw[qb][w8] = __builtin_bit_cast(int, __builtin_convertvector(ee, bf16x2));
         }
-        if (EPS == 2 || slot % 2 == 1)
-          psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][w8]), ones, psum[qb], false);
+        if (EPS == 2 || slot % 2 == 1) {
+          // the first pair starts the row sum: the three-operand form with a zero addend (the compiler's
+          // choice is a move of zero and the accumulating two-operand form)
+          if (w8 == 0)
+            asm("v_dot2_f32_bf16 %0, %1, %2, 0" : "=v"(psum[qb]) : "v"(Pw[qb][w8]), "s"(0x3f803f80));
+          else
+            psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, Pw[qb][w8]), ones, psum[qb], false);
+        }
       }
     };
     // transposing V^T reads per slot: one more than an even spread needs, so that the last reads
@@ -581,10 +614,10 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
             const int h2 = idx / (2 * NB), nb = (idx / 2) % NB, half = idx % 2;
             if (half == 0)
               asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
-                           : "=v"(Vr[h2][nb][0]) : "v"(va[nb]), "n"(16 * h2 * G::kRowBytes));
+                           : "=v"(Vr[h2][nb][0]) : "v"(va[nb]), "n"(16 * h2 * G::kRowBytes + vimm));
             else
               asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
-                           : "=v"(Vr[h2][nb][1]) : "v"(va[nb]), "n"((16 * h2 + 8) * G::kRowBytes));
+                           : "=v"(Vr[h2][nb][1]) : "v"(va[nb]), "n"((16 * h2 + 8) * G::kRowBytes + vimm));
           }
         }
       }
@@ -600,7 +633,7 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
       }
       if (slot > kSyncSlot && slot - kSyncSlot - 1 < NC) {
         const int kc = slot - kSyncSlot - 1;
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128 + kimm));
       }
       valu_chunk(slot);
       __builtin_amdgcn_sched_barrier(0);
@@ -666,15 +699,34 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
   // here and at the top of every iteration below: Sa = S^T(j), Pb = P(j-1), Kr = K operands of j+1
+  constexpr std::integral_constant<int, -1> anywhere{};
   while (j < n_act) {
+    // Blocks of eight unmasked steps at fixed ring positions (eight-slot ring): step j sits in slot
+    // j % 8 for the whole item, so from j = 1 (mod 8) on -- where the sequence starts -- the eight
+    // steps of a block read their operands at compile-time offsets; the slot variables return to
+    // where they were after eight steps and are left alone.
+    if constexpr (kStaticRing) {
+      while ((j & 7) == 1 && j + 7 < f && ld_js + 8 < ld_full_end) {
+        hot_step(no, yes, no, std::integral_constant<int, 0>{}, j, Kr, Sa, Sb, Pb, Pa);
+        hot_step(no, yes, yes, std::integral_constant<int, 1>{}, j + 1, Kr, Sb, Sa, Pa, Pb);
+        hot_step(no, yes, no, std::integral_constant<int, 2>{}, j + 2, Kr, Sa, Sb, Pb, Pa);
+        hot_step(no, yes, yes, std::integral_constant<int, 3>{}, j + 3, Kr, Sb, Sa, Pa, Pb);
+        hot_step(no, yes, no, std::integral_constant<int, 4>{}, j + 4, Kr, Sa, Sb, Pb, Pa);
+        hot_step(no, yes, yes, std::integral_constant<int, 5>{}, j + 5, Kr, Sb, Sa, Pa, Pb);
+        hot_step(no, yes, no, std::integral_constant<int, 6>{}, j + 6, Kr, Sa, Sb, Pb, Pa);
+        hot_step(no, yes, yes, std::integral_constant<int, 7>{}, j + 7, Kr, Sb, Sa, Pa, Pb);
+        j += 8;
+      }
+      if (j >= n_act) break;
+    }
     // pairs of steps that need no mask while the loader stays inside plain full steps of its span
     // (with the pair sync a pair is an odd step, which meets nobody, and the even step after it)
     if (!kPair || (j & 1)) {
       while (j + 1 < f && ld_js + 2 < ld_full_end) {
-        if constexpr (kPair) hot_step(no, yes, no, j, Kr, Sa, Sb, Pb, Pa);
-        else hot_step(no, yes, yes, j, Kr, Sa, Sb, Pb, Pa);
+        if constexpr (kPair) hot_step(no, yes, no, anywhere, j, Kr, Sa, Sb, Pb, Pa);
+        else hot_step(no, yes, yes, anywhere, j, Kr, Sa, Sb, Pb, Pa);
         advance();
-        hot_step(no, yes, yes, j + 1, Kr, Sb, Sa, Pa, Pb);
+        hot_step(no, yes, yes, anywhere, j + 1, Kr, Sb, Sa, Pa, Pb);
         advance();
         j += 2;
       }
@@ -684,8 +736,8 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
     // step needs a mask): the masked step with the loader's general advance; a mask that hides
     // nothing is harmless.  Its results move back into (Sa, Pb) so that the roles stay fixed
     // (choosing between the two register sets at run time would put them in memory).
-    if constexpr (kPair) hot_step(yes, no, !(j & 1), j, Kr, Sa, Sb, Pb, Pa);
-    else hot_step(yes, no, yes, j, Kr, Sa, Sb, Pb, Pa);
+    if constexpr (kPair) hot_step(yes, no, !(j & 1), anywhere, j, Kr, Sa, Sb, Pb, Pa);
+    else hot_step(yes, no, yes, anywhere, j, Kr, Sa, Sb, Pb, Pa);
     advance();
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
