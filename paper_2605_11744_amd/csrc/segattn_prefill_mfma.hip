@@ -81,10 +81,10 @@ struct StepGeom {
   static constexpr int kInstr = kTensorBytes / 1024;           // wave-wide 1 KB loads per tensor
   static constexpr int kRowsPerInstr = 1024 / kRowBytes;
   static constexpr int kRowsPer256 = 256 / kRowBytes;          // rows sharing one 64-bank window
-  // K rows are read 16 lanes = 16 consecutive rows at one logical chunk: XOR-ing the low three
-  // chunk bits with the row leaves a 2-way bank conflict for 256-byte rows (cheap: K reads are
-  // 8 per step) and keeps the upper chunk bit an immediate offset of the read.
-  __device__ static constexpr int swz_k(int row) { return (row / kRowsPer256) & 7; }
+  // K rows are read 16 lanes = 16 consecutive rows at one logical chunk: XOR-ing all chunk bits
+  // with the row (four bits for 256-byte rows) spreads the 16 rows over all 64 banks.  (With the
+  // low three bits only, rows r and r + 8 met in one bank: a two-way conflict on every K read.)
+  __device__ static constexpr int swz_k(int row) { return (row / kRowsPer256) & (kChunks - 1) & 15; }
   __device__ static constexpr int swz_v(int row) { return 4 * ((row / kRowsPer256) % (kChunks / 4)); }
 };
 
@@ -282,9 +282,10 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
   }
 
   // ---- per-lane LDS read offsets inside a slot
-  // K operand of k-chunk kc: row col, logical chunk 2kc+hi = 8 (kc/4) + (2 (kc%4) + hi); the
-  // swizzle touches the low three bits only, so 4 lane offsets + an immediate cover all kc.
-  constexpr int NKA = NC < 4 ? NC : 4;
+  // K operand of k-chunk kc: row col, logical chunk 2 kc + hi, swizzled with the row: one lane
+  // address per k-chunk
+  constexpr int NKA = NC;
+  static_assert(NC <= 8, "one lane address per k-chunk");
   int koff[NKA];
 #pragma unroll
   for (int i = 0; i < NKA; ++i) koff[i] = col * G::kRowBytes + (((2 * i + hi) ^ G::swz_k(col)) << 4);
@@ -334,7 +335,7 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
     for (int i = 0; i < NKA; ++i) ka[i] = kbase[0][i] + (unsigned)so;
 #pragma unroll
     for (int kc = 0; kc < NC; ++kc)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128));
+      asm volatile("ds_read_b128 %0, %1" : "=v"(Kr[kc]) : "v"(ka[kc]));
   };
   auto k_wait = [&](i32x4(&Kr)[NC]) __attribute__((always_inline)) {
     if constexpr (NC == 8) {
@@ -633,7 +634,7 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
       }
       if (slot > kSyncSlot && slot - kSyncSlot - 1 < NC) {
         const int kc = slot - kSyncSlot - 1;
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc % 4]), "n"((kc / 4) * 128 + kimm));
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Kr[kc]) : "v"(ka[kc]), "n"(kimm));
       }
       valu_chunk(slot);
       __builtin_amdgcn_sched_barrier(0);
