@@ -107,6 +107,9 @@ __device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillA
     if (f_left >= kBwdStep) {
 #pragma unroll
       for (int i = 0; i < LPW; ++i) {
+        // (through an empty asm, so that the lane offset is widened to 64 bits here, next to the
+        // addition: the load then takes a scalar base plus a 32-bit lane offset)
+        asm volatile("" : "+v"(f_off[i]));
         __builtin_amdgcn_global_load_lds((const GLB_AS void *)(f_k + f_off[i]), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((const GLB_AS void *)(f_v + f_off[i]), (LDS_AS void *)(dst + kTile + i * 1024), 16, 0, 0);
       }

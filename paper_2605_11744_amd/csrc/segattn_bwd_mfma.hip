@@ -189,9 +189,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
     const bool last = f_step == steps_per_head - 1;
     LDS_AS unsigned char *dst = lds + lds_off + wave * (LPW * 1024);
 #pragma unroll
-    for (int i = 0; i < LPW; ++i)
-      __builtin_amdgcn_global_load_lds((const GLB_AS void *)(base + f_at + (last ? f_off_last[i] : f_off[i])),
-                                       (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
+    for (int i = 0; i < LPW; ++i) {
+      // (the lane offset passes through an empty asm so that it is widened to 64 bits here, next to the
+      // addition: the load then takes a scalar base plus a 32-bit lane offset)
+      unsigned off = last ? f_off_last[i] : f_off[i];
+      asm volatile("" : "+v"(off));
+      __builtin_amdgcn_global_load_lds((const GLB_AS void *)(base + f_at + off), (LDS_AS void *)(dst + i * 1024), 16, 0, 0);
+    }
   };
   auto fetch_stats_and_advance = [&](int buf) __attribute__((always_inline)) {
     int r = f_step * kBwdStep + (lane & 31);
