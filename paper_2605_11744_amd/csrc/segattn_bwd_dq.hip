@@ -208,7 +208,7 @@ __device__ __forceinline__ unsigned bwd_dq_item(const Problem &p, const PrefillA
       }                                                                                                          \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
     }                                                                                                            \
-    if (!all_visible) {                                                                                          \
+    if (__builtin_expect(!all_visible, 0)) { /* rare: laid out off the step's straight path */                   \
       const int kmax = own ? (t < span_len - 1 ? t : span_len - 1) : span_len - 1; /* last visible key of the span */ \
       _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                             \
         S[r] = (k0 + 8 * (r / 4) + 4 * hi + r % 4 <= kmax) ? S[r] : -INFINITY; /* weight exactly 0 */            \

@@ -318,7 +318,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(const Problem p, const 
         _Pragma("unroll") for (int u = 0; u < 2; ++u)                                                            \
           asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(qt[kc][u]) : "v"(tro[kc][u]), "n"(BO));      \
       }                                                                                                          \
-      if (kc == 0 && !plain) {                                                                                   \
+      if (kc == 0 && __builtin_expect(!plain, 0)) { /* rare: laid out off the step's straight path */            \
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                         \
           const int i_rel = i_rel0 + 8 * (r / 4) + 4 * hi + r % 4; /* query row, relative to q_begin */          \
           S[r] = ((i_rel >= q_lo) & (i_rel < q_lim)) ? S[r] : -INFINITY;                                         \

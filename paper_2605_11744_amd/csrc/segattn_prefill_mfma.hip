@@ -462,7 +462,7 @@ __device__ __forceinline__ unsigned prefill_mfma_item(const Problem &p, const Pr
     bool any = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) any |= !(psum[qb] <= kLazyLimit);
-    if (__builtin_amdgcn_ballot_w64(any) != 0) {
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(any) != 0, 0)) {  // rare: laid out off the step's straight path
       // The first P stays "used" on this path too, so that its computation is not sunk below
       // the branch (it has to overlap with the matrix products above).
 #pragma unroll
