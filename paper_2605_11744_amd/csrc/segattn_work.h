@@ -80,12 +80,16 @@ __device__ __forceinline__ int take_item(unsigned *queue, int n_items, bool draw
   return bid;
 }
 
-// blockIdx -> (sequence, KV head, head sub-group, segment, query block): all PAST workgroups by
-// descending absolute query block (longest work first), then the others grouped so that the
-// query blocks sharing K/V rows run together on one XCD.
-__device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int bid, int rows_per_wg,
-                                   int heads_per_wg) {
-  WorkItem w;
+// Item index -> (segment, query block, head list position, sequence, head sub-group, prefix piece):
+// all PAST items by descending absolute query block (longest work first), then the others grouped
+// so that the query blocks sharing K/V rows run together on one XCD.  Pure integer arithmetic, the
+// same on the host (where it is tested for being a one-to-one map) and on the device.
+// total_items: items of the launch (PrefillArgs::grid_items, or the grid size).
+struct ItemCoords {
+  int seg, qblk, hidx, b, hs, part;
+};
+__host__ __device__ inline ItemCoords item_coords(const Problem &p, const PrefillArgs &a, int bid, int total_items,
+                                                  int heads_per_wg) {
   const int nhs = p.g / heads_per_wg;
   const int nqb = a.q_blocks_per_seg;
   // heads listed first, longest work first: the PAST heads -- unless they attend to a retrieved
@@ -115,7 +119,7 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
       hidx = rest - b * (int)dv.n_first.d;
     } else {
       const int pi = (int)past_items;
-      const int items = (a.grid_items > 0 ? a.grid_items : (int)gridDim.x) - pi;
+      const int items = total_items - pi;
       const int x = bid & 7;
       int start = 0, first = 0;
 #pragma unroll
@@ -161,7 +165,7 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     // 8 XCDs (one L2 each) round-robin by index: XCD x = bid % 8 takes the bids x, x+8, ... in
     // order.  Give each XCD a contiguous range of the list ordered by (segment, sequence, head,
     // head sub-group) and, inside one of those, by descending query block.
-    const long long items = (long long)(a.grid_items > 0 ? a.grid_items : (int)gridDim.x) - past_items;
+    const long long items = (long long)total_items - past_items;
     const int x = bid & 7;
     long long start = 0, first = 0;
 #pragma unroll
@@ -195,6 +199,16 @@ __device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int b
     b = rest % p.B;
     seg = rest / p.B;
   }
+  return ItemCoords{seg, qblk, hidx, b, hs, part};
+}
+
+// blockIdx -> work item: the coordinates above, then the item's key spans, query rows and outputs.
+__device__ inline WorkItem resolve(const Problem &p, const PrefillArgs &a, int bid, int rows_per_wg,
+                                   int heads_per_wg) {
+  WorkItem w;
+  const int parts = (a.cache != nullptr && a.parts > 1) ? a.parts : 1;
+  const ItemCoords ic = item_coords(p, a, bid, a.grid_items > 0 ? a.grid_items : (int)gridDim.x, heads_per_wg);
+  const int seg = ic.seg, qblk = ic.qblk, hidx = ic.hidx, b = ic.b, hs = ic.hs, part = ic.part;
   const int kv = p.order[hidx];
   const int pol = p.policy[kv];
   w.kv = kv;
