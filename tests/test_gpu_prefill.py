@@ -49,6 +49,24 @@ def test_fwd_seq_small(case, fp32_check, waves):
     G.assert_parity(o, l, o_ref, l_ref, fp32_check=fp32_check, what=f"small{case}")
 
 
+@pytest.mark.parametrize("item_queues", [1, 2])
+@pytest.mark.parametrize("seq_len,seg_len,tail_len", [(1400, 640, 200), (1100, 1100, 0), (2000, 512, 512)])
+def test_fwd_seq_items_of_many_steps(seq_len, seg_len, tail_len, item_queues, monkeypatch):
+    """Items of 2 to 60 key steps, every row against the oracle: the eight-wave kernel runs its
+    unmasked steps in blocks of eight at fixed ring positions, so an item's length decides how many
+    blocks it has (0 to 7), how many steps are left for the pairwise loop behind them, and where the
+    prefix ends inside a block (tail_len 200: a ragged prefix; 0: none; 512: whole steps)."""
+    import gpu_util as G
+    monkeypatch.setitem(G.TUNING, "prefill_waves", 8)
+    monkeypatch.setitem(G.TUNING, "item_queues", item_queues)
+    w = W.small("long_items", index=150, seq_len=seq_len, seg_len=seg_len, tail_len=tail_len, n_q_heads=8,
+                n_kv_heads=2, head_dim=128, kv_policy=[3, 1])
+    q, k, v = W.prefill_inputs(w)
+    o_ref, l_ref = _oracle(w, q, k, v)
+    o, l = G.fwd_seq(w, q, k, v, fp32_check=False)
+    G.assert_parity(o, l, o_ref, l_ref, fp32_check=False, what="long items")
+
+
 @pytest.mark.parametrize("fp32_check", [True, False])
 def test_fwd_seq_c1_full(fp32_check):
     import gpu_util as G
